@@ -1,0 +1,168 @@
+/*
+ * decoquant.h - C ABI of libdecoquant: decode-step attention over a KV cache held in
+ * DecoQuant form, and compression of newly appended K/V blocks, for AMD gfx950.
+ *
+ * Method: "DecoQuant" (arXiv 2405.12591).  A per-head block X[T_b, d] of keys or values is
+ * regrouped as M[b1, (t, b2)] = X[t, b1*j2 + b2] (Preliminary, Eq. 2 with n = 2, i_1 = 1) and
+ * factored exactly as M = T_S * T_L (Section 3.1, Eq. 3).  T_S (j1 x j1, carries the singular
+ * values and the outliers) stays in fp16; T_L (j1 x T_b*j2, orthonormal rows, narrow range) is
+ * quantized to `bits`-bit integers with one fp16 step per group (Preliminary, Eq. 1; Section
+ * 3.1 "Local Tensor Quantization").  Decode attention reads the codes directly and applies
+ * T_S by folding it into the query and into the P.V epilogue, which is the fused
+ * "dequantize + multiply the local tensors" of Section 3.2 ("Kernel Fusion for
+ * Dequantization") carried through the attention that follows it.
+ *
+ * Conventions for every entry point
+ *   - All buffers are caller-owned DEVICE memory unless marked "host".  The library never
+ *     allocates, frees or synchronises; all work is enqueued on the `hip_stream` argument
+ *     (a hipStream_t passed as void*; NULL is the default stream).
+ *   - fp16 values cross the boundary as uint16_t bit patterns (IEEE binary16).
+ *   - Return value: DQ_OK (0) or a negative dq_status.  After DQ_EHIP, dq_last_hip_error()
+ *     returns the hipError_t of the failed runtime call (as int).
+ *   - Inputs are read-only.  Calls that share a workspace must be ordered on one stream.
+ *
+ * Storage layout of a compressed cache (B sequences, H kv heads, NB block slots per head;
+ * tile = 128 tokens; c' = r*j2 + b2 is the element index inside a token row of T_L, r the
+ * bond index, b2 the minor channel index; u = c + 2^(bits-1) is the stored field of code c):
+ *   k_codes  u8   [B, H, NB, T_b, d*bits/8]   row t holds u of elements c' = 0..d-1, element e
+ *                                             at bit (e*bits)%8 of byte (e*bits)/8
+ *   k_scales f16  [B, H, NB, T_b, d/G]        step of group g = elements [g*G, (g+1)*G) of row t
+ *   k_small  f16  [B, H, NB, j1, j1]          T_S of keys TRANSPOSED: entry [r][b1] = T_S[b1][r]
+ *   v_codes  u8   [B, H, NB, T_b/128, j2, j1, 128*bits/8]
+ *                                             for tile, b2, r: the 128 tokens of that tile,
+ *                                             token tt at bit (tt*bits)%8 of byte (tt*bits)/8
+ *   v_scales f16  [B, H, NB, T_b, d/G]        same grouping (by c') as keys
+ *   v_small  f16  [B, H, NB, j1, j1]          T_S of values, entry [b1][r]
+ * Token t of sequence b lives in block t / T_b, row t % T_b.
+ */
+#ifndef DECOQUANT_H
+#define DECOQUANT_H
+
+#include <stddef.h>
+#include <stdint.h>
+
+#ifdef __cplusplus
+extern "C" {
+#endif
+
+typedef enum dq_status {
+  DQ_OK = 0,
+  DQ_EINVAL = -1,   /* null pointer, unsupported format, inconsistent sizes */
+  DQ_ENOSPACE = -2, /* workspace smaller than dq_*_workspace_bytes() */
+  DQ_EHIP = -3      /* a HIP runtime call failed; see dq_last_hip_error() */
+} dq_status;
+
+/* Format of a compressed cache.  Constraints: bits in {2, 4, 8}; head_dim == j1*j2;
+ * head_dim in {64, 128}; j1 in {8, 16, 32}; group divides head_dim and group >= head_dim/2
+ * or group divides head_dim/2; block_tokens is a positive multiple of 128. */
+typedef struct dq_format {
+  int32_t bits;         /* m of Eq. 1; qmax = 2^(m-1) - 1                         */
+  int32_t group;        /* G: elements per step, consecutive inside one token row  */
+  int32_t head_dim;     /* d                                                       */
+  int32_t j1;           /* side of the small tensor T_S (Eq. 2: j_1)               */
+  int32_t j2;           /* d / j1 (Eq. 2: j_2)                                     */
+  int32_t block_tokens; /* T_b: tokens per decomposed block (Eq. 2: i_2; i_1 = 1)  */
+} dq_format;
+
+/* Device pointers to the six arrays described above; shapes are fixed by (format, batch,
+ * kv_heads, block_capacity). */
+typedef struct dq_cache {
+  uint8_t* k_codes;
+  uint16_t* k_scales;
+  uint16_t* k_small;
+  uint8_t* v_codes;
+  uint16_t* v_scales;
+  uint16_t* v_small;
+  int32_t batch;
+  int32_t kv_heads;
+  int32_t block_capacity; /* NB */
+} dq_cache;
+
+/* Flags of dq_attn_decode. */
+#define DQ_DECODE_AUTO 0u          /* fastest kernel that supports the format           */
+#define DQ_DECODE_FORCE_GENERIC 1u /* scalar reference-grade HIP kernel, any format     */
+#define DQ_DECODE_FORCE_MFMA 2u    /* matrix-core kernel; DQ_EINVAL if format unsupported */
+
+int32_t dq_version(void);
+const char* dq_status_string(int32_t status);
+int32_t dq_last_hip_error(void);
+
+/* 1 if the matrix-core decode kernel supports (format, q_heads / kv_heads), else 0. */
+int32_t dq_decode_mfma_supported(const dq_format* fmt, int32_t q_heads, int32_t kv_heads);
+
+/* Bytes of workspace dq_attn_decode needs for these sizes (0 on invalid arguments).  The
+ * workspace holds split-sequence partial results; its first use must be preceded by one
+ * dq_workspace_init() call (it contains counters the kernels leave at zero afterwards). */
+size_t dq_decode_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t q_heads,
+                                 int32_t kv_heads, int32_t max_seq_len);
+
+/* Zero-fill a workspace with a kernel (safe under stream capture). */
+int32_t dq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream);
+
+/*
+ * Decode-step attention against the compressed cache (Section 3.2): for every sequence b and
+ * query head h_q, out[b, h_q, :] = softmax_t(q[b, h_q] . K_hat[t] * scale) . V_hat, over the
+ * tokens t < seq_lens[b] of kv head h_q / (q_heads / kv_heads), where K_hat and V_hat are the
+ * dequantized blocks T_S16 * (step * code).  No intermediate rounding to fp16; fp32
+ * accumulation; one final round-to-nearest-even to fp16.
+ *   q         f16 [B, q_heads, d]
+ *   seq_lens  i32 [B]; 0 <= seq_lens[b] <= max_seq_len; a sequence of length 0 yields zeros
+ *   max_seq_len  host integer upper bound on seq_lens, <= block_capacity * T_b (sizes the grid)
+ *   softmax_scale  <= 0 selects 1/sqrt(d)
+ *   out       f16 [B, q_heads, d]
+ *   out_f32   optional f32 [B, q_heads, d] copy of the result before the fp16 rounding, or NULL
+ * Tokens >= seq_lens[b] are never used: their codes, steps and whole blocks may hold anything.
+ */
+int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                       int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                       float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
+                       size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
+/* Bytes of workspace dq_compress_kv needs for n_blocks = B * H blocks of keys plus as many of
+ * values (0 on invalid arguments). */
+size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads);
+
+/*
+ * Compress one new block of keys and one of values per (sequence, kv head) and write them
+ * into block slot blk_idx[b] of the cache (Section 3.2 "KV Cache Quantization": DecoQuant is
+ * applied when a block of appended tokens has accumulated; Section 3.1 for the two steps).
+ *   k_new, v_new  f16 [B, H, t_new, d], 1 <= t_new <= T_b (host integer)
+ *   blk_idx       i32 [B] device, 0 <= blk_idx[b] < block_capacity; negative skips sequence b
+ *   n_valid       i32 [B] device, rows >= n_valid[b] (and rows >= t_new) count as zero; may be NULL
+ * The decomposition is an eigen-decomposition of the fp64 Gram matrix M M^T (j1 x j1) by
+ * cyclic Jacobi rotations: T_S = U diag(sigma), T_L = diag(1/sigma) U^T M; directions with
+ * sigma <= 1e-6 sigma_max are dropped (T_S column and T_L row zero).  T_S saturates to the
+ * fp16 range; bit 0 of the int32 at workspace[0] is set if that happened.
+ * The factors are not unique (signs, order of equal singular values): only their product and
+ * the orthonormality of T_L's rows are defined.
+ */
+int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                       const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                       const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                       void* hip_stream);
+
+/*
+ * Quantize and pack a caller-supplied large tensor (Preliminary, Eq. 1 per group; Section 3.1
+ * step 2).  step = fp16(max|x| / qmax), the exact quotient rounded once, ties to even;
+ * code = clamp(nearest integer of the exact x / step, ties to even, +-qmax); step == 0 gives
+ * codes 0.  Results are bit-exact functions of the input.
+ *   t_large  f32 [n_rows, d], token-major rows (element c' = r*j2 + b2); n_rows % 128 == 0
+ *   value_layout  0: write key layout (codes [n_rows, d*bits/8]);
+ *                 1: write value layout (codes [n_rows/128, j2, j1, 128*bits/8])
+ *   codes, scales  outputs; scales f16 [n_rows, d/G] in both layouts
+ */
+int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, int64_t n_rows,
+                         int32_t value_layout, uint8_t* codes, uint16_t* scales,
+                         void* hip_stream);
+
+/*
+ * Measurement helper: read `bytes` (multiple of 16) from src with 128-bit loads and fold them
+ * into sink[0..3] (u32) so the reads cannot be elided.  Gives the achievable read bandwidth
+ * that the decode kernel's rate is compared with.
+ */
+int32_t dq_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream);
+
+#ifdef __cplusplus
+}
+#endif
+#endif /* DECOQUANT_H */

@@ -309,8 +309,10 @@ def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
 def reconstruct_block(small: np.ndarray, steps: np.ndarray, codes: np.ndarray, fmt: Format
                       ) -> np.ndarray:
     """X_hat[block_tokens, head_dim] = un-matricise(T_S16 @ (Delta * c)) in fp64, no rounding."""
-    t_l_hat = token_major_to_large(dequantize(codes, steps, fmt.group), fmt.j1, fmt.j2)
-    m_hat = small.astype(np.float64) @ t_l_hat
+    # rows past the valid tokens of a partly filled block may hold anything (NaN steps included)
+    with np.errstate(invalid="ignore", over="ignore"):
+        t_l_hat = token_major_to_large(dequantize(codes, steps, fmt.group), fmt.j1, fmt.j2)
+        m_hat = small.astype(np.float64) @ t_l_hat
     return unmatricise(m_hat, fmt.block_tokens, fmt.head_dim, 1, fmt.j1)
 
 

@@ -1,0 +1,259 @@
+"""ctypes binding of libdecoquant.so; names follow include/decoquant.h."""
+from __future__ import annotations
+
+import ctypes as C
+import os
+from dataclasses import dataclass
+from typing import Dict, Optional
+
+import torch
+
+from . import build as _build
+
+DECODE_AUTO = 0
+DECODE_FORCE_GENERIC = 1
+DECODE_FORCE_MFMA = 2
+
+EXPORTED_SYMBOLS = [
+    "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
+    "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode",
+    "dq_compress_workspace_bytes", "dq_compress_kv", "dq_quantize_pack", "dq_stream_read",
+]
+
+
+class DQError(RuntimeError):
+    pass
+
+
+class _CFormat(C.Structure):
+    _fields_ = [("bits", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
+                ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32)]
+
+
+class _CCache(C.Structure):
+    _fields_ = [("k_codes", C.c_void_p), ("k_scales", C.c_void_p), ("k_small", C.c_void_p),
+                ("v_codes", C.c_void_p), ("v_scales", C.c_void_p), ("v_small", C.c_void_p),
+                ("batch", C.c_int32), ("kv_heads", C.c_int32), ("block_capacity", C.c_int32)]
+
+
+def _load() -> C.CDLL:
+    path = _build.LIB_PATH
+    if not os.path.exists(path):
+        _build.build_library()
+    if not os.path.exists(path):
+        raise DQError("libdecoquant.so is missing and could not be built")
+    l = C.CDLL(path)
+    l.dq_version.restype = C.c_int32
+    l.dq_status_string.restype = C.c_char_p
+    l.dq_status_string.argtypes = [C.c_int32]
+    l.dq_last_hip_error.restype = C.c_int32
+    l.dq_decode_mfma_supported.restype = C.c_int32
+    l.dq_decode_mfma_supported.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32]
+    l.dq_decode_workspace_bytes.restype = C.c_size_t
+    l.dq_decode_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32, C.c_int32, C.c_int32]
+    l.dq_workspace_init.restype = C.c_int32
+    l.dq_workspace_init.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p]
+    l.dq_attn_decode.restype = C.c_int32
+    l.dq_attn_decode.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_int32, C.c_void_p,
+                                 C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
+                                 C.c_uint32, C.c_void_p]
+    l.dq_compress_workspace_bytes.restype = C.c_size_t
+    l.dq_compress_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32]
+    l.dq_compress_kv.restype = C.c_int32
+    l.dq_compress_kv.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int32,
+                                 C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    l.dq_quantize_pack.restype = C.c_int32
+    l.dq_quantize_pack.argtypes = [C.POINTER(_CFormat), C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
+                                   C.c_void_p, C.c_void_p]
+    l.dq_stream_read.restype = C.c_int32
+    l.dq_stream_read.argtypes = [C.c_void_p, C.c_size_t, C.c_void_p, C.c_void_p]
+    return l
+
+
+lib = _load()
+
+
+def version() -> int:
+    return int(lib.dq_version())
+
+
+def status_string(status: int) -> str:
+    return lib.dq_status_string(status).decode()
+
+
+def _check(status: int, what: str) -> None:
+    if status != 0:
+        extra = ""
+        if status == -3:
+            extra = " (hipError %d)" % lib.dq_last_hip_error()
+        raise DQError("%s failed: %s%s" % (what, status_string(status), extra))
+
+
+@dataclass(frozen=True)
+class Format:
+    bits: int
+    group: int
+    head_dim: int
+    j1: int
+    j2: int
+    block_tokens: int
+
+    def c(self) -> _CFormat:
+        return _CFormat(self.bits, self.group, self.head_dim, self.j1, self.j2, self.block_tokens)
+
+    @property
+    def row_bytes(self) -> int:
+        return self.head_dim * self.bits // 8
+
+    @property
+    def groups(self) -> int:
+        return self.head_dim // self.group
+
+
+class Cache:
+    """Device tensors of a compressed cache plus the C struct that points at them."""
+
+    def __init__(self, fmt: Format, tensors: Dict[str, torch.Tensor], batch: int, kv_heads: int,
+                 block_capacity: int):
+        self.fmt, self.t = fmt, tensors
+        self.batch, self.kv_heads, self.block_capacity = batch, kv_heads, block_capacity
+        for name, ten in tensors.items():
+            if not (ten.is_cuda and ten.is_contiguous()):
+                raise DQError("cache tensor %s must be a contiguous device tensor" % name)
+        self.c = _CCache(*(tensors[n].data_ptr() for n in
+                           ("k_codes", "k_scales", "k_small", "v_codes", "v_scales", "v_small")),
+                         batch, kv_heads, block_capacity)
+
+    def nbytes(self) -> int:
+        return sum(t.numel() * t.element_size() for t in self.t.values())
+
+    def clone(self) -> "Cache":
+        return Cache(self.fmt, {k: v.clone() for k, v in self.t.items()}, self.batch, self.kv_heads,
+                     self.block_capacity)
+
+
+def _shapes(fmt: Format, b: int, h: int, nb: int):
+    tiles = fmt.block_tokens // 128
+    return {
+        "k_codes": ((b, h, nb, fmt.block_tokens, fmt.row_bytes), torch.uint8),
+        "k_scales": ((b, h, nb, fmt.block_tokens, fmt.groups), torch.float16),
+        "k_small": ((b, h, nb, fmt.j1, fmt.j1), torch.float16),
+        "v_codes": ((b, h, nb, tiles, fmt.j2, fmt.j1, 128 * fmt.bits // 8), torch.uint8),
+        "v_scales": ((b, h, nb, fmt.block_tokens, fmt.groups), torch.float16),
+        "v_small": ((b, h, nb, fmt.j1, fmt.j1), torch.float16),
+    }
+
+
+def alloc_cache(fmt: Format, batch: int, kv_heads: int, block_capacity: int, device="cuda:0",
+                fill: Optional[int] = 0) -> Cache:
+    """Allocate the six cache arrays.  fill=None leaves them uninitialised."""
+    tensors = {}
+    for name, (shape, dtype) in _shapes(fmt, batch, kv_heads, block_capacity).items():
+        t = torch.empty(shape, dtype=dtype, device=device)
+        if fill is not None:
+            t.view(torch.uint8).fill_(fill)
+        tensors[name] = t
+    return Cache(fmt, tensors, batch, kv_heads, block_capacity)
+
+
+def cache_from_numpy(fmt: Format, arrays, device="cuda:0") -> Cache:
+    """Upload host arrays that already follow the storage layout."""
+    b, h, nb = arrays["k_codes"].shape[:3]
+    tensors = {}
+    for name, (shape, dtype) in _shapes(fmt, b, h, nb).items():
+        a = arrays[name]
+        if tuple(a.shape) != tuple(shape):
+            raise DQError("array %s has shape %s, expected %s" % (name, a.shape, shape))
+        tensors[name] = torch.from_numpy(a).to(device).contiguous()
+        if tensors[name].dtype != dtype:
+            raise DQError("array %s has dtype %s" % (name, a.dtype))
+    return Cache(fmt, tensors, b, h, nb)
+
+
+def _stream_ptr(device) -> int:
+    return torch.cuda.current_stream(device).cuda_stream
+
+
+def decode_workspace(fmt: Format, batch: int, q_heads: int, kv_heads: int, max_seq_len: int,
+                     device="cuda:0") -> torch.Tensor:
+    cf = fmt.c()
+    n = lib.dq_decode_workspace_bytes(C.byref(cf), batch, q_heads, kv_heads, max_seq_len)
+    if n == 0:
+        raise DQError("dq_decode_workspace_bytes rejected the arguments")
+    n = (n + 15) // 16 * 16
+    ws = torch.empty(n, dtype=torch.uint8, device=device)
+    workspace_init(ws)
+    return ws
+
+
+def compress_workspace(fmt: Format, batch: int, kv_heads: int, device="cuda:0") -> torch.Tensor:
+    cf = fmt.c()
+    n = lib.dq_compress_workspace_bytes(C.byref(cf), batch, kv_heads)
+    if n == 0:
+        raise DQError("dq_compress_workspace_bytes rejected the arguments")
+    return torch.empty((n + 15) // 16 * 16, dtype=torch.uint8, device=device)
+
+
+def workspace_init(ws: torch.Tensor) -> None:
+    _check(lib.dq_workspace_init(ws.data_ptr(), ws.numel(), _stream_ptr(ws.device)), "dq_workspace_init")
+
+
+def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
+                workspace: torch.Tensor, out: Optional[torch.Tensor] = None,
+                out_f32: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
+                flags: int = DECODE_AUTO) -> torch.Tensor:
+    """out[b, h_q] = softmax(q . K_hat^T * scale) V_hat over the compressed cache (dq_attn_decode)."""
+    fmt = cache.fmt
+    if q.dtype != torch.float16 or not q.is_contiguous() or seq_lens.dtype != torch.int32:
+        raise DQError("q must be contiguous fp16 and seq_lens int32")
+    bsz, hq, d = q.shape
+    if out is None:
+        out = torch.empty_like(q)
+    cf = fmt.c()
+    st = lib.dq_attn_decode(C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
+                            softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), flags, _stream_ptr(q.device))
+    _check(st, "dq_attn_decode")
+    return out
+
+
+def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
+                n_valid: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    """Compress k_new, v_new [B, H, t_new, d] into block slot blk_idx[b] (dq_compress_kv)."""
+    for t in (k_new, v_new):
+        if t.dtype != torch.float16 or not t.is_contiguous():
+            raise DQError("k_new/v_new must be contiguous fp16")
+    cf = fmt_c = cache.fmt.c()
+    t_new = k_new.shape[2]
+    st = lib.dq_compress_kv(C.byref(fmt_c), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(), t_new,
+                            blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
+                            workspace.data_ptr(), workspace.numel(), _stream_ptr(k_new.device))
+    _check(st, "dq_compress_kv")
+
+
+def quantize_pack(fmt: Format, t_large: torch.Tensor, value_layout: bool):
+    """Quantize + pack fp32 rows [n_rows, d]; returns (codes u8, scales f16) (dq_quantize_pack)."""
+    if t_large.dtype != torch.float32 or not t_large.is_contiguous():
+        raise DQError("t_large must be contiguous fp32")
+    n_rows, d = t_large.shape
+    if value_layout:
+        codes = torch.empty((n_rows // 128, fmt.j2, fmt.j1, 128 * fmt.bits // 8), dtype=torch.uint8,
+                            device=t_large.device)
+    else:
+        codes = torch.empty((n_rows, fmt.row_bytes), dtype=torch.uint8, device=t_large.device)
+    scales = torch.empty((n_rows, fmt.groups), dtype=torch.float16, device=t_large.device)
+    cf = fmt.c()
+    st = lib.dq_quantize_pack(C.byref(cf), t_large.data_ptr(), n_rows, 1 if value_layout else 0,
+                              codes.data_ptr(), scales.data_ptr(), _stream_ptr(t_large.device))
+    _check(st, "dq_quantize_pack")
+    return codes, scales
+
+
+def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
+    nbytes = src.numel() * src.element_size()
+    _check(lib.dq_stream_read(src.data_ptr(), nbytes, sink.data_ptr(), _stream_ptr(src.device)), "dq_stream_read")
+
+
+def decode_mfma_supported(fmt: Format, q_heads: int, kv_heads: int) -> bool:
+    cf = fmt.c()
+    return bool(lib.dq_decode_mfma_supported(C.byref(cf), q_heads, kv_heads))

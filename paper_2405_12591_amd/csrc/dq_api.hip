@@ -1,0 +1,141 @@
+// Host side of the C ABI: argument checks, workspace carve-up, kernel selection.
+#include <atomic>
+
+#include "dq_decode.h"
+
+namespace dq {
+
+static std::atomic<int> g_last_hip_error{0};
+void set_last_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
+
+int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma) {
+  const int max_tiles = (max_seq_len + kTileTokens - 1) / kTileTokens;
+  if (max_tiles <= 0) return 1;
+  const int units = batch * (mfma ? kv_heads : q_heads);
+  // aim at >= 2048 workgroups, at least 2 tiles each, at most kMaxSplits splits
+  int want = (2048 + units - 1) / units;
+  int by_len = (max_tiles + 1) / 2;
+  int n = want < by_len ? want : by_len;
+  if (n < 1) n = 1;
+  if (n > kMaxSplits) n = kMaxSplits;
+  if (n > max_tiles) n = max_tiles;
+  return n;
+}
+
+__global__ void fill_zero_kernel(uint4* p, size_t n16) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  for (size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x; i < n16; i += stride) p[i] = make_uint4(0, 0, 0, 0);
+}
+
+typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
+
+__global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restrict__ src, size_t n16,
+                                                          uint32_t* __restrict__ sink) {
+  const size_t stride = (size_t)gridDim.x * blockDim.x;
+  u32x4 acc = {0, 0, 0, 0};
+  size_t i = (size_t)blockIdx.x * blockDim.x + threadIdx.x;
+  for (; i + 3 * stride < n16; i += 4 * stride) {
+    const u32x4 a = __builtin_nontemporal_load(src + i);
+    const u32x4 b = __builtin_nontemporal_load(src + i + stride);
+    const u32x4 c = __builtin_nontemporal_load(src + i + 2 * stride);
+    const u32x4 e = __builtin_nontemporal_load(src + i + 3 * stride);
+    acc ^= a ^ b ^ c ^ e;
+  }
+  for (; i < n16; i += stride) acc ^= __builtin_nontemporal_load(src + i);
+  // a data-dependent store that practically never happens keeps the loads alive
+  if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) {
+    sink[0] = acc.x; sink[1] = acc.y; sink[2] = acc.z; sink[3] = acc.w;
+  }
+}
+
+}  // namespace dq
+
+using namespace dq;
+
+extern "C" int32_t dq_version(void) { return 1; }
+
+extern "C" const char* dq_status_string(int32_t status) {
+  switch (status) {
+    case DQ_OK: return "ok";
+    case DQ_EINVAL: return "invalid argument or unsupported format";
+    case DQ_ENOSPACE: return "workspace too small";
+    case DQ_EHIP: return "HIP runtime error";
+    default: return "unknown status";
+  }
+}
+
+extern "C" int32_t dq_last_hip_error(void) { return g_last_hip_error.load(); }
+
+extern "C" int32_t dq_decode_mfma_supported(const dq_format* fmt, int32_t q_heads, int32_t kv_heads) {
+  return mfma_supported(fmt, q_heads, kv_heads) ? 1 : 0;
+}
+
+extern "C" size_t dq_decode_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t q_heads,
+                                            int32_t kv_heads, int32_t max_seq_len) {
+  if (!format_ok(fmt) || batch <= 0 || q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads ||
+      max_seq_len < 0)
+    return 0;
+  return (size_t)kWsHeaderBytes + decode_counter_bytes(batch, kv_heads) +
+         decode_partial_bytes(fmt, batch, q_heads);
+}
+
+extern "C" int32_t dq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_stream) {
+  if (!workspace || workspace_bytes % 16 || ((uintptr_t)workspace & 15)) return DQ_EINVAL;
+  if (workspace_bytes == 0) return DQ_OK;
+  const size_t n16 = workspace_bytes / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 1024) blocks = 1024;
+  hipLaunchKernelGGL(fill_zero_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     reinterpret_cast<uint4*>(workspace), n16);
+  DQ_HIP_CHECK(hipGetLastError());
+  return DQ_OK;
+}
+
+extern "C" int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                                  int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                  float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
+                                  size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+  if (!format_ok(fmt) || !cache || !q || !seq_lens || !out || !workspace) return DQ_EINVAL;
+  if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
+      !cache->v_small)
+    return DQ_EINVAL;
+  if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
+  if (q_heads <= 0 || q_heads % cache->kv_heads) return DQ_EINVAL;
+  if (max_seq_len < 0 || (long)max_seq_len > (long)cache->block_capacity * fmt->block_tokens) return DQ_EINVAL;
+  if ((flags & DQ_DECODE_FORCE_GENERIC) && (flags & DQ_DECODE_FORCE_MFMA)) return DQ_EINVAL;
+  const size_t need = dq_decode_workspace_bytes(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len);
+  if (need == 0) return DQ_EINVAL;
+  if (workspace_bytes < need) return DQ_ENOSPACE;
+  const bool can_mfma = mfma_supported(fmt, q_heads, cache->kv_heads);
+  if ((flags & DQ_DECODE_FORCE_MFMA) && !can_mfma) return DQ_EINVAL;
+  const bool use_mfma = can_mfma && !(flags & DQ_DECODE_FORCE_GENERIC);
+
+  DecodeArgs a;
+  a.fmt = *fmt;
+  a.cache = *cache;
+  a.q = q;
+  a.q_heads = q_heads;
+  a.seq_lens = seq_lens;
+  a.max_seq_len = max_seq_len;
+  a.scale = softmax_scale > 0.f ? softmax_scale : 1.0f / sqrtf((float)fmt->head_dim);
+  a.out = out;
+  a.out_f32 = out_f32;
+  char* ws = reinterpret_cast<char*>(workspace);
+  a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
+  a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, cache->kv_heads));
+  a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma);
+  hipStream_t st = (hipStream_t)hip_stream;
+  return use_mfma ? launch_decode_mfma(a, st) : launch_decode_generic(a, st);
+}
+
+extern "C" int32_t dq_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {
+  if (!src || !sink || bytes % 16 || ((uintptr_t)src & 15)) return DQ_EINVAL;
+  if (bytes == 0) return DQ_OK;
+  const size_t n16 = bytes / 16;
+  size_t blocks = (n16 + 255) / 256;
+  if (blocks > 256 * 16) blocks = 256 * 16;
+  hipLaunchKernelGGL(stream_read_kernel, dim3((unsigned)blocks), dim3(256), 0, (hipStream_t)hip_stream,
+                     reinterpret_cast<const u32x4*>(src), n16, sink);
+  DQ_HIP_CHECK(hipGetLastError());
+  return DQ_OK;
+}

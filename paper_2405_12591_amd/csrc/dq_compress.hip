@@ -1,0 +1,382 @@
+// Compression of K/V blocks into DecoQuant form (Section 3.1 of arXiv 2405.12591):
+//   step 1  two-site MPO split of the regrouped block, M = T_S * T_L            (Eq. 2, Eq. 3)
+//   step 2  per-group round-to-nearest quantization of T_L, T_S kept in fp16   (Eq. 1)
+// Two kernels: `decompose_kernel` (Gram matrix, Jacobi eigen-solver, projection) writes the
+// small tensor into the cache and the fp32 large tensor into the workspace;
+// `quantize_tiles_kernel` turns fp32 rows into packed codes and fp16 steps.
+#include "dq_common.h"
+
+namespace dq {
+
+// ------------------------------------------------------------------------------------------
+// Quantize + pack one tile of 128 token rows (Eq. 1 per group).  256 threads.
+// ------------------------------------------------------------------------------------------
+template <int BITS>
+__device__ void quantize_tile(const float* __restrict__ src,  // [128, d] fp32
+                              int d, int G, int j1, int j2, int value_layout,
+                              uint8_t* __restrict__ codes_out,    // tile's code bytes
+                              uint16_t* __restrict__ scales_out,  // [128, d/G]
+                              uint8_t* __restrict__ lds_u) {      // [128 * d] stored fields
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  constexpr int BIAS = 1 << (BITS - 1);
+  const int tid = threadIdx.x;
+  const int row = tid >> 1, half = tid & 1;
+  const int seg = d >> 1;
+  const float* x = src + (long)row * d + half * seg;
+  const int groups = d / G;
+
+  if (G == d) {
+    float amax = 0.f;
+    for (int e = 0; e < seg; e += 4) {
+      const float4 v = *reinterpret_cast<const float4*>(x + e);
+      amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+    }
+    amax = fmaxf(amax, __shfl_xor(amax, 1));
+    const uint16_t sbits = f64_to_f16_rne((double)amax / (double)QMAX, false, nullptr);
+    const double step = (double)h2f(sbits);
+    if (half == 0) scales_out[row] = sbits;
+    for (int e = 0; e < seg; ++e) {
+      int c = 0;
+      if (step > 0.0) {
+        double r = __builtin_rint((double)x[e] / step);
+        r = fmin(fmax(r, (double)-QMAX), (double)QMAX);
+        c = (int)r;
+      }
+      lds_u[row * d + half * seg + e] = (uint8_t)(c + BIAS);
+    }
+  } else {
+    const int gps = seg / G;  // groups per half row
+    for (int gi = 0; gi < gps; ++gi) {
+      const float* xg = x + gi * G;
+      float amax = 0.f;
+      for (int e = 0; e < G; e += 4) {
+        const float4 v = *reinterpret_cast<const float4*>(xg + e);
+        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+      }
+      const uint16_t sbits = f64_to_f16_rne((double)amax / (double)QMAX, false, nullptr);
+      const double step = (double)h2f(sbits);
+      scales_out[row * groups + half * gps + gi] = sbits;
+      for (int e = 0; e < G; ++e) {
+        int c = 0;
+        if (step > 0.0) {
+          double r = __builtin_rint((double)xg[e] / step);
+          r = fmin(fmax(r, (double)-QMAX), (double)QMAX);
+          c = (int)r;
+        }
+        lds_u[row * d + half * seg + gi * G + e] = (uint8_t)(c + BIAS);
+      }
+    }
+  }
+  __syncthreads();
+
+  constexpr int PER_WORD = 32 / BITS;
+  const int total_words = kTileTokens * d / PER_WORD;
+  uint32_t* out32 = reinterpret_cast<uint32_t*>(codes_out);
+  if (!value_layout) {
+    // key layout: rows of d elements, element index contiguous
+    for (int w = tid; w < total_words; w += blockDim.x) {
+      const int ebase = w * PER_WORD;
+      uint32_t word = 0;
+#pragma unroll
+      for (int k = 0; k < PER_WORD; ++k) word |= (uint32_t)lds_u[ebase + k] << (k * BITS);
+      out32[w] = word;
+    }
+  } else {
+    // value layout: [b2][r][128 tokens], tokens contiguous
+    const int words_per_row = kTileTokens / PER_WORD;
+    for (int w = tid; w < total_words; w += blockDim.x) {
+      const int rowid = w / words_per_row;  // b2 * j1 + r
+      const int wi = w % words_per_row;
+      const int b2 = rowid / j1, r = rowid % j1;
+      const int col = r * j2 + b2;
+      uint32_t word = 0;
+#pragma unroll
+      for (int k = 0; k < PER_WORD; ++k)
+        word |= (uint32_t)lds_u[(wi * PER_WORD + k) * d + col] << (k * BITS);
+      out32[w] = word;
+    }
+  }
+  __syncthreads();
+}
+
+// Stand-alone entry: contiguous input rows, contiguous outputs (dq_quantize_pack).
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restrict__ t_large, int d,
+                                                            int G, int j1, int j2, int value_layout,
+                                                            uint8_t* __restrict__ codes,
+                                                            uint16_t* __restrict__ scales) {
+  extern __shared__ uint8_t lds_u[];
+  const long tile = blockIdx.x;
+  const long tile_code_bytes = (long)kTileTokens * d * BITS / 8;
+  quantize_tile<BITS>(t_large + tile * kTileTokens * d, d, G, j1, j2, value_layout,
+                      codes + tile * tile_code_bytes, scales + tile * kTileTokens * (d / G), lds_u);
+}
+
+// Compress path: tile `blockIdx.x` of block (b, h, which) goes to cache slot blk_idx[b].
+template <int BITS>
+__global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __restrict__ large_ws,
+                                                             dq_format fmt, dq_cache cache,
+                                                             const int32_t* __restrict__ blk_idx) {
+  extern __shared__ uint8_t lds_u[];
+  const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
+  const int tile = blockIdx.x % g.tiles_per_block;
+  const int unit = blockIdx.x / g.tiles_per_block;  // (b*H + h)*2 + which
+  const int which = unit & 1;
+  const int bh = unit >> 1;
+  const int b = bh / g.H;
+  const int slot = blk_idx[b];
+  if (slot < 0 || slot >= g.NB) return;
+  const long blk = (long)bh * g.NB + slot;
+  const float* src = large_ws + ((long)unit * g.Tb + (long)tile * kTileTokens) * g.d;
+  uint8_t* codes = (which ? cache.v_codes : cache.k_codes) + blk * g.codes_per_block +
+                   (long)tile * kTileTokens * g.row_bytes;
+  uint16_t* scales = (which ? cache.v_scales : cache.k_scales) + blk * g.scales_per_block +
+                     (long)tile * kTileTokens * g.groups;
+  quantize_tile<BITS>(src, g.d, g.G, g.j1, g.j2, which, codes, scales, lds_u);
+}
+
+// ------------------------------------------------------------------------------------------
+// Decomposition: Gram matrix in fp64, parallel cyclic Jacobi, projection.  256 threads.
+// ------------------------------------------------------------------------------------------
+constexpr int kJMax = 32;
+constexpr int kGramTile = 32;  // tokens staged in LDS per Gram step
+
+__global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache cache,
+                                                        const uint16_t* __restrict__ k_new,
+                                                        const uint16_t* __restrict__ v_new,
+                                                        int t_new,
+                                                        const int32_t* __restrict__ blk_idx,
+                                                        const int32_t* __restrict__ n_valid,
+                                                        float* __restrict__ large_ws,
+                                                        int32_t* __restrict__ status) {
+  const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
+  const int unit = blockIdx.x;  // (b*H + h)*2 + which
+  const int which = unit & 1;
+  const int bh = unit >> 1;
+  const int b = bh / g.H;
+  const int slot = blk_idx[b];
+  if (slot < 0 || slot >= g.NB) return;
+  int nv = t_new;
+  if (n_valid) nv = min(max(n_valid[b], 0), t_new);
+  const int tid = threadIdx.x;
+  const int j1 = g.j1, j2 = g.j2, d = g.d;
+  const uint16_t* X = (which ? v_new : k_new) + (long)bh * t_new * d;  // [t_new, d] fp16 bits
+
+  __shared__ float xs[kGramTile * 128];
+  __shared__ double A[2][kJMax][kJMax + 1];  // Gram matrix, double buffered
+  __shared__ double V[2][kJMax][kJMax + 1];  // accumulated rotations
+  __shared__ double rc[kJMax], rs[kJMax];    // rotation (c, s) per index (shared by both partners)
+  __shared__ int partner[kJMax];
+  __shared__ int is_p[kJMax];                // 1 if index is the "p" (first) member of its pair
+  __shared__ double sigma[kJMax], lam[kJMax];
+  __shared__ int order[kJMax];
+  __shared__ double W[kJMax][kJMax + 1];     // W[r][b1] = U[b1][order r] / sigma_r
+  __shared__ double offarr[kJMax];           // per rotating thread: largest relative off-diagonal seen
+
+  // ---- Gram matrix: Gm[p][q] = sum_{t, b2} X[t, p*j2+b2] * X[t, q*j2+b2] ----
+  const int nent = j1 * j1;
+  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  for (int t0 = 0; t0 < nv; t0 += kGramTile) {
+    const int nt = min(kGramTile, nv - t0);
+    for (int i = tid; i < nt * d; i += blockDim.x) xs[i] = h2f(X[(long)t0 * d + i]);
+    __syncthreads();
+    for (int k = 0, idx = tid; idx < nent; idx += blockDim.x, ++k) {
+      const int p = idx / j1, q = idx % j1;
+      double a = 0.0;  // every product of two fp16 values is exact in fp64; only the sum rounds
+      for (int t = 0; t < nt; ++t) {
+        const float* xr = xs + t * d;
+        for (int b2 = 0; b2 < j2; ++b2) a = fma((double)xr[p * j2 + b2], (double)xr[q * j2 + b2], a);
+      }
+      acc[k] += a;
+    }
+    __syncthreads();
+  }
+  for (int k = 0, idx = tid; idx < nent; idx += blockDim.x, ++k) {
+    const int p = idx / j1, q = idx % j1;
+    A[0][p][q] = acc[k];
+    V[0][p][q] = (p == q) ? 1.0 : 0.0;
+  }
+  __syncthreads();
+  // symmetrise exactly (the accumulation order is the same for (p,q) and (q,p); keep it robust)
+  for (int idx = tid; idx < nent; idx += blockDim.x) {
+    const int p = idx / j1, q = idx % j1;
+    if (p < q) {
+      const double s = 0.5 * (A[0][p][q] + A[0][q][p]);
+      A[0][p][q] = s;
+    }
+  }
+  __syncthreads();
+  for (int idx = tid; idx < nent; idx += blockDim.x) {
+    const int p = idx / j1, q = idx % j1;
+    if (p > q) A[0][p][q] = A[0][q][p];
+  }
+  __syncthreads();
+
+  // ---- parallel cyclic Jacobi: j1-1 rounds of j1/2 disjoint rotations per sweep ----
+  int cur = 0;
+  const int nm1 = j1 - 1;
+  for (int sweep = 0; sweep < 16; ++sweep) {
+    if (tid < kJMax) offarr[tid] = 0.0;
+    __syncthreads();
+    for (int round = 0; round < nm1; ++round) {
+      if (tid < j1 / 2) {
+        int p, q;
+        if (tid == 0) { p = nm1; q = round; }
+        else { p = (round + tid) % nm1; q = (round - tid + nm1) % nm1; }
+        if (p > q) { const int t = p; p = q; q = t; }
+        const double app = A[cur][p][p], aqq = A[cur][q][q], apq = A[cur][p][q];
+        double c = 1.0, s = 0.0;
+        if (apq != 0.0 && fabs(apq) > 1e-300) {
+          const double tau = (aqq - app) / (2.0 * apq);
+          const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
+          c = 1.0 / sqrt(1.0 + t * t);
+          s = t * c;
+          const double rel = fabs(apq) / sqrt(fabs(app * aqq) + 1e-300);
+          if (rel > offarr[tid]) offarr[tid] = rel;
+        }
+        rc[p] = c; rs[p] = s; rc[q] = c; rs[q] = s;
+        partner[p] = q; partner[q] = p;
+        is_p[p] = 1; is_p[q] = 0;
+      }
+      __syncthreads();
+      // J has J[p][p] = c, J[p][q] = s, J[q][p] = -s, J[q][q] = c for each pair.
+      // A' = J^T A J ; V' = V J.  Entry (i, j) needs A at {i, pi} x {j, pj}.
+      for (int idx = tid; idx < nent; idx += blockDim.x) {
+        const int i = idx / j1, j = idx % j1;
+        const int pi = partner[i], pj = partner[j];
+        // column j of J: J[j][j] = c_j, J[pj][j] = (is_p[j] ? -s : +s)
+        const double cj = rc[j], sj = is_p[j] ? -rs[j] : rs[j];
+        const double ci = rc[i], si = is_p[i] ? -rs[i] : rs[i];
+        // (A J)[a][j] = A[a][j]*cj + A[a][pj]*sj
+        const double aj_i = A[cur][i][j] * cj + A[cur][i][pj] * sj;
+        const double aj_pi = A[cur][pi][j] * cj + A[cur][pi][pj] * sj;
+        // (J^T (A J))[i][j] = J[i][i]*(AJ)[i][j] + J[pi][i]*(AJ)[pi][j]
+        A[cur ^ 1][i][j] = ci * aj_i + si * aj_pi;
+        V[cur ^ 1][i][j] = V[cur][i][j] * cj + V[cur][i][pj] * sj;
+      }
+      __syncthreads();
+      cur ^= 1;
+    }
+    double om = 0.0;
+    for (int i = 0; i < j1 / 2; ++i) om = fmax(om, offarr[i]);
+    __syncthreads();
+    if (om < 1e-15) break;
+  }
+
+  // ---- singular values, ordering, small tensor ----
+  if (tid < j1) lam[tid] = A[cur][tid][tid];
+  __syncthreads();
+  if (tid < j1) {
+    int rank = 0;
+    const double me = lam[tid];
+    for (int s = 0; s < j1; ++s) rank += (lam[s] > me) || (lam[s] == me && s < tid);
+    order[rank] = tid;
+  }
+  __syncthreads();
+  if (tid < j1) {
+    const double lmax = fmax(lam[order[0]], 0.0);
+    const double l = lam[order[tid]];
+    sigma[tid] = (l > 1e-12 * lmax && l > 0.0) ? sqrt(l) : 0.0;
+  }
+  __syncthreads();
+  {
+    const long blk = (long)bh * g.NB + slot;
+    uint16_t* small = (which ? cache.v_small : cache.k_small) + blk * g.small_per_block;
+    bool sat = false;
+    for (int idx = tid; idx < nent; idx += blockDim.x) {
+      const int b1 = idx / j1, r = idx % j1;
+      const double u = V[cur][b1][order[r]];
+      const double sg = sigma[r];
+      W[r][b1] = sg > 0.0 ? u / sg : 0.0;
+      const uint16_t hb = f64_to_f16_rne(u * sg, true, &sat);
+      if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
+      else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
+    }
+    if (sat) atomicOr(status, 1);
+  }
+  __syncthreads();
+
+  // ---- projection: K'[t, r*j2+b2] = sum_b1 W[r][b1] * X[t, b1*j2+b2], fp64 -> fp32 ----
+  float* out = large_ws + (long)unit * g.Tb * d;
+  for (int item = tid; item < g.Tb * j2; item += blockDim.x) {
+    const int t = item / j2, b2 = item % j2;
+    if (t < nv) {
+      double xv[kJMax];
+      for (int b1 = 0; b1 < j1; ++b1) xv[b1] = (double)h2f(X[(long)t * d + b1 * j2 + b2]);
+      for (int r = 0; r < j1; ++r) {
+        double a = 0.0;
+        for (int b1 = 0; b1 < j1; ++b1) a = fma(W[r][b1], xv[b1], a);
+        out[(long)t * d + r * j2 + b2] = (float)a;
+      }
+    } else {
+      for (int r = 0; r < j1; ++r) out[(long)t * d + r * j2 + b2] = 0.f;
+    }
+  }
+}
+
+__global__ void clear_status_kernel(int32_t* status) {
+  if (threadIdx.x == 0) *status = 0;
+}
+
+}  // namespace dq
+
+// ------------------------------------------------------------------------------------------
+// C ABI
+// ------------------------------------------------------------------------------------------
+using namespace dq;
+
+extern "C" size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads) {
+  if (!format_ok(fmt) || batch <= 0 || kv_heads <= 0) return 0;
+  return (size_t)kWsHeaderBytes +
+         (size_t)batch * kv_heads * 2 * fmt->block_tokens * fmt->head_dim * sizeof(float);
+}
+
+extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, int64_t n_rows,
+                                    int32_t value_layout, uint8_t* codes, uint16_t* scales,
+                                    void* hip_stream) {
+  if (!format_ok(fmt) || !t_large || !codes || !scales) return DQ_EINVAL;
+  if (n_rows < 0 || n_rows % kTileTokens) return DQ_EINVAL;
+  if (n_rows == 0) return DQ_OK;
+  hipStream_t st = (hipStream_t)hip_stream;
+  const int tiles = (int)(n_rows / kTileTokens);
+  const size_t lds = (size_t)kTileTokens * fmt->head_dim;
+  const int d = fmt->head_dim, G = fmt->group, j1 = fmt->j1, j2 = fmt->j2;
+  switch (fmt->bits) {
+    case 2: hipLaunchKernelGGL(quantize_pack_kernel<2>, dim3(tiles), dim3(256), lds, st, t_large, d, G, j1, j2, value_layout, codes, scales); break;
+    case 4: hipLaunchKernelGGL(quantize_pack_kernel<4>, dim3(tiles), dim3(256), lds, st, t_large, d, G, j1, j2, value_layout, codes, scales); break;
+    default: hipLaunchKernelGGL(quantize_pack_kernel<8>, dim3(tiles), dim3(256), lds, st, t_large, d, G, j1, j2, value_layout, codes, scales); break;
+  }
+  DQ_HIP_CHECK(hipGetLastError());
+  return DQ_OK;
+}
+
+extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                                  const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                                  const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
+  if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
+      !cache->v_small)
+    return DQ_EINVAL;
+  if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
+  if (t_new < 1 || t_new > fmt->block_tokens) return DQ_EINVAL;
+  const size_t need = dq_compress_workspace_bytes(fmt, cache->batch, cache->kv_heads);
+  if (workspace_bytes < need) return DQ_ENOSPACE;
+  hipStream_t st = (hipStream_t)hip_stream;
+  int32_t* status = reinterpret_cast<int32_t*>(workspace);
+  float* large_ws = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kWsHeaderBytes);
+  const int units = cache->batch * cache->kv_heads * 2;
+  hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, status);
+  hipLaunchKernelGGL(decompose_kernel, dim3(units), dim3(256), 0, st, *fmt, *cache, k_new, v_new, t_new,
+                     blk_idx, n_valid, large_ws, status);
+  DQ_HIP_CHECK(hipGetLastError());
+  const int tiles = units * (fmt->block_tokens / kTileTokens);
+  const size_t lds = (size_t)kTileTokens * fmt->head_dim;
+  switch (fmt->bits) {
+    case 2: hipLaunchKernelGGL(quantize_tiles_kernel<2>, dim3(tiles), dim3(256), lds, st, large_ws, *fmt, *cache, blk_idx); break;
+    case 4: hipLaunchKernelGGL(quantize_tiles_kernel<4>, dim3(tiles), dim3(256), lds, st, large_ws, *fmt, *cache, blk_idx); break;
+    default: hipLaunchKernelGGL(quantize_tiles_kernel<8>, dim3(tiles), dim3(256), lds, st, large_ws, *fmt, *cache, blk_idx); break;
+  }
+  DQ_HIP_CHECK(hipGetLastError());
+  return DQ_OK;
+}

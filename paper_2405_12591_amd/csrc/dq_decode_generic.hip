@@ -1,0 +1,212 @@
+// Reference-grade decode attention over the compressed cache: plain fp32 HIP, any supported
+// format, one workgroup per (sequence, query head, sequence split).  It states the fused
+// computation of Section 3.2 (arXiv 2405.12591) in its simplest form:
+//   q'[r, b2]  = scale * sum_b1 T_S^K[b1, r] q[b1, b2]            (small tensor folded into q)
+//   s_t        = sum_g step^K[t, g] * sum_{c' in g} code^K[t, c'] q'[c']
+//   o'[c']     = sum_t p_t step^V[t, g(c')] code^V[t, c']          (per 128-token tile)
+//   acc[b1,b2] = alpha * acc[b1, b2] + sum_r T_S^V[b1, r] o'[r, b2]
+// followed by a log-sum-exp merge of the splits.
+#include "dq_decode.h"
+
+namespace dq {
+
+template <int BITS>
+__device__ inline float dot_codes(const uint32_t* __restrict__ words, const float* __restrict__ qf, int n) {
+  // sum over n consecutive elements (n * BITS multiple of 32) of code * qf
+  constexpr int PER = 32 / BITS;
+  constexpr int MASK = (1 << BITS) - 1;
+  constexpr int BIAS = 1 << (BITS - 1);
+  float s = 0.f;
+  for (int w = 0; w < n / PER; ++w) {
+    const uint32_t x = words[w];
+#pragma unroll
+    for (int k = 0; k < PER; ++k) s = fmaf((float)((int)((x >> (k * BITS)) & MASK) - BIAS), qf[w * PER + k], s);
+  }
+  return s;
+}
+
+template <int BITS>
+__global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
+  const Geometry g = make_geometry(a.fmt, a.cache.kv_heads, a.cache.block_capacity);
+  const int d = g.d, j1 = g.j1, j2 = g.j2, G = g.G;
+  const int split = blockIdx.x;
+  const int bhq = blockIdx.y;
+  const int b = bhq / a.q_heads, hq = bhq % a.q_heads;
+  const int rep = a.q_heads / g.H;
+  const int h = hq / rep;
+  const int tid = threadIdx.x;
+  const int S = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
+  const int max_tiles = (a.max_seq_len + kTileTokens - 1) / kTileTokens;
+  const int tps = (max_tiles + a.n_split - 1) / a.n_split;
+  const int tile_begin = split * tps;
+  const int tile_end = min(tile_begin + tps, tiles_total);
+
+  __shared__ float qs[128];        // the query as fp32
+  __shared__ float qf[128];        // folded query q'
+  __shared__ float sc[kTileTokens];
+  __shared__ float red[8];
+  __shared__ float opart[4][128];
+  __shared__ float sK[32 * 32];    // T_S^K as stored: [r][b1]
+  __shared__ float sV[32 * 32];    // T_S^V as stored: [b1][r]
+
+  if (tid < d) qs[tid] = h2f(a.q[(long)bhq * d + tid]);
+  float acc = 0.f;                 // thread c < d owns output channel c = b1*j2 + b2
+  float m_run = -INFINITY, l_run = 0.f;
+  const long bh = (long)b * g.H + h;
+  int cur_blk = -1;
+  const int nparts = 256 / d;      // token parts in the value phase
+  const int seg = d / 2;
+  __syncthreads();
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int blk = tile / g.tiles_per_block;
+    const int tib = tile % g.tiles_per_block;
+    const long blkid = bh * g.NB + blk;
+    if (blk != cur_blk) {
+      cur_blk = blk;
+      const uint16_t* ks = a.cache.k_small + blkid * g.small_per_block;
+      const uint16_t* vs = a.cache.v_small + blkid * g.small_per_block;
+      for (int i = tid; i < j1 * j1; i += blockDim.x) { sK[i] = h2f(ks[i]); sV[i] = h2f(vs[i]); }
+      __syncthreads();
+      if (tid < d) {
+        const int r = tid / j2, b2 = tid % j2;
+        float s = 0.f;
+        for (int b1 = 0; b1 < j1; ++b1) s = fmaf(sK[r * j1 + b1], qs[b1 * j2 + b2], s);
+        qf[tid] = s * a.scale;
+      }
+      __syncthreads();
+    }
+    // ---- scores: two threads per token, each one half row ----
+    {
+      const int tt = tid >> 1, half = tid & 1;
+      const int t = tile * kTileTokens + tt;
+      const int row = tib * kTileTokens + tt;
+      float s = 0.f;
+      if (t < S) {
+        const uint8_t* rowp = a.cache.k_codes + blkid * g.codes_per_block + (long)row * g.row_bytes;
+        const uint16_t* scp = a.cache.k_scales + blkid * g.scales_per_block + (long)row * g.groups;
+        const uint32_t* words = reinterpret_cast<const uint32_t*>(rowp) + half * seg * BITS / 32;
+        if (G >= seg) {
+          const int gi = (half * seg) / G;
+          s = h2f(scp[gi]) * dot_codes<BITS>(words, qf + half * seg, seg);
+        } else {
+          const int gps = seg / G;
+          for (int k = 0; k < gps; ++k)
+            s = fmaf(h2f(scp[half * gps + k]),
+                     dot_codes<BITS>(words + k * G * BITS / 32, qf + half * seg + k * G, G), s);
+        }
+      }
+      s += __shfl_xor(s, 1);
+      if (half == 0) sc[tt] = (t < S) ? s : -INFINITY;
+    }
+    __syncthreads();
+    // ---- tile max ----
+    float v = (tid < kTileTokens) ? sc[tid] : -INFINITY;
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    const float m_tile = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float m_new = fmaxf(m_run, m_tile);
+    const float alpha = __expf(m_run - m_new);  // m_run = -inf gives 0
+    __syncthreads();
+    float p = 0.f;
+    if (tid < kTileTokens) {
+      p = __expf(sc[tid] - m_new);
+      sc[tid] = p;
+    }
+    float ps = p;
+    for (int o = 32; o > 0; o >>= 1) ps += __shfl_xor(ps, o);
+    if ((tid & 63) == 0) red[4 + (tid >> 6)] = ps;
+    __syncthreads();
+    l_run = l_run * alpha + (red[4] + red[5] + red[6] + red[7]);
+    m_run = m_new;
+    // ---- values: thread (c', part) accumulates its share of the tile's tokens ----
+    {
+      const int cp = tid % d, part = tid / d;
+      const int r = cp / j2, b2 = cp % j2;
+      const int gi = cp / G;
+      const uint8_t* vrow = a.cache.v_codes + blkid * g.codes_per_block +
+                            ((long)(tib * j2 + b2) * j1 + r) * g.vrow_bytes;
+      const uint16_t* vsc = a.cache.v_scales + blkid * g.scales_per_block +
+                            (long)tib * kTileTokens * g.groups;
+      const int tok_per_part = kTileTokens / nparts;
+      const int t0 = part * tok_per_part;
+      constexpr int PER = 32 / BITS;
+      constexpr int MASK = (1 << BITS) - 1;
+      constexpr int BIAS = 1 << (BITS - 1);
+      const uint32_t* words = reinterpret_cast<const uint32_t*>(vrow) + t0 / PER;
+      float o = 0.f;
+      for (int w = 0; w < tok_per_part / PER; ++w) {
+        const uint32_t x = words[w];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int tt = t0 + w * PER + k;
+          const float pt = sc[tt];
+          if (pt != 0.f) {  // masked tokens may carry any step bits, never touch them
+            const float code = (float)((int)((x >> (k * BITS)) & MASK) - BIAS);
+            o = fmaf(pt * h2f(vsc[(long)tt * g.groups + gi]), code, o);
+          }
+        }
+      }
+      opart[part][cp] = o;
+    }
+    __syncthreads();
+    if (tid < d) {
+      const int b1 = tid / j2, b2 = tid % j2;
+      float s = 0.f;
+      for (int r = 0; r < j1; ++r) {
+        float o = 0.f;
+        for (int part = 0; part < nparts; ++part) o += opart[part][r * j2 + b2];
+        s = fmaf(sV[b1 * j1 + r], o, s);
+      }
+      acc = acc * alpha + s;
+    }
+    __syncthreads();
+  }
+  float* part = a.partials + ((long)bhq * a.n_split + split) * (d + 2);
+  if (tid < d) part[tid] = acc;
+  if (tid == 0) { part[d] = m_run; part[d + 1] = l_run; }
+}
+
+// Merge split partials: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
+__global__ void combine_kernel(const float* __restrict__ partials, int n_split, int d,
+                               uint16_t* __restrict__ out, float* __restrict__ out_f32) {
+  const int bhq = blockIdx.x;
+  const int c = threadIdx.x;
+  const float* base = partials + (long)bhq * n_split * (d + 2);
+  float M = -INFINITY;
+  for (int s = 0; s < n_split; ++s) M = fmaxf(M, base[s * (d + 2) + d]);
+  float L = 0.f, o = 0.f;
+  for (int s = 0; s < n_split; ++s) {
+    const float m = base[s * (d + 2) + d];
+    if (m == -INFINITY) continue;
+    const float w = __expf(m - M);
+    L = fmaf(base[s * (d + 2) + d + 1], w, L);
+    o = fmaf(base[s * (d + 2) + c], w, o);
+  }
+  const float r = (L > 0.f) ? o / L : 0.f;
+  out[(long)bhq * d + c] = f2h_rne(r);
+  if (out_f32) out_f32[(long)bhq * d + c] = r;
+}
+
+int32_t launch_combine(const DecodeArgs& a, hipStream_t st) {
+  const int d = a.fmt.head_dim;
+  hipLaunchKernelGGL(combine_kernel, dim3(a.cache.batch * a.q_heads), dim3(d), 0, st, a.partials, a.n_split, d,
+                     a.out, a.out_f32);
+  DQ_HIP_CHECK(hipGetLastError());
+  return DQ_OK;
+}
+
+int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st) {
+  const dim3 grid(a.n_split, a.cache.batch * a.q_heads);
+  switch (a.fmt.bits) {
+    case 2: hipLaunchKernelGGL(decode_generic_kernel<2>, grid, dim3(256), 0, st, a); break;
+    case 4: hipLaunchKernelGGL(decode_generic_kernel<4>, grid, dim3(256), 0, st, a); break;
+    default: hipLaunchKernelGGL(decode_generic_kernel<8>, grid, dim3(256), 0, st, a); break;
+  }
+  DQ_HIP_CHECK(hipGetLastError());
+  return launch_combine(a, st);
+}
+
+}  // namespace dq

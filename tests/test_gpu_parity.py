@@ -1,0 +1,213 @@
+"""GPU parity: the HIP library against the CPU oracle, through the C ABI."""
+import numpy as np
+import pytest
+import torch
+
+from oracle import decoquant_oracle as O
+import paper_2405_12591_amd as dq
+import workloads
+from gpu_util import DEV, formats, oracle_cache_for_pairs, tolerance, run_decode
+
+pytestmark = pytest.mark.gpu
+
+
+def _say(msg):
+    print(msg, flush=True)
+
+
+# ------------------------------------------------------------------------------------------
+# quantize + pack: bit-exact codes and steps from the same large tensor
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits,group,d,j1", [(4, 128, 128, 16), (4, 64, 128, 16), (2, 64, 128, 16),
+                                             (8, 128, 128, 16), (4, 64, 64, 8), (2, 32, 64, 8),
+                                             (4, 32, 128, 32)])
+def test_quantize_pack_bit_exact(bits, group, d, j1):
+    _say("quantize_pack bits=%d G=%d d=%d j1=%d" % (bits, group, d, j1))
+    j2 = d // j1
+    fmt, ofmt = dq.Format(bits, group, d, j1, j2, 128), O.Format(bits, group, d, j1, j2, 128)
+    r = np.random.default_rng(bits * 1000 + group)
+    rows = []
+    for i in range(3):                          # three real decomposed blocks (ragged: 3 tiles)
+        x = r.standard_normal((128, d))
+        x[:, r.choice(d, 3, replace=False)] *= 20
+        rows.append(O.compress_block(x.astype(np.float16), ofmt).large32)
+    kp = np.concatenate(rows)
+    qmax = ofmt.qmax
+    kp[5, :] = 0.0                                             # zero row -> step 0, codes 0
+    kp[6, :group] = np.float32(0.125) * (r.integers(-2 * qmax, 2 * qmax + 1, group) / 2.0)  # exact ties
+    kp[6, 0] = np.float32(0.125 * qmax)
+    kp[7, :group] = 1e-7 * r.standard_normal(group)            # subnormal steps
+    kp = kp.astype(np.float32)
+    steps = O.group_steps(kp, group, qmax)
+    codes = O.quantize_codes(kp, steps, group, qmax)
+    want_k = O.pack_rows(codes, bits)
+    want_v = O.pack_rows(np.concatenate([O.value_codes_to_tiles(codes[i * 128:(i + 1) * 128], j1, j2)
+                                         for i in range(3)]), bits)
+    t = torch.from_numpy(kp).to(DEV)
+    for layout, want in ((False, want_k), (True, want_v)):
+        got_c, got_s = dq.quantize_pack(fmt, t, layout)
+        torch.cuda.synchronize()
+        assert np.array_equal(got_s.cpu().numpy().view(np.uint16), steps.view(np.uint16))
+        assert np.array_equal(got_c.cpu().numpy().reshape(want.shape), want)
+
+
+# ------------------------------------------------------------------------------------------
+# decode attention on an oracle-compressed cache
+# ------------------------------------------------------------------------------------------
+def _decode_case(w, lens, flags, pairs=None):
+    fmt, ofmt = formats(w)
+    lens = np.asarray(lens, np.int32)
+    all_pairs = [(b, h) for b in range(w.batch) for h in range(w.kv_heads)]
+    pairs = all_pairs if pairs is None else pairs
+    cache = oracle_cache_for_pairs(w, ofmt, pairs, lens)
+    q = workloads.query(w)
+    want = O.attention_decode(cache, ofmt, q, lens, pairs=pairs)
+    got16, got32 = run_decode(fmt, cache, q, lens, int(w.max_seq), flags)
+    rep = w.q_heads // w.kv_heads
+    worst = 0.0
+    for b, h in pairs:
+        for hq in range(h * rep, (h + 1) * rep):
+            e16 = np.abs(got16[b, hq].astype(np.float64) - want[b, hq])
+            assert (e16 <= tolerance(want[b, hq])).all(), (b, hq, e16.max())
+            e32 = np.abs(got32[b, hq].astype(np.float64) - want[b, hq])
+            assert (e32 <= np.maximum(2e-3, 1e-4 * np.abs(want[b, hq]))).all(), (b, hq, e32.max())
+            worst = max(worst, e32.max())
+    return worst
+
+
+def test_decode_generic_tiny_full():
+    w = workloads.get_workload("tiny")
+    _say("decode generic tiny")
+    worst = _decode_case(w, workloads.seq_lens(w), dq.DECODE_FORCE_GENERIC)
+    _say("  worst fp32 abs err %.3g" % worst)
+
+
+@pytest.mark.parametrize("lens", [[256], [1], [0], [129], [255]])
+def test_decode_generic_tiny_ragged(lens):
+    w = workloads.get_workload("tiny")
+    _say("decode generic tiny lens=%s" % lens)
+    _decode_case(w, lens, dq.DECODE_FORCE_GENERIC)
+
+
+def _small(name, **kw):
+    import dataclasses
+    return dataclasses.replace(workloads.get_workload(name), **kw)
+
+
+@pytest.mark.parametrize("name,kw,lens", [
+    ("llama7b_4bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=1000, min_seq=1000), [1000, 257]),
+    ("llama7b_2bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=700, min_seq=700), [700, 128]),
+    ("gqa_long", dict(batch=2, q_heads=8, kv_heads=2, max_seq=900, min_seq=900), [900, 5]),
+    ("llama13b_mixed", dict(batch=3, q_heads=4, kv_heads=4, max_seq=640, min_seq=1), [640, 0, 383]),
+])
+def test_decode_generic_multi_block(name, kw, lens):
+    w = _small(name, **kw)
+    _say("decode generic %s %s lens=%s" % (name, kw, lens))
+    worst = _decode_case(w, lens, dq.DECODE_FORCE_GENERIC)
+    _say("  worst fp32 abs err %.3g" % worst)
+
+
+# ------------------------------------------------------------------------------------------
+# compress_kv: the GPU's own decomposition, checked through properties
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,t_new,n_valid", [
+    ("tiny", 256, None), ("llama7b_4bit", 128, None), ("llama7b_2bit", 128, None),
+    ("llama13b_mixed", 128, [128, 37, 1]), ("gqa_long", 100, None),
+])
+def test_compress_kv_properties(name, t_new, n_valid):
+    w = _small(name, batch=3 if n_valid else 2, q_heads=4, kv_heads=2 if name == "gqa_long" else 4)
+    w = _small(name, batch=w.batch, q_heads=w.q_heads, kv_heads=w.kv_heads,
+               n_outlier=min(w.n_outlier, 8))
+    fmt, ofmt = formats(w)
+    _say("compress_kv %s t_new=%d n_valid=%s" % (name, t_new, n_valid))
+    tb, d, j1, j2 = fmt.block_tokens, fmt.head_dim, fmt.j1, fmt.j2
+    k = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[0] for h in range(w.kv_heads)]) for b in range(w.batch)])
+    v = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[1] for h in range(w.kv_heads)]) for b in range(w.batch)])
+    nb = 3
+    cache = dq.alloc_cache(fmt, w.batch, w.kv_heads, nb, DEV, fill=0xA5)
+    before = {n: t.clone() for n, t in cache.t.items()}
+    ws = dq.compress_workspace(fmt, w.batch, w.kv_heads, DEV)
+    slots = np.array([1, 2, 0][:w.batch], np.int32)
+    if w.batch == 2:
+        slots = np.array([1, -1], np.int32)      # second sequence is skipped
+    nv = None if n_valid is None else torch.tensor(n_valid, dtype=torch.int32, device=DEV)
+    dq.compress_kv(cache, torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV),
+                   torch.from_numpy(slots).to(DEV), nv, ws)
+    torch.cuda.synchronize()
+    arrs = {n: t.cpu().numpy() for n, t in cache.t.items()}
+    status = int(ws[:4].view(torch.int32).item())
+    assert status == 0
+    large = ws[256:].view(torch.float32).cpu().numpy().reshape(w.batch * w.kv_heads * 2, tb, d)
+    for b in range(w.batch):
+        for h in range(w.kv_heads):
+            for which, x_all in (("k", k), ("v", v)):
+                slot = int(slots[b])
+                if slot < 0:
+                    for n in arrs:   # skipped sequence: nothing written anywhere
+                        assert np.array_equal(arrs[n][b, h], before[n][b, h].cpu().numpy())
+                    continue
+                n_ok = t_new if n_valid is None else min(n_valid[b], t_new)
+                x = np.zeros((tb, d))
+                x[:n_ok] = x_all[b, h, :n_ok].astype(np.float64)
+                small, steps, codes = O.load_block(arrs, ofmt, b, h, slot, which)
+                kp = large[(b * w.kv_heads + h) * 2 + (which == "v")]
+                t_l = O.token_major_to_large(kp.astype(np.float64), j1, j2)
+                # (1) rows of T_L orthonormal (or zero for dropped directions)
+                gram = t_l @ t_l.T
+                diag = np.diag(gram)
+                live = diag > 0.5
+                assert np.abs(gram - np.diag(live.astype(np.float64))).max() <= 1e-4, (b, h, which)
+                # (2) exact factorisation up to the fp16 rounding of T_S and fp32 of T_L
+                m = O.matricise(x, 1, j1)
+                resid = np.abs(small.astype(np.float64) @ t_l - m)
+                slack = 2.0 ** -10 * (np.abs(small.astype(np.float64)) @ np.abs(t_l)) + 1e-6 * np.abs(m).max() + 1e-7
+                assert (resid <= slack).all(), (b, h, which, resid.max())
+                # (3) codes and steps are the oracle's quantization of that very T_L
+                steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax)
+                codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax)
+                assert np.array_equal(steps.view(np.uint16), steps_o.view(np.uint16))
+                assert np.array_equal(codes, codes_o)
+                # (4) reconstruction within the half-step bound
+                x_hat = O.reconstruct_block(small, steps, codes, ofmt)
+                bound = O.reconstruction_bound(small, steps, ofmt)
+                slack_x = O.unmatricise(slack, tb, d, 1, j1)
+                assert (np.abs(x_hat - x) <= bound + slack_x).all(), (b, h, which)
+                # (5) other block slots of this head untouched
+                for other in range(nb):
+                    if other != slot:
+                        assert np.array_equal(arrs["k_codes"][b, h, other], before["k_codes"][b, h, other].cpu().numpy())
+
+
+def test_gpu_compressed_cache_decodes_like_its_own_oracle_reading():
+    """Compress on the GPU, then decode on the GPU and with the oracle from the same arrays."""
+    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=4, max_seq=512, min_seq=512)
+    fmt, ofmt = formats(w)
+    _say("gpu compress -> gpu decode vs oracle decode")
+    k, v = workloads.kv_tensor(w)
+    nb = w.max_seq // fmt.block_tokens
+    cache = dq.alloc_cache(fmt, w.batch, w.kv_heads, nb, DEV)
+    ws = dq.compress_workspace(fmt, w.batch, w.kv_heads, DEV)
+    kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
+    for blk in range(nb):
+        sl = slice(blk * 128, (blk + 1) * 128)
+        dq.compress_kv(cache, kd[:, :, sl].contiguous(), vd[:, :, sl].contiguous(),
+                       torch.full((w.batch,), blk, dtype=torch.int32, device=DEV), None, ws)
+    torch.cuda.synchronize()
+    arrs = {n: t.cpu().numpy() for n, t in cache.t.items()}
+    q = workloads.query(w)
+    lens = np.array([512, 300], np.int32)
+    want = O.attention_decode(arrs, ofmt, q, lens)
+    got16, got32 = run_decode(fmt, arrs, q, lens, 512, dq.DECODE_FORCE_GENERIC)
+    assert (np.abs(got16.astype(np.float64) - want) <= tolerance(want)).all()
+    # and the lossy cache still approximates attention on the original K, V
+    for b in range(w.batch):
+        for h in range(w.kv_heads):
+            ref = O.dense_attention(q[b, h], k[b, h, :lens[b]], v[b, h, :lens[b]])
+            assert np.abs(want[b, h] - ref).max() < 0.15 * np.abs(v[b, h].astype(np.float64)).max()
+
+
+def test_stream_read_runs():
+    src = torch.arange(1 << 20, dtype=torch.int32, device=DEV)
+    sink = torch.zeros(4, dtype=torch.int32, device=DEV)
+    dq.stream_read(src, sink)
+    torch.cuda.synchronize()
