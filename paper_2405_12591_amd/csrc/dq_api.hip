@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument checks, workspace carve-up, kernel selection.
 #include <atomic>
+#include <cstdlib>
 
 #include "dq_decode.h"
 
@@ -11,11 +12,24 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma) {
   const int max_tiles = (max_seq_len + kTileTokens - 1) / kTileTokens;
   if (max_tiles <= 0) return 1;
-  const int units = batch * (mfma ? kv_heads : q_heads);
-  // aim at >= 2048 workgroups, at least 2 tiles each, at most kMaxSplits splits
-  int want = (2048 + units - 1) / units;
-  int by_len = (max_tiles + 1) / 2;
-  int n = want < by_len ? want : by_len;
+  int n;
+  if (mfma) {
+    // one workgroup = 4 waves streaming one (sequence, kv head) split; two workgroups fit a CU,
+    // so about 512 workgroups fill the 256 CUs once; keep at least one tile per wave
+    const int units = batch * kv_heads;
+    n = (512 + units / 2) / units;
+    const int by_len = (max_tiles + 3) / 4;
+    if (n > by_len) n = by_len;
+  } else {
+    const int units = batch * q_heads;
+    n = (2048 + units - 1) / units;
+    const int by_len = (max_tiles + 1) / 2;
+    if (n > by_len) n = by_len;
+  }
+  if (const char* env = getenv("DQ_DECODE_SPLITS")) {  // tuning aid
+    const int v = atoi(env);
+    if (v > 0) n = v;
+  }
   if (n < 1) n = 1;
   if (n > kMaxSplits) n = kMaxSplits;
   if (n > max_tiles) n = max_tiles;

@@ -211,3 +211,37 @@ def test_stream_read_runs():
     sink = torch.zeros(4, dtype=torch.int32, device=DEV)
     dq.stream_read(src, sink)
     torch.cuda.synchronize()
+
+
+# ------------------------------------------------------------------------------------------
+# matrix-core decode kernel (4-bit, d = 128, G = 128)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,kw,lens", [
+    ("llama7b_4bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=1000, min_seq=1000), [1000, 257]),
+    ("llama7b_4bit", dict(batch=3, q_heads=2, kv_heads=2, max_seq=2300, min_seq=2300), [2300, 1, 128]),
+    ("gqa_long", dict(batch=2, q_heads=8, kv_heads=2, max_seq=900, min_seq=900), [900, 5]),
+    ("gqa_long", dict(batch=2, q_heads=4, kv_heads=2, max_seq=700, min_seq=700), [513, 700]),
+    ("llama13b_mixed", dict(batch=3, q_heads=4, kv_heads=4, max_seq=640, min_seq=1), [640, 0, 383]),
+    ("llama7b_4bit", dict(batch=1, q_heads=2, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=256), [777]),
+])
+def test_decode_mfma_multi_block(name, kw, lens):
+    w = _small(name, **kw)
+    fmt, _ = formats(w)
+    assert dq.decode_mfma_supported(fmt, w.q_heads, w.kv_heads)
+    _say("decode mfma %s %s lens=%s" % (name, kw, lens))
+    worst = _decode_case(w, lens, dq.DECODE_FORCE_MFMA)
+    _say("  worst fp32 abs err %.3g" % worst)
+
+
+def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
+    fmt4 = dq.Format(4, 128, 128, 16, 8, 128)
+    assert dq.decode_mfma_supported(fmt4, 32, 32) and dq.decode_mfma_supported(fmt4, 32, 8)
+    assert not dq.decode_mfma_supported(dq.Format(2, 64, 128, 16, 8, 128), 32, 32)
+    assert not dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 4, 4)
+    w = workloads.get_workload("tiny")
+    fmt, ofmt = formats(w)
+    cache = dq.alloc_cache(fmt, 1, 4, 1, DEV)
+    ws = dq.decode_workspace(fmt, 1, 4, 4, 256, DEV)
+    q = torch.zeros((1, 4, 64), dtype=torch.float16, device=DEV)
+    with pytest.raises(dq.DQError):
+        dq.attn_decode(cache, q, torch.zeros(1, dtype=torch.int32, device=DEV), 256, ws, flags=dq.DECODE_FORCE_MFMA)
