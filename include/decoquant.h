@@ -118,6 +118,19 @@ int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16
                        float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
                        size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
+/*
+ * Same operation as dq_attn_decode, with two caller-created hipEvent_t handles recorded on
+ * `hip_stream` immediately before and after the main streaming kernel (the kernel that reads
+ * the codes; the small merge of split partials that follows it is outside the bracket).  For
+ * measurement of that kernel's duration (Section 4.4 of the paper measures decode latency);
+ * either handle may be NULL.
+ */
+int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                             int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                             float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
+                             size_t workspace_bytes, uint32_t flags, void* hip_stream,
+                             void* ev_kernel_start, void* ev_kernel_stop);
+
 /* Bytes of workspace dq_compress_kv needs for n_blocks = B * H blocks of keys plus as many of
  * values (0 on invalid arguments). */
 size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads);

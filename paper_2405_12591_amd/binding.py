@@ -16,7 +16,7 @@ DECODE_FORCE_MFMA = 2
 
 EXPORTED_SYMBOLS = [
     "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
-    "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode",
+    "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed",
     "dq_compress_workspace_bytes", "dq_compress_kv", "dq_quantize_pack", "dq_stream_read",
 ]
 
@@ -57,6 +57,8 @@ def _load() -> C.CDLL:
     l.dq_attn_decode.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_int32, C.c_void_p,
                                  C.c_int32, C.c_float, C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t,
                                  C.c_uint32, C.c_void_p]
+    l.dq_attn_decode_timed.restype = C.c_int32
+    l.dq_attn_decode_timed.argtypes = l.dq_attn_decode.argtypes + [C.c_void_p, C.c_void_p]
     l.dq_compress_workspace_bytes.restype = C.c_size_t
     l.dq_compress_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32]
     l.dq_compress_kv.restype = C.c_int32
@@ -201,8 +203,12 @@ def workspace_init(ws: torch.Tensor) -> None:
 def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
                 workspace: torch.Tensor, out: Optional[torch.Tensor] = None,
                 out_f32: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
-                flags: int = DECODE_AUTO) -> torch.Tensor:
-    """out[b, h_q] = softmax(q . K_hat^T * scale) V_hat over the compressed cache (dq_attn_decode)."""
+                flags: int = DECODE_AUTO, kernel_events=None) -> torch.Tensor:
+    """out[b, h_q] = softmax(q . K_hat^T * scale) V_hat over the compressed cache (dq_attn_decode).
+
+    kernel_events: optional (start, stop) torch.cuda.Event pair, each already recorded once so
+    that its handle exists; they are re-recorded around the main kernel (dq_attn_decode_timed).
+    """
     fmt = cache.fmt
     if q.dtype != torch.float16 or not q.is_contiguous() or seq_lens.dtype != torch.int32:
         raise DQError("q must be contiguous fp16 and seq_lens int32")
@@ -210,9 +216,13 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
     if out is None:
         out = torch.empty_like(q)
     cf = fmt.c()
-    st = lib.dq_attn_decode(C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
-                            softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
-                            workspace.data_ptr(), workspace.numel(), flags, _stream_ptr(q.device))
+    args = (C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
+            softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
+            workspace.data_ptr(), workspace.numel(), flags, _stream_ptr(q.device))
+    if kernel_events is None:
+        st = lib.dq_attn_decode(*args)
+    else:
+        st = lib.dq_attn_decode_timed(*args, kernel_events[0].cuda_event, kernel_events[1].cuda_event)
     _check(st, "dq_attn_decode")
     return out
 

@@ -105,10 +105,11 @@ extern "C" int32_t dq_workspace_init(void* workspace, size_t workspace_bytes, vo
   return DQ_OK;
 }
 
-extern "C" int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
-                                  int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
-                                  float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
-                                  size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+extern "C" int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                                        int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                        float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
+                                        size_t workspace_bytes, uint32_t flags, void* hip_stream,
+                                        void* ev_kernel_start, void* ev_kernel_stop) {
   if (!format_ok(fmt) || !cache || !q || !seq_lens || !out || !workspace) return DQ_EINVAL;
   if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
       !cache->v_small)
@@ -138,8 +139,18 @@ extern "C" int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, c
   a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
   a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, cache->kv_heads));
   a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma);
+  a.ev_start = (hipEvent_t)ev_kernel_start;
+  a.ev_stop = (hipEvent_t)ev_kernel_stop;
   hipStream_t st = (hipStream_t)hip_stream;
   return use_mfma ? launch_decode_mfma(a, st) : launch_decode_generic(a, st);
+}
+
+extern "C" int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                                  int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                  float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
+                                  size_t workspace_bytes, uint32_t flags, void* hip_stream) {
+  return dq_attn_decode_timed(fmt, cache, q, q_heads, seq_lens, max_seq_len, softmax_scale, out, out_f32,
+                              workspace, workspace_bytes, flags, hip_stream, nullptr, nullptr);
 }
 
 extern "C" int32_t dq_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {

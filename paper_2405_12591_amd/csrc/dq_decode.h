@@ -17,6 +17,8 @@ struct DecodeArgs {
   float* partials;         // [B*Hq, n_split, d + 2]
   int32_t* counters;       // [B*Hkv] zero between calls
   int n_split;
+  hipEvent_t ev_start;     // optional: recorded around the main kernel
+  hipEvent_t ev_stop;
 };
 
 // Workspace carve-up shared by the host entry points.

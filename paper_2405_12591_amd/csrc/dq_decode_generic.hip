@@ -200,12 +200,14 @@ int32_t launch_combine(const DecodeArgs& a, hipStream_t st) {
 
 int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.q_heads);
+  if (a.ev_start) DQ_HIP_CHECK(hipEventRecord(a.ev_start, st));
   switch (a.fmt.bits) {
     case 2: hipLaunchKernelGGL(decode_generic_kernel<2>, grid, dim3(256), 0, st, a); break;
     case 4: hipLaunchKernelGGL(decode_generic_kernel<4>, grid, dim3(256), 0, st, a); break;
     default: hipLaunchKernelGGL(decode_generic_kernel<8>, grid, dim3(256), 0, st, a); break;
   }
   DQ_HIP_CHECK(hipGetLastError());
+  if (a.ev_stop) DQ_HIP_CHECK(hipEventRecord(a.ev_stop, st));
   return launch_combine(a, st);
 }
 

@@ -3,66 +3,80 @@
 //   q_heads / kv_heads in {1, 2, 4}.
 //
 // This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
-// 2405.12591) carried through the attention that follows it.  Per 128-token tile, one
-// wavefront
-//   1. folds the keys' small tensor into the query,  q'[r, b2] = sum_b1 T_S^K[b1, r] q[b1, b2],
-//      with one 16x16x16 f16 MFMA, and splits q' into fp16 hi + lo parts (columns of B);
-//   2. streams the 4-bit key codes with 128-bit loads, turns each 32-bit word into eight
-//      fp16 values 64 + u by mask/shift/or (u = code + 8, so the value is code + 72), and
-//      contracts them with q' on 16x16x32 f16 MFMAs; the constant 72 is removed by starting
-//      the accumulator at -72 * sum(q');
-//   3. runs the online softmax with one or two tokens per lane (scores cross from the MFMA
-//      layout through wave-private LDS), multiplies p by the value step and splits it into
-//      fp16 hi + lo, again as B columns;
-//   4. streams the value codes (stored token-contiguous) the same way, o'[r, b2] = sum_t p'_t c;
+// 2405.12591) carried through the attention that follows it.  The 4-bit codes never become
+// floating point: a 32-bit word of eight codes is split into two words of four bytes each
+// (x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F) and fed to the int8 matrix cores; the other operand
+// (the folded query, then the softmax weights times the value steps) is expressed as three
+// 7-bit integer limbs relative to a per-tile power of two, one B column per limb, so the
+// contraction is exact integer arithmetic.  Per 128-token tile, one wavefront
+//   1. folds the keys' small tensor into the query,  q'[r, b2] = sum_b1 T_S^K[b1, r] q[b1, b2]
+//      (one 16x16x16 f16 MFMA per two heads; T_S and q are fp16, so the products are exact),
+//      and writes the limbs of q' * scale * log2(e) as B operands;
+//   2. streams the key codes with 128-bit loads: S[t][limb] = sum_c u[t, c] limb[c]
+//      (16x16x64 i8 MFMA, u = code + 8; the 8 is removed with a constant-A MFMA);
+//   3. online softmax with two tokens per lane (scores cross from the MFMA layout through
+//      wave-private LDS); w_t = p_t * step^V_t is cut into limbs, again B columns;
+//   4. streams the value codes (stored token-contiguous): o'[r, b2] = sum_t u[t, r, b2] limb[t];
 //   5. applies the values' small tensor with fp32 16x16x4 MFMAs,
 //      acc[b1, b2] = alpha * acc + sum_r T_S^V[b1, r] o'[r, b2].
-// Sixteen B columns are available; a query head uses two (hi, lo), so up to eight heads
-// sharing a kv head ride on the same code stream.
+// A query head takes four of the sixteen B columns (three limbs, one spare), so up to four
+// heads that share a kv head ride on the same code stream.
 //
-// MFMA operand layouts used below (lane l: n = l % 16, g = l / 16):
-//   A[m][k]: lane holds row m = n, k = S*g + i (S = values per lane);  B[k][n]: column n, same k;
+// MFMA operand layouts (lane l: n = l % 16, g = l / 16):
+//   A[m][k]: lane holds row m = n, k = S*g + i (S values per lane);  B[k][n]: column n, same k;
 //   D[m][n]: lane holds column n, rows m = 4*g + i.
 #include "dq_decode.h"
 
 namespace dq {
 
-typedef _Float16 half8 __attribute__((ext_vector_type(8)));
 typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef _Float16 half2v __attribute__((ext_vector_type(2)));
 typedef float f32x4 __attribute__((ext_vector_type(4)));
+typedef int i32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr float kLn2 = 0.6931471805599453f;
-constexpr float kCodeOffset = 72.0f;  // fp16 pattern 0x5400 | (u << 4) is 64 + u = code + 72
+constexpr int kLimbBits = 7;
+constexpr int kMantBits = 3 * kLimbBits;  // 21-bit integers: limb0 * 2^14 + limb1 * 2^7 + limb2
 
-// Eight 4-bit fields of x -> eight fp16 values (64 + field), slot order [1,5,3,7,0,4,2,6].
-__device__ __forceinline__ half8 unpack8(uint32_t x) {
-  const uint32_t M = 0x00F000F0u, K = 0x54005400u;
-  u32x4 v;
-  v.x = (x & M) | K;          // fields 1, 5
-  v.y = ((x >> 8) & M) | K;   // fields 3, 7
-  v.z = ((x << 4) & M) | K;   // fields 0, 4
-  v.w = ((x >> 4) & M) | K;   // fields 2, 6
-  return __builtin_bit_cast(half8, v);
-}
-
-__device__ __forceinline__ float wave_max(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  return v;
-}
-__device__ __forceinline__ float wave_sum(float v) {
-#pragma unroll
-  for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
+// two words of eight 4-bit fields -> sixteen bytes; slot order per word [0,2,4,6,1,3,5,7]
+__device__ __forceinline__ i32x4 unpack16(uint32_t x0, uint32_t x1) {
+  const uint32_t M = 0x0F0F0F0Fu;
+  i32x4 v;
+  v.x = (int)(x0 & M);
+  v.y = (int)((x0 >> 4) & M);
+  v.z = (int)(x1 & M);
+  v.w = (int)((x1 >> 4) & M);
   return v;
 }
 
-__device__ __forceinline__ uint32_t pack_half2(_Float16 lo, _Float16 hi) {
-  half2v h = {lo, hi};
-  return __builtin_bit_cast(uint32_t, h);
+template <int CTRL>
+__device__ __forceinline__ float dpp_f(float v) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+// all-reduce over the 16 lanes of a row, then over the four rows
+__device__ __forceinline__ float wave_allmax(float v) {
+  v = fmaxf(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
+  v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
+  v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
+  v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+  return fmaxf(fmaxf(a, b), fmaxf(c, d));
+}
+__device__ __forceinline__ float wave_allsum(float v) {
+  v += dpp_f<0xB1>(v);
+  v += dpp_f<0x4E>(v);
+  v += dpp_f<0x141>(v);
+  v += dpp_f<0x140>(v);
+  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
+  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
+  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
+  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
+  return (a + b) + (c + d);
 }
 
 // 2^e as a float for -126 <= e <= 127
@@ -72,15 +86,17 @@ __device__ __forceinline__ float pow2i(int e) {
 
 template <int R>
 __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
-  constexpr int NC = 2 * R;            // B columns in use: (hi, lo) per query head
+  constexpr int NC = 4 * R;            // B columns in use: column 4*head + limb, limb 3 unused
   constexpr int F = (R + 1) / 2;       // fold MFMAs (two heads each)
   constexpr int D = 128, J1 = 16, J2 = 8, ROWB = 64;
-  constexpr int WAVE_LDS = NC * 1024;  // Qs NC*256 + Ps NC*256 + Ss NC*512 bytes
+  constexpr int SS = 132;              // ints per column of the score staging (128 tokens + bias + pad)
+  constexpr int QS_BYTES = NC * 128, PS_BYTES = NC * 128, SS_BYTES = NC * SS * 4;
+  constexpr int WAVE_LDS = QS_BYTES + PS_BYTES + SS_BYTES;
+  static_assert(WAVE_LDS >= NC * D * 4 + 2 * R * 4, "merge area must fit the wave's LDS");
   __shared__ __attribute__((aligned(16))) unsigned char smem[4 * WAVE_LDS];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, g = lane >> 4;
-  const int sa = lane >> 2, sk = lane & 3;  // softmax layout: token group sa, tokens sk and sk + 4
   const int split = blockIdx.x;
   const int bh = blockIdx.y;
   const int H = a.cache.kv_heads, NB = a.cache.block_capacity;
@@ -96,9 +112,15 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   const int tile_end = min(tile_begin + tps, tiles_total);
 
   unsigned char* wl = smem + wave * WAVE_LDS;
-  _Float16* Qs = reinterpret_cast<_Float16*>(wl);                // [NC][16 r][8 slots]
-  uint32_t* Ps = reinterpret_cast<uint32_t*>(wl + NC * 256);     // [NC][16 groups][4 pairs]
-  float* Ss = reinterpret_cast<float*>(wl + NC * 512);           // [NC][128 tokens]
+  unsigned char* Qs = wl;                                        // [NC][16 r][8 slots] bytes
+  unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 groups][16 slots] bytes
+  int* Ss = reinterpret_cast<int*>(wl + QS_BYTES + PS_BYTES);    // [NC][SS] ints
+  const bool col_live = (n < NC) && ((n & 3) != 3);
+
+  // softmax layout: lane = 8*G16 + pi owns tokens tA and tA + 2 of the tile (adjacent B slots)
+  const int G16 = lane >> 3, pi = lane & 7;
+  const int tA = 16 * G16 + 8 * (pi >> 2) + ((0x5140 >> (4 * (pi & 3))) & 7);  // 0,4,1,5
+  const int tB = tA + 2;
 
   // ---- loop-invariant B operands of the fold: q[k = b1][n' = (b2, head)] ----
   half4 bq[F];
@@ -116,9 +138,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
       bq[f] = v;
     }
   }
-  half8 neg_off;
-#pragma unroll
-  for (int i = 0; i < 8; ++i) neg_off[i] = (_Float16)(-kCodeOffset);
+  const int qslot = (n & 1) * 4 + ((n & 7) >> 1);  // B slot of channel b2 = n & 7 inside its row
 
   float m_run[R], l_run[R];
 #pragma unroll
@@ -128,8 +148,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   for (int b2 = 0; b2 < J2; ++b2) acc[b2] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const float qk_scale = a.scale * kLog2e;
-  const int slotpos = (0x37152604 >> (4 * (n & 7))) & 7;  // b2 -> slot: 0->4 1->0 2->6 3->2 4->5 5->1 6->7 7->3
-  const int pairpos = (0x1302 >> (4 * sk)) & 3;            // sk -> pair register: 0->2 1->0 2->3 3->1
+  const i32x4 a_plus8 = {0x08080808, 0x08080808, 0x08080808, 0x08080808};
+  const i32x4 a_minus8 = {(int)0xF8F8F8F8, (int)0xF8F8F8F8, (int)0xF8F8F8F8, (int)0xF8F8F8F8};
+  const i32x4 izero = {0, 0, 0, 0};
 
   // ---- prefetch the first tile's key codes and small tensor ----
   u32x4 kreg[8];
@@ -160,10 +181,9 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
     const u32x2 vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
     const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens;
     const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens;
-    const int tA = 8 * sa + sk, tB = tA + 4;
     const uint16_t dkA_b = ksc[tA], dkB_b = ksc[tB], dvA_b = vsc[tA], dvB_b = vsc[tB];
 
-    // ---- 1. fold T_S^K into q, normalise, split hi/lo, stage as B operands ----
+    // ---- 1. fold T_S^K into q; limbs of q' relative to 2^e >= max |q'| ----
     float q_unscale;
     {
       const half4 aK = __builtin_bit_cast(half4, ksm);
@@ -175,51 +195,47 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
 #pragma unroll
         for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(fd[f][i]));
       }
-      amax = wave_max(amax) * qk_scale;
-      // bring the largest |q'| into [1024, 2048) so that hi and lo are both well inside fp16
+      amax = wave_allmax(amax) * qk_scale;
       int e = 0;
       if (amax > 0.f && amax < INFINITY) e = __builtin_amdgcn_frexp_expf(amax);  // amax = f * 2^e, f in [0.5, 1)
       e = max(min(e, 100), -100);
-      const float qn = qk_scale * pow2i(11 - e);
-      q_unscale = pow2i(e - 11);
+      const float qn = qk_scale * pow2i(kMantBits - 1 - e);   // |q' * qn| < 2^20
+      q_unscale = pow2i(e - (kMantBits - 1));
 #pragma unroll
       for (int f = 0; f < F; ++f) {
         const int hd = 2 * f + (n >> 3);
         if (hd < R) {
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
-            const float v = fd[f][i] * qn;
-            const _Float16 hi = (_Float16)v;
-            const _Float16 lo = (_Float16)(v - (float)hi);
+            const int vi = (int)__builtin_rintf(fd[f][i] * qn);
             const int r = 4 * g + i;
-            Qs[((2 * hd) * 16 + r) * 8 + slotpos] = hi;
-            Qs[((2 * hd + 1) * 16 + r) * 8 + slotpos] = lo;
+            unsigned char* dst = Qs + (4 * hd) * 128 + r * 8 + qslot;
+            dst[0] = (unsigned char)(vi >> (2 * kLimbBits));
+            dst[128] = (unsigned char)((vi >> kLimbBits) & 127);
+            dst[256] = (unsigned char)(vi & 127);
           }
         }
       }
     }
     __builtin_amdgcn_wave_barrier();
-    half8 bqs[4];
+    i32x4 bqs[2];
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
-      u32x4 t = {0, 0, 0, 0};
-      if (n < NC) t = *reinterpret_cast<const u32x4*>(Qs + (n * 16 + 4 * g + w) * 8);
-      bqs[w] = __builtin_bit_cast(half8, t);
+    for (int w = 0; w < 2; ++w) {
+      i32x4 t = izero;
+      if (col_live) t = *reinterpret_cast<const i32x4*>(Qs + n * 128 + (4 * g + 2 * w) * 8);
+      bqs[w] = t;
     }
 
-    // ---- 2. scores: S[t][col] = sum_c (c + 72) q''[col][c] - 72 sum_c q''[col][c] ----
+    // ---- 2. scores: S[t][col] = sum_c u[t, c] limb[col][c];  bias row: 8 * sum_c limb[col][c] ----
     {
-      f32x4 cinit = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-      for (int w = 0; w < 4; ++w) cinit = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg_off, bqs[w], cinit, 0, 0, 0);
+      i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus8, bqs[0], izero, 0, 0, 0);
+      bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus8, bqs[1], bias, 0, 0, 0);
+      if (col_live && g == 0) Ss[n * SS + 128] = bias[0];
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        f32x4 s = cinit;
-        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(kreg[j].x), bqs[0], s, 0, 0, 0);
-        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(kreg[j].y), bqs[1], s, 0, 0, 0);
-        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(kreg[j].z), bqs[2], s, 0, 0, 0);
-        s = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(kreg[j].w), bqs[3], s, 0, 0, 0);
-        if (n < NC) *reinterpret_cast<f32x4*>(Ss + n * kTileTokens + 16 * j + 4 * g) = s;
+        i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(kreg[j].x, kreg[j].y), bqs[0], izero, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(kreg[j].z, kreg[j].w), bqs[1], s, 0, 0, 0);
+        if (col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * j + 4 * g) = s;
       }
     }
 
@@ -241,87 +257,87 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
     const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
     const float dkA = h2f(dkA_b) * q_unscale, dkB = h2f(dkB_b) * q_unscale;
     const float dvA = okA ? h2f(dvA_b) : 0.f, dvB = okB ? h2f(dvB_b) : 0.f;
-    float v_unscale;
-    float dvAs, dvBs;
+    float v_unscale, dvAs, dvBs;
     {
-      const float dvmax = wave_max(fmaxf(dvA, dvB));
+      const float dvmax = wave_allmax(fmaxf(dvA, dvB));
       int e = 0;
       if (dvmax > 0.f && dvmax < INFINITY) e = __builtin_amdgcn_frexp_expf(dvmax);
-      const float vs = pow2i(12 - e);  // p * step * vs <= 4096
-      v_unscale = pow2i(e - 12);
+      const float vs = pow2i(kMantBits - e);   // p * step * vs < 2^21
+      v_unscale = pow2i(e - kMantBits);
       dvAs = dvA * vs; dvBs = dvB * vs;
     }
     float alpha[R];
 #pragma unroll
     for (int hd = 0; hd < R; ++hd) {
-      float sA = (Ss[(2 * hd) * kTileTokens + tA] + Ss[(2 * hd + 1) * kTileTokens + tA]) * dkA;
-      float sB = (Ss[(2 * hd) * kTileTokens + tB] + Ss[(2 * hd + 1) * kTileTokens + tB]) * dkB;
+      const int* s0 = Ss + (4 * hd) * SS;
+      const int* s1 = s0 + SS;
+      const int* s2 = s1 + SS;
+      const int b0 = s0[128], b1 = s1[128], b2v = s2[128];
+      float sA = ((float)(s0[tA] - b0) * 16384.f + (float)(s1[tA] - b1) * 128.f + (float)(s2[tA] - b2v)) * dkA;
+      float sB = ((float)(s0[tB] - b0) * 16384.f + (float)(s1[tB] - b1) * 128.f + (float)(s2[tB] - b2v)) * dkB;
       sA = okA ? sA : -INFINITY;
       sB = okB ? sB : -INFINITY;
-      const float mt = wave_max(fmaxf(sA, sB));
+      const float mt = wave_allmax(fmaxf(sA, sB));
       const float m_new = fmaxf(m_run[hd], mt);          // finite: the tile has a valid token
       alpha[hd] = __builtin_amdgcn_exp2f(m_run[hd] - m_new);
       const float pA = __builtin_amdgcn_exp2f(sA - m_new);
       const float pB = __builtin_amdgcn_exp2f(sB - m_new);
       l_run[hd] = l_run[hd] * alpha[hd] + (pA + pB);
       m_run[hd] = m_new;
-      const float ppA = okA ? pA * dvAs : 0.f;
-      const float ppB = okB ? pB * dvBs : 0.f;
-      const _Float16 hA = (_Float16)ppA, hB = (_Float16)ppB;
-      const _Float16 lA = (_Float16)(ppA - (float)hA), lB = (_Float16)(ppB - (float)hB);
-      Ps[((2 * hd) * 16 + sa) * 4 + pairpos] = pack_half2(hA, hB);
-      Ps[((2 * hd + 1) * 16 + sa) * 4 + pairpos] = pack_half2(lA, lB);
+      const float wA = okA ? pA * dvAs : 0.f;
+      const float wB = okB ? pB * dvBs : 0.f;
+      const uint32_t iA = min((uint32_t)(wA + 0.5f), (1u << kMantBits) - 1u);
+      const uint32_t iB = min((uint32_t)(wB + 0.5f), (1u << kMantBits) - 1u);
+      unsigned char* dst = Ps + (4 * hd) * 128 + G16 * 16 + 2 * pi;
+      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((iA >> 14) | ((iB >> 14) << 8));
+      *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127u) | (((iB >> 7) & 127u) << 8));
+      *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127u) | ((iB & 127u) << 8));
     }
     __builtin_amdgcn_wave_barrier();
 
-    // ---- 4 + 5. o' = P' V' per b2, then the small-tensor epilogue ----
-    half8 bp[4];
+    // ---- 4 + 5. o' = sum_t u limb per b2, then the small-tensor epilogue ----
+    i32x4 bp[2];
 #pragma unroll
-    for (int v = 0; v < 4; ++v) {
-      u32x4 t = {0, 0, 0, 0};
-      if (n < NC) t = *reinterpret_cast<const u32x4*>(Ps + (n * 16 + 4 * g + v) * 4);
-      bp[v] = __builtin_bit_cast(half8, t);
+    for (int v = 0; v < 2; ++v) {
+      i32x4 t = izero;
+      if (col_live) t = *reinterpret_cast<const i32x4*>(Ps + n * 128 + (2 * g + v) * 16);
+      bp[v] = t;
     }
     float alpha_col = 1.f;
 #pragma unroll
-    for (int hd = 0; hd < R; ++hd) alpha_col = ((n >> 1) == hd) ? alpha[hd] : alpha_col;
+    for (int hd = 0; hd < R; ++hd) alpha_col = ((n >> 2) == hd) ? alpha[hd] : alpha_col;
     float aT[4];
     {
       const half4 t = __builtin_bit_cast(half4, vsm);
 #pragma unroll
       for (int i = 0; i < 4; ++i) aT[i] = (float)t[i] * v_unscale;
     }
-    f32x4 cinitv = {0.f, 0.f, 0.f, 0.f};
-#pragma unroll
-    for (int v = 0; v < 4; ++v) cinitv = __builtin_amdgcn_mfma_f32_16x16x32_f16(neg_off, bp[v], cinitv, 0, 0, 0);
+    i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus8, bp[0], izero, 0, 0, 0);
+    cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus8, bp[1], cinitv, 0, 0, 0);
     const bool rescale = __any(alpha_col != 1.f);
 #pragma unroll
     for (int b2 = 0; b2 < J2; ++b2) {
-      f32x4 o = cinitv;
-      o = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(vreg[b2].x), bp[0], o, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(vreg[b2].y), bp[1], o, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(vreg[b2].z), bp[2], o, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_f32_16x16x32_f16(unpack8(vreg[b2].w), bp[3], o, 0, 0, 0);
+      i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(vreg[b2].x, vreg[b2].y), bp[0], cinitv, 0, 0, 0);
+      o = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(vreg[b2].z, vreg[b2].w), bp[1], o, 0, 0, 0);
       f32x4 c = acc[b2];
       if (rescale) c *= alpha_col;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], o[i], c, 0, 0, 0);
+      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)o[i], c, 0, 0, 0);
       acc[b2] = c;
     }
     __builtin_amdgcn_wave_barrier();
   }
 
   // ---- merge the four waves of the workgroup, write one partial per query head ----
-  float* Macc = reinterpret_cast<float*>(wl);            // [R][128] per wave (reuses the wave's LDS)
-  float* Mml = Macc + R * D;                             // [R] m, [R] l
+  float* Macc = reinterpret_cast<float*>(wl);            // [NC][128] per wave (reuses the wave's LDS)
+  float* Mml = Macc + NC * D;                            // [R] m, [R] l
 #pragma unroll
-  for (int hd = 0; hd < R; ++hd) l_run[hd] = wave_sum(l_run[hd]);
+  for (int hd = 0; hd < R; ++hd) l_run[hd] = wave_allsum(l_run[hd]);
+  if (col_live) {
 #pragma unroll
-  for (int b2 = 0; b2 < J2; ++b2) {
+    for (int b2 = 0; b2 < J2; ++b2) {
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const float v = acc[b2][i] + __shfl_xor(acc[b2][i], 1);  // hi column + lo column
-      if (n < NC && !(n & 1)) Macc[(n >> 1) * D + (4 * g + i) * J2 + b2] = v;
+      for (int i = 0; i < 4; ++i) Macc[n * D + (4 * g + i) * J2 + b2] = acc[b2][i];
     }
   }
   if (lane == 0) {
@@ -333,15 +349,16 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
     const int hd = idx / D, c = idx % D;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, reinterpret_cast<const float*>(smem + w * WAVE_LDS)[R * D + hd]);
+    for (int w = 0; w < 4; ++w) M = fmaxf(M, reinterpret_cast<const float*>(smem + w * WAVE_LDS)[NC * D + hd]);
     float o = 0.f, L = 0.f;
 #pragma unroll
     for (int w = 0; w < 4; ++w) {
       const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
-      const float mw = base[R * D + hd];
+      const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      o = fmaf(base[hd * D + c], wgt, o);
-      L = fmaf(base[R * D + R + hd], wgt, L);
+      const float* col = base + (4 * hd) * D + c;
+      o = fmaf(col[0] * 16384.f + col[D] * 128.f + col[2 * D], wgt, o);
+      L = fmaf(base[NC * D + R + hd], wgt, L);
     }
     float* part = a.partials + (((long)b * a.q_heads + (long)h * R + hd) * a.n_split + split) * (D + 2);
     part[c] = o;
@@ -361,6 +378,7 @@ int32_t launch_combine(const DecodeArgs& a, hipStream_t st);
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   const int rep = a.q_heads / a.cache.kv_heads;
+  if (a.ev_start) DQ_HIP_CHECK(hipEventRecord(a.ev_start, st));
   switch (rep) {
     case 1: hipLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(256), 0, st, a); break;
     case 2: hipLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(256), 0, st, a); break;
@@ -368,6 +386,7 @@ int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
     default: return DQ_EINVAL;
   }
   DQ_HIP_CHECK(hipGetLastError());
+  if (a.ev_stop) DQ_HIP_CHECK(hipEventRecord(a.ev_stop, st));
   return launch_combine(a, st);
 }
 

@@ -245,3 +245,24 @@ def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
     q = torch.zeros((1, 4, 64), dtype=torch.float16, device=DEV)
     with pytest.raises(dq.DQError):
         dq.attn_decode(cache, q, torch.zeros(1, dtype=torch.int32, device=DEV), 256, ws, flags=dq.DECODE_FORCE_MFMA)
+
+
+def test_decode_full_size_llama7b_sampled_pairs():
+    """The benchmark's configuration (batch 8, 32 heads, 4096 tokens, default kernel choice and
+    split count): sampled (sequence, head) pairs are oracle-compressed and checked element by
+    element; every other pair holds garbage bytes."""
+    w = workloads.get_workload("llama7b_4bit")
+    fmt, ofmt = formats(w)
+    pairs = [(0, 0), (7, 31), (3, 17), (5, 2)]
+    _say("decode full-size llama7b_4bit pairs=%s" % pairs)
+    lens = workloads.seq_lens(w)
+    cache = oracle_cache_for_pairs(w, ofmt, pairs, lens)
+    q = workloads.query(w)
+    want = O.attention_decode(cache, ofmt, q, lens, pairs=pairs)
+    got16, got32 = run_decode(fmt, cache, q, lens, int(w.max_seq), dq.DECODE_AUTO)
+    for b, h in pairs:
+        e16 = np.abs(got16[b, h].astype(np.float64) - want[b, h])
+        assert (e16 <= tolerance(want[b, h])).all(), (b, h, e16.max())
+        e32 = np.abs(got32[b, h].astype(np.float64) - want[b, h])
+        assert (e32 <= np.maximum(2e-3, 1e-4 * np.abs(want[b, h]))).all(), (b, h, e32.max())
+        _say("  pair %s max fp32 err %.3g, max |out| %.3g" % ((b, h), e32.max(), np.abs(want[b, h]).max()))
