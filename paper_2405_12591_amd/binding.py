@@ -37,8 +37,8 @@ class _CCache(C.Structure):
 
 
 def _load() -> C.CDLL:
-    path = _build.LIB_PATH
-    if not os.path.exists(path):
+    path = os.environ.get("DQ_LIBRARY_PATH") or _build.LIB_PATH   # an alternative build, for experiments
+    if path == _build.LIB_PATH and not os.path.exists(path):
         _build.build_library()
     if not os.path.exists(path):
         raise DQError("libdecoquant.so is missing and could not be built")

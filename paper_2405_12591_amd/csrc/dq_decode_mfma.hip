@@ -25,6 +25,8 @@
 // MFMA operand layouts (lane l: n = l % 16, g = l / 16):
 //   A[m][k]: lane holds row m = n, k = S*g + i (S values per lane);  B[k][n]: column n, same k;
 //   D[m][n]: lane holds column n, rows m = 4*g + i.
+#include <type_traits>
+
 #include "dq_decode.h"
 
 namespace dq {
@@ -105,11 +107,14 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   const long codes_per_block = (long)a.fmt.block_tokens * ROWB;
   const long scales_per_block = a.fmt.block_tokens;
 
-  const int S = min(max(a.seq_lens[b], 0), a.max_seq_len);
-  const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
-  const int tps = (tiles_total + a.n_split - 1) / a.n_split;
-  const int tile_begin = split * tps;
-  const int tile_end = min(tile_begin + tps, tiles_total);
+  // The split of the sequence depends on its length, which lives in device memory.  The first
+  // tile's loads are issued for the length the host passed as the upper bound (right whenever
+  // the batch is not ragged) and re-issued only if the real length moves this wave's first tile.
+  const int spec_total = (a.max_seq_len + kTileTokens - 1) / kTileTokens;
+  const int spec_tps = (spec_total + a.n_split - 1) / a.n_split;
+  const int spec_tile = split * spec_tps + wave;
+  const bool spec_ok = spec_tile < min(split * spec_tps + spec_tps, spec_total);
+  int S = 0;  // the sequence's real length, read after the speculative loads are on their way
 
   unsigned char* wl = smem + wave * WAVE_LDS;
   unsigned char* Qs = wl;                                        // [NC][16 r][8 slots] bytes
@@ -152,41 +157,62 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   const i32x4 a_minus8 = {(int)0xF8F8F8F8, (int)0xF8F8F8F8, (int)0xF8F8F8F8, (int)0xF8F8F8F8};
   const i32x4 izero = {0, 0, 0, 0};
 
-  // ---- prefetch the first tile's key codes and small tensor ----
-  u32x4 kreg[8];
-  u32x2 ksm = {0, 0};
-  int tile = tile_begin + wave;
-  if (tile < tile_end) {
-    const long blkid = (long)bh * NB + tile / tpb;
-    const unsigned char* kc = a.cache.k_codes + blkid * codes_per_block + (long)(tile % tpb) * kTileTokens * ROWB;
-#pragma unroll
-    for (int j = 0; j < 8; ++j)
-      kreg[j] = *reinterpret_cast<const u32x4*>(kc + (16 * j + n) * ROWB + 16 * g);
-    ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + blkid * (J1 * J1) + n * J1 + 4 * g);
-  }
+  // ---- the code stream of one wave: 16 chunks of 1 KB per tile (keys j = 0..7 in slots 0..7,
+  // values b2 = 0..7 in slots 8..15) flow through a 16-slot register ring; a slot is refilled in
+  // place with the same chunk of the wave's next tile as soon as it has been unpacked, so one
+  // whole tile (16 KB) per wave is in flight at all times.  The memory counter retires loads in
+  // issue order, so everything is requested in the order it will be used: the next tile's small
+  // tensors and steps first (needed before its first key chunk), then the refills.
+  u32x4 ring[16];
+  struct Side { u32x2 ksm, vsm; uint16_t dkA, dkB, dvA, dvB; };   // small tensors + the lane's four steps
+  Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0};
 
-  for (; tile < tile_end; tile += 4) {
-    const int blk = tile / tpb, tib = tile % tpb;
-    const long blkid = (long)bh * NB + blk;
-    const int tok0 = tile * kTileTokens;
-
-    // ---- issue this tile's value-side loads ----
-    u32x4 vreg[8];
-    {
-      const unsigned char* vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB;
-#pragma unroll
-      for (int b2 = 0; b2 < J2; ++b2)
-        vreg[b2] = *reinterpret_cast<const u32x4*>(vc + b2 * (J1 * 64) + n * 64 + 16 * g);
-    }
-    const u32x2 vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
+  auto tile_ptrs = [&](int tile, const unsigned char*& kc, const unsigned char*& vc, long& blkid, int& tib) {
+    blkid = (long)bh * NB + tile / tpb;
+    tib = tile % tpb;
+    kc = a.cache.k_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + 16 * g;
+    vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * 64 + 16 * g;
+  };
+  auto load_side = [&](Side& sd, long blkid, int tib) {
+    sd.ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + blkid * (J1 * J1) + n * J1 + 4 * g);
+    sd.vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
     const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens;
     const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens;
-    const uint16_t dkA_b = ksc[tA], dkB_b = ksc[tB], dvA_b = vsc[tA], dvB_b = vsc[tB];
+    sd.dkA = ksc[tA]; sd.dkB = ksc[tB]; sd.dvA = vsc[tA]; sd.dvB = vsc[tB];
+  };
+  auto issue_tile = [&](int tile) {
+    const unsigned char *kc, *vc;
+    long blkid;
+    int tib;
+    tile_ptrs(tile, kc, vc, blkid, tib);
+    load_side(cur, blkid, tib);
+    __builtin_amdgcn_sched_barrier(0);
+#pragma unroll
+    for (int j = 0; j < 8; ++j) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kc + j * (16 * ROWB)));
+#pragma unroll
+    for (int b2 = 0; b2 < 8; ++b2) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vc + b2 * (J1 * 64)));
+  };
+
+  // One tile.  HAS_NEXT: the wave has another tile after this one.
+  auto compute_tile = [&](const int tile, auto has_next_tag) __attribute__((always_inline)) {
+    constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
+    const int tok0 = tile * kTileTokens;
+    const unsigned char *kc_next = nullptr, *vc_next = nullptr;
+    long blkid_next = 0;
+    int tib_next = 0;
+    if (HAS_NEXT) tile_ptrs(tile + 4, kc_next, vc_next, blkid_next, tib_next);
+    Side nxt = cur;
+    if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
+    __builtin_amdgcn_sched_barrier(0);
+    const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
+    const float dvA = okA ? h2f(cur.dvA) : 0.f, dvB = okB ? h2f(cur.dvB) : 0.f;
+    const float dkA_f = h2f(cur.dkA), dkB_f = h2f(cur.dkB);
+    const half4 vsm_h = __builtin_bit_cast(half4, cur.vsm);
 
     // ---- 1. fold T_S^K into q; limbs of q' relative to 2^e >= max |q'| ----
     float q_unscale;
     {
-      const half4 aK = __builtin_bit_cast(half4, ksm);
+      const half4 aK = __builtin_bit_cast(half4, cur.ksm);
       f32x4 fd[F];
       float amax = 0.f;
 #pragma unroll
@@ -231,32 +257,25 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
       i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus8, bqs[0], izero, 0, 0, 0);
       bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus8, bqs[1], bias, 0, 0, 0);
       if (col_live && g == 0) Ss[n * SS + 128] = bias[0];
+      i32x4 s_prev = izero;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(kreg[j].x, kreg[j].y), bqs[0], izero, 0, 0, 0);
-        s = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(kreg[j].z, kreg[j].w), bqs[1], s, 0, 0, 0);
-        if (col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * j + 4 * g) = s;
+        const i32x4 a0 = unpack16(ring[j].x, ring[j].y), a1 = unpack16(ring[j].z, ring[j].w);
+        __builtin_amdgcn_sched_barrier(0);   // the slot is dead from here on: refill it in place
+        if (HAS_NEXT) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kc_next + j * (16 * ROWB)));
+        __builtin_amdgcn_sched_barrier(0);
+        i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bqs[0], izero, 0, 0, 0);
+        s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bqs[1], s, 0, 0, 0);
+        // the previous chunk's scores are stored while this chunk's MFMAs run
+        if (j > 0 && col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * (j - 1) + 4 * g) = s_prev;
+        s_prev = s;
       }
-    }
-
-    // ---- prefetch the next tile's key codes ----
-    {
-      const int nt = tile + 4;
-      if (nt < tile_end) {
-        const long nblkid = (long)bh * NB + nt / tpb;
-        const unsigned char* kc = a.cache.k_codes + nblkid * codes_per_block + (long)(nt % tpb) * kTileTokens * ROWB;
-#pragma unroll
-        for (int j = 0; j < 8; ++j)
-          kreg[j] = *reinterpret_cast<const u32x4*>(kc + (16 * j + n) * ROWB + 16 * g);
-        ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + nblkid * (J1 * J1) + n * J1 + 4 * g);
-      }
+      if (col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * 7 + 4 * g) = s_prev;
     }
     __builtin_amdgcn_wave_barrier();
 
     // ---- 3. online softmax, tokens tA and tB per lane ----
-    const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
-    const float dkA = h2f(dkA_b) * q_unscale, dkB = h2f(dkB_b) * q_unscale;
-    const float dvA = okA ? h2f(dvA_b) : 0.f, dvB = okB ? h2f(dvB_b) : 0.f;
+    const float dkA = dkA_f * q_unscale, dkB = dkB_f * q_unscale;
     float v_unscale, dvAs, dvBs;
     {
       const float dvmax = wave_allmax(fmaxf(dvA, dvB));
@@ -307,25 +326,55 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
 #pragma unroll
     for (int hd = 0; hd < R; ++hd) alpha_col = ((n >> 2) == hd) ? alpha[hd] : alpha_col;
     float aT[4];
-    {
-      const half4 t = __builtin_bit_cast(half4, vsm);
 #pragma unroll
-      for (int i = 0; i < 4; ++i) aT[i] = (float)t[i] * v_unscale;
-    }
+    for (int i = 0; i < 4; ++i) aT[i] = (float)vsm_h[i] * v_unscale;
     i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus8, bp[0], izero, 0, 0, 0);
     cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus8, bp[1], cinitv, 0, 0, 0);
-    const bool rescale = __any(alpha_col != 1.f);
+    if (__any(alpha_col != 1.f)) {   // the running maximum moved: rare after the first tiles
+#pragma unroll
+      for (int b2 = 0; b2 < J2; ++b2) acc[b2] *= alpha_col;
+    }
+    i32x4 o_prev = izero;
 #pragma unroll
     for (int b2 = 0; b2 < J2; ++b2) {
-      i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(vreg[b2].x, vreg[b2].y), bp[0], cinitv, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_i32_16x16x64_i8(unpack16(vreg[b2].z, vreg[b2].w), bp[1], o, 0, 0, 0);
-      f32x4 c = acc[b2];
-      if (rescale) c *= alpha_col;
+      const i32x4 a0 = unpack16(ring[8 + b2].x, ring[8 + b2].y), a1 = unpack16(ring[8 + b2].z, ring[8 + b2].w);
+      __builtin_amdgcn_sched_barrier(0);
+      if (HAS_NEXT) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vc_next + b2 * (J1 * 64)));
+      __builtin_amdgcn_sched_barrier(0);
+      i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bp[0], cinitv, 0, 0, 0);
+      o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bp[1], o, 0, 0, 0);
+      if (b2 > 0) {   // epilogue of the previous b2 while this one's integer MFMAs run
+        f32x4 c = acc[b2 - 1];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)o[i], c, 0, 0, 0);
-      acc[b2] = c;
+        for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)o_prev[i], c, 0, 0, 0);
+        acc[b2 - 1] = c;
+      }
+      o_prev = o;
     }
+    {
+      f32x4 c = acc[J2 - 1];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)o_prev[i], c, 0, 0, 0);
+      acc[J2 - 1] = c;
+    }
+    cur = nxt;
     __builtin_amdgcn_wave_barrier();
+  };
+
+  if (spec_ok) issue_tile(spec_tile);   // in bounds: max_seq_len <= block_capacity * block_tokens
+
+  S = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
+  const int tps = (tiles_total + a.n_split - 1) / a.n_split;
+  const int tile_begin = split * tps;
+  const int tile_end = min(tile_begin + tps, tiles_total);
+  {
+    int tile = tile_begin + wave;
+    if (tile < tile_end) {
+      if (!(spec_ok && tile == spec_tile)) issue_tile(tile);
+      for (; tile + 4 < tile_end; tile += 4) compute_tile(tile, std::true_type{});
+      compute_tile(tile, std::false_type{});
+    }
   }
 
   // ---- merge the four waves of the workgroup, write one partial per query head ----
