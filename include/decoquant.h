@@ -119,9 +119,8 @@ int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16
                        size_t workspace_bytes, uint32_t flags, void* hip_stream);
 
 /*
- * Same operation as dq_attn_decode, with two caller-created hipEvent_t handles recorded on
- * `hip_stream` immediately before and after the main streaming kernel (the kernel that reads
- * the codes; the small merge of split partials that follows it is outside the bracket).  For
+ * Same operation as dq_attn_decode, with two caller-created hipEvent_t handles that receive
+ * the begin and end timestamps of the streaming kernel (the kernel that reads the codes).  For
  * measurement of that kernel's duration (Section 4.4 of the paper measures decode latency);
  * either handle may be NULL.
  */

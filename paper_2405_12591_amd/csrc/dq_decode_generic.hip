@@ -6,6 +6,8 @@
 //   o'[c']     = sum_t p_t step^V[t, g(c')] code^V[t, c']          (per 128-token tile)
 //   acc[b1,b2] = alpha * acc[b1, b2] + sum_r T_S^V[b1, r] o'[r, b2]
 // followed by a log-sum-exp merge of the splits.
+#include <hip/hip_ext.h>
+
 #include "dq_decode.h"
 
 namespace dq {
@@ -200,14 +202,13 @@ int32_t launch_combine(const DecodeArgs& a, hipStream_t st) {
 
 int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.q_heads);
-  if (a.ev_start) DQ_HIP_CHECK(hipEventRecord(a.ev_start, st));
+  // the events, when given, receive the streaming kernel's own begin and end timestamps
   switch (a.fmt.bits) {
-    case 2: hipLaunchKernelGGL(decode_generic_kernel<2>, grid, dim3(256), 0, st, a); break;
-    case 4: hipLaunchKernelGGL(decode_generic_kernel<4>, grid, dim3(256), 0, st, a); break;
-    default: hipLaunchKernelGGL(decode_generic_kernel<8>, grid, dim3(256), 0, st, a); break;
+    case 2: hipExtLaunchKernelGGL(decode_generic_kernel<2>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
+    case 4: hipExtLaunchKernelGGL(decode_generic_kernel<4>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
+    default: hipExtLaunchKernelGGL(decode_generic_kernel<8>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
   }
   DQ_HIP_CHECK(hipGetLastError());
-  if (a.ev_stop) DQ_HIP_CHECK(hipEventRecord(a.ev_stop, st));
   return launch_combine(a, st);
 }
 

@@ -27,6 +27,8 @@
 //   D[m][n]: lane holds column n, rows m = 4*g + i.
 #include <type_traits>
 
+#include <hip/hip_ext.h>
+
 #include "dq_decode.h"
 
 namespace dq {
@@ -394,6 +396,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
     for (int hd = 0; hd < R; ++hd) { Mml[hd] = m_run[hd]; Mml[R + hd] = l_run[hd]; }
   }
   __syncthreads();
+  const long bhq0 = (long)b * a.q_heads + (long)h * R;
   for (int idx = tid; idx < R * D; idx += 256) {
     const int hd = idx / D, c = idx % D;
     float M = -INFINITY;
@@ -409,9 +412,52 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
       o = fmaf(col[0] * 16384.f + col[D] * 128.f + col[2 * D], wgt, o);
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
-    float* part = a.partials + (((long)b * a.q_heads + (long)h * R + hd) * a.n_split + split) * (D + 2);
-    part[c] = o;
-    if (c == 0) { part[D] = M * kLn2; part[D + 1] = L; }
+    if (a.n_split == 1) {   // this workgroup saw the whole sequence: finish here
+      const float r = (L > 0.f) ? o / L : 0.f;
+      a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
+      if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
+    } else {
+      // device-scope stores: they go through to memory, past the per-XCD L2, so that a workgroup
+      // on another XCD can read them without any cache write-back or invalidation
+      float* part = a.partials + ((bhq0 + hd) * a.n_split + split) * (D + 2);
+      __hip_atomic_store(part + c, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (c == 0) {
+        __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // M in log2 units
+        __hip_atomic_store(part + D + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+    }
+  }
+  if (a.n_split == 1) return;
+
+  // ---- the last workgroup of this (sequence, kv head) to arrive merges the split partials ----
+  // The barrier waits for every thread's stores above to be acknowledged; only then does one
+  // thread take a ticket.  The merging workgroup reads the partials with device-scope loads.
+  __shared__ int s_last;
+  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+  __syncthreads();
+  if (tid == 0) {
+    const int ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    s_last = (ticket == a.n_split - 1);
+    if (s_last) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next call
+  }
+  __syncthreads();
+  if (!s_last) return;
+  for (int idx = tid; idx < R * D; idx += 256) {
+    const int hd = idx / D, c = idx % D;
+    const float* base = a.partials + (bhq0 + hd) * a.n_split * (D + 2);
+    float M = -INFINITY;
+    for (int sp = 0; sp < a.n_split; ++sp) M = fmaxf(M, __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    float o = 0.f, L = 0.f;
+    for (int sp = 0; sp < a.n_split; ++sp) {
+      const float m = __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      if (m == -INFINITY) continue;
+      const float wgt = __builtin_amdgcn_exp2f(m - M);
+      L = fmaf(__hip_atomic_load(base + sp * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, L);
+      o = fmaf(__hip_atomic_load(base + sp * (D + 2) + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, o);
+    }
+    const float r = (L > 0.f) ? o / L : 0.f;
+    a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
+    if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
   }
 }
 
@@ -422,21 +468,18 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   return f->bits == 4 && f->head_dim == 128 && f->j1 == 16 && f->j2 == 8 && f->group == 128;
 }
 
-int32_t launch_combine(const DecodeArgs& a, hipStream_t st);
-
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   const int rep = a.q_heads / a.cache.kv_heads;
-  if (a.ev_start) DQ_HIP_CHECK(hipEventRecord(a.ev_start, st));
+  // the events, when given, receive the kernel's own begin and end timestamps
   switch (rep) {
-    case 1: hipLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(256), 0, st, a); break;
-    case 2: hipLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(256), 0, st, a); break;
-    case 4: hipLaunchKernelGGL(decode_mfma_kernel<4>, grid, dim3(256), 0, st, a); break;
+    case 1: hipExtLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
+    case 2: hipExtLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
+    case 4: hipExtLaunchKernelGGL(decode_mfma_kernel<4>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
     default: return DQ_EINVAL;
   }
   DQ_HIP_CHECK(hipGetLastError());
-  if (a.ev_stop) DQ_HIP_CHECK(hipEventRecord(a.ev_stop, st));
-  return launch_combine(a, st);
+  return DQ_OK;
 }
 
 }  // namespace dq
