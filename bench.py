@@ -29,6 +29,13 @@ import workloads  # noqa: E402
 
 HBM_PEAK_GBPS = 8000.0
 
+# HBM bytes per launch of the streaming kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE runs kept
+# under profiles/ (counter values scaled by what the same counters read for the plain read kernel
+# of known size).  None where no such run exists.
+PROFILED_TRAFFIC_BYTES = {
+    ("llama7b_4bit", "mfma"): (71827 + 64) * 1.9987 * 1024,
+}
+
 
 # --------------------------------------------------------------------------------------------
 # CPU baseline: the oracle as it stands, forked workers, before the GPU is initialised
@@ -228,14 +235,14 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u4 codes, f16 MFMA inputs, f32 accumulate" if path == "mfma" else "u%d codes, f32" % w.bits,
+        "dtype": "u4 codes on int8 MFMA, f32 accumulate" if path == "mfma" else "u%d codes, f32" % w.bits,
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "seq_len": [int(lens.min()), int(lens.max())], "bits": w.bits,
                    "group": w.group, "block_tokens": w.block_tokens, "j1": w.j1, "kernel_path": path,
                    "cache_copies_rotated": n_layers, "cache_bytes_per_layer": cache0.nbytes()},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None,
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": PROFILED_TRAFFIC_BYTES.get((w.name, path)),
                      "kernel_ms_mean": float(kernel_ms.mean()), "kernel_ms_median": float(np.median(kernel_ms)),
                      "algorithmic_bytes_per_launch": alg},
         "cpu_baseline": cpu,
