@@ -25,6 +25,7 @@
 // MFMA operand layouts (lane l: n = l % 16, g = l / 16):
 //   A[m][k]: lane holds row m = n, k = S*g + i (S values per lane);  B[k][n]: column n, same k;
 //   D[m][n]: lane holds column n, rows m = 4*g + i.
+#include <cstdlib>
 #include <type_traits>
 
 #include <hip/hip_ext.h>
@@ -88,8 +89,10 @@ __device__ __forceinline__ float pow2i(int e) {
   return __builtin_bit_cast(float, (uint32_t)(e + 127) << 23);
 }
 
-template <int R>
-__global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
+// R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles of one (sequence,
+// kv head, split) are dealt round-robin to the NW waves.
+template <int R, int NW>
+__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
   constexpr int NC = 4 * R;            // B columns in use: column 4*head + limb, limb 3 unused
   constexpr int F = (R + 1) / 2;       // fold MFMAs (two heads each)
   constexpr int D = 128, J1 = 16, J2 = 8, ROWB = 64;
@@ -97,7 +100,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   constexpr int QS_BYTES = NC * 128, PS_BYTES = NC * 128, SS_BYTES = NC * SS * 4;
   constexpr int WAVE_LDS = QS_BYTES + PS_BYTES + SS_BYTES;
   static_assert(WAVE_LDS >= NC * D * 4 + 2 * R * 4, "merge area must fit the wave's LDS");
-  __shared__ __attribute__((aligned(16))) unsigned char smem[4 * WAVE_LDS];
+  __shared__ __attribute__((aligned(16))) unsigned char smem[NW * WAVE_LDS];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, g = lane >> 4;
@@ -202,7 +205,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
     const unsigned char *kc_next = nullptr, *vc_next = nullptr;
     long blkid_next = 0;
     int tib_next = 0;
-    if (HAS_NEXT) tile_ptrs(tile + 4, kc_next, vc_next, blkid_next, tib_next);
+    if (HAS_NEXT) tile_ptrs(tile + NW, kc_next, vc_next, blkid_next, tib_next);
     Side nxt = cur;
     if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
     __builtin_amdgcn_sched_barrier(0);
@@ -374,7 +377,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
     int tile = tile_begin + wave;
     if (tile < tile_end) {
       if (!(spec_ok && tile == spec_tile)) issue_tile(tile);
-      for (; tile + 4 < tile_end; tile += 4) compute_tile(tile, std::true_type{});
+      for (; tile + NW < tile_end; tile += NW) compute_tile(tile, std::true_type{});
       compute_tile(tile, std::false_type{});
     }
   }
@@ -397,14 +400,14 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   }
   __syncthreads();
   const long bhq0 = (long)b * a.q_heads + (long)h * R;
-  for (int idx = tid; idx < R * D; idx += 256) {
+  for (int idx = tid; idx < R * D; idx += 64 * NW) {
     const int hd = idx / D, c = idx % D;
     float M = -INFINITY;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) M = fmaxf(M, reinterpret_cast<const float*>(smem + w * WAVE_LDS)[NC * D + hd]);
+    for (int w = 0; w < NW; ++w) M = fmaxf(M, reinterpret_cast<const float*>(smem + w * WAVE_LDS)[NC * D + hd]);
     float o = 0.f, L = 0.f;
 #pragma unroll
-    for (int w = 0; w < 4; ++w) {
+    for (int w = 0; w < NW; ++w) {
       const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
       const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
@@ -442,7 +445,7 @@ __global__ __launch_bounds__(256, 2) void decode_mfma_kernel(DecodeArgs a) {
   }
   __syncthreads();
   if (!s_last) return;
-  for (int idx = tid; idx < R * D; idx += 256) {
+  for (int idx = tid; idx < R * D; idx += 64 * NW) {
     const int hd = idx / D, c = idx % D;
     const float* base = a.partials + (bhq0 + hd) * a.n_split * (D + 2);
     float M = -INFINITY;
@@ -468,14 +471,27 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   return f->bits == 4 && f->head_dim == 128 && f->j1 == 16 && f->j2 == 8 && f->group == 128;
 }
 
-int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
+template <int R>
+static void launch_r(const DecodeArgs& a, hipStream_t st, int nw) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
-  const int rep = a.q_heads / a.cache.kv_heads;
   // the events, when given, receive the kernel's own begin and end timestamps
+  if (nw == 8)
+    hipExtLaunchKernelGGL((decode_mfma_kernel<R, 8>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+  else
+    hipExtLaunchKernelGGL((decode_mfma_kernel<R, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+}
+
+int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
+  const int rep = a.q_heads / a.cache.kv_heads;
+  int nw = 4;   // four waves per workgroup measured faster than eight on every workload tried
+  if (const char* env = getenv("DQ_DECODE_WAVES")) {  // tuning aid
+    const int v = atoi(env);
+    if (v == 4 || v == 8) nw = v;
+  }
   switch (rep) {
-    case 1: hipExtLaunchKernelGGL(decode_mfma_kernel<1>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
-    case 2: hipExtLaunchKernelGGL(decode_mfma_kernel<2>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
-    case 4: hipExtLaunchKernelGGL(decode_mfma_kernel<4>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
+    case 1: launch_r<1>(a, st, nw); break;
+    case 2: launch_r<2>(a, st, nw); break;
+    case 4: launch_r<4>(a, st, nw); break;
     default: return DQ_EINVAL;
   }
   DQ_HIP_CHECK(hipGetLastError());

@@ -266,3 +266,38 @@ def test_decode_full_size_llama7b_sampled_pairs():
         e32 = np.abs(got32[b, h].astype(np.float64) - want[b, h])
         assert (e32 <= np.maximum(2e-3, 1e-4 * np.abs(want[b, h]))).all(), (b, h, e32.max())
         _say("  pair %s max fp32 err %.3g, max |out| %.3g" % ((b, h), e32.max(), np.abs(want[b, h]).max()))
+
+
+def _full_size_case(name, pairs, flags=0, append=False):
+    """Sampled (sequence, kv head) pairs of a full-size workload, default launch configuration."""
+    w = workloads.get_workload(name)
+    fmt, ofmt = formats(w)
+    lens = workloads.seq_lens(w)
+    _say("decode full-size %s pairs=%s lens=%s" % (name, pairs, sorted(set(int(x) for x in lens))[:4]))
+    cache = oracle_cache_for_pairs(w, ofmt, pairs, lens)
+    q = workloads.query(w)
+    want = O.attention_decode(cache, ofmt, q, lens, pairs=pairs)
+    got16, got32 = run_decode(fmt, cache, q, lens, int(lens.max()), flags)
+    rep = w.q_heads // w.kv_heads
+    for b, h in pairs:
+        for hq in range(h * rep, (h + 1) * rep):
+            e16 = np.abs(got16[b, hq].astype(np.float64) - want[b, hq])
+            assert (e16 <= tolerance(want[b, hq])).all(), (b, hq, e16.max())
+            e32 = np.abs(got32[b, hq].astype(np.float64) - want[b, hq])
+            assert (e32 <= np.maximum(2e-3, 1e-4 * np.abs(want[b, hq]))).all(), (b, hq, e32.max())
+        _say("  pair %s max fp32 err %.3g" % ((b, h), e32.max()))
+
+
+def test_decode_full_size_llama13b_mixed_lengths():
+    w = workloads.get_workload("llama13b_mixed")
+    lens = workloads.seq_lens(w)
+    b_short, b_long = int(np.argmin(lens)), int(np.argmax(lens))
+    _full_size_case("llama13b_mixed", [(b_short, 0), (b_long, 39), (1, 20)])
+
+
+def test_decode_full_size_gqa_long():
+    _full_size_case("gqa_long", [(0, 0), (15, 7)])
+
+
+def test_decode_full_size_llama7b_2bit_generic_path():
+    _full_size_case("llama7b_2bit", [(0, 0), (15, 31)])
