@@ -9,31 +9,59 @@ namespace dq {
 static std::atomic<int> g_last_hip_error{0};
 void set_last_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 
-int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma) {
-  const int max_tiles = (max_seq_len + kTileTokens - 1) / kTileTokens;
-  if (max_tiles <= 0) return 1;
-  int n;
-  if (mfma) {
-    // one workgroup = 4 waves streaming one (sequence, kv head) split.  A workgroup per CU
-    // already saturates the memory system and a split costs a partial write, a ticket and a
-    // merge at the end, so only split when there are fewer units than CUs.
-    const int units = batch * kv_heads;
-    n = (256 + units / 2) / units;
-    const int by_len = (max_tiles + 3) / 4;
-    if (n > by_len) n = by_len;
-  } else {
-    const int units = batch * q_heads;
-    n = (2048 + units - 1) / units;
-    const int by_len = (max_tiles + 1) / 2;
-    if (n > by_len) n = by_len;
+// Launch shape of the matrix-core kernel: n splits of every (sequence, kv head) and nw waves per
+// workgroup.  Measured on MI355X: a wave needs about eight 128-token tiles to amortise its start-up
+// and its share of the merge; about 2048 resident waves (8 per CU) stream fastest when they can be
+// had at that depth, 1024 (one 4-wave workgroup per CU) otherwise; every extra split costs a partial
+// write, a ticket and a merge.
+static void choose_mfma_shape(int units, int max_tiles, int* n_out, int* nw_out) {
+  auto tiles_per_wave = [&](int n, int nw) { return max_tiles / (n * nw); };
+  // A: deep and wide
+  for (int nw = 8; nw >= 4; nw -= 4) {
+    const int cap = 256 * (8 / nw);            // workgroups resident on the chip
+    for (int n = cap / units; n >= 1; --n) {
+      if (n > kMaxSplits) continue;
+      if (tiles_per_wave(n, nw) >= 8 && (long)units * n * nw >= 1536) { *n_out = n; *nw_out = nw; return; }
+    }
   }
-  if (const char* env = getenv("DQ_DECODE_SPLITS")) {  // tuning aid
+  // B: deep, at least half the chip
+  for (int n = 512 / units; n >= 1; --n) {
+    if (n > kMaxSplits) continue;
+    if (tiles_per_wave(n, 4) >= 8 && (long)units * n * 4 >= 512) { *n_out = n; *nw_out = 4; return; }
+  }
+  // C: small problem: as many workgroups as leave two tiles per wave
+  for (int n = (512 / units < kMaxSplits ? 512 / units : kMaxSplits); n >= 1; --n) {
+    if (tiles_per_wave(n, 4) >= 2) { *n_out = n; *nw_out = 4; return; }
+  }
+  *n_out = 1; *nw_out = 4;
+}
+
+int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma,
+                  int* nw_out) {
+  const int max_tiles = (max_seq_len + kTileTokens - 1) / kTileTokens;
+  int n = 1, nw = 4;
+  if (max_tiles > 0) {
+    if (mfma) {
+      choose_mfma_shape(batch * kv_heads, max_tiles, &n, &nw);
+    } else {
+      const int units = batch * q_heads;
+      n = (2048 + units - 1) / units;
+      const int by_len = (max_tiles + 1) / 2;
+      if (n > by_len) n = by_len;
+    }
+  }
+  if (const char* env = getenv("DQ_DECODE_SPLITS")) {  // tuning aids
     const int v = atoi(env);
     if (v > 0) n = v;
   }
+  if (const char* env = getenv("DQ_DECODE_WAVES")) {
+    const int v = atoi(env);
+    if (v == 4 || v == 8) nw = v;
+  }
   if (n < 1) n = 1;
   if (n > kMaxSplits) n = kMaxSplits;
-  if (n > max_tiles) n = max_tiles;
+  if (max_tiles > 0 && n > max_tiles) n = max_tiles;
+  if (nw_out) *nw_out = nw;
   return n;
 }
 
@@ -52,21 +80,22 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
   const size_t waves = (size_t)gridDim.x * 4;
   const size_t wave = (size_t)blockIdx.x * 4 + (threadIdx.x >> 6);
   const int lane = threadIdx.x & 63;
-  // slices are multiples of one load group (INF * 64 elements); the last wave takes the tail
+  // slices are multiples of one load group (INF * 64 elements); what is left over after the
+  // slices is dealt out in 64-element pieces
   const size_t group = (size_t)INF * 64;
   const size_t per_wave = (n16 / waves) / group * group;
   const size_t begin = wave * per_wave;
-  const size_t end = (wave == waves - 1) ? n16 : begin + per_wave;
+  const size_t end = begin + per_wave;
   u32x4 acc = {0, 0, 0, 0};
-  size_t i = begin + lane;
-  for (; i + (INF - 1) * 64 < end; i += group) {
+  for (size_t i = begin + lane; i < end; i += group) {
     u32x4 v[INF];
 #pragma unroll
     for (int k = 0; k < INF; ++k) v[k] = __builtin_nontemporal_load(src + i + k * 64);
 #pragma unroll
     for (int k = 0; k < INF; ++k) acc ^= v[k];
   }
-  for (; i < end; i += 64) acc ^= __builtin_nontemporal_load(src + i);
+  for (size_t i = waves * per_wave + wave * 64 + lane; i < n16; i += waves * 64)
+    acc ^= __builtin_nontemporal_load(src + i);
   // a data-dependent store that practically never happens keeps the loads alive
   if ((acc.x ^ acc.y ^ acc.z ^ acc.w) == 0x9E3779B9u) {
     sink[0] = acc.x; sink[1] = acc.y; sink[2] = acc.z; sink[3] = acc.w;
@@ -149,7 +178,7 @@ extern "C" int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* ca
   char* ws = reinterpret_cast<char*>(workspace);
   a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
   a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, cache->kv_heads));
-  a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma);
+  a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, &a.nw);
   a.ev_start = (hipEvent_t)ev_kernel_start;
   a.ev_stop = (hipEvent_t)ev_kernel_stop;
   hipStream_t st = (hipStream_t)hip_stream;

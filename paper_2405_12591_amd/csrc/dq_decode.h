@@ -17,6 +17,7 @@ struct DecodeArgs {
   float* partials;         // [B*Hq, n_split, d + 2]
   int32_t* counters;       // [B*Hkv] zero between calls
   int n_split;
+  int nw;                  // waves per workgroup of the matrix-core kernel (4 or 8)
   hipEvent_t ev_start;     // optional: recorded around the main kernel
   hipEvent_t ev_stop;
 };
@@ -32,6 +33,7 @@ inline size_t decode_partial_bytes(const dq_format* f, int batch, int q_heads) {
 int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st);
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads);
-int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma);
+int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma,
+                  int* nw_out);
 
 }  // namespace dq

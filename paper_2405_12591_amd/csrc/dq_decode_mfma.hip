@@ -483,11 +483,7 @@ static void launch_r(const DecodeArgs& a, hipStream_t st, int nw) {
 
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   const int rep = a.q_heads / a.cache.kv_heads;
-  int nw = 4;   // four waves per workgroup measured faster than eight on every workload tried
-  if (const char* env = getenv("DQ_DECODE_WAVES")) {  // tuning aid
-    const int v = atoi(env);
-    if (v == 4 || v == 8) nw = v;
-  }
+  const int nw = a.nw;
   switch (rep) {
     case 1: launch_r<1>(a, st, nw); break;
     case 2: launch_r<2>(a, st, nw); break;
