@@ -1,34 +1,38 @@
-// Matrix-core decode attention over the compressed cache for the format
-//   bits = 4, head_dim = 128, j1 = 16, j2 = 8, group = 128, block_tokens % 128 == 0,
-//   q_heads / kv_heads in {1, 2, 4}.
+// Matrix-core decode attention over the compressed cache for the formats
+//   bits = 4, group = 128, q_heads / kv_heads in {1, 2, 4}
+//   bits = 2, group = 64,  q_heads / kv_heads in {1, 2}
+// with head_dim = 128, j1 = 16, j2 = 8, block_tokens % 128 == 0.
 //
 // This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
-// 2405.12591) carried through the attention that follows it.  The 4-bit codes never become
-// floating point: a 32-bit word of eight codes is split into two words of four bytes each
-// (x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F) and fed to the int8 matrix cores; the other operand
-// (the folded query, then the softmax weights times the value steps) is expressed as three
-// 7-bit integer limbs relative to a per-tile power of two, one B column per limb, so the
-// contraction is exact integer arithmetic.  Per 128-token tile, one wavefront
+// 2405.12591) carried through the attention that follows it.  The low-bit codes never become
+// floating point: a 32-bit word of codes is split into words of four bytes each
+// (4-bit: x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F; 2-bit: (x >> 2k) & 0x03030303) and fed to the
+// int8 matrix cores; the other operand (the folded query, then the softmax weights times the
+// value steps) is expressed as three 7-bit integer limbs relative to a per-tile power of two,
+// one B column per limb, so the contraction is exact integer arithmetic.  Per 128-token tile,
+// one wavefront
 //   1. folds the keys' small tensor into the query,  q'[r, b2] = sum_b1 T_S^K[b1, r] q[b1, b2]
 //      (one 16x16x16 f16 MFMA per two heads; T_S and q are fp16, so the products are exact),
 //      and writes the limbs of q' * scale * log2(e) as B operands;
-//   2. streams the key codes with 128-bit loads: S[t][limb] = sum_c u[t, c] limb[c]
-//      (16x16x64 i8 MFMA, u = code + 8; the 8 is removed with a constant-A MFMA);
+//   2. streams the key codes: S[t][limb] = sum_c u[t, c] limb[c]  (16x16x64 i8 MFMA,
+//      u = code + 2^(bits-1); the offset is removed with a constant-A MFMA);
 //   3. online softmax with two tokens per lane (scores cross from the MFMA layout through
 //      wave-private LDS); w_t = p_t * step^V_t is cut into limbs, again B columns;
 //   4. streams the value codes (stored token-contiguous): o'[r, b2] = sum_t u[t, r, b2] limb[t];
 //   5. applies the values' small tensor with fp32 16x16x4 MFMAs,
 //      acc[b1, b2] = alpha * acc + sum_r T_S^V[b1, r] o'[r, b2].
-// A query head takes four of the sixteen B columns (three limbs, one spare), so up to four
-// heads that share a kv head ride on the same code stream.
+// With two step groups per token row (group = 64: rows r < 8 and r >= 8 of the large tensor)
+// every limb gets one B column per group: the key side zeroes the limbs of the other group's
+// channels, the value side keeps only the rows of its group when o' enters the epilogue.
+// A query head takes 4 (one group) or 8 (two groups) of the sixteen B columns.
 //
 // MFMA operand layouts (lane l: n = l % 16, g = l / 16):
 //   A[m][k]: lane holds row m = n, k = S*g + i (S values per lane);  B[k][n]: column n, same k;
 //   D[m][n]: lane holds column n, rows m = 4*g + i.
+#include <hip/hip_ext.h>
+
 #include <cstdlib>
 #include <type_traits>
-
-#include <hip/hip_ext.h>
 
 #include "dq_decode.h"
 
@@ -41,24 +45,52 @@ typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
 typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
-constexpr float kLn2 = 0.6931471805599453f;
 constexpr int kLimbBits = 7;
 constexpr int kMantBits = 3 * kLimbBits;  // 21-bit integers: limb0 * 2^14 + limb1 * 2^7 + limb2
 
-// two words of eight 4-bit fields -> sixteen bytes; slot order per word [0,2,4,6,1,3,5,7]
-__device__ __forceinline__ i32x4 unpack16(uint32_t x0, uint32_t x1) {
-  const uint32_t M = 0x0F0F0F0Fu;
-  i32x4 v;
-  v.x = (int)(x0 & M);
-  v.y = (int)((x0 >> 4) & M);
-  v.z = (int)(x1 & M);
-  v.w = (int)((x1 >> 4) & M);
-  return v;
-}
+// ---- per-bit-width pieces -------------------------------------------------------------------
+// Chunk: what one lane loads of a 16-row piece of codes (16 bytes at 4 bits, 8 at 2 bits); it
+// feeds two int8 MFMAs of 16 codes per lane each.  `slot(e)` is the byte position, inside the 16
+// bytes a lane hands to one MFMA, of the e-th of its 16 consecutive codes.
+template <int BITS> struct Codec;
+template <> struct Codec<4> {
+  typedef u32x4 chunk_t;
+  static constexpr int kOffset = 8;
+  // first MFMA: words x, y (codes 0..15 of the lane's 32); second: words z, w
+  static __device__ __forceinline__ i32x4 half(const chunk_t& c, int which) {
+    const uint32_t M = 0x0F0F0F0Fu;
+    const uint32_t x0 = which ? c.z : c.x, x1 = which ? c.w : c.y;
+    i32x4 v;
+    v.x = (int)(x0 & M);          // codes 0, 2, 4, 6
+    v.y = (int)((x0 >> 4) & M);   // codes 1, 3, 5, 7
+    v.z = (int)(x1 & M);          // codes 8, 10, 12, 14
+    v.w = (int)((x1 >> 4) & M);   // codes 9, 11, 13, 15
+    return v;
+  }
+  static __device__ __forceinline__ int slot(int e) { return (e & 8) + (e & 1) * 4 + ((e & 7) >> 1); }
+};
+template <> struct Codec<2> {
+  typedef u32x2 chunk_t;
+  static constexpr int kOffset = 2;
+  static __device__ __forceinline__ i32x4 half(const chunk_t& c, int which) {
+    const uint32_t M = 0x03030303u;
+    const uint32_t x = which ? c.y : c.x;
+    i32x4 v;
+    v.x = (int)(x & M);           // codes 0, 4, 8, 12
+    v.y = (int)((x >> 2) & M);    // codes 1, 5, 9, 13
+    v.z = (int)((x >> 4) & M);    // codes 2, 6, 10, 14
+    v.w = (int)((x >> 6) & M);    // codes 3, 7, 11, 15
+    return v;
+  }
+  static __device__ __forceinline__ int slot(int e) { return (e & 3) * 4 + (e >> 2); }
+};
 
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
+}
+__device__ __forceinline__ float lane_f(float v, int l) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
 // all-reduce over the 16 lanes of a row, then over the four rows
 __device__ __forceinline__ float wave_allmax(float v) {
@@ -66,22 +98,14 @@ __device__ __forceinline__ float wave_allmax(float v) {
   v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
   v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
   v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror
-  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-  return fmaxf(fmaxf(a, b), fmaxf(c, d));
+  return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
 }
 __device__ __forceinline__ float wave_allsum(float v) {
   v += dpp_f<0xB1>(v);
   v += dpp_f<0x4E>(v);
   v += dpp_f<0x141>(v);
   v += dpp_f<0x140>(v);
-  const float a = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 0));
-  const float b = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 16));
-  const float c = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 32));
-  const float d = __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), 48));
-  return (a + b) + (c + d);
+  return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
 }
 
 // 2^e as a float for -126 <= e <= 127
@@ -89,14 +113,22 @@ __device__ __forceinline__ float pow2i(int e) {
   return __builtin_bit_cast(float, (uint32_t)(e + 127) << 23);
 }
 
-// R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles of one (sequence,
-// kv head, split) are dealt round-robin to the NW waves.
-template <int R, int NW>
+// BITS: code width.  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
+// of one (sequence, kv head, split) are dealt round-robin to the NW waves.
+template <int BITS, int R, int NW>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
-  constexpr int NC = 4 * R;            // B columns in use: column 4*head + limb, limb 3 unused
-  constexpr int F = (R + 1) / 2;       // fold MFMAs (two heads each)
-  constexpr int D = 128, J1 = 16, J2 = 8, ROWB = 64;
-  constexpr int SS = 132;              // ints per column of the score staging (128 tokens + bias + pad)
+  typedef Codec<BITS> C;
+  typedef typename C::chunk_t chunk_t;
+  constexpr int NG = (BITS == 4) ? 1 : 2;     // step groups per token row
+  constexpr int CPH = 4 * NG;                 // B columns per head: column CPH*head + 4*group + limb
+  constexpr int NC = CPH * R;
+  static_assert(NC <= 16, "too many heads for sixteen B columns");
+  constexpr int F = (R + 1) / 2;              // fold MFMAs (two heads each)
+  constexpr int D = 128, J1 = 16, J2 = 8;
+  constexpr int ROWB = D * BITS / 8;          // bytes of a key row
+  constexpr int VROWB = kTileTokens * BITS / 8;   // bytes of a value row (one r, one b2) in a tile
+  constexpr int CHUNKB = sizeof(chunk_t);
+  constexpr int SS = 132;                     // ints per column of the score staging (128 tokens + bias + pad)
   constexpr int QS_BYTES = NC * 128, PS_BYTES = NC * 128, SS_BYTES = NC * SS * 4;
   constexpr int WAVE_LDS = QS_BYTES + PS_BYTES + SS_BYTES;
   static_assert(WAVE_LDS >= NC * D * 4 + 2 * R * 4, "merge area must fit the wave's LDS");
@@ -110,7 +142,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   const int b = bh / H, h = bh % H;
   const int tpb = a.fmt.block_tokens / kTileTokens;
   const long codes_per_block = (long)a.fmt.block_tokens * ROWB;
-  const long scales_per_block = a.fmt.block_tokens;
+  const long scales_per_block = (long)a.fmt.block_tokens * NG;
 
   // The split of the sequence depends on its length, which lives in device memory.  The first
   // tile's loads are issued for the length the host passed as the upper bound (right whenever
@@ -122,15 +154,18 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   int S = 0;  // the sequence's real length, read after the speculative loads are on their way
 
   unsigned char* wl = smem + wave * WAVE_LDS;
-  unsigned char* Qs = wl;                                        // [NC][16 r][8 slots] bytes
-  unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 groups][16 slots] bytes
+  unsigned char* Qs = wl;                                        // [NC][8 row pairs][16 slots] bytes
+  unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 token groups][16 slots] bytes
   int* Ss = reinterpret_cast<int*>(wl + QS_BYTES + PS_BYTES);    // [NC][SS] ints
   const bool col_live = (n < NC) && ((n & 3) != 3);
+  const int col_grp = (n >> 2) & (NG - 1);                       // step group of this lane's B column
 
-  // softmax layout: lane = 8*G16 + pi owns tokens tA and tA + 2 of the tile (adjacent B slots)
+  // softmax layout: lane = 8*G16 + pi owns the two tokens of token group G16 whose weights sit in
+  // B slots 2*pi and 2*pi + 1
   const int G16 = lane >> 3, pi = lane & 7;
-  const int tA = 16 * G16 + 8 * (pi >> 2) + ((0x5140 >> (4 * (pi & 3))) & 7);  // 0,4,1,5
-  const int tB = tA + 2;
+  int tA, tB;
+  if (BITS == 4) { tA = 16 * G16 + 8 * (pi >> 2) + ((0x5140 >> (4 * (pi & 3))) & 7); tB = tA + 2; }
+  else { tA = 16 * G16 + 8 * (pi & 1) + (pi >> 1); tB = tA + 4; }
 
   // ---- loop-invariant B operands of the fold: q[k = b1][n' = (b2, head)] ----
   half4 bq[F];
@@ -148,7 +183,6 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
       bq[f] = v;
     }
   }
-  const int qslot = (n & 1) * 4 + ((n & 7) >> 1);  // B slot of channel b2 = n & 7 inside its row
 
   float m_run[R], l_run[R];
 #pragma unroll
@@ -158,32 +192,39 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   for (int b2 = 0; b2 < J2; ++b2) acc[b2] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const float qk_scale = a.scale * kLog2e;
-  const i32x4 a_plus8 = {0x08080808, 0x08080808, 0x08080808, 0x08080808};
-  const i32x4 a_minus8 = {(int)0xF8F8F8F8, (int)0xF8F8F8F8, (int)0xF8F8F8F8, (int)0xF8F8F8F8};
+  constexpr int kPlusWord = C::kOffset * 0x01010101;                       // four bytes of +offset
+  constexpr int kMinusWord = (int)((uint32_t)(256 - C::kOffset) * 0x01010101u);  // four bytes of -offset
+  const i32x4 a_plus = {kPlusWord, kPlusWord, kPlusWord, kPlusWord};
+  const i32x4 a_minus = {kMinusWord, kMinusWord, kMinusWord, kMinusWord};
   const i32x4 izero = {0, 0, 0, 0};
 
-  // ---- the code stream of one wave: 16 chunks of 1 KB per tile (keys j = 0..7 in slots 0..7,
-  // values b2 = 0..7 in slots 8..15) flow through a 16-slot register ring; a slot is refilled in
-  // place with the same chunk of the wave's next tile as soon as it has been unpacked, so one
-  // whole tile (16 KB) per wave is in flight at all times.  The memory counter retires loads in
-  // issue order, so everything is requested in the order it will be used: the next tile's small
-  // tensors and steps first (needed before its first key chunk), then the refills.
-  u32x4 ring[16];
-  struct Side { u32x2 ksm, vsm; uint16_t dkA, dkB, dvA, dvB; };   // small tensors + the lane's four steps
+  // ---- the code stream of one wave: 16 chunks per tile (keys j = 0..7 in slots 0..7, values
+  // b2 = 0..7 in slots 8..15) flow through a 16-slot register ring; a slot is refilled in place
+  // with the same chunk of the wave's next tile as soon as it has been unpacked, so one whole
+  // tile per wave is in flight at all times.  The memory counter retires loads in issue order,
+  // so everything is requested in the order it will be used: the next tile's small tensors and
+  // steps first (needed before its first key chunk), then the refills.
+  chunk_t ring[16];
+  struct Side { u32x2 ksm, vsm; uint32_t dkA, dkB, dvA, dvB; };   // small tensors + the lane's steps
   Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0};
 
   auto tile_ptrs = [&](int tile, const unsigned char*& kc, const unsigned char*& vc, long& blkid, int& tib) {
     blkid = (long)bh * NB + tile / tpb;
     tib = tile % tpb;
-    kc = a.cache.k_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + 16 * g;
-    vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * 64 + 16 * g;
+    kc = a.cache.k_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + CHUNKB * g;
+    vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * VROWB + CHUNKB * g;
+  };
+  auto load_steps = [&](const uint16_t* p, int t) -> uint32_t {   // the NG fp16 steps of token t
+    if (NG == 1) return p[t];
+    return *reinterpret_cast<const uint32_t*>(p + 2 * t);
   };
   auto load_side = [&](Side& sd, long blkid, int tib) {
     sd.ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + blkid * (J1 * J1) + n * J1 + 4 * g);
     sd.vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
-    const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens;
-    const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens;
-    sd.dkA = ksc[tA]; sd.dkB = ksc[tB]; sd.dvA = vsc[tA]; sd.dvB = vsc[tB];
+    const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens * NG;
+    const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens * NG;
+    sd.dkA = load_steps(ksc, tA); sd.dkB = load_steps(ksc, tB);
+    sd.dvA = load_steps(vsc, tA); sd.dvB = load_steps(vsc, tB);
   };
   auto issue_tile = [&](int tile) {
     const unsigned char *kc, *vc;
@@ -193,9 +234,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     load_side(cur, blkid, tib);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
-    for (int j = 0; j < 8; ++j) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kc + j * (16 * ROWB)));
+    for (int j = 0; j < 8; ++j) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc + j * (16 * ROWB)));
 #pragma unroll
-    for (int b2 = 0; b2 < 8; ++b2) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vc + b2 * (J1 * 64)));
+    for (int b2 = 0; b2 < 8; ++b2) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc + b2 * (J1 * VROWB)));
+  };
+  auto step_of = [&](uint32_t packed, int grp) -> float {   // fp16 step of group grp from the packed word
+    return h2f((uint16_t)(grp ? (packed >> 16) : (packed & 0xFFFFu)));
   };
 
   // One tile.  HAS_NEXT: the wave has another tile after this one.
@@ -210,8 +254,14 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
     __builtin_amdgcn_sched_barrier(0);
     const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
-    const float dvA = okA ? h2f(cur.dvA) : 0.f, dvB = okB ? h2f(cur.dvB) : 0.f;
-    const float dkA_f = h2f(cur.dkA), dkB_f = h2f(cur.dkB);
+    float dvA[NG], dvB[NG], dkA[NG], dkB[NG];
+#pragma unroll
+    for (int gr = 0; gr < NG; ++gr) {
+      dvA[gr] = okA ? step_of(cur.dvA, gr) : 0.f;
+      dvB[gr] = okB ? step_of(cur.dvB, gr) : 0.f;
+      dkA[gr] = step_of(cur.dkA, gr);
+      dkB[gr] = step_of(cur.dkB, gr);
+    }
     const half4 vsm_h = __builtin_bit_cast(half4, cur.vsm);
 
     // ---- 1. fold T_S^K into q; limbs of q' relative to 2^e >= max |q'| ----
@@ -232,6 +282,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
       e = max(min(e, 100), -100);
       const float qn = qk_scale * pow2i(kMantBits - 1 - e);   // |q' * qn| < 2^20
       q_unscale = pow2i(e - (kMantBits - 1));
+      // the fold's D layout: lane (n' = b2 + 8*head, g) holds rows r = 4g + i.  Channel (r, b2) is
+      // code number (r & 1)*8 + b2 of the 16 codes that row pair r >> 1 contributes to one MFMA.
 #pragma unroll
       for (int f = 0; f < F; ++f) {
         const int hd = 2 * f + (n >> 3);
@@ -240,10 +292,16 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
           for (int i = 0; i < 4; ++i) {
             const int vi = (int)__builtin_rintf(fd[f][i] * qn);
             const int r = 4 * g + i;
-            unsigned char* dst = Qs + (4 * hd) * 128 + r * 8 + qslot;
+            const int grp = (NG == 2) ? (r >> 3) : 0;
+            const int pos = (r >> 1) * 16 + C::slot((r & 1) * 8 + (n & 7));
+            unsigned char* dst = Qs + (CPH * hd + 4 * grp) * 128 + pos;
             dst[0] = (unsigned char)(vi >> (2 * kLimbBits));
             dst[128] = (unsigned char)((vi >> kLimbBits) & 127);
             dst[256] = (unsigned char)(vi & 127);
+            if (NG == 2) {   // this channel contributes nothing to the other group's columns
+              unsigned char* oth = Qs + (CPH * hd + 4 * (1 - grp)) * 128 + pos;
+              oth[0] = 0; oth[128] = 0; oth[256] = 0;
+            }
           }
         }
       }
@@ -253,21 +311,21 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
 #pragma unroll
     for (int w = 0; w < 2; ++w) {
       i32x4 t = izero;
-      if (col_live) t = *reinterpret_cast<const i32x4*>(Qs + n * 128 + (4 * g + 2 * w) * 8);
+      if (col_live) t = *reinterpret_cast<const i32x4*>(Qs + n * 128 + (2 * g + w) * 16);
       bqs[w] = t;
     }
 
-    // ---- 2. scores: S[t][col] = sum_c u[t, c] limb[col][c];  bias row: 8 * sum_c limb[col][c] ----
+    // ---- 2. scores: S[t][col] = sum_c u[t, c] limb[col][c];  bias row: offset * sum_c limb[col][c] ----
     {
-      i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus8, bqs[0], izero, 0, 0, 0);
-      bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus8, bqs[1], bias, 0, 0, 0);
+      i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[0], izero, 0, 0, 0);
+      bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[1], bias, 0, 0, 0);
       if (col_live && g == 0) Ss[n * SS + 128] = bias[0];
       i32x4 s_prev = izero;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
-        const i32x4 a0 = unpack16(ring[j].x, ring[j].y), a1 = unpack16(ring[j].z, ring[j].w);
+        const i32x4 a0 = C::half(ring[j], 0), a1 = C::half(ring[j], 1);
         __builtin_amdgcn_sched_barrier(0);   // the slot is dead from here on: refill it in place
-        if (HAS_NEXT) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(kc_next + j * (16 * ROWB)));
+        if (HAS_NEXT) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc_next + j * (16 * ROWB)));
         __builtin_amdgcn_sched_barrier(0);
         i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bqs[0], izero, 0, 0, 0);
         s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bqs[1], s, 0, 0, 0);
@@ -280,27 +338,31 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     __builtin_amdgcn_wave_barrier();
 
     // ---- 3. online softmax, tokens tA and tB per lane ----
-    const float dkA = dkA_f * q_unscale, dkB = dkB_f * q_unscale;
-    float v_unscale, dvAs, dvBs;
+    float v_unscale, vs;
     {
-      const float dvmax = wave_allmax(fmaxf(dvA, dvB));
+      float dvm = fmaxf(dvA[0], dvB[0]);
+      if (NG == 2) dvm = fmaxf(dvm, fmaxf(dvA[NG - 1], dvB[NG - 1]));
+      const float dvmax = wave_allmax(dvm);
       int e = 0;
       if (dvmax > 0.f && dvmax < INFINITY) e = __builtin_amdgcn_frexp_expf(dvmax);
-      const float vs = pow2i(kMantBits - e);   // p * step * vs < 2^21
+      vs = pow2i(kMantBits - e);   // p * step * vs < 2^21
       v_unscale = pow2i(e - kMantBits);
-      dvAs = dvA * vs; dvBs = dvB * vs;
     }
     float alpha[R];
 #pragma unroll
     for (int hd = 0; hd < R; ++hd) {
-      const int* s0 = Ss + (4 * hd) * SS;
-      const int* s1 = s0 + SS;
-      const int* s2 = s1 + SS;
-      const int b0 = s0[128], b1 = s1[128], b2v = s2[128];
-      float sA = ((float)(s0[tA] - b0) * 16384.f + (float)(s1[tA] - b1) * 128.f + (float)(s2[tA] - b2v)) * dkA;
-      float sB = ((float)(s0[tB] - b0) * 16384.f + (float)(s1[tB] - b1) * 128.f + (float)(s2[tB] - b2v)) * dkB;
-      sA = okA ? sA : -INFINITY;
-      sB = okB ? sB : -INFINITY;
+      float sA = 0.f, sB = 0.f;
+#pragma unroll
+      for (int gr = 0; gr < NG; ++gr) {
+        const int* s0 = Ss + (CPH * hd + 4 * gr) * SS;
+        const int* s1 = s0 + SS;
+        const int* s2 = s1 + SS;
+        const int b0 = s0[128], b1 = s1[128], b2v = s2[128];
+        sA += ((float)(s0[tA] - b0) * 16384.f + (float)(s1[tA] - b1) * 128.f + (float)(s2[tA] - b2v)) * dkA[gr];
+        sB += ((float)(s0[tB] - b0) * 16384.f + (float)(s1[tB] - b1) * 128.f + (float)(s2[tB] - b2v)) * dkB[gr];
+      }
+      sA = okA ? sA * q_unscale : -INFINITY;
+      sB = okB ? sB * q_unscale : -INFINITY;
       const float mt = wave_allmax(fmaxf(sA, sB));
       const float m_new = fmaxf(m_run[hd], mt);          // finite: the tile has a valid token
       alpha[hd] = __builtin_amdgcn_exp2f(m_run[hd] - m_new);
@@ -308,14 +370,17 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
       const float pB = __builtin_amdgcn_exp2f(sB - m_new);
       l_run[hd] = l_run[hd] * alpha[hd] + (pA + pB);
       m_run[hd] = m_new;
-      const float wA = okA ? pA * dvAs : 0.f;
-      const float wB = okB ? pB * dvBs : 0.f;
-      const uint32_t iA = min((uint32_t)(wA + 0.5f), (1u << kMantBits) - 1u);
-      const uint32_t iB = min((uint32_t)(wB + 0.5f), (1u << kMantBits) - 1u);
-      unsigned char* dst = Ps + (4 * hd) * 128 + G16 * 16 + 2 * pi;
-      *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((iA >> 14) | ((iB >> 14) << 8));
-      *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127u) | (((iB >> 7) & 127u) << 8));
-      *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127u) | ((iB & 127u) << 8));
+#pragma unroll
+      for (int gr = 0; gr < NG; ++gr) {
+        const float wA = okA ? pA * (dvA[gr] * vs) : 0.f;
+        const float wB = okB ? pB * (dvB[gr] * vs) : 0.f;
+        const uint32_t iA = min((uint32_t)(wA + 0.5f), (1u << kMantBits) - 1u);
+        const uint32_t iB = min((uint32_t)(wB + 0.5f), (1u << kMantBits) - 1u);
+        unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
+        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((iA >> 14) | ((iB >> 14) << 8));
+        *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127u) | (((iB >> 7) & 127u) << 8));
+        *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127u) | ((iB & 127u) << 8));
+      }
     }
     __builtin_amdgcn_wave_barrier();
 
@@ -329,39 +394,42 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     }
     float alpha_col = 1.f;
 #pragma unroll
-    for (int hd = 0; hd < R; ++hd) alpha_col = ((n >> 2) == hd) ? alpha[hd] : alpha_col;
+    for (int hd = 0; hd < R; ++hd) alpha_col = ((n / CPH) == hd) ? alpha[hd] : alpha_col;
     float aT[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) aT[i] = (float)vsm_h[i] * v_unscale;
-    i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus8, bp[0], izero, 0, 0, 0);
-    cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus8, bp[1], cinitv, 0, 0, 0);
+    // with two step groups a column's weights carry the step of one group only: rows r = 4g + i
+    // of the other group (g >= 2 for group 0, g < 2 for group 1) are dropped on the way in
+    const bool keep = (NG == 1) || ((g >> 1) == col_grp);
+    i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[0], izero, 0, 0, 0);
+    cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[1], cinitv, 0, 0, 0);
     if (__any(alpha_col != 1.f)) {   // the running maximum moved: rare after the first tiles
 #pragma unroll
       for (int b2 = 0; b2 < J2; ++b2) acc[b2] *= alpha_col;
     }
+    auto epilogue = [&](int b2, const i32x4& o) __attribute__((always_inline)) {
+      f32x4 c = acc[b2];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        float of = (float)o[i];
+        if (NG == 2) of = keep ? of : 0.f;
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], of, c, 0, 0, 0);
+      }
+      acc[b2] = c;
+    };
     i32x4 o_prev = izero;
 #pragma unroll
     for (int b2 = 0; b2 < J2; ++b2) {
-      const i32x4 a0 = unpack16(ring[8 + b2].x, ring[8 + b2].y), a1 = unpack16(ring[8 + b2].z, ring[8 + b2].w);
+      const i32x4 a0 = C::half(ring[8 + b2], 0), a1 = C::half(ring[8 + b2], 1);
       __builtin_amdgcn_sched_barrier(0);
-      if (HAS_NEXT) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const u32x4*>(vc_next + b2 * (J1 * 64)));
+      if (HAS_NEXT) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc_next + b2 * (J1 * VROWB)));
       __builtin_amdgcn_sched_barrier(0);
       i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bp[0], cinitv, 0, 0, 0);
       o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bp[1], o, 0, 0, 0);
-      if (b2 > 0) {   // epilogue of the previous b2 while this one's integer MFMAs run
-        f32x4 c = acc[b2 - 1];
-#pragma unroll
-        for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)o_prev[i], c, 0, 0, 0);
-        acc[b2 - 1] = c;
-      }
+      if (b2 > 0) epilogue(b2 - 1, o_prev);   // while this b2's integer MFMAs run
       o_prev = o;
     }
-    {
-      f32x4 c = acc[J2 - 1];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)o_prev[i], c, 0, 0, 0);
-      acc[J2 - 1] = c;
-    }
+    epilogue(J2 - 1, o_prev);
     cur = nxt;
     __builtin_amdgcn_wave_barrier();
   };
@@ -382,7 +450,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     }
   }
 
-  // ---- merge the four waves of the workgroup, write one partial per query head ----
+  // ---- merge the waves of the workgroup ----
   float* Macc = reinterpret_cast<float*>(wl);            // [NC][128] per wave (reuses the wave's LDS)
   float* Mml = Macc + NC * D;                            // [R] m, [R] l
 #pragma unroll
@@ -411,8 +479,13 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
       const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
       const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      const float* col = base + (4 * hd) * D + c;
-      o = fmaf(col[0] * 16384.f + col[D] * 128.f + col[2 * D], wgt, o);
+      float v = 0.f;
+#pragma unroll
+      for (int gr = 0; gr < NG; ++gr) {
+        const float* col = base + (CPH * hd + 4 * gr) * D + c;
+        v += col[0] * 16384.f + col[D] * 128.f + col[2 * D];
+      }
+      o = fmaf(v, wgt, o);
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
     if (a.n_split == 1) {   // this workgroup saw the whole sequence: finish here
@@ -449,7 +522,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     const int hd = idx / D, c = idx % D;
     const float* base = a.partials + (bhq0 + hd) * a.n_split * (D + 2);
     float M = -INFINITY;
-    for (int sp = 0; sp < a.n_split; ++sp) M = fmaxf(M, __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
+    for (int sp = 0; sp < a.n_split; ++sp)
+      M = fmaxf(M, __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     float o = 0.f, L = 0.f;
     for (int sp = 0; sp < a.n_split; ++sp) {
       const float m = __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -466,29 +540,38 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
 
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads % kv_heads) return false;
+  if (f->head_dim != 128 || f->j1 != 16 || f->j2 != 8) return false;
   const int rep = q_heads / kv_heads;
-  if (rep != 1 && rep != 2 && rep != 4) return false;
-  return f->bits == 4 && f->head_dim == 128 && f->j1 == 16 && f->j2 == 8 && f->group == 128;
+  if (f->bits == 4 && f->group == 128) return rep == 1 || rep == 2 || rep == 4;
+  if (f->bits == 2 && f->group == 64) return rep == 1 || rep == 2;
+  return false;
 }
 
-template <int R>
-static void launch_r(const DecodeArgs& a, hipStream_t st, int nw) {
+template <int BITS, int R>
+static void launch_r(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   // the events, when given, receive the kernel's own begin and end timestamps
-  if (nw == 8)
-    hipExtLaunchKernelGGL((decode_mfma_kernel<R, 8>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+  if (a.nw == 8)
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, R, 8>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
   else
-    hipExtLaunchKernelGGL((decode_mfma_kernel<R, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, R, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
 }
 
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   const int rep = a.q_heads / a.cache.kv_heads;
-  const int nw = a.nw;
-  switch (rep) {
-    case 1: launch_r<1>(a, st, nw); break;
-    case 2: launch_r<2>(a, st, nw); break;
-    case 4: launch_r<4>(a, st, nw); break;
-    default: return DQ_EINVAL;
+  if (a.fmt.bits == 4) {
+    switch (rep) {
+      case 1: launch_r<4, 1>(a, st); break;
+      case 2: launch_r<4, 2>(a, st); break;
+      case 4: launch_r<4, 4>(a, st); break;
+      default: return DQ_EINVAL;
+    }
+  } else {
+    switch (rep) {
+      case 1: launch_r<2, 1>(a, st); break;
+      case 2: launch_r<2, 2>(a, st); break;
+      default: return DQ_EINVAL;
+    }
   }
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;

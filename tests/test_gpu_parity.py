@@ -223,6 +223,9 @@ def test_stream_read_runs():
     ("gqa_long", dict(batch=2, q_heads=4, kv_heads=2, max_seq=700, min_seq=700), [513, 700]),
     ("llama13b_mixed", dict(batch=3, q_heads=4, kv_heads=4, max_seq=640, min_seq=1), [640, 0, 383]),
     ("llama7b_4bit", dict(batch=1, q_heads=2, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=256), [777]),
+    ("llama7b_2bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=700, min_seq=700), [700, 128]),
+    ("llama7b_2bit", dict(batch=3, q_heads=4, kv_heads=2, max_seq=1300, min_seq=1300), [1300, 0, 257]),
+    ("llama7b_2bit", dict(batch=1, q_heads=2, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=256), [1000]),
 ])
 def test_decode_mfma_multi_block(name, kw, lens):
     w = _small(name, **kw)
@@ -236,7 +239,9 @@ def test_decode_mfma_multi_block(name, kw, lens):
 def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
     fmt4 = dq.Format(4, 128, 128, 16, 8, 128)
     assert dq.decode_mfma_supported(fmt4, 32, 32) and dq.decode_mfma_supported(fmt4, 32, 8)
-    assert not dq.decode_mfma_supported(dq.Format(2, 64, 128, 16, 8, 128), 32, 32)
+    assert dq.decode_mfma_supported(dq.Format(2, 64, 128, 16, 8, 128), 32, 32)
+    assert not dq.decode_mfma_supported(dq.Format(2, 64, 128, 16, 8, 128), 32, 8)
+    assert not dq.decode_mfma_supported(dq.Format(2, 128, 128, 16, 8, 128), 32, 32)
     assert not dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 4, 4)
     w = workloads.get_workload("tiny")
     fmt, ofmt = formats(w)
@@ -299,5 +304,5 @@ def test_decode_full_size_gqa_long():
     _full_size_case("gqa_long", [(0, 0), (15, 7)])
 
 
-def test_decode_full_size_llama7b_2bit_generic_path():
+def test_decode_full_size_llama7b_2bit():
     _full_size_case("llama7b_2bit", [(0, 0), (15, 31)])
