@@ -306,3 +306,70 @@ def test_decode_full_size_gqa_long():
 
 def test_decode_full_size_llama7b_2bit():
     _full_size_case("llama7b_2bit", [(0, 0), (15, 31)])
+
+
+# ------------------------------------------------------------------------------------------
+# widening: 8-bit codes, identity small tensor (plain group round-to-nearest), graph replay
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits,group", [(8, 128), (8, 64)])
+def test_decode_8bit_generic(bits, group):
+    """Section 3.2 names 2/4/8-bit variants of the fused kernel; 8-bit runs on the generic path."""
+    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=600, min_seq=600, bits=bits, group=group)
+    _say("decode 8-bit G=%d" % group)
+    worst = _decode_case(w, [600, 130], dq.DECODE_AUTO)
+    _say("  worst fp32 abs err %.3g" % worst)
+
+
+@pytest.mark.parametrize("name,flags", [("llama7b_4bit", 2), ("llama7b_2bit", 2), ("llama7b_4bit", 1)])
+def test_identity_small_tensor_is_plain_rtn_attention(name, flags):
+    """With T_S = I the cache is plain group round-to-nearest of K and V (the paper's RTN
+    baseline, Section 4.1); the same kernels must decode it.  Steps are then as large as the
+    data (|x| up to 512), which exercises the kernels' range normalisation."""
+    w = _small(name, batch=2, q_heads=4, kv_heads=2, max_seq=520, min_seq=520)
+    fmt, ofmt = formats(w)
+    lens = np.array([520, 300], np.int32)
+    _say("identity small tensor %s flags=%d" % (name, flags))
+    cache = O.empty_cache(ofmt, w.batch, w.kv_heads, -(-w.max_seq // w.block_tokens))
+    for b in range(w.batch):
+        for h in range(w.kv_heads):
+            k, v = workloads.kv_pair(w, b, h, int(lens[b]))
+            O.compress_sequence(cache, ofmt, b, h, k, v, identity_small=True)
+    q = workloads.query(w)
+    want = O.attention_decode(cache, ofmt, q, lens)
+    got16, got32 = run_decode(fmt, cache, q, lens, 520, flags)
+    assert (np.abs(got16.astype(np.float64) - want) <= tolerance(want)).all()
+    assert (np.abs(got32.astype(np.float64) - want) <= np.maximum(2e-3, 1e-4 * np.abs(want))).all()
+
+
+def test_decode_under_graph_capture_replays_identically():
+    """The decode call records no memset and allocates nothing, so it can be captured; every
+    replay, with eager work and synchronisations in between, must equal the eager result."""
+    w = _small("llama7b_4bit", batch=4, q_heads=8, kv_heads=8, max_seq=3000, min_seq=3000)
+    fmt, ofmt = formats(w)
+    lens = np.array([3000, 1, 1500, 2999], np.int32)
+    pairs = [(b, h) for b in range(w.batch) for h in range(w.kv_heads)]
+    cache_np = oracle_cache_for_pairs(w, ofmt, pairs[:6], lens)       # six real pairs, rest garbage
+    cache = dq.cache_from_numpy(fmt, cache_np, DEV)
+    q = torch.from_numpy(workloads.query(w)).to(DEV)
+    ld = torch.from_numpy(lens).to(DEV)
+    ws = dq.decode_workspace(fmt, w.batch, w.q_heads, w.kv_heads, 3000, DEV)
+    eager = dq.attn_decode(cache, q, ld, 3000, ws).clone()
+    torch.cuda.synchronize()
+    out = torch.empty_like(q)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        dq.attn_decode(cache, q, ld, 3000, ws, out=out)      # warm-up on the capture stream
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            dq.attn_decode(cache, q, ld, 3000, ws, out=out)
+    torch.cuda.synchronize()
+    for rep in range(4):
+        out.fill_(float("nan"))
+        scratch = torch.randn(1 << 20, device=DEV).sum()     # eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        real = [(b, h) for b, h in pairs[:6]]
+        for b, h in real:
+            assert torch.equal(out[b, h], eager[b, h]), (rep, b, h)
+        del scratch

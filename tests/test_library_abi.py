@@ -55,3 +55,39 @@ def test_entry_points_reject_null_pointers_before_touching_the_gpu(dq):
     assert st == -1
     assert dq.lib.dq_stream_read(None, 16, None, None) == -1
     assert dq.lib.dq_workspace_init(None, 16, None) == -1
+
+
+def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
+    good = dq.Format(4, 128, 128, 16, 8, 128).c()
+
+    class FakeCache(C.Structure):
+        _fields_ = [("p", C.c_void_p * 6), ("batch", C.c_int32), ("kv_heads", C.c_int32), ("cap", C.c_int32)]
+
+    fake = FakeCache()
+    for i in range(6):
+        fake.p[i] = 0x1000          # never dereferenced: the checks below fail first
+    fake.batch, fake.kv_heads, fake.cap = 2, 4, 8
+    need = dq.lib.dq_decode_workspace_bytes(C.byref(good), 2, 4, 4, 1024)
+    ptr = C.c_void_p(0x1000)
+    cache_p = C.cast(C.byref(fake), C.POINTER(type(dq.Cache.__init__.__globals__["_CCache"]())))
+    # workspace one byte short
+    st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need - 1, 0, None)
+    assert st == -2
+    # max_seq_len beyond the cache capacity (8 blocks x 128 tokens)
+    st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1025, 0.0, ptr, None, ptr, need, 0, None)
+    assert st == -1
+    # q_heads not a multiple of kv_heads
+    st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 6, ptr, 1024, 0.0, ptr, None, ptr, need, 0, None)
+    assert st == -1
+    # both force flags
+    st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need, 3, None)
+    assert st == -1
+    # compress: t_new out of range, workspace too small
+    cneed = dq.lib.dq_compress_workspace_bytes(C.byref(good), 2, 4)
+    st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 129, ptr, None, ptr, cneed, None)
+    assert st == -1
+    st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, None)
+    assert st == -2
+    # quantize_pack: rows not a multiple of 128
+    st = dq.lib.dq_quantize_pack(C.byref(good), ptr, 100, 0, ptr, ptr, None)
+    assert st == -1
