@@ -1,7 +1,7 @@
 // Compression of K/V blocks into DecoQuant form (Section 3.1 of arXiv 2405.12591):
 //   step 1  two-site MPO split of the regrouped block, M = T_S * T_L            (Eq. 2, Eq. 3)
 //   step 2  per-group round-to-nearest quantization of T_L, T_S kept in fp16   (Eq. 1)
-// Two kernels: `decompose_kernel` (Gram matrix, Jacobi eigen-solver, projection) writes the
+// Two kernels: `decompose_kernel` (Gram matrix, Jacobi eigen-solver, projection; one wave per block) writes the
 // small tensor into the cache and the fp32 large tensor into the workspace;
 // `quantize_tiles_kernel` turns fp32 rows into packed codes and fp16 steps.
 #include "dq_common.h"
@@ -136,19 +136,43 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __rest
 }
 
 // ------------------------------------------------------------------------------------------
-// Decomposition: Gram matrix in fp64, parallel cyclic Jacobi, projection.  256 threads.
+// Decomposition: Gram matrix in fp64, parallel cyclic Jacobi, projection.  One wavefront per
+// (sequence, kv head, K|V) block, so all synchronisation is inside one wave.
 // ------------------------------------------------------------------------------------------
 constexpr int kJMax = 32;
-constexpr int kGramTile = 32;  // tokens staged in LDS per Gram step
+constexpr int kGramTile = 8;  // tokens staged in LDS per Gram step
 
-__global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache cache,
-                                                        const uint16_t* __restrict__ k_new,
-                                                        const uint16_t* __restrict__ v_new,
-                                                        int t_new,
-                                                        const int32_t* __restrict__ blk_idx,
-                                                        const int32_t* __restrict__ n_valid,
-                                                        float* __restrict__ large_ws,
-                                                        int32_t* __restrict__ status) {
+// Reciprocal and reciprocal square root in fp64 from the hardware estimates plus Newton steps
+// (relative error about 1e-16).  The Jacobi rotations sit on a serial path of a few lanes, where the
+// compiler's IEEE-exact division and square root sequences cost several times more.
+__device__ __forceinline__ double fast_rcp(double x) {
+  double r = __builtin_amdgcn_rcp(x);
+  r = r * (2.0 - x * r);
+  r = r * (2.0 - x * r);
+  return r;
+}
+__device__ __forceinline__ double fast_rsqrt(double x) {
+  double y = __builtin_amdgcn_rsq(x);
+  y = y * (1.5 - 0.5 * x * y * y);
+  y = y * (1.5 - 0.5 * x * y * y);
+  return y;
+}
+
+__host__ __device__ inline size_t decompose_lds_bytes(int j1, int d) {
+  const size_t mat = (size_t)j1 * (j1 + 1);
+  return (5 * mat + 5 * (size_t)j1) * sizeof(double) + 3 * (size_t)j1 * sizeof(int) +
+         (size_t)kGramTile * d * sizeof(float) + 64;
+}
+
+template <int J1, int DD>
+__global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache cache,
+                                                       const uint16_t* __restrict__ k_new,
+                                                       const uint16_t* __restrict__ v_new,
+                                                       int t_new,
+                                                       const int32_t* __restrict__ blk_idx,
+                                                       const int32_t* __restrict__ n_valid,
+                                                       float* __restrict__ large_ws,
+                                                       int32_t* __restrict__ status) {
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
   const int unit = blockIdx.x;  // (b*H + h)*2 + which
   const int which = unit & 1;
@@ -159,64 +183,73 @@ __global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache 
   int nv = t_new;
   if (n_valid) nv = min(max(n_valid[b], 0), t_new);
   const int tid = threadIdx.x;
-  const int j1 = g.j1, j2 = g.j2, d = g.d;
+  constexpr int j1 = J1, d = DD, j2 = DD / J1;   // compile-time shapes: loops unroll, no divisions
+  constexpr int ld = j1 + 1;             // padded leading dimension of the small matrices
+  constexpr int nent = j1 * j1;
   const uint16_t* X = (which ? v_new : k_new) + (long)bh * t_new * d;  // [t_new, d] fp16 bits
 
-  __shared__ float xs[kGramTile * 128];
-  __shared__ double A[2][kJMax][kJMax + 1];  // Gram matrix, double buffered
-  __shared__ double V[2][kJMax][kJMax + 1];  // accumulated rotations
-  __shared__ double rc[kJMax], rs[kJMax];    // rotation (c, s) per index (shared by both partners)
-  __shared__ int partner[kJMax];
-  __shared__ int is_p[kJMax];                // 1 if index is the "p" (first) member of its pair
-  __shared__ double sigma[kJMax], lam[kJMax];
-  __shared__ int order[kJMax];
-  __shared__ double W[kJMax][kJMax + 1];     // W[r][b1] = U[b1][order r] / sigma_r
-  __shared__ double offarr[kJMax];           // per rotating thread: largest relative off-diagonal seen
+  extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
+  double* A0 = reinterpret_cast<double*>(lds_raw);   // Gram matrix, double buffered
+  double* A1 = A0 + j1 * ld;
+  double* V0 = A1 + j1 * ld;                         // accumulated rotations, double buffered
+  double* V1 = V0 + j1 * ld;
+  double* W = V1 + j1 * ld;                          // W[r][b1] = U[b1][order r] / sigma_r
+  double* rc = W + j1 * ld;                          // rotation (c, s) per index (both partners)
+  double* rs = rc + j1;
+  double* lam = rs + j1;
+  double* sigma = lam + j1;
+  double* offarr = sigma + j1;                       // per rotating lane: largest relative off-diagonal
+  int* partner = reinterpret_cast<int*>(offarr + j1);
+  int* is_p = partner + j1;                          // 1 if the index is the first member of its pair
+  int* order = is_p + j1;
+  float* xs = reinterpret_cast<float*>(order + j1 + (j1 & 1));   // [kGramTile][d]
 
   // ---- Gram matrix: Gm[p][q] = sum_{t, b2} X[t, p*j2+b2] * X[t, q*j2+b2] ----
-  const int nent = j1 * j1;
-  double acc[4] = {0.0, 0.0, 0.0, 0.0};
+  // lane (pb, qb) of an 8 x 8 grid owns a (j1/8) x (j1/8) block of entries
+  constexpr int BS = j1 / 8;
+  const int pb = (tid >> 3) * BS, qb = (tid & 7) * BS;
+  double acc[BS][BS];
+#pragma unroll
+  for (int i = 0; i < BS; ++i)
+#pragma unroll
+    for (int j = 0; j < BS; ++j) acc[i][j] = 0.0;
   for (int t0 = 0; t0 < nv; t0 += kGramTile) {
     const int nt = min(kGramTile, nv - t0);
-    for (int i = tid; i < nt * d; i += blockDim.x) xs[i] = h2f(X[(long)t0 * d + i]);
+    for (int i = tid; i < nt * d; i += 64) xs[i] = h2f(X[(long)t0 * d + i]);
     __syncthreads();
-    for (int k = 0, idx = tid; idx < nent; idx += blockDim.x, ++k) {
-      const int p = idx / j1, q = idx % j1;
-      double a = 0.0;  // every product of two fp16 values is exact in fp64; only the sum rounds
-      for (int t = 0; t < nt; ++t) {
-        const float* xr = xs + t * d;
-        for (int b2 = 0; b2 < j2; ++b2) a = fma((double)xr[p * j2 + b2], (double)xr[q * j2 + b2], a);
+    for (int t = 0; t < nt; ++t) {
+      const float* xr = xs + t * d;
+#pragma unroll
+      for (int b2 = 0; b2 < j2; ++b2) {
+        double xp[BS], xq[BS];
+#pragma unroll
+        for (int i = 0; i < BS; ++i) {
+          xp[i] = (double)xr[(pb + i) * j2 + b2];
+          xq[i] = (double)xr[(qb + i) * j2 + b2];
+        }
+        // every product of two fp16 values is exact in fp64; only the sum rounds
+#pragma unroll
+        for (int i = 0; i < BS; ++i)
+#pragma unroll
+          for (int j = 0; j < BS; ++j) acc[i][j] = fma(xp[i], xq[j], acc[i][j]);
       }
-      acc[k] += a;
     }
     __syncthreads();
   }
-  for (int k = 0, idx = tid; idx < nent; idx += blockDim.x, ++k) {
-    const int p = idx / j1, q = idx % j1;
-    A[0][p][q] = acc[k];
-    V[0][p][q] = (p == q) ? 1.0 : 0.0;
-  }
-  __syncthreads();
-  // symmetrise exactly (the accumulation order is the same for (p,q) and (q,p); keep it robust)
-  for (int idx = tid; idx < nent; idx += blockDim.x) {
-    const int p = idx / j1, q = idx % j1;
-    if (p < q) {
-      const double s = 0.5 * (A[0][p][q] + A[0][q][p]);
-      A[0][p][q] = s;
-    }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < nent; idx += blockDim.x) {
-    const int p = idx / j1, q = idx % j1;
-    if (p > q) A[0][p][q] = A[0][q][p];
-  }
+#pragma unroll
+  for (int i = 0; i < BS; ++i)
+#pragma unroll
+    for (int j = 0; j < BS; ++j) A0[(pb + i) * ld + qb + j] = acc[i][j];
+  for (int idx = tid; idx < nent; idx += 64) V0[(idx / j1) * ld + idx % j1] = (idx / j1 == idx % j1) ? 1.0 : 0.0;
   __syncthreads();
 
   // ---- parallel cyclic Jacobi: j1-1 rounds of j1/2 disjoint rotations per sweep ----
-  int cur = 0;
+  double* Ac = A0; double* An = A1; double* Vc = V0; double* Vn = V1;
   const int nm1 = j1 - 1;
+  int sweeps = 0;
   for (int sweep = 0; sweep < 16; ++sweep) {
-    if (tid < kJMax) offarr[tid] = 0.0;
+    ++sweeps;
+    if (tid < j1) offarr[tid] = 0.0;
     __syncthreads();
     for (int round = 0; round < nm1; ++round) {
       if (tid < j1 / 2) {
@@ -224,15 +257,17 @@ __global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache 
         if (tid == 0) { p = nm1; q = round; }
         else { p = (round + tid) % nm1; q = (round - tid + nm1) % nm1; }
         if (p > q) { const int t = p; p = q; q = t; }
-        const double app = A[cur][p][p], aqq = A[cur][q][q], apq = A[cur][p][q];
+        const double app = Ac[p * ld + p], aqq = Ac[q * ld + q], apq = Ac[p * ld + q];
         double c = 1.0, s = 0.0;
-        if (apq != 0.0 && fabs(apq) > 1e-300) {
-          const double tau = (aqq - app) / (2.0 * apq);
-          const double t = (tau >= 0.0 ? 1.0 : -1.0) / (fabs(tau) + sqrt(1.0 + tau * tau));
-          c = 1.0 / sqrt(1.0 + t * t);
+        // skip off-diagonals that are already negligible against the diagonal (also keeps tau finite)
+        if (fabs(apq) > 1e-300 && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq))) {
+          const double tau = (aqq - app) * 0.5 * fast_rcp(apq);
+          const double w = 1.0 + tau * tau;                       // sqrt(w) = w * rsqrt(w)
+          const double t = (tau >= 0.0 ? 1.0 : -1.0) * fast_rcp(fabs(tau) + w * fast_rsqrt(w));
+          c = fast_rsqrt(1.0 + t * t);
           s = t * c;
-          const double rel = fabs(apq) / sqrt(fabs(app * aqq) + 1e-300);
-          if (rel > offarr[tid]) offarr[tid] = rel;
+          const double rel2 = apq * apq * fast_rcp(fabs(app * aqq) + 1e-300);   // squared relative size
+          if (rel2 > offarr[tid]) offarr[tid] = rel2;
         }
         rc[p] = c; rs[p] = s; rc[q] = c; rs[q] = s;
         partner[p] = q; partner[q] = p;
@@ -241,30 +276,29 @@ __global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache 
       __syncthreads();
       // J has J[p][p] = c, J[p][q] = s, J[q][p] = -s, J[q][q] = c for each pair.
       // A' = J^T A J ; V' = V J.  Entry (i, j) needs A at {i, pi} x {j, pj}.
-      for (int idx = tid; idx < nent; idx += blockDim.x) {
+      for (int idx = tid; idx < nent; idx += 64) {
         const int i = idx / j1, j = idx % j1;
         const int pi = partner[i], pj = partner[j];
         // column j of J: J[j][j] = c_j, J[pj][j] = (is_p[j] ? -s : +s)
         const double cj = rc[j], sj = is_p[j] ? -rs[j] : rs[j];
         const double ci = rc[i], si = is_p[i] ? -rs[i] : rs[i];
-        // (A J)[a][j] = A[a][j]*cj + A[a][pj]*sj
-        const double aj_i = A[cur][i][j] * cj + A[cur][i][pj] * sj;
-        const double aj_pi = A[cur][pi][j] * cj + A[cur][pi][pj] * sj;
-        // (J^T (A J))[i][j] = J[i][i]*(AJ)[i][j] + J[pi][i]*(AJ)[pi][j]
-        A[cur ^ 1][i][j] = ci * aj_i + si * aj_pi;
-        V[cur ^ 1][i][j] = V[cur][i][j] * cj + V[cur][i][pj] * sj;
+        const double aj_i = Ac[i * ld + j] * cj + Ac[i * ld + pj] * sj;     // (A J)[i][j]
+        const double aj_pi = Ac[pi * ld + j] * cj + Ac[pi * ld + pj] * sj;  // (A J)[pi][j]
+        An[i * ld + j] = ci * aj_i + si * aj_pi;                            // (J^T (A J))[i][j]
+        Vn[i * ld + j] = Vc[i * ld + j] * cj + Vc[i * ld + pj] * sj;
       }
       __syncthreads();
-      cur ^= 1;
+      double* t = Ac; Ac = An; An = t;
+      t = Vc; Vc = Vn; Vn = t;
     }
     double om = 0.0;
     for (int i = 0; i < j1 / 2; ++i) om = fmax(om, offarr[i]);
     __syncthreads();
-    if (om < 1e-15) break;
+    if (om < 1e-24) break;   // every rotated off-diagonal was below 1e-12 of its diagonal pair
   }
 
   // ---- singular values, ordering, small tensor ----
-  if (tid < j1) lam[tid] = A[cur][tid][tid];
+  if (tid < j1) lam[tid] = Ac[tid * ld + tid];
   __syncthreads();
   if (tid < j1) {
     int rank = 0;
@@ -283,29 +317,32 @@ __global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache 
     const long blk = (long)bh * g.NB + slot;
     uint16_t* small = (which ? cache.v_small : cache.k_small) + blk * g.small_per_block;
     bool sat = false;
-    for (int idx = tid; idx < nent; idx += blockDim.x) {
+    for (int idx = tid; idx < nent; idx += 64) {
       const int b1 = idx / j1, r = idx % j1;
-      const double u = V[cur][b1][order[r]];
+      const double u = Vc[b1 * ld + order[r]];
       const double sg = sigma[r];
-      W[r][b1] = sg > 0.0 ? u / sg : 0.0;
+      W[r * ld + b1] = sg > 0.0 ? u / sg : 0.0;
       const uint16_t hb = f64_to_f16_rne(u * sg, true, &sat);
       if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
       else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
     }
     if (sat) atomicOr(status, 1);
+    if (tid == 0) atomicMax(status + 1, sweeps);   // diagnostic: most Jacobi sweeps any block needed
   }
   __syncthreads();
 
   // ---- projection: K'[t, r*j2+b2] = sum_b1 W[r][b1] * X[t, b1*j2+b2], fp64 -> fp32 ----
   float* out = large_ws + (long)unit * g.Tb * d;
-  for (int item = tid; item < g.Tb * j2; item += blockDim.x) {
+  for (int item = tid; item < g.Tb * j2; item += 64) {
     const int t = item / j2, b2 = item % j2;
     if (t < nv) {
-      double xv[kJMax];
+      double xv[j1];
+#pragma unroll
       for (int b1 = 0; b1 < j1; ++b1) xv[b1] = (double)h2f(X[(long)t * d + b1 * j2 + b2]);
       for (int r = 0; r < j1; ++r) {
         double a = 0.0;
-        for (int b1 = 0; b1 < j1; ++b1) a = fma(W[r][b1], xv[b1], a);
+#pragma unroll
+        for (int b1 = 0; b1 < j1; ++b1) a = fma(W[r * ld + b1], xv[b1], a);
         out[(long)t * d + r * j2 + b2] = (float)a;
       }
     } else {
@@ -315,7 +352,7 @@ __global__ __launch_bounds__(256) void decompose_kernel(dq_format fmt, dq_cache 
 }
 
 __global__ void clear_status_kernel(int32_t* status) {
-  if (threadIdx.x == 0) *status = 0;
+  if (threadIdx.x < 2) status[threadIdx.x] = 0;
 }
 
 }  // namespace dq
@@ -367,8 +404,20 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   float* large_ws = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kWsHeaderBytes);
   const int units = cache->batch * cache->kv_heads * 2;
   hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, status);
-  hipLaunchKernelGGL(decompose_kernel, dim3(units), dim3(256), 0, st, *fmt, *cache, k_new, v_new, t_new,
-                     blk_idx, n_valid, large_ws, status);
+  const size_t dlds = decompose_lds_bytes(fmt->j1, fmt->head_dim);
+#define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                   \
+  hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, k_new, \
+                     v_new, t_new, blk_idx, n_valid, large_ws, status)
+  if (fmt->head_dim == 128) {
+    if (fmt->j1 == 8) DQ_LAUNCH_DECOMPOSE(8, 128);
+    else if (fmt->j1 == 16) DQ_LAUNCH_DECOMPOSE(16, 128);
+    else DQ_LAUNCH_DECOMPOSE(32, 128);
+  } else {
+    if (fmt->j1 == 8) DQ_LAUNCH_DECOMPOSE(8, 64);
+    else if (fmt->j1 == 16) DQ_LAUNCH_DECOMPOSE(16, 64);
+    else DQ_LAUNCH_DECOMPOSE(32, 64);
+  }
+#undef DQ_LAUNCH_DECOMPOSE
   DQ_HIP_CHECK(hipGetLastError());
   const int tiles = units * (fmt->block_tokens / kTileTokens);
   const size_t lds = (size_t)kTileTokens * fmt->head_dim;
