@@ -417,13 +417,20 @@ def dense_attention(q: np.ndarray, k: np.ndarray, v: np.ndarray, scale: Optional
 
 def attention_decode(cache: Dict[str, np.ndarray], fmt: Format, q: np.ndarray, seq_lens: np.ndarray,
                      scale: Optional[float] = None,
-                     pairs: Optional[Sequence[Tuple[int, int]]] = None) -> np.ndarray:
+                     pairs: Optional[Sequence[Tuple[int, int]]] = None,
+                     k_tail: Optional[np.ndarray] = None, v_tail: Optional[np.ndarray] = None,
+                     tail_lens: Optional[np.ndarray] = None) -> np.ndarray:
     """Decode-step attention against the compressed cache (Section 3.2): dequantize the
     blocks of each (sequence, kv head) and run ordinary attention for every query head
     mapped to that kv head (h_kv = h_q // (H_q / H_kv)).
 
     q: fp16 [B, H_q, d]; returns fp64 [B, H_q, d].  With `pairs`, only the listed
     (b, h_kv) pairs are computed; other rows stay NaN.
+
+    k_tail, v_tail [B, H_kv, cap, d] with tail_lens [B]: the tokens generated since the last
+    compression, still held in fp16 (Section 3.2: new rows are buffered and DecoQuant runs only
+    when a block's worth has accumulated).  They follow the compressed tokens and are attended
+    to at full precision.
     """
     bsz, hq, d = q.shape
     hkv = cache["k_codes"].shape[1]
@@ -433,6 +440,10 @@ def attention_decode(cache: Dict[str, np.ndarray], fmt: Format, q: np.ndarray, s
     for b, h in todo:
         n_tok = int(seq_lens[b])
         k_hat, v_hat = reconstruct_sequence(cache, fmt, b, h, n_tok)
+        if k_tail is not None:
+            n_tail = int(tail_lens[b])
+            k_hat = np.concatenate([k_hat, k_tail[b, h, :n_tail].astype(np.float64)])
+            v_hat = np.concatenate([v_hat, v_tail[b, h, :n_tail].astype(np.float64)])
         for hq_i in range(h * rep, (h + 1) * rep):
             out[b, hq_i] = dense_attention(q[b, hq_i], k_hat, v_hat, scale)
     return out

@@ -155,3 +155,28 @@ def test_pairs_argument_restricts_the_work():
     O.compress_sequence(cache, fmt, 0, 2, k, v)
     out = O.attention_decode(cache, fmt, workloads.query(w), workloads.seq_lens(w), pairs=[(0, 2)])
     assert np.isfinite(out[0, 2]).all() and np.isnan(out[0, 0]).all()
+
+
+def test_fp16_tail_is_attended_like_extra_tokens():
+    # Section 3.2: rows generated since the last compression stay in fp16.  With a lossless code
+    # the result must equal brute-force dense attention over [compressed tokens, tail tokens];
+    # an empty tail changes nothing; a tail alone (no compressed token) is plain attention.
+    fmt = O.Format(4, 64, 128, 16, 8, 128)
+    r = np.random.default_rng(11)
+    k, v = _lossless_kv(1, 200, 128, 7), _lossless_kv(2, 200, 128, 7)
+    cache = O.empty_cache(fmt, 2, 1, 2)
+    for b in range(2):
+        O.compress_sequence(cache, fmt, b, 0, k, v, identity_small=True)
+    kt = r.standard_normal((2, 1, 16, 128)).astype(np.float16)
+    vt = r.standard_normal((2, 1, 16, 128)).astype(np.float16)
+    q = r.standard_normal((2, 2, 128)).astype(np.float16)
+    lens, tl = np.array([200, 0], np.int32), np.array([5, 16], np.int32)
+    out = O.attention_decode(cache, fmt, q, lens, k_tail=kt, v_tail=vt, tail_lens=tl)
+    for hq in range(2):
+        want = O.dense_attention(q[0, hq], np.concatenate([k[:200], kt[0, 0, :5]]), np.concatenate([v[:200], vt[0, 0, :5]]))
+        assert np.abs(out[0, hq] - want).max() <= 1e-10
+        want = O.dense_attention(q[1, hq], kt[1, 0], vt[1, 0])
+        assert np.abs(out[1, hq] - want).max() <= 1e-10
+    none = O.attention_decode(cache, fmt, q, lens, k_tail=kt, v_tail=vt, tail_lens=np.zeros(2, np.int32))
+    base = O.attention_decode(cache, fmt, q, lens)
+    assert np.array_equal(none, base)
