@@ -130,6 +130,30 @@ int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* cache, const 
                              size_t workspace_bytes, uint32_t flags, void* hip_stream,
                              void* ev_kernel_start, void* ev_kernel_stop);
 
+/*
+ * The tokens generated since the last compression, still in fp16 (Section 3.2: new key/value rows
+ * are buffered and DecoQuant runs only once a block's worth has accumulated).  They follow the
+ * compressed tokens of their sequence.
+ *   k_tail, v_tail  f16 [B, kv_heads, capacity, d]
+ *   tail_lens       i32 [B] device, 0 <= tail_lens[b] <= capacity; capacity <= 256 (host integer)
+ */
+typedef struct dq_tail {
+  const uint16_t* k_tail;
+  const uint16_t* v_tail;
+  const int32_t* tail_lens;
+  int32_t capacity;
+} dq_tail;
+
+/*
+ * dq_attn_decode over the compressed tokens t < seq_lens[b] followed by the fp16 tail tokens:
+ * one softmax over the union.  A small kernel turns the tail into one more partial result,
+ * which the streaming kernel's merge folds in.  `tail` may be NULL (then this is dq_attn_decode).
+ */
+int32_t dq_attn_decode_tail(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                            int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                            const dq_tail* tail, float softmax_scale, uint16_t* out, float* out_f32,
+                            void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
 /* Bytes of workspace dq_compress_kv needs for n_blocks = B * H blocks of keys plus as many of
  * values (0 on invalid arguments). */
 size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads);

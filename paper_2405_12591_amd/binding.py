@@ -16,7 +16,7 @@ DECODE_FORCE_MFMA = 2
 
 EXPORTED_SYMBOLS = [
     "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
-    "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed",
+    "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed", "dq_attn_decode_tail",
     "dq_compress_workspace_bytes", "dq_compress_kv", "dq_quantize_pack", "dq_stream_read",
 ]
 
@@ -28,6 +28,10 @@ class DQError(RuntimeError):
 class _CFormat(C.Structure):
     _fields_ = [("bits", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
                 ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32)]
+
+
+class _CTail(C.Structure):
+    _fields_ = [("k_tail", C.c_void_p), ("v_tail", C.c_void_p), ("tail_lens", C.c_void_p), ("capacity", C.c_int32)]
 
 
 class _CCache(C.Structure):
@@ -59,6 +63,10 @@ def _load() -> C.CDLL:
                                  C.c_uint32, C.c_void_p]
     l.dq_attn_decode_timed.restype = C.c_int32
     l.dq_attn_decode_timed.argtypes = l.dq_attn_decode.argtypes + [C.c_void_p, C.c_void_p]
+    l.dq_attn_decode_tail.restype = C.c_int32
+    l.dq_attn_decode_tail.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_int32, C.c_void_p,
+                                      C.c_int32, C.POINTER(_CTail), C.c_float, C.c_void_p, C.c_void_p,
+                                      C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
     l.dq_compress_workspace_bytes.restype = C.c_size_t
     l.dq_compress_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32]
     l.dq_compress_kv.restype = C.c_int32
@@ -203,11 +211,13 @@ def workspace_init(ws: torch.Tensor) -> None:
 def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
                 workspace: torch.Tensor, out: Optional[torch.Tensor] = None,
                 out_f32: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
-                flags: int = DECODE_AUTO, kernel_events=None) -> torch.Tensor:
+                flags: int = DECODE_AUTO, kernel_events=None, tail=None) -> torch.Tensor:
     """out[b, h_q] = softmax(q . K_hat^T * scale) V_hat over the compressed cache (dq_attn_decode).
 
     kernel_events: optional (start, stop) torch.cuda.Event pair, each already recorded once so
     that its handle exists; they are re-recorded around the main kernel (dq_attn_decode_timed).
+    tail: optional (k_tail, v_tail, tail_lens) fp16 [B, H_kv, cap, d] + int32 [B]: the tokens not
+    yet compressed (dq_attn_decode_tail).
     """
     fmt = cache.fmt
     if q.dtype != torch.float16 or not q.is_contiguous() or seq_lens.dtype != torch.int32:
@@ -219,7 +229,14 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
     args = (C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
             softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
             workspace.data_ptr(), workspace.numel(), flags, _stream_ptr(q.device))
-    if kernel_events is None:
+    if tail is not None:
+        kt, vt, tl = tail
+        if kt.dtype != torch.float16 or vt.dtype != torch.float16 or tl.dtype != torch.int32 \
+                or not kt.is_contiguous() or not vt.is_contiguous():
+            raise DQError("tail tensors must be contiguous fp16 with int32 lengths")
+        ct = _CTail(kt.data_ptr(), vt.data_ptr(), tl.data_ptr(), kt.shape[2])
+        st = lib.dq_attn_decode_tail(*args[:6], C.byref(ct), *args[6:])
+    elif kernel_events is None:
         st = lib.dq_attn_decode(*args)
     else:
         st = lib.dq_attn_decode_timed(*args, kernel_events[0].cuda_event, kernel_events[1].cuda_event)

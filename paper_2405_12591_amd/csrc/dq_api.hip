@@ -145,11 +145,11 @@ extern "C" int32_t dq_workspace_init(void* workspace, size_t workspace_bytes, vo
   return DQ_OK;
 }
 
-extern "C" int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
-                                        int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
-                                        float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
-                                        size_t workspace_bytes, uint32_t flags, void* hip_stream,
-                                        void* ev_kernel_start, void* ev_kernel_stop) {
+static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                           int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                           const dq_tail* tail, float softmax_scale, uint16_t* out, float* out_f32,
+                           void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream,
+                           void* ev_kernel_start, void* ev_kernel_stop) {
   if (!format_ok(fmt) || !cache || !q || !seq_lens || !out || !workspace) return DQ_EINVAL;
   if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
       !cache->v_small)
@@ -161,6 +161,8 @@ extern "C" int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* ca
   const size_t need = dq_decode_workspace_bytes(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len);
   if (need == 0) return DQ_EINVAL;
   if (workspace_bytes < need) return DQ_ENOSPACE;
+  if (tail && (!tail->k_tail || !tail->v_tail || !tail->tail_lens || tail->capacity < 1 || tail->capacity > 256))
+    return DQ_EINVAL;
   const bool can_mfma = mfma_supported(fmt, q_heads, cache->kv_heads);
   if ((flags & DQ_DECODE_FORCE_MFMA) && !can_mfma) return DQ_EINVAL;
   const bool use_mfma = can_mfma && !(flags & DQ_DECODE_FORCE_GENERIC);
@@ -179,10 +181,31 @@ extern "C" int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* ca
   a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
   a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, cache->kv_heads));
   a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, &a.nw);
+  a.n_slots = a.n_split + (tail ? 1 : 0);
+  if (tail) a.tail = *tail;
+  else a.tail = dq_tail{nullptr, nullptr, nullptr, 0};
   a.ev_start = (hipEvent_t)ev_kernel_start;
   a.ev_stop = (hipEvent_t)ev_kernel_stop;
   hipStream_t st = (hipStream_t)hip_stream;
   return use_mfma ? launch_decode_mfma(a, st) : launch_decode_generic(a, st);
+}
+
+extern "C" int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                                        int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                        float softmax_scale, uint16_t* out, float* out_f32, void* workspace,
+                                        size_t workspace_bytes, uint32_t flags, void* hip_stream,
+                                        void* ev_kernel_start, void* ev_kernel_stop) {
+  return decode_impl(fmt, cache, q, q_heads, seq_lens, max_seq_len, nullptr, softmax_scale, out, out_f32,
+                     workspace, workspace_bytes, flags, hip_stream, ev_kernel_start, ev_kernel_stop);
+}
+
+extern "C" int32_t dq_attn_decode_tail(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                                       int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                       const dq_tail* tail, float softmax_scale, uint16_t* out,
+                                       float* out_f32, void* workspace, size_t workspace_bytes,
+                                       uint32_t flags, void* hip_stream) {
+  return decode_impl(fmt, cache, q, q_heads, seq_lens, max_seq_len, tail, softmax_scale, out, out_f32,
+                     workspace, workspace_bytes, flags, hip_stream, nullptr, nullptr);
 }
 
 extern "C" int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,

@@ -166,7 +166,7 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
     }
     __syncthreads();
   }
-  float* part = a.partials + ((long)bhq * a.n_split + split) * (d + 2);
+  float* part = a.partials + ((long)bhq * a.n_slots + split) * (d + 2);
   if (tid < d) part[tid] = acc;
   if (tid == 0) { part[d] = m_run; part[d + 1] = l_run; }
 }
@@ -194,13 +194,74 @@ __global__ void combine_kernel(const float* __restrict__ partials, int n_split, 
 
 int32_t launch_combine(const DecodeArgs& a, hipStream_t st) {
   const int d = a.fmt.head_dim;
-  hipLaunchKernelGGL(combine_kernel, dim3(a.cache.batch * a.q_heads), dim3(d), 0, st, a.partials, a.n_split, d,
+  hipLaunchKernelGGL(combine_kernel, dim3(a.cache.batch * a.q_heads), dim3(d), 0, st, a.partials, a.n_slots, d,
                      a.out, a.out_f32);
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
 }
 
+// The fp16 tail (tokens not yet compressed, Section 3.2) as one more partial result: plain fp32
+// attention of one query head over at most 256 rows.  m_unit converts the running maximum from
+// log2 units to the unit the merging kernel expects (1 for log2, ln 2 for natural logarithms).
+__global__ __launch_bounds__(256) void tail_partial_kernel(DecodeArgs a, float m_unit) {
+  const int d = a.fmt.head_dim;
+  const int bhq = blockIdx.x;
+  const int b = bhq / a.q_heads, hq = bhq % a.q_heads;
+  const int h = hq / (a.q_heads / a.cache.kv_heads);
+  const int tid = threadIdx.x;
+  const int cap = a.tail.capacity;
+  const int n_tail = min(max(a.tail.tail_lens[b], 0), cap);
+  __shared__ float qs[128];
+  __shared__ float ps[256];
+  __shared__ float red[8];
+  const uint16_t* kt = a.tail.k_tail + ((long)b * a.cache.kv_heads + h) * cap * d;
+  const uint16_t* vt = a.tail.v_tail + ((long)b * a.cache.kv_heads + h) * cap * d;
+  if (tid < d) qs[tid] = h2f(a.q[(long)bhq * d + tid]) * (a.scale * 1.4426950408889634f);
+  __syncthreads();
+  float s = -INFINITY;
+  if (tid < n_tail) {
+    float acc = 0.f;
+    for (int c = 0; c < d; c += 2) {
+      const uint32_t w = *reinterpret_cast<const uint32_t*>(kt + (long)tid * d + c);
+      acc = fmaf(h2f((uint16_t)(w & 0xFFFFu)), qs[c], acc);
+      acc = fmaf(h2f((uint16_t)(w >> 16)), qs[c + 1], acc);
+    }
+    s = acc;
+  }
+  float v = s;
+  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+  if ((tid & 63) == 0) red[tid >> 6] = v;
+  __syncthreads();
+  const float m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+  const float p = (tid < n_tail) ? exp2f(s - m) : 0.f;
+  ps[tid] = p;
+  float l = p;
+  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
+  if ((tid & 63) == 0) red[4 + (tid >> 6)] = l;
+  __syncthreads();
+  float* part = a.partials + ((long)bhq * a.n_slots + a.n_split) * (d + 2);
+  if (tid < d) {
+    float o = 0.f;
+    for (int t = 0; t < n_tail; ++t) o = fmaf(ps[t], h2f(vt[(long)t * d + tid]), o);
+    part[tid] = o;
+  }
+  if (tid == 0) {
+    part[d] = (n_tail > 0) ? m * m_unit : -INFINITY;
+    part[d + 1] = red[4] + red[5] + red[6] + red[7];
+  }
+}
+
+int32_t launch_tail_partial(const DecodeArgs& a, float m_unit, hipStream_t st) {
+  hipLaunchKernelGGL(tail_partial_kernel, dim3(a.cache.batch * a.q_heads), dim3(256), 0, st, a, m_unit);
+  DQ_HIP_CHECK(hipGetLastError());
+  return DQ_OK;
+}
+
 int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st) {
+  if (a.tail.k_tail) {   // the tail's partial is in natural-log units like this path's
+    const int32_t rc = launch_tail_partial(a, 0.6931471805599453f, st);
+    if (rc != DQ_OK) return rc;
+  }
   const dim3 grid(a.n_split, a.cache.batch * a.q_heads);
   // the events, when given, receive the streaming kernel's own begin and end timestamps
   switch (a.fmt.bits) {

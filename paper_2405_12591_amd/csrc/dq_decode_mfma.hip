@@ -489,13 +489,22 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
     if (a.n_split == 1) {   // this workgroup saw the whole sequence: finish here
+      if (a.tail.k_tail) {  // fold in the fp16 tail's partial (written by the kernel launched before this one)
+        const float* tp = a.partials + ((bhq0 + hd) * a.n_slots + 1) * (D + 2);
+        const float mt = tp[D];
+        const float Mn = fmaxf(M, mt);
+        const float w0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
+        const float w1 = (mt == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mt - Mn);
+        o = o * w0 + tp[c] * w1;
+        L = L * w0 + tp[D + 1] * w1;
+      }
       const float r = (L > 0.f) ? o / L : 0.f;
       a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
       if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
     } else {
       // device-scope stores: they go through to memory, past the per-XCD L2, so that a workgroup
       // on another XCD can read them without any cache write-back or invalidation
-      float* part = a.partials + ((bhq0 + hd) * a.n_split + split) * (D + 2);
+      float* part = a.partials + ((bhq0 + hd) * a.n_slots + split) * (D + 2);
       __hip_atomic_store(part + c, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (c == 0) {
         __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // M in log2 units
@@ -520,12 +529,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   if (!s_last) return;
   for (int idx = tid; idx < R * D; idx += 64 * NW) {
     const int hd = idx / D, c = idx % D;
-    const float* base = a.partials + (bhq0 + hd) * a.n_split * (D + 2);
+    const float* base = a.partials + (bhq0 + hd) * a.n_slots * (D + 2);   // the tail's slot included
     float M = -INFINITY;
-    for (int sp = 0; sp < a.n_split; ++sp)
+    for (int sp = 0; sp < a.n_slots; ++sp)
       M = fmaxf(M, __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
     float o = 0.f, L = 0.f;
-    for (int sp = 0; sp < a.n_split; ++sp) {
+    for (int sp = 0; sp < a.n_slots; ++sp) {
       const float m = __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (m == -INFINITY) continue;
       const float wgt = __builtin_amdgcn_exp2f(m - M);
@@ -559,6 +568,10 @@ static void launch_r(const DecodeArgs& a, hipStream_t st) {
 
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
   const int rep = a.q_heads / a.cache.kv_heads;
+  if (a.tail.k_tail) {   // the tail's partial, with its maximum in log2 units like this path's
+    const int32_t rc = launch_tail_partial(a, 1.0f, st);
+    if (rc != DQ_OK) return rc;
+  }
   if (a.fmt.bits == 4) {
     switch (rep) {
       case 1: launch_r<4, 1>(a, st); break;

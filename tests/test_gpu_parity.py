@@ -373,3 +373,46 @@ def test_decode_under_graph_capture_replays_identically():
         for b, h in real:
             assert torch.equal(out[b, h], eager[b, h]), (rep, b, h)
         del scratch
+
+
+# ------------------------------------------------------------------------------------------
+# fp16 residual tail: tokens generated since the last compression (Section 3.2)
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("name,kw,lens,tail_lens,flags", [
+    ("llama7b_4bit", dict(batch=4, q_heads=4, kv_heads=4, max_seq=1024, min_seq=1024), [1024, 0, 384, 128], [5, 128, 0, 77], 0),
+    ("llama7b_4bit", dict(batch=4, q_heads=4, kv_heads=4, max_seq=1024, min_seq=1024), [1024, 0, 384, 128], [5, 128, 0, 77], 1),
+    ("gqa_long", dict(batch=2, q_heads=8, kv_heads=2, max_seq=8192, min_seq=8192), [8192, 4096], [100, 1], 0),
+    ("llama7b_2bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=640, min_seq=640), [640, 256], [64, 127], 0),
+    ("tiny", dict(), [256], [200], 0),
+])
+def test_decode_with_fp16_tail(name, kw, lens, tail_lens, flags):
+    w = _small(name, **kw)
+    fmt, ofmt = formats(w)
+    lens = np.asarray(lens, np.int32)
+    tl = np.asarray(tail_lens, np.int32)
+    cap = int(min(w.block_tokens, 256))
+    _say("decode with tail %s lens=%s tail=%s flags=%d" % (name, list(lens), list(tl), flags))
+    pairs = [(b, h) for b in range(w.batch) for h in range(w.kv_heads)]
+    cache = oracle_cache_for_pairs(w, ofmt, pairs, lens)
+    r = np.random.default_rng(5)
+    kt = (r.standard_normal((w.batch, w.kv_heads, cap, w.head_dim)) * 2).astype(np.float16)
+    vt = (r.standard_normal((w.batch, w.kv_heads, cap, w.head_dim)) * 2).astype(np.float16)
+    for b in range(w.batch):            # rows beyond the tail length may hold anything
+        kt[b, :, tl[b]:] = np.float16(np.nan)
+        vt[b, :, tl[b]:] = np.float16(np.inf)
+    q = workloads.query(w)
+    want = O.attention_decode(cache, ofmt, q, lens, k_tail=kt, v_tail=vt, tail_lens=tl)
+    dcache = dq.cache_from_numpy(fmt, cache, DEV)
+    ws = dq.decode_workspace(fmt, w.batch, w.q_heads, w.kv_heads, int(w.max_seq), DEV)
+    qd, ld = torch.from_numpy(q).to(DEV), torch.from_numpy(lens).to(DEV)
+    tail = (torch.from_numpy(kt).to(DEV), torch.from_numpy(vt).to(DEV), torch.from_numpy(tl).to(DEV))
+    o32 = torch.empty((w.batch, w.q_heads, w.head_dim), dtype=torch.float32, device=DEV)
+    out = dq.attn_decode(dcache, qd, ld, int(w.max_seq), ws, out_f32=o32, flags=flags, tail=tail)
+    # the same workspace then serves a call without tail
+    out_plain = dq.attn_decode(dcache, qd, ld, int(w.max_seq), ws, flags=flags)
+    torch.cuda.synchronize()
+    got16, got32 = out.cpu().numpy().astype(np.float64), o32.cpu().numpy().astype(np.float64)
+    assert (np.abs(got16 - want) <= tolerance(want)).all(), np.abs(got16 - want).max()
+    assert (np.abs(got32 - want) <= np.maximum(2e-3, 1e-4 * np.abs(want))).all(), np.abs(got32 - want).max()
+    want_plain = O.attention_decode(cache, ofmt, q, lens)
+    assert (np.abs(out_plain.cpu().numpy().astype(np.float64) - want_plain) <= tolerance(want_plain)).all()
