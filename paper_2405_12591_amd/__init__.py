@@ -7,6 +7,7 @@ from .binding import (  # noqa: F401
     DQError,
     Format,
     Cache,
+    KVCacheLayer,
     DECODE_AUTO,
     DECODE_FORCE_GENERIC,
     DECODE_FORCE_MFMA,

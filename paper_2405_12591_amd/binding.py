@@ -284,3 +284,62 @@ def stream_read(src: torch.Tensor, sink: torch.Tensor) -> None:
 def decode_mfma_supported(fmt: Format, q_heads: int, kv_heads: int) -> bool:
     cf = fmt.c()
     return bool(lib.dq_decode_mfma_supported(C.byref(cf), q_heads, kv_heads))
+
+
+class KVCacheLayer:
+    """One layer's KV cache under the paper's policy (Section 3.2): new key/value rows go to an
+    fp16 tail; whenever a sequence's tail holds a whole block it is compressed into the next block
+    slot; decode attends to the compressed blocks and the tail.  Host bookkeeping only: the
+    compression and the attention run in the library's kernels."""
+
+    def __init__(self, fmt: Format, batch: int, q_heads: int, kv_heads: int, max_tokens: int, device="cuda:0"):
+        self.fmt, self.batch, self.q_heads, self.kv_heads, self.device = fmt, batch, q_heads, kv_heads, device
+        tb = fmt.block_tokens
+        self.capacity_blocks = -(-max_tokens // tb)
+        self.cache = alloc_cache(fmt, batch, kv_heads, self.capacity_blocks, device)
+        self.k_tail = torch.zeros((batch, kv_heads, tb, fmt.head_dim), dtype=torch.float16, device=device)
+        self.v_tail = torch.zeros_like(self.k_tail)
+        self.n_blocks = [0] * batch          # compressed blocks per sequence (host mirror)
+        self.n_tail = [0] * batch            # tail rows per sequence (host mirror)
+        self.seq_lens = torch.zeros(batch, dtype=torch.int32, device=device)
+        self.tail_lens = torch.zeros(batch, dtype=torch.int32, device=device)
+        self.ws_decode = decode_workspace(fmt, batch, q_heads, kv_heads, self.capacity_blocks * tb, device)
+        self.ws_compress = compress_workspace(fmt, batch, kv_heads, device)
+
+    def append(self, k_new: torch.Tensor, v_new: torch.Tensor, counts=None) -> None:
+        """Append rows k_new, v_new [B, H_kv, n, d]; sequence b takes the first counts[b] rows
+        (default: all n).  Full tails are compressed on the way."""
+        tb = self.fmt.block_tokens
+        n = k_new.shape[2]
+        counts = [n] * self.batch if counts is None else list(counts)
+        done = [0] * self.batch
+        while any(done[b] < counts[b] for b in range(self.batch)):
+            for b in range(self.batch):
+                take = min(counts[b] - done[b], tb - self.n_tail[b])
+                if take > 0:
+                    self.k_tail[b, :, self.n_tail[b]:self.n_tail[b] + take] = k_new[b, :, done[b]:done[b] + take]
+                    self.v_tail[b, :, self.n_tail[b]:self.n_tail[b] + take] = v_new[b, :, done[b]:done[b] + take]
+                    self.n_tail[b] += take
+                    done[b] += take
+            full = [b for b in range(self.batch) if self.n_tail[b] == tb]
+            if full:
+                self._compress(full)
+        self.tail_lens.copy_(torch.tensor(self.n_tail, dtype=torch.int32))
+
+    def _compress(self, seqs) -> None:
+        idx = [-1] * self.batch
+        for b in seqs:
+            if self.n_blocks[b] >= self.capacity_blocks:
+                raise DQError("sequence %d exceeds the cache capacity" % b)
+            idx[b] = self.n_blocks[b]
+        blk_idx = torch.tensor(idx, dtype=torch.int32, device=self.device)
+        compress_kv(self.cache, self.k_tail, self.v_tail, blk_idx, None, self.ws_compress)
+        for b in seqs:
+            self.n_blocks[b] += 1
+            self.n_tail[b] = 0
+        self.seq_lens.copy_(torch.tensor([nb * self.fmt.block_tokens for nb in self.n_blocks], dtype=torch.int32))
+
+    def decode(self, q: torch.Tensor, out: Optional[torch.Tensor] = None, flags: int = DECODE_AUTO) -> torch.Tensor:
+        max_seq = max(self.n_blocks) * self.fmt.block_tokens
+        return attn_decode(self.cache, q, self.seq_lens, max_seq, self.ws_decode, out=out, flags=flags,
+                           tail=(self.k_tail, self.v_tail, self.tail_lens))

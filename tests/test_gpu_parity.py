@@ -416,3 +416,45 @@ def test_decode_with_fp16_tail(name, kw, lens, tail_lens, flags):
     assert (np.abs(got32 - want) <= np.maximum(2e-3, 1e-4 * np.abs(want))).all(), np.abs(got32 - want).max()
     want_plain = O.attention_decode(cache, ofmt, q, lens)
     assert (np.abs(out_plain.cpu().numpy().astype(np.float64) - want_plain) <= tolerance(want_plain)).all()
+
+
+def test_kv_cache_layer_policy_prefill_then_decode_steps():
+    """Section 3.2 end to end: a ragged prefill goes through the tail, whole blocks are compressed
+    as they fill, then single tokens are appended step by step and every decode attends to blocks +
+    tail.  Checked against the oracle reading the GPU's own compressed arrays."""
+    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=400, min_seq=400)
+    fmt, ofmt = formats(w)
+    _say("KVCacheLayer policy")
+    layer = dq.KVCacheLayer(fmt, w.batch, w.q_heads, w.kv_heads, 512, DEV)
+    k, v = workloads.kv_tensor(w)                      # [2, 2, 400, 128]
+    kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
+    prefill = [300, 130]
+    layer.append(kd[:, :, :300].contiguous(), vd[:, :, :300].contiguous(), counts=prefill)
+    assert layer.n_blocks == [2, 1] and layer.n_tail == [44, 2]
+    q = workloads.query(w)
+    qd = torch.from_numpy(q).to(DEV)
+    pos = list(prefill)
+    for step in range(90):                             # sequence 0 crosses a block boundary at 384
+        rows_k = torch.stack([kd[b, :, pos[b]:pos[b] + 1] for b in range(w.batch)])
+        rows_v = torch.stack([vd[b, :, pos[b]:pos[b] + 1] for b in range(w.batch)])
+        layer.append(rows_k.contiguous(), rows_v.contiguous())
+        pos = [p + 1 for p in pos]
+        if step in (0, 83, 84, 89):
+            out = layer.decode(qd)
+            torch.cuda.synchronize()
+            arrs = {n: t.cpu().numpy() for n, t in layer.cache.t.items()}
+            lens = np.array([nb * 128 for nb in layer.n_blocks], np.int32)
+            want = O.attention_decode(arrs, ofmt, q, lens, k_tail=layer.k_tail.cpu().numpy(),
+                                      v_tail=layer.v_tail.cpu().numpy(), tail_lens=np.array(layer.n_tail, np.int32))
+            got = out.cpu().numpy().astype(np.float64)
+            assert (np.abs(got - want) <= tolerance(want)).all(), (step, np.abs(got - want).max())
+            # and the blocks hold the right rows: they reconstruct the original K, V to 4-bit accuracy
+            for b in range(w.batch):
+                for h in range(w.kv_heads):
+                    k_hat, v_hat = O.reconstruct_sequence(arrs, ofmt, b, h, int(lens[b]))
+                    for x_hat, x in ((k_hat, k[b, h, :lens[b]]), (v_hat, v[b, h, :lens[b]])):
+                        x = x.astype(np.float64)
+                        assert np.linalg.norm(x_hat - x) < 0.2 * np.linalg.norm(x)
+                    nt = layer.n_tail[b]
+                    assert np.array_equal(layer.k_tail[b, h, :nt].cpu().numpy(), k[b, h, lens[b]:lens[b] + nt])
+    assert layer.n_blocks == [3, 1] and layer.n_tail == [6, 92]
