@@ -220,6 +220,17 @@ def dequantize(codes: np.ndarray, steps: np.ndarray, group: int) -> np.ndarray:
     return np.repeat(steps.astype(np.float64), group, axis=1) * codes.astype(np.float64)
 
 
+def rtn_whole_matrix(w: np.ndarray, bits: int) -> np.ndarray:
+    """Eq. 1 as printed, one step for the whole matrix: returns the dequantized matrix
+    Delta * round(W / Delta), Delta = max|W| / (2^(bits-1) - 1), in fp64 (no fp16 step here)."""
+    qmax = (1 << (bits - 1)) - 1
+    a = np.abs(w).max()
+    if a == 0:
+        return np.zeros_like(w, dtype=np.float64)
+    delta = a / qmax
+    return delta * np.clip(np.rint(w / delta), -qmax, qmax)
+
+
 # --------------------------------------------------------------------------------------
 # Bit packing of codes (storage format)
 # --------------------------------------------------------------------------------------
