@@ -6,6 +6,8 @@
 // `quantize_tiles_kernel` turns fp32 rows into packed codes and fp16 steps.
 #include "dq_common.h"
 
+#include <stdlib.h>
+
 namespace dq {
 
 // ------------------------------------------------------------------------------------------
@@ -351,6 +353,227 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Fast decomposition for the common shape d = 128, j1 = 16, j2 = 8: one wave per block, the two
+// dense contractions (Gram matrix, projection) on the fp64 matrix cores, the Jacobi solver with the
+// 16 x 16 matrices cut into 64 blocks of 2 x 2, one per lane.
+//
+// v_mfma_f64_16x16x4_f64 operand layout (one double per lane for A and B, four for D):
+//   A[m][k]: lane l -> m = l % 16, k = l / 16;  B[k][n]: lane l -> n = l % 16, k = l / 16;
+//   D[m][n]: lane l, register i -> n = l % 16, m = l / 16 + 4 i.
+// ------------------------------------------------------------------------------------------
+typedef double f64x4 __attribute__((ext_vector_type(4)));
+typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
+typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
+
+// Rotation (c, s) that annihilates entry (p, q) of a symmetric matrix, and the squared size of
+// that entry relative to its diagonal pair.  The angle comes from the hardware estimates alone
+// (relative error near 1e-7: the entry shrinks by that factor instead of vanishing, which does not
+// slow the quadratic convergence); c is refined to full precision so that c^2 + s^2 = 1 and the
+// accumulated rotations stay orthogonal.
+__device__ __forceinline__ void jacobi_rotation(double app, double aqq, double apq, double& c, double& s,
+                                                double& rel2) {
+  c = 1.0; s = 0.0; rel2 = 0.0;
+  // skip entries that are already negligible against the diagonal (also keeps tau finite)
+  if (fabs(apq) > 1e-300 && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq))) {
+    const double tau = (aqq - app) * 0.5 * __builtin_amdgcn_rcp(apq);
+    const double root = __builtin_amdgcn_sqrt(fma(tau, tau, 1.0));
+    const double t = copysign(__builtin_amdgcn_rcp(fabs(tau) + root), tau);
+    c = fast_rsqrt(fma(t, t, 1.0));
+    s = t * c;
+    rel2 = apq * apq * __builtin_amdgcn_rcp(fabs(app * aqq) + 1e-300);
+  }
+}
+
+// Pair `k` (0..7) of round `round` (0..14) of the round-robin schedule over 16 indices.
+__device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
+  if (k == 0) { p = 15; q = round; return; }
+  p = round + k; if (p >= 15) p -= 15;
+  q = round - k; if (q < 0) q += 15;
+}
+
+__global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache cache,
+                                                         const uint16_t* __restrict__ k_new,
+                                                         const uint16_t* __restrict__ v_new, int t_new,
+                                                         const int32_t* __restrict__ blk_idx,
+                                                         const int32_t* __restrict__ n_valid,
+                                                         float* __restrict__ large_ws,
+                                                         int32_t* __restrict__ status) {
+  const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
+  const int unit = blockIdx.x;  // (b*H + h)*2 + which
+  const int which = unit & 1;
+  const int bh = unit >> 1;
+  const int b = bh / g.H;
+  const int slot = blk_idx[b];
+  if (slot < 0 || slot >= g.NB) return;
+  int nv = t_new;
+  if (n_valid) nv = min(max(n_valid[b], 0), t_new);
+  const int l = threadIdx.x;
+  constexpr int j1 = 16, j2 = 8, d = 128, ld = 17;
+  const uint16_t* X = (which ? v_new : k_new) + (long)bh * t_new * d;  // [t_new, d] fp16 bits
+
+  __shared__ double A[j1 * ld], V[j1 * ld], W[j1 * ld];
+  __shared__ double lam[j1], sigma[j1], offs[8];
+  __shared__ int order[j1];
+
+  // ---- Gram matrix G[p][q] = sum_{t, b2} X[t, p*8+b2] X[t, q*8+b2] ----
+  // A and B operand of one MFMA are the same register: lane (b1 = l%16, k = l/16) holds
+  // X[t0 + k][b1*8 + b2] for the 4 tokens of a group and one b2.  A lane loads the 8 b2 of its
+  // (token, b1) as one 16-byte chunk; 16 lanes cover a 256-byte row.
+  {
+    const int b1 = l & 15, tk = l >> 4;
+    f64x4 acc[4];
+#pragma unroll
+    for (int i = 0; i < 4; ++i) acc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
+    for (int t0 = 0; t0 < nv; t0 += 128) {
+      u32x4 x[32];
+#pragma unroll
+      for (int u = 0; u < 32; ++u) {
+        const int t = t0 + 4 * u + tk;
+        x[u] = u32x4{0u, 0u, 0u, 0u};
+        if (t < nv) x[u] = *reinterpret_cast<const u32x4*>(X + (long)t * d + b1 * 8);
+      }
+#pragma unroll
+      for (int u = 0; u < 32; ++u) {
+        const f16x8 h = __builtin_bit_cast(f16x8, x[u]);
+#pragma unroll
+        for (int b2 = 0; b2 < 8; ++b2) {
+          const double a = (double)(float)h[b2];
+          acc[b2 & 3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, a, acc[b2 & 3], 0, 0, 0);
+        }
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      const double gsum = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
+      A[((l >> 4) + 4 * i) * ld + (l & 15)] = gsum;
+    }
+    for (int idx = l; idx < j1 * j1; idx += 64) V[(idx >> 4) * ld + (idx & 15)] = ((idx >> 4) == (idx & 15)) ? 1.0 : 0.0;
+  }
+  __syncthreads();
+
+  // ---- parallel cyclic Jacobi: 15 rounds of 8 disjoint rotations per sweep ----
+  // Lane (I, J) owns the 2 x 2 block rows(pair I) x columns(pair J) of the matrix and rows
+  // {2I, 2I+1} x columns(pair J) of the accumulated rotations; it derives both rotations itself
+  // from the three entries of each pair, so a round is: read, rotate, write.
+  const int I = l >> 3, J = l & 7;
+  int sweeps = 0;
+  for (int sweep = 0; sweep < 16; ++sweep) {
+    ++sweeps;
+    double offmax = 0.0;
+    for (int round = 0; round < 15; ++round) {
+      int p, q, u, v;
+      pair16(round, I, p, q);
+      pair16(round, J, u, v);
+      const double app = A[p * ld + p], aqq = A[q * ld + q], apq = A[p * ld + q];
+      const double auu = A[u * ld + u], avv = A[v * ld + v], auv = A[u * ld + v];
+      const double b00 = A[p * ld + u], b01 = A[p * ld + v], b10 = A[q * ld + u], b11 = A[q * ld + v];
+      const int r0 = 2 * I * ld, r1 = r0 + ld;
+      const double v00 = V[r0 + u], v01 = V[r0 + v], v10 = V[r1 + u], v11 = V[r1 + v];
+      double cI, sI, relI, cJ, sJ, relJ;
+      jacobi_rotation(app, aqq, apq, cI, sI, relI);
+      jacobi_rotation(auu, avv, auv, cJ, sJ, relJ);
+      offmax = fmax(offmax, relI);
+      // Jm has Jm[p][p] = c, Jm[p][q] = s, Jm[q][p] = -s, Jm[q][q] = c;  A' = Jm^T A Jm,  V' = V Jm
+      const double x00 = b00 * cJ - b01 * sJ, x01 = b00 * sJ + b01 * cJ;
+      const double x10 = b10 * cJ - b11 * sJ, x11 = b10 * sJ + b11 * cJ;
+      A[p * ld + u] = cI * x00 - sI * x10;
+      A[p * ld + v] = cI * x01 - sI * x11;
+      A[q * ld + u] = sI * x00 + cI * x10;
+      A[q * ld + v] = sI * x01 + cI * x11;
+      V[r0 + u] = v00 * cJ - v01 * sJ;
+      V[r0 + v] = v00 * sJ + v01 * cJ;
+      V[r1 + u] = v10 * cJ - v11 * sJ;
+      V[r1 + v] = v10 * sJ + v11 * cJ;
+      __syncthreads();
+    }
+    if (J == 0) offs[I] = offmax;
+    __syncthreads();
+    double om = 0.0;
+#pragma unroll
+    for (int i = 0; i < 8; ++i) om = fmax(om, offs[i]);
+    __syncthreads();
+    // every entry rotated in this sweep was below 1e-9 of its diagonal pair: one more quadratic
+    // step has taken them below 1e-16
+    if (om < 1e-18) break;
+  }
+
+  // ---- singular values, ordering, small tensor ----
+  if (l < j1) lam[l] = A[l * ld + l];
+  __syncthreads();
+  if (l < j1) {
+    int rank = 0;
+    const double me = lam[l];
+    for (int s = 0; s < j1; ++s) rank += (lam[s] > me) || (lam[s] == me && s < l);
+    order[rank] = l;
+  }
+  __syncthreads();
+  if (l < j1) {
+    const double lmax = fmax(lam[order[0]], 0.0);
+    const double lv = lam[order[l]];
+    sigma[l] = (lv > 1e-12 * lmax && lv > 0.0) ? sqrt(lv) : 0.0;
+  }
+  __syncthreads();
+  {
+    const long blk = (long)bh * g.NB + slot;
+    uint16_t* small = (which ? cache.v_small : cache.k_small) + blk * g.small_per_block;
+    bool sat = false;
+    for (int idx = l; idx < j1 * j1; idx += 64) {
+      const int b1 = idx >> 4, r = idx & 15;
+      const double uv = V[b1 * ld + order[r]];
+      const double sg = sigma[r];
+      W[r * ld + b1] = sg > 0.0 ? uv / sg : 0.0;
+      const uint16_t hb = f64_to_f16_rne(uv * sg, true, &sat);
+      if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
+      else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
+    }
+    if (sat) atomicOr(status, 1);
+    if (l == 0) atomicMax(status + 1, sweeps);   // diagnostic: most Jacobi sweeps any block needed
+  }
+  __syncthreads();
+
+  // ---- projection: K'[t, r*8+b2] = sum_b1 W[r][b1] X[t, b1*8+b2], fp64 -> fp32 ----
+  // One MFMA chain per b2: rows r, columns 16 tokens, contraction over b1 in 4 steps of 4.
+  {
+    double wreg[4];
+#pragma unroll
+    for (int s = 0; s < 4; ++s) wreg[s] = W[(l & 15) * ld + 4 * s + (l >> 4)];
+    float* out = large_ws + (long)unit * g.Tb * d;
+    for (int t0 = 0; t0 < g.Tb; t0 += 128) {
+      u32x4 x[8][4];
+#pragma unroll
+      for (int tg = 0; tg < 8; ++tg) {
+        const int t = t0 + 16 * tg + (l & 15);
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          x[tg][s] = u32x4{0u, 0u, 0u, 0u};
+          if (t < nv) x[tg][s] = *reinterpret_cast<const u32x4*>(X + (long)t * d + (4 * s + (l >> 4)) * 8);
+        }
+      }
+#pragma unroll
+      for (int tg = 0; tg < 8; ++tg) {
+        const int t = t0 + 16 * tg + (l & 15);
+        f64x4 acc[8];
+#pragma unroll
+        for (int b2 = 0; b2 < 8; ++b2) acc[b2] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const f16x8 h = __builtin_bit_cast(f16x8, x[tg][s]);
+#pragma unroll
+          for (int b2 = 0; b2 < 8; ++b2)
+            acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64(wreg[s], (double)(float)h[b2], acc[b2], 0, 0, 0);
+        }
+#pragma unroll
+        for (int i = 0; i < 4; ++i) {
+          float* dst = out + (long)t * d + ((l >> 4) + 4 * i) * 8;
+          *reinterpret_cast<float4*>(dst) = make_float4((float)acc[0][i], (float)acc[1][i], (float)acc[2][i], (float)acc[3][i]);
+          *reinterpret_cast<float4*>(dst + 4) = make_float4((float)acc[4][i], (float)acc[5][i], (float)acc[6][i], (float)acc[7][i]);
+        }
+      }
+    }
+  }
+}
+
 __global__ void clear_status_kernel(int32_t* status) {
   if (threadIdx.x < 2) status[threadIdx.x] = 0;
 }
@@ -408,7 +631,11 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
 #define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                   \
   hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, k_new, \
                      v_new, t_new, blk_idx, n_valid, large_ws, status)
-  if (fmt->head_dim == 128) {
+  static const bool force_general = getenv("DQ_COMPRESS_GENERAL") != nullptr;   // for A/B timing
+  if (fmt->head_dim == 128 && fmt->j1 == 16 && !force_general) {
+    hipLaunchKernelGGL(decompose16_kernel, dim3(units), dim3(64), 0, st, *fmt, *cache, k_new, v_new, t_new,
+                       blk_idx, n_valid, large_ws, status);
+  } else if (fmt->head_dim == 128) {
     if (fmt->j1 == 8) DQ_LAUNCH_DECOMPOSE(8, 128);
     else if (fmt->j1 == 16) DQ_LAUNCH_DECOMPOSE(16, 128);
     else DQ_LAUNCH_DECOMPOSE(32, 128);
