@@ -13,61 +13,77 @@ namespace dq {
 // ------------------------------------------------------------------------------------------
 // Quantize + pack one tile of 128 token rows (Eq. 1 per group).  256 threads.
 // ------------------------------------------------------------------------------------------
-template <int BITS>
-__device__ void quantize_tile(const float* __restrict__ src,  // [128, d] fp32
-                              int d, int G, int j1, int j2, int value_layout,
+
+// Step of a group: fp16(amax / qmax), the exact quotient rounded once (nearest, ties to even).
+// The quotient is first rounded to odd in fp32 (13 more bits than fp16), which makes the second
+// rounding to fp16 land where a single rounding of the exact quotient would.
+template <int QMAX>
+__device__ __forceinline__ uint16_t group_step_bits(float amax) {
+  if (QMAX == 1) return f2h_rne(amax);
+  const float q = amax / (float)QMAX;                  // correctly rounded fp32 division
+  const float e = fmaf(-(float)QMAX, q, amax);         // sign of (exact quotient - q); 0 iff q is exact
+  uint32_t bits = __builtin_bit_cast(uint32_t, q);
+  if (e > 0.f) bits |= 1u;                             // exact lies above q: odd end of [q, next]
+  else if (e < 0.f) bits -= (bits & 1u) ? 0u : 1u;     // exact lies below q: odd end of [prev, q]
+  return f2h_rne(__builtin_bit_cast(float, bits));
+}
+
+// Code of one element: nearest integer of the exact x / step, ties to even, clamped.  The candidate
+// from an fp32 product with the reciprocal estimate is within one of the answer; the residual
+// x - c*step is exact in fp64 (24-bit x, 7-bit c, 11-bit step) and settles it, ties included.
+template <int QMAX>
+__device__ __forceinline__ int exact_code(float x, float step, float inv_step, double half_step) {
+  const float c0 = __builtin_rintf(x * inv_step);
+  const double r = fma(-(double)c0, (double)step, (double)x);
+  int c = (int)c0;
+  const bool odd = c & 1;
+  const double ar = fabs(r);
+  const bool move = ar > half_step || (ar == half_step && odd);   // also false when r is NaN (step = inf)
+  c += move ? (r > 0.0 ? 1 : -1) : 0;
+  return min(max(c, -QMAX), QMAX);
+}
+
+template <int BITS, int D>
+__device__ void quantize_tile(const float* __restrict__ src,  // [128, D] fp32
+                              int G, int j1, int j2, int value_layout,
                               uint8_t* __restrict__ codes_out,    // tile's code bytes
-                              uint16_t* __restrict__ scales_out,  // [128, d/G]
-                              uint8_t* __restrict__ lds_u) {      // [128 * d] stored fields
+                              uint16_t* __restrict__ scales_out,  // [128, D/G]
+                              uint8_t* __restrict__ lds_u) {      // [128 * D] stored fields (+ value staging)
   constexpr int QMAX = (1 << (BITS - 1)) - 1;
   constexpr int BIAS = 1 << (BITS - 1);
+  constexpr int d = D;
+  constexpr int LPR = D / 4;                 // lanes per row, 4 elements each: 32 or 16
+  constexpr int ROWS_PER_PASS = 256 / LPR;
+  constexpr int PASSES = kTileTokens / ROWS_PER_PASS;
   const int tid = threadIdx.x;
-  const int row = tid >> 1, half = tid & 1;
-  const int seg = d >> 1;
-  const float* x = src + (long)row * d + half * seg;
+  const int li = tid & (LPR - 1), rp = tid / LPR;
+  const int gl = G >> 2;                     // lanes per group, a power of two
   const int groups = d / G;
 
-  if (G == d) {
-    float amax = 0.f;
-    for (int e = 0; e < seg; e += 4) {
-      const float4 v = *reinterpret_cast<const float4*>(x + e);
-      amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
+  float4 v[PASSES];                          // the whole tile in flight before the first use
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps)
+    v[ps] = *reinterpret_cast<const float4*>(src + (long)(ps * ROWS_PER_PASS + rp) * d + 4 * li);
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps) {
+    const int row = ps * ROWS_PER_PASS + rp;
+    float amax = fmaxf(fmaxf(fabsf(v[ps].x), fabsf(v[ps].y)), fmaxf(fabsf(v[ps].z), fabsf(v[ps].w)));
+#pragma unroll
+    for (int off = LPR / 2; off >= 1; off >>= 1)
+      if (off < gl) amax = fmaxf(amax, __shfl_xor(amax, off));
+    const uint16_t sbits = group_step_bits<QMAX>(amax);
+    const float step = h2f(sbits);
+    if ((li & (gl - 1)) == 0) scales_out[row * groups + li / gl] = sbits;
+    uint32_t fields = 0x01010101u * BIAS;    // step 0: every code 0
+    if (step > 0.f) {
+      const float inv = __builtin_amdgcn_rcpf(step);
+      const double hs = 0.5 * (double)step;
+      const int c0 = exact_code<QMAX>(v[ps].x, step, inv, hs), c1 = exact_code<QMAX>(v[ps].y, step, inv, hs);
+      const int c2 = exact_code<QMAX>(v[ps].z, step, inv, hs), c3 = exact_code<QMAX>(v[ps].w, step, inv, hs);
+      fields = (uint32_t)(c0 + BIAS) | ((uint32_t)(c1 + BIAS) << 8) | ((uint32_t)(c2 + BIAS) << 16) |
+               ((uint32_t)(c3 + BIAS) << 24);
     }
-    amax = fmaxf(amax, __shfl_xor(amax, 1));
-    const uint16_t sbits = f64_to_f16_rne((double)amax / (double)QMAX, false, nullptr);
-    const double step = (double)h2f(sbits);
-    if (half == 0) scales_out[row] = sbits;
-    for (int e = 0; e < seg; ++e) {
-      int c = 0;
-      if (step > 0.0) {
-        double r = __builtin_rint((double)x[e] / step);
-        r = fmin(fmax(r, (double)-QMAX), (double)QMAX);
-        c = (int)r;
-      }
-      lds_u[row * d + half * seg + e] = (uint8_t)(c + BIAS);
-    }
-  } else {
-    const int gps = seg / G;  // groups per half row
-    for (int gi = 0; gi < gps; ++gi) {
-      const float* xg = x + gi * G;
-      float amax = 0.f;
-      for (int e = 0; e < G; e += 4) {
-        const float4 v = *reinterpret_cast<const float4*>(xg + e);
-        amax = fmaxf(amax, fmaxf(fmaxf(fabsf(v.x), fabsf(v.y)), fmaxf(fabsf(v.z), fabsf(v.w))));
-      }
-      const uint16_t sbits = f64_to_f16_rne((double)amax / (double)QMAX, false, nullptr);
-      const double step = (double)h2f(sbits);
-      scales_out[row * groups + half * gps + gi] = sbits;
-      for (int e = 0; e < G; ++e) {
-        int c = 0;
-        if (step > 0.0) {
-          double r = __builtin_rint((double)xg[e] / step);
-          r = fmin(fmax(r, (double)-QMAX), (double)QMAX);
-          c = (int)r;
-        }
-        lds_u[row * d + half * seg + gi * G + e] = (uint8_t)(c + BIAS);
-      }
-    }
+    *reinterpret_cast<uint32_t*>(lds_u + row * d + 4 * li) = fields;
   }
   __syncthreads();
 
@@ -76,46 +92,58 @@ __device__ void quantize_tile(const float* __restrict__ src,  // [128, d] fp32
   uint32_t* out32 = reinterpret_cast<uint32_t*>(codes_out);
   if (!value_layout) {
     // key layout: rows of d elements, element index contiguous
-    for (int w = tid; w < total_words; w += blockDim.x) {
-      const int ebase = w * PER_WORD;
+    for (int w = tid; w < total_words; w += 256) {
+      const uint32_t* f = reinterpret_cast<const uint32_t*>(lds_u + w * PER_WORD);
       uint32_t word = 0;
 #pragma unroll
-      for (int k = 0; k < PER_WORD; ++k) word |= (uint32_t)lds_u[ebase + k] << (k * BITS);
+      for (int k4 = 0; k4 < PER_WORD / 4; ++k4) {
+        const uint32_t x = f[k4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) word |= ((x >> (8 * k)) & 0xFFu) << ((4 * k4 + k) * BITS);
+      }
       out32[w] = word;
     }
   } else {
-    // value layout: [b2][r][128 tokens], tokens contiguous
-    const int words_per_row = kTileTokens / PER_WORD;
-    for (int w = tid; w < total_words; w += blockDim.x) {
-      const int rowid = w / words_per_row;  // b2 * j1 + r
-      const int wi = w % words_per_row;
-      const int b2 = rowid / j1, r = rowid % j1;
-      const int col = r * j2 + b2;
+    // value layout: [b2][r][128 tokens], tokens contiguous.  Consecutive lanes take consecutive
+    // columns (conflict-free byte reads), the words are transposed through a padded LDS buffer and
+    // leave in output order.
+    constexpr int WPR = kTileTokens / PER_WORD;   // words per (b2, r) row
+    uint32_t* stage = reinterpret_cast<uint32_t*>(lds_u + kTileTokens * d);
+    for (int idx = tid; idx < total_words; idx += 256) {
+      const int col = idx % d, wi = idx / d;
+      const int b2 = col % j2, r = col / j2;
       uint32_t word = 0;
 #pragma unroll
       for (int k = 0; k < PER_WORD; ++k)
         word |= (uint32_t)lds_u[(wi * PER_WORD + k) * d + col] << (k * BITS);
-      out32[w] = word;
+      stage[(b2 * j1 + r) * (WPR + 1) + wi] = word;
     }
+    __syncthreads();
+    for (int w = tid; w < total_words; w += 256) out32[w] = stage[(w / WPR) * (WPR + 1) + w % WPR];
   }
   __syncthreads();
 }
 
+// LDS bytes quantize_tile needs: one byte per element plus the padded transpose buffer.
+__host__ __device__ inline size_t quantize_lds_bytes(int d, int bits) {
+  return (size_t)kTileTokens * d + (size_t)d * (kTileTokens * bits / 32 + 1) * sizeof(uint32_t);
+}
+
 // Stand-alone entry: contiguous input rows, contiguous outputs (dq_quantize_pack).
-template <int BITS>
-__global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restrict__ t_large, int d,
-                                                            int G, int j1, int j2, int value_layout,
+template <int BITS, int D>
+__global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restrict__ t_large, int G, int j1,
+                                                            int j2, int value_layout,
                                                             uint8_t* __restrict__ codes,
                                                             uint16_t* __restrict__ scales) {
   extern __shared__ uint8_t lds_u[];
   const long tile = blockIdx.x;
-  const long tile_code_bytes = (long)kTileTokens * d * BITS / 8;
-  quantize_tile<BITS>(t_large + tile * kTileTokens * d, d, G, j1, j2, value_layout,
-                      codes + tile * tile_code_bytes, scales + tile * kTileTokens * (d / G), lds_u);
+  const long tile_code_bytes = (long)kTileTokens * D * BITS / 8;
+  quantize_tile<BITS, D>(t_large + tile * kTileTokens * D, G, j1, j2, value_layout,
+                         codes + tile * tile_code_bytes, scales + tile * kTileTokens * (D / G), lds_u);
 }
 
 // Compress path: tile `blockIdx.x` of block (b, h, which) goes to cache slot blk_idx[b].
-template <int BITS>
+template <int BITS, int D>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __restrict__ large_ws,
                                                              dq_format fmt, dq_cache cache,
                                                              const int32_t* __restrict__ blk_idx) {
@@ -129,12 +157,12 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __rest
   const int slot = blk_idx[b];
   if (slot < 0 || slot >= g.NB) return;
   const long blk = (long)bh * g.NB + slot;
-  const float* src = large_ws + ((long)unit * g.Tb + (long)tile * kTileTokens) * g.d;
+  const float* src = large_ws + ((long)unit * g.Tb + (long)tile * kTileTokens) * D;
   uint8_t* codes = (which ? cache.v_codes : cache.k_codes) + blk * g.codes_per_block +
                    (long)tile * kTileTokens * g.row_bytes;
   uint16_t* scales = (which ? cache.v_scales : cache.k_scales) + blk * g.scales_per_block +
                      (long)tile * kTileTokens * g.groups;
-  quantize_tile<BITS>(src, g.d, g.G, g.j1, g.j2, which, codes, scales, lds_u);
+  quantize_tile<BITS, D>(src, g.G, g.j1, g.j2, which, codes, scales, lds_u);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -373,16 +401,16 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 // accumulated rotations stay orthogonal.
 __device__ __forceinline__ void jacobi_rotation(double app, double aqq, double apq, double& c, double& s,
                                                 double& rel2) {
-  c = 1.0; s = 0.0; rel2 = 0.0;
-  // skip entries that are already negligible against the diagonal (also keeps tau finite)
-  if (fabs(apq) > 1e-300 && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq))) {
-    const double tau = (aqq - app) * 0.5 * __builtin_amdgcn_rcp(apq);
-    const double root = __builtin_amdgcn_sqrt(fma(tau, tau, 1.0));
-    const double t = copysign(__builtin_amdgcn_rcp(fabs(tau) + root), tau);
-    c = fast_rsqrt(fma(t, t, 1.0));
-    s = t * c;
-    rel2 = apq * apq * __builtin_amdgcn_rcp(fabs(app * aqq) + 1e-300);
-  }
+  // entries that are already negligible against the diagonal are skipped (also keeps tau finite);
+  // written without branches so that the two rotations a lane needs interleave
+  const bool live = fabs(apq) > 1e-300 && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq));
+  const double tau = (aqq - app) * 0.5 * __builtin_amdgcn_rcp(apq);
+  const double root = __builtin_amdgcn_sqrt(fma(tau, tau, 1.0));
+  const double t = copysign(__builtin_amdgcn_rcp(fabs(tau) + root), tau);
+  const double cc = fast_rsqrt(fma(t, t, 1.0));
+  c = live ? cc : 1.0;
+  s = live ? t * cc : 0.0;
+  rel2 = live ? apq * apq * __builtin_amdgcn_rcp(fabs(app * aqq) + 1e-300) : 0.0;
 }
 
 // Pair `k` (0..7) of round `round` (0..14) of the round-robin schedule over 16 indices.
@@ -461,6 +489,8 @@ __global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache
   for (int sweep = 0; sweep < 16; ++sweep) {
     ++sweeps;
     double offmax = 0.0;
+    // unrolled: the LDS addresses of a round depend only on the lane and are computed once
+#pragma unroll
     for (int round = 0; round < 15; ++round) {
       int p, q, u, v;
       pair16(round, I, p, q);
@@ -485,7 +515,9 @@ __global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache
       V[r0 + v] = v00 * sJ + v01 * cJ;
       V[r1 + u] = v10 * cJ - v11 * sJ;
       V[r1 + v] = v10 * sJ + v11 * cJ;
-      __syncthreads();
+      // One wave: its LDS operations execute in program order, so the next round's reads see these
+      // writes without waiting for them; the compiler only has to keep the order.
+      __builtin_amdgcn_wave_barrier();
     }
     if (J == 0) offs[I] = offmax;
     __syncthreads();
@@ -599,13 +631,21 @@ extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, 
   if (n_rows == 0) return DQ_OK;
   hipStream_t st = (hipStream_t)hip_stream;
   const int tiles = (int)(n_rows / kTileTokens);
-  const size_t lds = (size_t)kTileTokens * fmt->head_dim;
+  const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
   const int d = fmt->head_dim, G = fmt->group, j1 = fmt->j1, j2 = fmt->j2;
-  switch (fmt->bits) {
-    case 2: hipLaunchKernelGGL(quantize_pack_kernel<2>, dim3(tiles), dim3(256), lds, st, t_large, d, G, j1, j2, value_layout, codes, scales); break;
-    case 4: hipLaunchKernelGGL(quantize_pack_kernel<4>, dim3(tiles), dim3(256), lds, st, t_large, d, G, j1, j2, value_layout, codes, scales); break;
-    default: hipLaunchKernelGGL(quantize_pack_kernel<8>, dim3(tiles), dim3(256), lds, st, t_large, d, G, j1, j2, value_layout, codes, scales); break;
+#define DQ_LAUNCH_QPACK(B_, D_)                                                                          \
+  hipLaunchKernelGGL((quantize_pack_kernel<B_, D_>), dim3(tiles), dim3(256), lds, st, t_large, G, j1, j2, \
+                     value_layout, codes, scales)
+  if (d == 128) {
+    if (fmt->bits == 2) DQ_LAUNCH_QPACK(2, 128);
+    else if (fmt->bits == 4) DQ_LAUNCH_QPACK(4, 128);
+    else DQ_LAUNCH_QPACK(8, 128);
+  } else {
+    if (fmt->bits == 2) DQ_LAUNCH_QPACK(2, 64);
+    else if (fmt->bits == 4) DQ_LAUNCH_QPACK(4, 64);
+    else DQ_LAUNCH_QPACK(8, 64);
   }
+#undef DQ_LAUNCH_QPACK
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
 }
@@ -647,12 +687,20 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
 #undef DQ_LAUNCH_DECOMPOSE
   DQ_HIP_CHECK(hipGetLastError());
   const int tiles = units * (fmt->block_tokens / kTileTokens);
-  const size_t lds = (size_t)kTileTokens * fmt->head_dim;
-  switch (fmt->bits) {
-    case 2: hipLaunchKernelGGL(quantize_tiles_kernel<2>, dim3(tiles), dim3(256), lds, st, large_ws, *fmt, *cache, blk_idx); break;
-    case 4: hipLaunchKernelGGL(quantize_tiles_kernel<4>, dim3(tiles), dim3(256), lds, st, large_ws, *fmt, *cache, blk_idx); break;
-    default: hipLaunchKernelGGL(quantize_tiles_kernel<8>, dim3(tiles), dim3(256), lds, st, large_ws, *fmt, *cache, blk_idx); break;
+  const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
+#define DQ_LAUNCH_QTILES(B_, D_)                                                                       \
+  hipLaunchKernelGGL((quantize_tiles_kernel<B_, D_>), dim3(tiles), dim3(256), lds, st, large_ws, *fmt, \
+                     *cache, blk_idx)
+  if (fmt->head_dim == 128) {
+    if (fmt->bits == 2) DQ_LAUNCH_QTILES(2, 128);
+    else if (fmt->bits == 4) DQ_LAUNCH_QTILES(4, 128);
+    else DQ_LAUNCH_QTILES(8, 128);
+  } else {
+    if (fmt->bits == 2) DQ_LAUNCH_QTILES(2, 64);
+    else if (fmt->bits == 4) DQ_LAUNCH_QTILES(4, 64);
+    else DQ_LAUNCH_QTILES(8, 64);
   }
+#undef DQ_LAUNCH_QTILES
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
 }

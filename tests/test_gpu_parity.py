@@ -38,6 +38,26 @@ def test_quantize_pack_bit_exact(bits, group, d, j1):
     kp[6, 0] = np.float32(0.125 * qmax)
     kp[7, :group] = 1e-7 * r.standard_normal(group)            # subnormal steps
     kp = kp.astype(np.float32)
+    # a step that is not a power of two, with elements on, just above and just below every tie
+    s16 = np.float32(np.float16(0.01234))
+    ties = np.array([(k + 0.5) * float(s16) for k in range(-qmax, qmax)], np.float32)
+    near = np.concatenate([ties, np.nextafter(ties, np.float32(np.inf)), np.nextafter(ties, np.float32(-np.inf))])
+    near = np.resize(near, group).astype(np.float32)
+    near[0] = np.float32(float(s16) * qmax)                     # fixes the group's step at s16
+    kp[8, :group] = near
+    # group maxima whose quotient by qmax sits on, or one and two fp32 steps beside, an fp16 midpoint
+    h = np.float16(0.0371)
+    for i in range(12):
+        lo = np.float16(h) if i < 8 else np.float16(3e-6)       # normal and subnormal fp16 steps
+        mid = (float(lo) + float(np.nextafter(lo, np.float16(np.inf)))) / 2.0
+        a = np.float32(mid * qmax)
+        for _ in range(abs(i % 5 - 2)):
+            a = np.nextafter(a, np.float32(np.inf) if i % 5 > 2 else np.float32(0))
+        row = (0.3 * float(a) * r.standard_normal(group)).astype(np.float32)
+        row = np.clip(row, -float(a), float(a))
+        row[i % group] = a
+        kp[9 + i, :group] = row
+        h = np.nextafter(np.nextafter(h, np.float16(np.inf)), np.float16(np.inf))
     steps = O.group_steps(kp, group, qmax)
     codes = O.quantize_codes(kp, steps, group, qmax)
     want_k = O.pack_rows(codes, bits)
