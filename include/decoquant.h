@@ -168,8 +168,11 @@ size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t 
  * The decomposition is an eigen-decomposition of the fp64 Gram matrix M M^T (j1 x j1) by
  * cyclic Jacobi rotations: T_S = U diag(sigma), T_L = diag(1/sigma) U^T M; directions with
  * sigma <= 1e-6 sigma_max are dropped (T_S column and T_L row zero).  T_S saturates to the
- * fp16 range; bit 0 of the int32 at workspace[0] is set if that happened.  The int32 at
- * workspace[4] receives the largest number of Jacobi sweeps any block needed (diagnostic).
+ * fp16 range; bit 0 of the int32 at workspace[0] is set if that happened in any block of this
+ * call, cleared otherwise.  The int32 at workspace[4] receives the largest number of Jacobi
+ * sweeps any block needed (diagnostic).  Workspace layout: a 256-byte header (those two words),
+ * the fp32 large tensors [B*H*2, T_b, d] in token-major form (readable after the call: K block
+ * of (b, h) at index 2*(b*H+h), V block next), then one status word per block.
  * The factors are not unique (signs, order of equal singular values): only their product and
  * the orthonormality of T_L's rows are defined.
  */

@@ -28,23 +28,30 @@ __device__ __forceinline__ uint16_t group_step_bits(float amax) {
   return f2h_rne(__builtin_bit_cast(float, bits));
 }
 
-// Code of one element: nearest integer of the exact x / step, ties to even, clamped.  The candidate
-// from an fp32 product with the reciprocal estimate is within one of the answer; the residual
-// x - c*step is exact in fp64 (24-bit x, 7-bit c, 11-bit step) and settles it, ties included.
-template <int QMAX>
-__device__ __forceinline__ int exact_code(float x, float step, float inv_step, double half_step) {
-  const float c0 = __builtin_rintf(x * inv_step);
+// Code of one element: nearest integer of the exact x / step, ties to even, clamped.
+// `q` = x * (1/step) from the fp32 reciprocal estimate is within 4e-5 of the exact quotient
+// (|q| <= 128, three roundings of 2^-23), so rint(q) is the answer unless q sits that close to a
+// half-integer.  Only then the exact path runs: the residual x - c*step is exact in fp64 (24-bit x,
+// 7-bit c, 11-bit step) and settles the candidate, ties included.
+constexpr float kNearTie = 0.5f - 0x1p-12f;
+
+// Value of another lane by a fixed data-parallel-primitive pattern (no LDS round trip).
+template <int CTRL>
+__device__ __forceinline__ float lane_exchange(float x) {
+  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, x), CTRL, 0xF, 0xF, true));
+}
+
+__device__ __forceinline__ int settle_code(float x, float c0, float step, double half_step) {
   const double r = fma(-(double)c0, (double)step, (double)x);
   int c = (int)c0;
-  const bool odd = c & 1;
   const double ar = fabs(r);
-  const bool move = ar > half_step || (ar == half_step && odd);   // also false when r is NaN (step = inf)
+  const bool move = (ar > half_step) | ((ar == half_step) & ((c & 1) != 0));   // false when r is NaN (step = inf)
   c += move ? (r > 0.0 ? 1 : -1) : 0;
-  return min(max(c, -QMAX), QMAX);
+  return c;
 }
 
 template <int BITS, int D>
-__device__ void quantize_tile(const float* __restrict__ src,  // [128, D] fp32
+__device__ __forceinline__ void quantize_tile(const float* __restrict__ src,  // [128, D] fp32
                               int G, int j1, int j2, int value_layout,
                               uint8_t* __restrict__ codes_out,    // tile's code bytes
                               uint16_t* __restrict__ scales_out,  // [128, D/G]
@@ -60,30 +67,76 @@ __device__ void quantize_tile(const float* __restrict__ src,  // [128, D] fp32
   const int gl = G >> 2;                     // lanes per group, a power of two
   const int groups = d / G;
 
+  // Straight-line over the passes, stage by stage, so that the 8 or 16 independent rows a thread
+  // handles overlap their latencies (loads, cross-lane steps, the division) instead of queueing.
   float4 v[PASSES];                          // the whole tile in flight before the first use
 #pragma unroll
   for (int ps = 0; ps < PASSES; ++ps)
     v[ps] = *reinterpret_cast<const float4*>(src + (long)(ps * ROWS_PER_PASS + rp) * d + 4 * li);
+  float amax[PASSES];
+#pragma unroll
+  for (int ps = 0; ps < PASSES; ++ps)
+    amax[ps] = fmaxf(fmaxf(fabsf(v[ps].x), fabsf(v[ps].y)), fmaxf(fabsf(v[ps].z), fabsf(v[ps].w)));
+  // group maximum over gl lanes: lane exchanges inside a row of 16 lanes, then across the two rows
+  if (gl > 1) {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0xB1>(amax[ps]));    // i ^ 1
+  }
+  if (gl > 2) {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0x4E>(amax[ps]));    // i ^ 2
+  }
+  if (gl > 4) {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0x141>(amax[ps]));   // 7 - i in 8
+  }
+  if (gl > 8) {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0x140>(amax[ps]));   // 15 - i in 16
+  }
+  if (LPR > 16 && gl > 16) {
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], __shfl_xor(amax[ps], 16));
+  }
+  float step[PASSES], inv[PASSES];
 #pragma unroll
   for (int ps = 0; ps < PASSES; ++ps) {
-    const int row = ps * ROWS_PER_PASS + rp;
-    float amax = fmaxf(fmaxf(fabsf(v[ps].x), fabsf(v[ps].y)), fmaxf(fabsf(v[ps].z), fabsf(v[ps].w)));
+    const uint16_t sbits = group_step_bits<QMAX>(amax[ps]);
+    step[ps] = h2f(sbits);
+    inv[ps] = step[ps] > 0.f ? __builtin_amdgcn_rcpf(step[ps]) : 0.f;   // step 0 (and inf): every code 0
+    if ((li & (gl - 1)) == 0) scales_out[(ps * ROWS_PER_PASS + rp) * groups + li / gl] = sbits;
+  }
+  uint32_t near_mask = 0;
 #pragma unroll
-    for (int off = LPR / 2; off >= 1; off >>= 1)
-      if (off < gl) amax = fmaxf(amax, __shfl_xor(amax, off));
-    const uint16_t sbits = group_step_bits<QMAX>(amax);
-    const float step = h2f(sbits);
-    if ((li & (gl - 1)) == 0) scales_out[row * groups + li / gl] = sbits;
-    uint32_t fields = 0x01010101u * BIAS;    // step 0: every code 0
-    if (step > 0.f) {
-      const float inv = __builtin_amdgcn_rcpf(step);
-      const double hs = 0.5 * (double)step;
-      const int c0 = exact_code<QMAX>(v[ps].x, step, inv, hs), c1 = exact_code<QMAX>(v[ps].y, step, inv, hs);
-      const int c2 = exact_code<QMAX>(v[ps].z, step, inv, hs), c3 = exact_code<QMAX>(v[ps].w, step, inv, hs);
-      fields = (uint32_t)(c0 + BIAS) | ((uint32_t)(c1 + BIAS) << 8) | ((uint32_t)(c2 + BIAS) << 16) |
-               ((uint32_t)(c3 + BIAS) << 24);
+  for (int ps = 0; ps < PASSES; ++ps) {
+    const float xs[4] = {v[ps].x, v[ps].y, v[ps].z, v[ps].w};
+    uint32_t fields = 0;
+    bool near = false;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const float q = xs[e] * inv[ps];
+      const float cf = __builtin_rintf(q);
+      near |= fabsf(q - cf) > kNearTie;
+      fields |= (uint32_t)(min(max((int)cf, -QMAX), QMAX) + BIAS) << (8 * e);
     }
-    *reinterpret_cast<uint32_t*>(lds_u + row * d + 4 * li) = fields;
+    near_mask |= (near ? 1u : 0u) << ps;
+    *reinterpret_cast<uint32_t*>(lds_u + (ps * ROWS_PER_PASS + rp) * d + 4 * li) = fields;
+  }
+  if (near_mask) {   // rare: some quotient sits within 2^-12 of a half-integer
+#pragma unroll
+    for (int ps = 0; ps < PASSES; ++ps) {
+      if ((near_mask >> ps) & 1u) {
+        const float xs[4] = {v[ps].x, v[ps].y, v[ps].z, v[ps].w};
+        const double hs = 0.5 * (double)step[ps];
+        uint32_t fields = 0;
+#pragma unroll
+        for (int e = 0; e < 4; ++e) {
+          const int c = settle_code(xs[e], __builtin_rintf(xs[e] * inv[ps]), step[ps], hs);
+          fields |= (uint32_t)(min(max(c, -QMAX), QMAX) + BIAS) << (8 * e);
+        }
+        *reinterpret_cast<uint32_t*>(lds_u + (ps * ROWS_PER_PASS + rp) * d + 4 * li) = fields;
+      }
+    }
   }
   __syncthreads();
 
@@ -146,9 +199,27 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restr
 template <int BITS, int D>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __restrict__ large_ws,
                                                              dq_format fmt, dq_cache cache,
-                                                             const int32_t* __restrict__ blk_idx) {
+                                                             const int32_t* __restrict__ blk_idx,
+                                                             const int32_t* __restrict__ unit_status,
+                                                             int n_units, int32_t* __restrict__ status) {
   extern __shared__ uint8_t lds_u[];
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
+  if (blockIdx.x == 0) {
+    // fold the per-block status words of the decomposition into the call's two status words
+    __shared__ int red[2];
+    if (threadIdx.x < 2) red[threadIdx.x] = 0;
+    __syncthreads();
+    int flags = 0, sweeps = 0;
+    for (int u = threadIdx.x; u < n_units; u += 256) {
+      const int w = unit_status[u];
+      flags |= w & 0xFF;
+      sweeps = max(sweeps, w >> 8);
+    }
+    atomicOr(&red[0], flags);
+    atomicMax(&red[1], sweeps);
+    __syncthreads();
+    if (threadIdx.x < 2) status[threadIdx.x] = red[threadIdx.x];
+  }
   const int tile = blockIdx.x % g.tiles_per_block;
   const int unit = blockIdx.x / g.tiles_per_block;  // (b*H + h)*2 + which
   const int which = unit & 1;
@@ -202,14 +273,17 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
                                                        const int32_t* __restrict__ blk_idx,
                                                        const int32_t* __restrict__ n_valid,
                                                        float* __restrict__ large_ws,
-                                                       int32_t* __restrict__ status) {
+                                                       int32_t* __restrict__ unit_status) {
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
   const int unit = blockIdx.x;  // (b*H + h)*2 + which
   const int which = unit & 1;
   const int bh = unit >> 1;
   const int b = bh / g.H;
   const int slot = blk_idx[b];
-  if (slot < 0 || slot >= g.NB) return;
+  if (slot < 0 || slot >= g.NB) {
+    if (threadIdx.x == 0) unit_status[unit] = 0;
+    return;
+  }
   int nv = t_new;
   if (n_valid) nv = min(max(n_valid[b], 0), t_new);
   const int tid = threadIdx.x;
@@ -356,8 +430,9 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
       if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
       else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
     }
-    if (sat) atomicOr(status, 1);
-    if (tid == 0) atomicMax(status + 1, sweeps);   // diagnostic: most Jacobi sweeps any block needed
+    // this block's status word: bit 0 = T_S saturated, bits 8.. = Jacobi sweeps used
+    const bool any_sat = __any(sat);
+    if (tid == 0) unit_status[unit] = (any_sat ? 1 : 0) | (sweeps << 8);
   }
   __syncthreads();
 
@@ -399,11 +474,13 @@ typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 // (relative error near 1e-7: the entry shrinks by that factor instead of vanishing, which does not
 // slow the quadratic convergence); c is refined to full precision so that c^2 + s^2 = 1 and the
 // accumulated rotations stay orthogonal.
-__device__ __forceinline__ void jacobi_rotation(double app, double aqq, double apq, double& c, double& s,
-                                                double& rel2) {
-  // entries that are already negligible against the diagonal are skipped (also keeps tau finite);
-  // written without branches so that the two rotations a lane needs interleave
-  const bool live = fabs(apq) > 1e-300 && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq));
+__device__ __forceinline__ void jacobi_rotation(double app, double aqq, double apq, double floor_abs,
+                                                double& c, double& s, double& rel2) {
+  // Entries at the rounding level of the whole matrix (floor_abs = 1e-17 * trace) or negligible
+  // against their own diagonal pair are skipped: rotating them changes nothing that is kept, and
+  // between two numerically zero eigenvalues they would never settle.  Written without branches so
+  // that the two rotations a lane needs interleave.
+  const bool live = fabs(apq) > floor_abs && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq));
   const double tau = (aqq - app) * 0.5 * __builtin_amdgcn_rcp(apq);
   const double root = __builtin_amdgcn_sqrt(fma(tau, tau, 1.0));
   const double t = copysign(__builtin_amdgcn_rcp(fabs(tau) + root), tau);
@@ -420,49 +497,59 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
   q = round - k; if (q < 0) q += 15;
 }
 
-__global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache cache,
-                                                         const uint16_t* __restrict__ k_new,
-                                                         const uint16_t* __restrict__ v_new, int t_new,
-                                                         const int32_t* __restrict__ blk_idx,
-                                                         const int32_t* __restrict__ n_valid,
-                                                         float* __restrict__ large_ws,
-                                                         int32_t* __restrict__ status) {
+// NWV waves per block: the two contractions are split over the waves by token, the eigen-solver
+// runs in one of them.  The host picks NWV so that the launch has about one wave per SIMD.
+template <int NWV>
+__global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq_cache cache,
+                                                               const uint16_t* __restrict__ k_new,
+                                                               const uint16_t* __restrict__ v_new, int t_new,
+                                                               const int32_t* __restrict__ blk_idx,
+                                                               const int32_t* __restrict__ n_valid,
+                                                               float* __restrict__ large_ws,
+                                                               int32_t* __restrict__ unit_status) {
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
   const int unit = blockIdx.x;  // (b*H + h)*2 + which
   const int which = unit & 1;
   const int bh = unit >> 1;
   const int b = bh / g.H;
   const int slot = blk_idx[b];
-  if (slot < 0 || slot >= g.NB) return;
+  if (slot < 0 || slot >= g.NB) {
+    if (threadIdx.x == 0) unit_status[unit] = 0;
+    return;
+  }
   int nv = t_new;
   if (n_valid) nv = min(max(n_valid[b], 0), t_new);
-  const int l = threadIdx.x;
-  constexpr int j1 = 16, j2 = 8, d = 128, ld = 17;
+  const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
+  const int solver = unit % NWV;   // the wave that runs the eigen-solver (spread over the SIMDs)
+  constexpr int j1 = 16, d = 128, ld = 17;
   const uint16_t* X = (which ? v_new : k_new) + (long)bh * t_new * d;  // [t_new, d] fp16 bits
 
   __shared__ double A[j1 * ld], V[j1 * ld], W[j1 * ld];
+  __shared__ double P[(NWV > 1 ? NWV - 1 : 1) * j1 * ld];   // Gram partials of the other waves
   __shared__ double lam[j1], sigma[j1], offs[8];
   __shared__ int order[j1];
 
   // ---- Gram matrix G[p][q] = sum_{t, b2} X[t, p*8+b2] X[t, q*8+b2] ----
   // A and B operand of one MFMA are the same register: lane (b1 = l%16, k = l/16) holds
   // X[t0 + k][b1*8 + b2] for the 4 tokens of a group and one b2.  A lane loads the 8 b2 of its
-  // (token, b1) as one 16-byte chunk; 16 lanes cover a 256-byte row.
+  // (token, b1) as one 16-byte chunk; 16 lanes cover a 256-byte row.  Wave wv takes every NWV-th
+  // group of 4 tokens.
   {
     const int b1 = l & 15, tk = l >> 4;
+    constexpr int NG = 32 / NWV;   // groups per wave in a chunk of 128 tokens
     f64x4 acc[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
     for (int t0 = 0; t0 < nv; t0 += 128) {
-      u32x4 x[32];
+      u32x4 x[NG];
 #pragma unroll
-      for (int u = 0; u < 32; ++u) {
-        const int t = t0 + 4 * u + tk;
+      for (int u = 0; u < NG; ++u) {
+        const int t = t0 + 4 * (u * NWV + wv) + tk;
         x[u] = u32x4{0u, 0u, 0u, 0u};
         if (t < nv) x[u] = *reinterpret_cast<const u32x4*>(X + (long)t * d + b1 * 8);
       }
 #pragma unroll
-      for (int u = 0; u < 32; ++u) {
+      for (int u = 0; u < NG; ++u) {
         const f16x8 h = __builtin_bit_cast(f16x8, x[u]);
 #pragma unroll
         for (int b2 = 0; b2 < 8; ++b2) {
@@ -471,82 +558,96 @@ __global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache
         }
       }
     }
+    double* dst = wv == 0 ? A : P + (wv - 1) * j1 * ld;
 #pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      const double gsum = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
-      A[((l >> 4) + 4 * i) * ld + (l & 15)] = gsum;
-    }
-    for (int idx = l; idx < j1 * j1; idx += 64) V[(idx >> 4) * ld + (idx & 15)] = ((idx >> 4) == (idx & 15)) ? 1.0 : 0.0;
+    for (int i = 0; i < 4; ++i)
+      dst[((l >> 4) + 4 * i) * ld + (l & 15)] = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
+    for (int idx = threadIdx.x; idx < j1 * j1; idx += 64 * NWV)
+      V[(idx >> 4) * ld + (idx & 15)] = ((idx >> 4) == (idx & 15)) ? 1.0 : 0.0;
   }
   __syncthreads();
-
-  // ---- parallel cyclic Jacobi: 15 rounds of 8 disjoint rotations per sweep ----
-  // Lane (I, J) owns the 2 x 2 block rows(pair I) x columns(pair J) of the matrix and rows
-  // {2I, 2I+1} x columns(pair J) of the accumulated rotations; it derives both rotations itself
-  // from the three entries of each pair, so a round is: read, rotate, write.
-  const int I = l >> 3, J = l & 7;
-  int sweeps = 0;
-  for (int sweep = 0; sweep < 16; ++sweep) {
-    ++sweeps;
-    double offmax = 0.0;
-    // unrolled: the LDS addresses of a round depend only on the lane and are computed once
+  if (NWV > 1) {
+    for (int idx = threadIdx.x; idx < j1 * j1; idx += 64 * NWV) {
+      const int e = (idx >> 4) * ld + (idx & 15);
+      double sum = A[e];
 #pragma unroll
-    for (int round = 0; round < 15; ++round) {
-      int p, q, u, v;
-      pair16(round, I, p, q);
-      pair16(round, J, u, v);
-      const double app = A[p * ld + p], aqq = A[q * ld + q], apq = A[p * ld + q];
-      const double auu = A[u * ld + u], avv = A[v * ld + v], auv = A[u * ld + v];
-      const double b00 = A[p * ld + u], b01 = A[p * ld + v], b10 = A[q * ld + u], b11 = A[q * ld + v];
-      const int r0 = 2 * I * ld, r1 = r0 + ld;
-      const double v00 = V[r0 + u], v01 = V[r0 + v], v10 = V[r1 + u], v11 = V[r1 + v];
-      double cI, sI, relI, cJ, sJ, relJ;
-      jacobi_rotation(app, aqq, apq, cI, sI, relI);
-      jacobi_rotation(auu, avv, auv, cJ, sJ, relJ);
-      offmax = fmax(offmax, relI);
-      // Jm has Jm[p][p] = c, Jm[p][q] = s, Jm[q][p] = -s, Jm[q][q] = c;  A' = Jm^T A Jm,  V' = V Jm
-      const double x00 = b00 * cJ - b01 * sJ, x01 = b00 * sJ + b01 * cJ;
-      const double x10 = b10 * cJ - b11 * sJ, x11 = b10 * sJ + b11 * cJ;
-      A[p * ld + u] = cI * x00 - sI * x10;
-      A[p * ld + v] = cI * x01 - sI * x11;
-      A[q * ld + u] = sI * x00 + cI * x10;
-      A[q * ld + v] = sI * x01 + cI * x11;
-      V[r0 + u] = v00 * cJ - v01 * sJ;
-      V[r0 + v] = v00 * sJ + v01 * cJ;
-      V[r1 + u] = v10 * cJ - v11 * sJ;
-      V[r1 + v] = v10 * sJ + v11 * cJ;
-      // One wave: its LDS operations execute in program order, so the next round's reads see these
-      // writes without waiting for them; the compiler only has to keep the order.
+      for (int k = 0; k < NWV - 1; ++k) sum += P[k * j1 * ld + e];   // fixed order: reproducible
+      A[e] = sum;
+    }
+    __syncthreads();
+  }
+
+  if (wv == solver) {
+    // ---- parallel cyclic Jacobi: 15 rounds of 8 disjoint rotations per sweep ----
+    // Lane (I, J) owns the 2 x 2 block rows(pair I) x columns(pair J) of the matrix and rows
+    // {2I, 2I+1} x columns(pair J) of the accumulated rotations; it derives both rotations itself
+    // from the three entries of each pair, so a round is: read, rotate, write.
+    const int I = l >> 3, J = l & 7;
+    double floor_abs = 0.0;
+#pragma unroll
+    for (int i = 0; i < j1; ++i) floor_abs += A[i * ld + i];
+    floor_abs = fmax(floor_abs * 1e-17, 1e-300);
+    int sweeps = 0;
+    for (int sweep = 0; sweep < 16; ++sweep) {
+      ++sweeps;
+      double offmax = 0.0;
+      // unrolled: the LDS addresses of a round depend only on the lane and are computed once
+#pragma unroll
+      for (int round = 0; round < 15; ++round) {
+        int p, q, u, v;
+        pair16(round, I, p, q);
+        pair16(round, J, u, v);
+        const double app = A[p * ld + p], aqq = A[q * ld + q], apq = A[p * ld + q];
+        const double auu = A[u * ld + u], avv = A[v * ld + v], auv = A[u * ld + v];
+        const double b00 = A[p * ld + u], b01 = A[p * ld + v], b10 = A[q * ld + u], b11 = A[q * ld + v];
+        const int r0 = 2 * I * ld, r1 = r0 + ld;
+        const double v00 = V[r0 + u], v01 = V[r0 + v], v10 = V[r1 + u], v11 = V[r1 + v];
+        double cI, sI, relI, cJ, sJ, relJ;
+        jacobi_rotation(app, aqq, apq, floor_abs, cI, sI, relI);
+        jacobi_rotation(auu, avv, auv, floor_abs, cJ, sJ, relJ);
+        offmax = fmax(offmax, relI);
+        // Jm has Jm[p][p] = c, Jm[p][q] = s, Jm[q][p] = -s, Jm[q][q] = c;  A' = Jm^T A Jm,  V' = V Jm
+        const double x00 = b00 * cJ - b01 * sJ, x01 = b00 * sJ + b01 * cJ;
+        const double x10 = b10 * cJ - b11 * sJ, x11 = b10 * sJ + b11 * cJ;
+        A[p * ld + u] = cI * x00 - sI * x10;
+        A[p * ld + v] = cI * x01 - sI * x11;
+        A[q * ld + u] = sI * x00 + cI * x10;
+        A[q * ld + v] = sI * x01 + cI * x11;
+        V[r0 + u] = v00 * cJ - v01 * sJ;
+        V[r0 + v] = v00 * sJ + v01 * cJ;
+        V[r1 + u] = v10 * cJ - v11 * sJ;
+        V[r1 + v] = v10 * sJ + v11 * cJ;
+        // One wave: its LDS operations execute in program order, so the next round's reads see these
+        // writes without waiting for them; the compiler only has to keep the order.
+        __builtin_amdgcn_wave_barrier();
+      }
+      if (J == 0) offs[I] = offmax;
       __builtin_amdgcn_wave_barrier();
-    }
-    if (J == 0) offs[I] = offmax;
-    __syncthreads();
-    double om = 0.0;
+      double om = 0.0;
 #pragma unroll
-    for (int i = 0; i < 8; ++i) om = fmax(om, offs[i]);
-    __syncthreads();
-    // every entry rotated in this sweep was below 1e-9 of its diagonal pair: one more quadratic
-    // step has taken them below 1e-16
-    if (om < 1e-18) break;
-  }
+      for (int i = 0; i < 8; ++i) om = fmax(om, offs[i]);
+      __builtin_amdgcn_wave_barrier();
+      // every entry rotated in this sweep was below 1e-6 of its diagonal pair, so the sweep (one more
+      // quadratic step) has left them near 1e-12
+      if (om < 1e-12) break;
+    }
 
-  // ---- singular values, ordering, small tensor ----
-  if (l < j1) lam[l] = A[l * ld + l];
-  __syncthreads();
-  if (l < j1) {
-    int rank = 0;
-    const double me = lam[l];
-    for (int s = 0; s < j1; ++s) rank += (lam[s] > me) || (lam[s] == me && s < l);
-    order[rank] = l;
-  }
-  __syncthreads();
-  if (l < j1) {
-    const double lmax = fmax(lam[order[0]], 0.0);
-    const double lv = lam[order[l]];
-    sigma[l] = (lv > 1e-12 * lmax && lv > 0.0) ? sqrt(lv) : 0.0;
-  }
-  __syncthreads();
-  {
+    // ---- singular values, ordering, small tensor ----
+    if (l < j1) lam[l] = A[l * ld + l];
+    __builtin_amdgcn_wave_barrier();
+    if (l < j1) {
+      int rank = 0;
+      const double me = lam[l];
+      for (int s = 0; s < j1; ++s) rank += (lam[s] > me) || (lam[s] == me && s < l);
+      order[rank] = l;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (l < j1) {
+      const double lmax = fmax(lam[order[0]], 0.0);
+      const double lv = lam[order[l]];
+      sigma[l] = (lv > 1e-12 * lmax && lv > 0.0) ? sqrt(lv) : 0.0;
+    }
+    __builtin_amdgcn_wave_barrier();
     const long blk = (long)bh * g.NB + slot;
     uint16_t* small = (which ? cache.v_small : cache.k_small) + blk * g.small_per_block;
     bool sat = false;
@@ -559,23 +660,26 @@ __global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache
       if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
       else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
     }
-    if (sat) atomicOr(status, 1);
-    if (l == 0) atomicMax(status + 1, sweeps);   // diagnostic: most Jacobi sweeps any block needed
+    // this block's status word: bit 0 = T_S saturated, bits 8.. = Jacobi sweeps used
+    const bool any_sat = __any(sat);
+    if (l == 0) unit_status[unit] = (any_sat ? 1 : 0) | (sweeps << 8);
   }
   __syncthreads();
 
   // ---- projection: K'[t, r*8+b2] = sum_b1 W[r][b1] X[t, b1*8+b2], fp64 -> fp32 ----
   // One MFMA chain per b2: rows r, columns 16 tokens, contraction over b1 in 4 steps of 4.
+  // Wave wv takes every NWV-th group of 16 tokens.
   {
+    constexpr int NT = 8 / NWV;   // token groups per wave in a chunk of 128 tokens
     double wreg[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) wreg[s] = W[(l & 15) * ld + 4 * s + (l >> 4)];
     float* out = large_ws + (long)unit * g.Tb * d;
     for (int t0 = 0; t0 < g.Tb; t0 += 128) {
-      u32x4 x[8][4];
+      u32x4 x[NT][4];
 #pragma unroll
-      for (int tg = 0; tg < 8; ++tg) {
-        const int t = t0 + 16 * tg + (l & 15);
+      for (int tg = 0; tg < NT; ++tg) {
+        const int t = t0 + 16 * (tg * NWV + wv) + (l & 15);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           x[tg][s] = u32x4{0u, 0u, 0u, 0u};
@@ -583,8 +687,8 @@ __global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache
         }
       }
 #pragma unroll
-      for (int tg = 0; tg < 8; ++tg) {
-        const int t = t0 + 16 * tg + (l & 15);
+      for (int tg = 0; tg < NT; ++tg) {
+        const int t = t0 + 16 * (tg * NWV + wv) + (l & 15);
         f64x4 acc[8];
 #pragma unroll
         for (int b2 = 0; b2 < 8; ++b2) acc[b2] = f64x4{0.0, 0.0, 0.0, 0.0};
@@ -606,10 +710,6 @@ __global__ __launch_bounds__(64) void decompose16_kernel(dq_format fmt, dq_cache
   }
 }
 
-__global__ void clear_status_kernel(int32_t* status) {
-  if (threadIdx.x < 2) status[threadIdx.x] = 0;
-}
-
 }  // namespace dq
 
 // ------------------------------------------------------------------------------------------
@@ -619,8 +719,10 @@ using namespace dq;
 
 extern "C" size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads) {
   if (!format_ok(fmt) || batch <= 0 || kv_heads <= 0) return 0;
+  // header (status words), the fp32 large tensors, one status word per block
   return (size_t)kWsHeaderBytes +
-         (size_t)batch * kv_heads * 2 * fmt->block_tokens * fmt->head_dim * sizeof(float);
+         (size_t)batch * kv_heads * 2 * fmt->block_tokens * fmt->head_dim * sizeof(float) +
+         align_up((size_t)batch * kv_heads * 2 * sizeof(int32_t), 256);
 }
 
 extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, int64_t n_rows,
@@ -666,15 +768,24 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   int32_t* status = reinterpret_cast<int32_t*>(workspace);
   float* large_ws = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kWsHeaderBytes);
   const int units = cache->batch * cache->kv_heads * 2;
-  hipLaunchKernelGGL(clear_status_kernel, dim3(1), dim3(64), 0, st, status);
+  int32_t* unit_status = reinterpret_cast<int32_t*>(large_ws + (size_t)units * fmt->block_tokens * fmt->head_dim);
   const size_t dlds = decompose_lds_bytes(fmt->j1, fmt->head_dim);
 #define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                   \
   hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, k_new, \
-                     v_new, t_new, blk_idx, n_valid, large_ws, status)
+                     v_new, t_new, blk_idx, n_valid, large_ws, unit_status)
   static const bool force_general = getenv("DQ_COMPRESS_GENERAL") != nullptr;   // for A/B timing
   if (fmt->head_dim == 128 && fmt->j1 == 16 && !force_general) {
-    hipLaunchKernelGGL(decompose16_kernel, dim3(units), dim3(64), 0, st, *fmt, *cache, k_new, v_new, t_new,
-                       blk_idx, n_valid, large_ws, status);
+    // At most one workgroup per compute unit (256 on the chip) gets more waves per block: the
+    // eigen-solver wave is issue-bound and slows down when two of them share a SIMD.
+#define DQ_LAUNCH_D16(N_)                                                                                \
+  hipLaunchKernelGGL((decompose16_kernel<N_>), dim3(units), dim3(64 * N_), 0, st, *fmt, *cache, k_new, \
+                     v_new, t_new, blk_idx, n_valid, large_ws, unit_status)
+    int nwv = units <= 256 ? 4 : units <= 512 ? 2 : 1;
+    if (const char* e = getenv("DQ_COMPRESS_WAVES")) nwv = atoi(e);   // for sweeps
+    if (nwv >= 4) DQ_LAUNCH_D16(4);
+    else if (nwv >= 2) DQ_LAUNCH_D16(2);
+    else DQ_LAUNCH_D16(1);
+#undef DQ_LAUNCH_D16
   } else if (fmt->head_dim == 128) {
     if (fmt->j1 == 8) DQ_LAUNCH_DECOMPOSE(8, 128);
     else if (fmt->j1 == 16) DQ_LAUNCH_DECOMPOSE(16, 128);
@@ -690,7 +801,7 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
 #define DQ_LAUNCH_QTILES(B_, D_)                                                                       \
   hipLaunchKernelGGL((quantize_tiles_kernel<B_, D_>), dim3(tiles), dim3(256), lds, st, large_ws, *fmt, \
-                     *cache, blk_idx)
+                     *cache, blk_idx, unit_status, units, status)
   if (fmt->head_dim == 128) {
     if (fmt->bits == 2) DQ_LAUNCH_QTILES(2, 128);
     else if (fmt->bits == 4) DQ_LAUNCH_QTILES(4, 128);

@@ -157,7 +157,9 @@ def test_compress_kv_properties(name, t_new, n_valid):
     arrs = {n: t.cpu().numpy() for n, t in cache.t.items()}
     status = int(ws[:4].view(torch.int32).item())
     assert status == 0
-    large = ws[256:].view(torch.float32).cpu().numpy().reshape(w.batch * w.kv_heads * 2, tb, d)
+    n_large = w.batch * w.kv_heads * 2 * tb * d                     # fp32 large tensors follow the 256-byte header
+    large = ws[256:256 + 4 * n_large].view(torch.float32).cpu().numpy().reshape(w.batch * w.kv_heads * 2, tb, d)
+    worst_ortho = 0.0
     for b in range(w.batch):
         for h in range(w.kv_heads):
             for which, x_all in (("k", k), ("v", v)):
@@ -176,7 +178,8 @@ def test_compress_kv_properties(name, t_new, n_valid):
                 gram = t_l @ t_l.T
                 diag = np.diag(gram)
                 live = diag > 0.5
-                assert np.abs(gram - np.diag(live.astype(np.float64))).max() <= 1e-4, (b, h, which)
+                worst_ortho = max(worst_ortho, np.abs(gram - np.diag(live.astype(np.float64))).max())
+                assert worst_ortho <= 2e-6, (b, h, which)     # fp32 storage of T_L allows about 1e-6
                 # (2) exact factorisation up to the fp16 rounding of T_S and fp32 of T_L
                 m = O.matricise(x, 1, j1)
                 resid = np.abs(small.astype(np.float64) @ t_l - m)
@@ -196,6 +199,7 @@ def test_compress_kv_properties(name, t_new, n_valid):
                 for other in range(nb):
                     if other != slot:
                         assert np.array_equal(arrs["k_codes"][b, h, other], before["k_codes"][b, h, other].cpu().numpy())
+    _say("  worst |T_L T_L^T - I| = %.3g, sweeps %d" % (worst_ortho, int(ws[4:8].view(torch.int32).item())))
 
 
 def test_gpu_compressed_cache_decodes_like_its_own_oracle_reading():

@@ -34,7 +34,8 @@ def test_status_strings_and_version(dq):
 def test_workspace_queries_validate_the_format(dq):
     good = dq.Format(4, 128, 128, 16, 8, 128).c()
     assert dq.lib.dq_decode_workspace_bytes(C.byref(good), 8, 32, 32, 4096) > 0
-    assert dq.lib.dq_compress_workspace_bytes(C.byref(good), 4, 40) == 256 + 4 * 40 * 2 * 128 * 128 * 4
+    # header + fp32 large tensors + one status word per block (padded to 256 bytes)
+    assert dq.lib.dq_compress_workspace_bytes(C.byref(good), 4, 40) == 256 + 4 * 40 * 2 * 128 * 128 * 4 + 1280
     for bad in [dq.Format(3, 128, 128, 16, 8, 128), dq.Format(4, 128, 128, 16, 4, 128),
                 dq.Format(4, 96, 128, 16, 8, 128), dq.Format(4, 128, 128, 16, 8, 100),
                 dq.Format(4, 128, 256, 16, 16, 128)]:
