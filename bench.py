@@ -174,8 +174,9 @@ def algorithmic_bytes(w, lens) -> float:
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--gpus", type=int, default=1)
-    ap.add_argument("--steps", type=int, default=400)
-    ap.add_argument("--warmup", type=int, default=40)
+    ap.add_argument("--steps", type=int, default=2000)
+    ap.add_argument("--warmup", type=int, default=2000,
+                    help="untimed steps first; the GPU clocks take tens of milliseconds of load to settle")
     ap.add_argument("--workload", default="llama7b_4bit", choices=sorted(workloads.WORKLOADS))
     ap.add_argument("--layers", type=int, default=8, help="distinct cache copies the steps rotate over")
     ap.add_argument("--cpu-pairs", type=int, default=256, help="(sequence, head) pairs the CPU oracle is timed on")

@@ -147,10 +147,12 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   // The split of the sequence depends on its length, which lives in device memory.  The first
   // tile's loads are issued for the length the host passed as the upper bound (right whenever
   // the batch is not ragged) and re-issued only if the real length moves this wave's first tile.
-  const int spec_total = (a.max_seq_len + kTileTokens - 1) / kTileTokens;
-  const int spec_tps = (spec_total + a.n_split - 1) / a.n_split;
-  const int spec_tile = split * spec_tps + wave;
-  const bool spec_ok = spec_tile < min(split * spec_tps + spec_tps, spec_total);
+  // Tiles are dealt round-robin over all waves of all splits of this (sequence, kv head), so a wave's
+  // first tile does not depend on the sequence length and its loads can start before the length is
+  // known; they are wasted only if the sequence is shorter than that tile.
+  const int first_tile = split * NW + wave;
+  const int tile_stride = a.n_split * NW;
+  const bool spec_ok = first_tile * kTileTokens < a.max_seq_len;
   int S = 0;  // the sequence's real length, read after the speculative loads are on their way
 
   unsigned char* wl = smem + wave * WAVE_LDS;
@@ -249,7 +251,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     const unsigned char *kc_next = nullptr, *vc_next = nullptr;
     long blkid_next = 0;
     int tib_next = 0;
-    if (HAS_NEXT) tile_ptrs(tile + NW, kc_next, vc_next, blkid_next, tib_next);
+    if (HAS_NEXT) tile_ptrs(tile + tile_stride, kc_next, vc_next, blkid_next, tib_next);
     Side nxt = cur;
     if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
     __builtin_amdgcn_sched_barrier(0);
@@ -434,18 +436,15 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
     __builtin_amdgcn_wave_barrier();
   };
 
-  if (spec_ok) issue_tile(spec_tile);   // in bounds: max_seq_len <= block_capacity * block_tokens
+  if (spec_ok) issue_tile(first_tile);   // in bounds: max_seq_len <= block_capacity * block_tokens
 
   S = min(max(a.seq_lens[b], 0), a.max_seq_len);
   const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
-  const int tps = (tiles_total + a.n_split - 1) / a.n_split;
-  const int tile_begin = split * tps;
-  const int tile_end = min(tile_begin + tps, tiles_total);
   {
-    int tile = tile_begin + wave;
-    if (tile < tile_end) {
-      if (!(spec_ok && tile == spec_tile)) issue_tile(tile);
-      for (; tile + NW < tile_end; tile += NW) compute_tile(tile, std::true_type{});
+    int tile = first_tile;
+    if (tile < tiles_total) {
+      if (!spec_ok) issue_tile(tile);
+      for (; tile + tile_stride < tiles_total; tile += tile_stride) compute_tile(tile, std::true_type{});
       compute_tile(tile, std::false_type{});
     }
   }
