@@ -114,7 +114,7 @@ __device__ __forceinline__ float pow2i(int e) {
 }
 
 // BITS: code width.  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
-// of one (sequence, kv head, split) are dealt round-robin to the NW waves.
+// of one (sequence, kv head) are dealt round-robin to the NW waves of each of its n_split workgroups.
 template <int BITS, int R, int NW>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
   typedef Codec<BITS> C;
@@ -144,10 +144,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   const long codes_per_block = (long)a.fmt.block_tokens * ROWB;
   const long scales_per_block = (long)a.fmt.block_tokens * NG;
 
-  // The split of the sequence depends on its length, which lives in device memory.  The first
-  // tile's loads are issued for the length the host passed as the upper bound (right whenever
-  // the batch is not ragged) and re-issued only if the real length moves this wave's first tile.
-  // Tiles are dealt round-robin over all waves of all splits of this (sequence, kv head), so a wave's
+  // The sequence length lives in device memory and takes a memory round trip to read.  Tiles are dealt round-robin over all waves of all splits of this (sequence, kv head), so a wave's
   // first tile does not depend on the sequence length and its loads can start before the length is
   // known; they are wasted only if the sequence is shorter than that tile.
   const int first_tile = split * NW + wave;
