@@ -113,13 +113,12 @@ __device__ __forceinline__ float pow2i(int e) {
   return __builtin_bit_cast(float, (uint32_t)(e + 127) << 23);
 }
 
-// BITS: code width.  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
+// BITS: code width.  NG: step groups per token row (group = 128 / NG).  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
 // of one (sequence, kv head) are dealt round-robin to the NW waves of each of its n_split workgroups.
-template <int BITS, int R, int NW>
+template <int BITS, int NG, int R, int NW>
 __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
   typedef Codec<BITS> C;
   typedef typename C::chunk_t chunk_t;
-  constexpr int NG = (BITS == 4) ? 1 : 2;     // step groups per token row
   constexpr int CPH = 4 * NG;                 // B columns per head: column CPH*head + 4*group + limb
   constexpr int NC = CPH * R;
   static_assert(NC <= 16, "too many heads for sixteen B columns");
@@ -547,41 +546,50 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads % kv_heads) return false;
   if (f->head_dim != 128 || f->j1 != 16 || f->j2 != 8) return false;
   const int rep = q_heads / kv_heads;
-  if (f->bits == 4 && f->group == 128) return rep == 1 || rep == 2 || rep == 4;
-  if (f->bits == 2 && f->group == 64) return rep == 1 || rep == 2;
+  if (f->bits != 4 && f->bits != 2) return false;
+  // a head takes four B columns per step group of the sixteen
+  if (f->group == 128) return rep == 1 || rep == 2 || rep == 4;
+  if (f->group == 64) return rep == 1 || rep == 2;
   return false;
 }
 
-template <int BITS, int R>
+template <int BITS, int NG, int R>
 static void launch_r(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   // the events, when given, receive the kernel's own begin and end timestamps
   if (a.nw == 8)
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, R, 8>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
   else
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, R, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
 }
 
-int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
+template <int BITS>
+static int32_t launch_bits(const DecodeArgs& a, hipStream_t st) {
   const int rep = a.q_heads / a.cache.kv_heads;
-  if (a.tail.k_tail) {   // the tail's partial, with its maximum in log2 units like this path's
-    const int32_t rc = launch_tail_partial(a, 1.0f, st);
-    if (rc != DQ_OK) return rc;
-  }
-  if (a.fmt.bits == 4) {
+  if (a.fmt.group == 128) {
     switch (rep) {
-      case 1: launch_r<4, 1>(a, st); break;
-      case 2: launch_r<4, 2>(a, st); break;
-      case 4: launch_r<4, 4>(a, st); break;
+      case 1: launch_r<BITS, 1, 1>(a, st); break;
+      case 2: launch_r<BITS, 1, 2>(a, st); break;
+      case 4: launch_r<BITS, 1, 4>(a, st); break;
       default: return DQ_EINVAL;
     }
   } else {
     switch (rep) {
-      case 1: launch_r<2, 1>(a, st); break;
-      case 2: launch_r<2, 2>(a, st); break;
+      case 1: launch_r<BITS, 2, 1>(a, st); break;
+      case 2: launch_r<BITS, 2, 2>(a, st); break;
       default: return DQ_EINVAL;
     }
   }
+  return DQ_OK;
+}
+
+int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
+  if (a.tail.k_tail) {   // the tail's partial, with its maximum in log2 units like this path's
+    const int32_t rc = launch_tail_partial(a, 1.0f, st);
+    if (rc != DQ_OK) return rc;
+  }
+  const int32_t rc = (a.fmt.bits == 4) ? launch_bits<4>(a, st) : launch_bits<2>(a, st);
+  if (rc != DQ_OK) return rc;
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
 }

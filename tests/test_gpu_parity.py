@@ -250,6 +250,9 @@ def test_stream_read_runs():
     ("llama7b_2bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=700, min_seq=700), [700, 128]),
     ("llama7b_2bit", dict(batch=3, q_heads=4, kv_heads=2, max_seq=1300, min_seq=1300), [1300, 0, 257]),
     ("llama7b_2bit", dict(batch=1, q_heads=2, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=256), [1000]),
+    # the other two pairings of code width and group size
+    ("llama7b_4bit", dict(batch=2, q_heads=4, kv_heads=2, max_seq=900, min_seq=900, group=64), [900, 130]),
+    ("llama7b_2bit", dict(batch=2, q_heads=8, kv_heads=2, max_seq=900, min_seq=900, group=128), [900, 385]),
 ])
 def test_decode_mfma_multi_block(name, kw, lens):
     w = _small(name, **kw)
@@ -265,7 +268,11 @@ def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
     assert dq.decode_mfma_supported(fmt4, 32, 32) and dq.decode_mfma_supported(fmt4, 32, 8)
     assert dq.decode_mfma_supported(dq.Format(2, 64, 128, 16, 8, 128), 32, 32)
     assert not dq.decode_mfma_supported(dq.Format(2, 64, 128, 16, 8, 128), 32, 8)
-    assert not dq.decode_mfma_supported(dq.Format(2, 128, 128, 16, 8, 128), 32, 32)
+    assert dq.decode_mfma_supported(dq.Format(2, 128, 128, 16, 8, 128), 32, 8)
+    assert dq.decode_mfma_supported(dq.Format(4, 64, 128, 16, 8, 128), 32, 16)
+    assert not dq.decode_mfma_supported(dq.Format(4, 64, 128, 16, 8, 128), 32, 8)
+    assert not dq.decode_mfma_supported(dq.Format(4, 32, 128, 16, 8, 128), 32, 32)
+    assert not dq.decode_mfma_supported(dq.Format(8, 128, 128, 16, 8, 128), 32, 32)
     assert not dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 4, 4)
     w = workloads.get_workload("tiny")
     fmt, ofmt = formats(w)
