@@ -265,7 +265,7 @@ def main():
         "higher_is_better": True,
         "scaling": "weak",
         "vs_baseline": None,
-        "dtype": "u4 codes on int8 MFMA, f32 accumulate" if path == "mfma" else "u%d codes, f32" % w.bits,
+        "dtype": ("u%d codes on int8 MFMA, f32 accumulate" if path == "mfma" else "u%d codes, f32") % w.bits,
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "seq_len": [int(lens.min()), int(lens.max())], "bits": w.bits,

@@ -1,12 +1,12 @@
 // Matrix-core decode attention over the compressed cache for the formats
-//   bits = 4, group = 128, q_heads / kv_heads in {1, 2, 4}
-//   bits = 2, group = 64,  q_heads / kv_heads in {1, 2}
+//   bits in {2, 4, 8};  group = 128 with q_heads / kv_heads in {1, 2, 4},
+//                       group = 64  with q_heads / kv_heads in {1, 2}
 // with head_dim = 128, j1 = 16, j2 = 8, block_tokens % 128 == 0.
 //
 // This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
 // 2405.12591) carried through the attention that follows it.  The low-bit codes never become
 // floating point: a 32-bit word of codes is split into words of four bytes each
-// (4-bit: x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F; 2-bit: (x >> 2k) & 0x03030303) and fed to the
+// (4-bit: x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F; 2-bit: (x >> 2k) & 0x03030303; 8-bit: x ^ 0x80808080) and fed to the
 // int8 matrix cores; the other operand (the folded query, then the softmax weights times the
 // value steps) is expressed as three 7-bit integer limbs relative to a per-tile power of two,
 // one B column per limb, so the contraction is exact integer arithmetic.  Per 128-token tile,
@@ -49,7 +49,7 @@ constexpr int kLimbBits = 7;
 constexpr int kMantBits = 3 * kLimbBits;  // 21-bit integers: limb0 * 2^14 + limb1 * 2^7 + limb2
 
 // ---- per-bit-width pieces -------------------------------------------------------------------
-// Chunk: what one lane loads of a 16-row piece of codes (16 bytes at 4 bits, 8 at 2 bits); it
+// Chunk: what one lane loads of a 16-row piece of codes (32 bytes at 8 bits, 16 at 4, 8 at 2); it
 // feeds two int8 MFMAs of 16 codes per lane each.  `slot(e)` is the byte position, inside the 16
 // bytes a lane hands to one MFMA, of the e-th of its 16 consecutive codes.
 template <int BITS> struct Codec;
@@ -85,6 +85,21 @@ template <> struct Codec<2> {
   static __device__ __forceinline__ int slot(int e) { return (e & 3) * 4 + (e >> 2); }
 };
 
+template <> struct Codec<8> {
+  typedef uint32_t chunk_t __attribute__((ext_vector_type(8)));
+  static constexpr int kOffset = 0;   // the stored byte becomes the signed code by flipping its top bit
+  static __device__ __forceinline__ i32x4 half(const chunk_t& c, int which) {
+    const uint32_t F = 0x80808080u;
+    i32x4 v;
+    v.x = (int)((which ? c.s4 : c.s0) ^ F);
+    v.y = (int)((which ? c.s5 : c.s1) ^ F);
+    v.z = (int)((which ? c.s6 : c.s2) ^ F);
+    v.w = (int)((which ? c.s7 : c.s3) ^ F);
+    return v;
+  }
+  static __device__ __forceinline__ int slot(int e) { return e; }
+};
+
 template <int CTRL>
 __device__ __forceinline__ float dpp_f(float v) {
   return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
@@ -116,7 +131,7 @@ __device__ __forceinline__ float pow2i(int e) {
 // BITS: code width.  NG: step groups per token row (group = 128 / NG).  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
 // of one (sequence, kv head) are dealt round-robin to the NW waves of each of its n_split workgroups.
 template <int BITS, int NG, int R, int NW>
-__global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
+__global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
   typedef Codec<BITS> C;
   typedef typename C::chunk_t chunk_t;
   constexpr int CPH = 4 * NG;                 // B columns per head: column CPH*head + 4*group + limb
@@ -163,7 +178,8 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
   const int G16 = lane >> 3, pi = lane & 7;
   int tA, tB;
   if (BITS == 4) { tA = 16 * G16 + 8 * (pi >> 2) + ((0x5140 >> (4 * (pi & 3))) & 7); tB = tA + 2; }
-  else { tA = 16 * G16 + 8 * (pi & 1) + (pi >> 1); tB = tA + 4; }
+  else if (BITS == 2) { tA = 16 * G16 + 8 * (pi & 1) + (pi >> 1); tB = tA + 4; }
+  else { tA = 16 * G16 + 2 * pi; tB = tA + 1; }
 
   // ---- loop-invariant B operands of the fold: q[k = b1][n' = (b2, head)] ----
   half4 bq[F];
@@ -191,7 +207,7 @@ __global__ __launch_bounds__(64 * NW, NW == 4 ? 2 : 1) void decode_mfma_kernel(D
 
   const float qk_scale = a.scale * kLog2e;
   constexpr int kPlusWord = C::kOffset * 0x01010101;                       // four bytes of +offset
-  constexpr int kMinusWord = (int)((uint32_t)(256 - C::kOffset) * 0x01010101u);  // four bytes of -offset
+  constexpr int kMinusWord = (int)((uint32_t)((256 - C::kOffset) & 255) * 0x01010101u);  // four bytes of -offset
   const i32x4 a_plus = {kPlusWord, kPlusWord, kPlusWord, kPlusWord};
   const i32x4 a_minus = {kMinusWord, kMinusWord, kMinusWord, kMinusWord};
   const i32x4 izero = {0, 0, 0, 0};
@@ -546,7 +562,7 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads % kv_heads) return false;
   if (f->head_dim != 128 || f->j1 != 16 || f->j2 != 8) return false;
   const int rep = q_heads / kv_heads;
-  if (f->bits != 4 && f->bits != 2) return false;
+  if (f->bits != 8 && f->bits != 4 && f->bits != 2) return false;
   // a head takes four B columns per step group of the sixteen
   if (f->group == 128) return rep == 1 || rep == 2 || rep == 4;
   if (f->group == 64) return rep == 1 || rep == 2;
@@ -588,7 +604,8 @@ int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
     const int32_t rc = launch_tail_partial(a, 1.0f, st);
     if (rc != DQ_OK) return rc;
   }
-  const int32_t rc = (a.fmt.bits == 4) ? launch_bits<4>(a, st) : launch_bits<2>(a, st);
+  const int32_t rc = (a.fmt.bits == 8) ? launch_bits<8>(a, st)
+                     : (a.fmt.bits == 4) ? launch_bits<4>(a, st) : launch_bits<2>(a, st);
   if (rc != DQ_OK) return rc;
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;

@@ -253,6 +253,10 @@ def test_stream_read_runs():
     # the other two pairings of code width and group size
     ("llama7b_4bit", dict(batch=2, q_heads=4, kv_heads=2, max_seq=900, min_seq=900, group=64), [900, 130]),
     ("llama7b_2bit", dict(batch=2, q_heads=8, kv_heads=2, max_seq=900, min_seq=900, group=128), [900, 385]),
+    # 8-bit codes
+    ("llama7b_8bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=1000, min_seq=1000), [1000, 257]),
+    ("llama7b_8bit", dict(batch=3, q_heads=8, kv_heads=2, max_seq=1300, min_seq=1300), [1300, 0, 129]),
+    ("llama7b_8bit", dict(batch=2, q_heads=4, kv_heads=2, max_seq=640, min_seq=640, group=64, block_tokens=256), [640, 511]),
 ])
 def test_decode_mfma_multi_block(name, kw, lens):
     w = _small(name, **kw)
@@ -272,7 +276,8 @@ def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
     assert dq.decode_mfma_supported(dq.Format(4, 64, 128, 16, 8, 128), 32, 16)
     assert not dq.decode_mfma_supported(dq.Format(4, 64, 128, 16, 8, 128), 32, 8)
     assert not dq.decode_mfma_supported(dq.Format(4, 32, 128, 16, 8, 128), 32, 32)
-    assert not dq.decode_mfma_supported(dq.Format(8, 128, 128, 16, 8, 128), 32, 32)
+    assert dq.decode_mfma_supported(dq.Format(8, 128, 128, 16, 8, 128), 32, 32)
+    assert not dq.decode_mfma_supported(dq.Format(8, 32, 128, 16, 8, 128), 32, 32)
     assert not dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 4, 4)
     w = workloads.get_workload("tiny")
     fmt, ofmt = formats(w)
@@ -344,14 +349,14 @@ def test_decode_full_size_llama7b_2bit():
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bits,group", [(8, 128), (8, 64)])
 def test_decode_8bit_generic(bits, group):
-    """Section 3.2 names 2/4/8-bit variants of the fused kernel; 8-bit runs on the generic path."""
+    """Section 3.2 names 2/4/8-bit variants of the fused kernel; here 8-bit on the plain fp32 kernel."""
     w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=600, min_seq=600, bits=bits, group=group)
     _say("decode 8-bit G=%d" % group)
-    worst = _decode_case(w, [600, 130], dq.DECODE_AUTO)
+    worst = _decode_case(w, [600, 130], dq.DECODE_FORCE_GENERIC)
     _say("  worst fp32 abs err %.3g" % worst)
 
 
-@pytest.mark.parametrize("name,flags", [("llama7b_4bit", 2), ("llama7b_2bit", 2), ("llama7b_4bit", 1)])
+@pytest.mark.parametrize("name,flags", [("llama7b_4bit", 2), ("llama7b_2bit", 2), ("llama7b_8bit", 2), ("llama7b_4bit", 1)])
 def test_identity_small_tensor_is_plain_rtn_attention(name, flags):
     """With T_S = I the cache is plain group round-to-nearest of K and V (the paper's RTN
     baseline, Section 4.1); the same kernels must decode it.  Steps are then as large as the

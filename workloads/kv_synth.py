@@ -54,6 +54,9 @@ WORKLOADS = {
                                "layer_outliers", 51, 30.0, append_tokens=128),
     "gqa_long": Workload("gqa_long", 1005, 16, 32, 8, 128, 32768, 32768, 4, 128, 16, 8, 128,
                          "student_t", 4, 10.0),
+    # the 8-bit variant of the benchmark shape (the paper's fused kernel covers 2, 4 and 8 bits)
+    "llama7b_8bit": Workload("llama7b_8bit", 1006, 8, 32, 32, 128, 4096, 4096, 8, 128, 16, 8, 128,
+                             "lognormal_tokens", 4, 20.0),
 }
 
 
