@@ -469,17 +469,18 @@ typedef double f64x4 __attribute__((ext_vector_type(4)));
 typedef unsigned int u32x4 __attribute__((ext_vector_type(4)));
 typedef _Float16 f16x8 __attribute__((ext_vector_type(8)));
 
-// Rotation (c, s) that annihilates entry (p, q) of a symmetric matrix, and the squared size of
-// that entry relative to its diagonal pair.  The angle comes from the hardware estimates alone
-// (relative error near 1e-7: the entry shrinks by that factor instead of vanishing, which does not
-// slow the quadratic convergence); c is refined to full precision so that c^2 + s^2 = 1 and the
-// accumulated rotations stay orthogonal.
+// Rotation (c, s) that annihilates entry (p, q) of a symmetric matrix; `big` reports whether that
+// entry was still above kSettled relative to its diagonal pair.  The angle comes from the hardware
+// estimates alone (relative error near 1e-7: the entry shrinks by that factor instead of
+// vanishing, which does not slow the quadratic convergence); c is refined to full precision so
+// that c^2 + s^2 = 1 and the accumulated rotations stay orthogonal.
+constexpr double kSettled2 = 1e-9;   // (3e-5)^2: one more sweep squares 3e-5 to about 1e-9
+
 __device__ __forceinline__ void jacobi_rotation(double app, double aqq, double apq, double floor_abs,
-                                                double& c, double& s, double& rel2) {
+                                                double& c, double& s, bool& big) {
   // Entries at the rounding level of the whole matrix (floor_abs = 1e-17 * trace) or negligible
   // against their own diagonal pair are skipped: rotating them changes nothing that is kept, and
-  // between two numerically zero eigenvalues they would never settle.  Written without branches so
-  // that the two rotations a lane needs interleave.
+  // between two numerically zero eigenvalues they would never settle.  Written without branches.
   const bool live = fabs(apq) > floor_abs && fabs(apq) > 1e-40 * (fabs(app) + fabs(aqq));
   const double tau = (aqq - app) * 0.5 * __builtin_amdgcn_rcp(apq);
   const double root = __builtin_amdgcn_sqrt(fma(tau, tau, 1.0));
@@ -487,7 +488,7 @@ __device__ __forceinline__ void jacobi_rotation(double app, double aqq, double a
   const double cc = fast_rsqrt(fma(t, t, 1.0));
   c = live ? cc : 1.0;
   s = live ? t * cc : 0.0;
-  rel2 = live ? apq * apq * __builtin_amdgcn_rcp(fabs(app * aqq) + 1e-300) : 0.0;
+  big = live && apq * apq > kSettled2 * fabs(app * aqq);
 }
 
 // Pair `k` (0..7) of round `round` (0..14) of the round-robin schedule over 16 indices.
@@ -526,7 +527,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
 
   __shared__ double A[j1 * ld], V[j1 * ld], W[j1 * ld];
   __shared__ double P[(NWV > 1 ? NWV - 1 : 1) * j1 * ld];   // Gram partials of the other waves
-  __shared__ double lam[j1], sigma[j1], offs[8];
+  __shared__ double lam[j1], sigma[j1];
   __shared__ int order[j1];
 
   // ---- Gram matrix G[p][q] = sum_{t, b2} X[t, p*8+b2] X[t, q*8+b2] ----
@@ -580,8 +581,8 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   if (wv == solver) {
     // ---- parallel cyclic Jacobi: 15 rounds of 8 disjoint rotations per sweep ----
     // Lane (I, J) owns the 2 x 2 block rows(pair I) x columns(pair J) of the matrix and rows
-    // {2I, 2I+1} x columns(pair J) of the accumulated rotations; it derives both rotations itself
-    // from the three entries of each pair, so a round is: read, rotate, write.
+    // {2I, 2I+1} x columns(pair J) of the accumulated rotations; it derives the rotation of pair I
+    // from that pair's three entries and takes the one of pair J from lane (J, I).
     const int I = l >> 3, J = l & 7;
     double floor_abs = 0.0;
 #pragma unroll
@@ -590,7 +591,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     int sweeps = 0;
     for (int sweep = 0; sweep < 16; ++sweep) {
       ++sweeps;
-      double offmax = 0.0;
+      bool unsettled = false;
       // unrolled: the LDS addresses of a round depend only on the lane and are computed once
 #pragma unroll
       for (int round = 0; round < 15; ++round) {
@@ -598,14 +599,16 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
         pair16(round, I, p, q);
         pair16(round, J, u, v);
         const double app = A[p * ld + p], aqq = A[q * ld + q], apq = A[p * ld + q];
-        const double auu = A[u * ld + u], avv = A[v * ld + v], auv = A[u * ld + v];
         const double b00 = A[p * ld + u], b01 = A[p * ld + v], b10 = A[q * ld + u], b11 = A[q * ld + v];
         const int r0 = 2 * I * ld, r1 = r0 + ld;
         const double v00 = V[r0 + u], v01 = V[r0 + v], v10 = V[r1 + u], v11 = V[r1 + v];
-        double cI, sI, relI, cJ, sJ, relJ;
-        jacobi_rotation(app, aqq, apq, floor_abs, cI, sI, relI);
-        jacobi_rotation(auu, avv, auv, floor_abs, cJ, sJ, relJ);
-        offmax = fmax(offmax, relI);
+        // the rotation of the row pair is computed here; that of the column pair J is the row-pair
+        // rotation of the transposed lane (J, I)
+        double cI, sI;
+        bool big;
+        jacobi_rotation(app, aqq, apq, floor_abs, cI, sI, big);
+        const double cJ = __shfl(cI, 8 * J + I), sJ = __shfl(sI, 8 * J + I);
+        unsettled |= big;
         // Jm has Jm[p][p] = c, Jm[p][q] = s, Jm[q][p] = -s, Jm[q][q] = c;  A' = Jm^T A Jm,  V' = V Jm
         const double x00 = b00 * cJ - b01 * sJ, x01 = b00 * sJ + b01 * cJ;
         const double x10 = b10 * cJ - b11 * sJ, x11 = b10 * sJ + b11 * cJ;
@@ -621,15 +624,9 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
         // writes without waiting for them; the compiler only has to keep the order.
         __builtin_amdgcn_wave_barrier();
       }
-      if (J == 0) offs[I] = offmax;
-      __builtin_amdgcn_wave_barrier();
-      double om = 0.0;
-#pragma unroll
-      for (int i = 0; i < 8; ++i) om = fmax(om, offs[i]);
-      __builtin_amdgcn_wave_barrier();
-      // every entry rotated in this sweep was below 1e-6 of its diagonal pair, so the sweep (one more
-      // quadratic step) has left them near 1e-12
-      if (om < 1e-12) break;
+      // every entry rotated in this sweep was below 3e-5 of its diagonal pair, so the sweep (one
+      // more quadratic step) has left them near 1e-9, two orders under the fp32 rounding of T_L
+      if (!__any(unsettled)) break;
     }
 
     // ---- singular values, ordering, small tensor ----
