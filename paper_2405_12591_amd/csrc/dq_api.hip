@@ -11,17 +11,20 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 
 // Launch shape of the matrix-core kernel: n splits of every (sequence, kv head) and nw waves per
 // workgroup.  Measured on MI355X: a wave needs about eight 128-token tiles to amortise its start-up
-// and its share of the merge; about 2048 resident waves (8 per CU) stream fastest when they can be
-// had at that depth, 1024 (one 4-wave workgroup per CU) otherwise; every extra split costs a partial
-// write, a ticket and a merge.
-static void choose_mfma_shape(int units, int max_tiles, int* n_out, int* nw_out) {
+// and its share of the merge (four when it serves four query heads: more arithmetic per tile to
+// overlap); about 2048 resident waves (8 per CU) stream fastest when they can be had at that depth,
+// 1024 (one 4-wave workgroup per CU) otherwise; every extra split costs a partial write, a ticket
+// and a merge.  Small problems are bound by the fixed start-up and merge latencies: there one tile
+// per wave is best as long as every workgroup finds a compute unit of its own.
+static void choose_mfma_shape(int units, int max_tiles, int rep, int* n_out, int* nw_out) {
   auto tiles_per_wave = [&](int n, int nw) { return max_tiles / (n * nw); };
+  const int deep = rep >= 4 ? 4 : 8;
   // A: deep and wide
   for (int nw = 8; nw >= 4; nw -= 4) {
     const int cap = 256 * (8 / nw);            // workgroups resident on the chip
     for (int n = cap / units; n >= 1; --n) {
       if (n > kMaxSplits) continue;
-      if (tiles_per_wave(n, nw) >= 8 && (long)units * n * nw >= 1536) { *n_out = n; *nw_out = nw; return; }
+      if (tiles_per_wave(n, nw) >= deep && (long)units * n * nw >= 1536) { *n_out = n; *nw_out = nw; return; }
     }
   }
   // B: deep, at least half the chip
@@ -29,9 +32,10 @@ static void choose_mfma_shape(int units, int max_tiles, int* n_out, int* nw_out)
     if (n > kMaxSplits) continue;
     if (tiles_per_wave(n, 4) >= 8 && (long)units * n * 4 >= 512) { *n_out = n; *nw_out = 4; return; }
   }
-  // C: small problem: as many workgroups as leave two tiles per wave
+  // C: small problem: one tile per wave while a workgroup per compute unit is enough, else two
   for (int n = (512 / units < kMaxSplits ? 512 / units : kMaxSplits); n >= 1; --n) {
-    if (tiles_per_wave(n, 4) >= 2) { *n_out = n; *nw_out = 4; return; }
+    const int need = (units * n <= 256) ? 1 : 2;
+    if (tiles_per_wave(n, 4) >= need) { *n_out = n; *nw_out = 4; return; }
   }
   *n_out = 1; *nw_out = 4;
 }
@@ -42,7 +46,7 @@ int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int 
   int n = 1, nw = 4;
   if (max_tiles > 0) {
     if (mfma) {
-      choose_mfma_shape(batch * kv_heads, max_tiles, &n, &nw);
+      choose_mfma_shape(batch * kv_heads, max_tiles, q_heads / kv_heads, &n, &nw);
     } else {
       const int units = batch * q_heads;
       n = (2048 + units - 1) / units;

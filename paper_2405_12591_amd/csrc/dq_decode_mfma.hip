@@ -538,20 +538,53 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   }
   __syncthreads();
   if (!s_last) return;
+  // Wave hd reads the maxima and sums of head hd's partials, one slot per lane (all loads in
+  // flight together), and leaves each slot's weight in LDS; then every thread adds up its output
+  // element over the slots, eight device-scope loads at a time.
+  __shared__ float s_wgt[4][kMaxSplits + 1];
+  __shared__ float s_sum[4];
+  const int ns = a.n_slots;   // <= kMaxSplits + 1 (the tail's slot included)
+  if (wave < R) {
+    const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
+    float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
+    if (lane < ns) {
+      m0 = __hip_atomic_load(base + lane * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      l0 = __hip_atomic_load(base + lane * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    if (lane + 64 < ns) {
+      m1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      l1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    const float M = wave_allmax(fmaxf(m0, m1));
+    const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m0 - M);
+    const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - M);
+    if (lane < ns) s_wgt[wave][lane] = w0;
+    if (lane + 64 < ns) s_wgt[wave][lane + 64] = w1;
+    const float L = wave_allsum(l0 * w0 + l1 * w1);
+    if (lane == 0) s_sum[wave] = L;
+  }
+  __syncthreads();
   for (int idx = tid; idx < R * D; idx += 64 * NW) {
     const int hd = idx / D, c = idx % D;
-    const float* base = a.partials + (bhq0 + hd) * a.n_slots * (D + 2);   // the tail's slot included
-    float M = -INFINITY;
-    for (int sp = 0; sp < a.n_slots; ++sp)
-      M = fmaxf(M, __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT));
-    float o = 0.f, L = 0.f;
-    for (int sp = 0; sp < a.n_slots; ++sp) {
-      const float m = __hip_atomic_load(base + sp * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (m == -INFINITY) continue;
-      const float wgt = __builtin_amdgcn_exp2f(m - M);
-      L = fmaf(__hip_atomic_load(base + sp * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, L);
-      o = fmaf(__hip_atomic_load(base + sp * (D + 2) + c, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT), wgt, o);
+    const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
+    float o = 0.f;
+    int sp = 0;
+    for (; sp + 8 <= ns; sp += 8) {
+      float v[8];
+#pragma unroll
+      for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+      for (int k = 0; k < 8; ++k) {
+        const float wk = s_wgt[hd][sp + k];
+        o = (wk != 0.f) ? fmaf(v[k], wk, o) : o;   // an empty slot contributes nothing whatever it holds
+      }
     }
+    for (; sp < ns; ++sp) {
+      const float wk = s_wgt[hd][sp];
+      const float vk = __hip_atomic_load(col + sp * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      o = (wk != 0.f) ? fmaf(vk, wk, o) : o;
+    }
+    const float L = s_sum[hd];
     const float r = (L > 0.f) ? o / L : 0.f;
     a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
     if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
