@@ -16,11 +16,12 @@ void set_last_hip_error(hipError_t e) { g_last_hip_error.store((int)e); }
 // 1024 (one 4-wave workgroup per CU) otherwise; every extra split costs a partial write, a ticket
 // and a merge.  Small problems are bound by the fixed start-up and merge latencies: there one tile
 // per wave is best as long as every workgroup finds a compute unit of its own.
-static void choose_mfma_shape(int units, int max_tiles, int rep, int* n_out, int* nw_out) {
+static void choose_mfma_shape(int units, int max_tiles, int rep, int bits, int* n_out, int* nw_out) {
   auto tiles_per_wave = [&](int n, int nw) { return max_tiles / (n * nw); };
   const int deep = rep >= 4 ? 4 : 8;
-  // A: deep and wide
-  for (int nw = 8; nw >= 4; nw -= 4) {
+  // A: deep and wide (8-bit codes: a wave's ring of chunks is twice as large and an 8-wave
+  // workgroup would run out of registers)
+  for (int nw = (bits == 8 ? 4 : 8); nw >= 4; nw -= 4) {
     const int cap = 256 * (8 / nw);            // workgroups resident on the chip
     for (int n = cap / units; n >= 1; --n) {
       if (n > kMaxSplits) continue;
@@ -46,7 +47,7 @@ int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int 
   int n = 1, nw = 4;
   if (max_tiles > 0) {
     if (mfma) {
-      choose_mfma_shape(batch * kv_heads, max_tiles, q_heads / kv_heads, &n, &nw);
+      choose_mfma_shape(batch * kv_heads, max_tiles, q_heads / kv_heads, f->bits, &n, &nw);
     } else {
       const int units = batch * q_heads;
       n = (2048 + units - 1) / units;

@@ -9,6 +9,7 @@
 #include <hip/hip_ext.h>
 
 #include "dq_decode.h"
+#include "dq_tail.h"
 
 namespace dq {
 
@@ -200,59 +201,38 @@ int32_t launch_combine(const DecodeArgs& a, hipStream_t st) {
   return DQ_OK;
 }
 
-// The fp16 tail (tokens not yet compressed, Section 3.2) as one more partial result: plain fp32
-// attention of one query head over at most 256 rows.  m_unit converts the running maximum from
-// log2 units to the unit the merging kernel expects (1 for log2, ln 2 for natural logarithms).
+// The fp16 tail as a kernel of its own (for the plain fp32 decode path): one workgroup per
+// (sequence, kv head), query heads in groups of four; the partial goes to slot n_split.  m_unit
+// converts the running maximum from log2 units to the unit the merging kernel expects (ln 2 for
+// natural logarithms).
+template <int D>
 __global__ __launch_bounds__(256) void tail_partial_kernel(DecodeArgs a, float m_unit) {
-  const int d = a.fmt.head_dim;
-  const int bhq = blockIdx.x;
-  const int b = bhq / a.q_heads, hq = bhq % a.q_heads;
-  const int h = hq / (a.q_heads / a.cache.kv_heads);
-  const int tid = threadIdx.x;
-  const int cap = a.tail.capacity;
-  const int n_tail = min(max(a.tail.tail_lens[b], 0), cap);
-  __shared__ float qs[128];
-  __shared__ float ps[256];
-  __shared__ float red[8];
-  const uint16_t* kt = a.tail.k_tail + ((long)b * a.cache.kv_heads + h) * cap * d;
-  const uint16_t* vt = a.tail.v_tail + ((long)b * a.cache.kv_heads + h) * cap * d;
-  if (tid < d) qs[tid] = h2f(a.q[(long)bhq * d + tid]) * (a.scale * 1.4426950408889634f);
-  __syncthreads();
-  float s = -INFINITY;
-  if (tid < n_tail) {
-    float acc = 0.f;
-    for (int c = 0; c < d; c += 2) {
-      const uint32_t w = *reinterpret_cast<const uint32_t*>(kt + (long)tid * d + c);
-      acc = fmaf(h2f((uint16_t)(w & 0xFFFFu)), qs[c], acc);
-      acc = fmaf(h2f((uint16_t)(w >> 16)), qs[c + 1], acc);
+  typedef TailBlock<D, 4, 4> TB;
+  const int H = a.cache.kv_heads, rep = a.q_heads / H;
+  const int b = blockIdx.x / H, h = blockIdx.x % H;
+  __shared__ float scratch[TB::kScratchFloats];
+  __shared__ float result[TB::kResultFloats];
+  for (int hg = 0; hg < rep; hg += TB::HB) {
+    const int nh = min(TB::HB, rep - hg);
+    const long hq0 = (long)h * rep + hg;
+    const int tail_len = a.tail.tail_lens[b];
+    TB tb;
+    tb.issue_keys(a, b, h, hq0, nh);
+    tb.finish(tail_len, nh, scratch, result);
+    for (int idx = threadIdx.x; idx < nh * (D + 2); idx += 256) {
+      const int hd = idx / (D + 2), c = idx % (D + 2);
+      float v = result[idx];
+      if (c == D) v *= m_unit;   // -inf stays -inf
+      a.partials[(((long)b * a.q_heads + hq0 + hd) * a.n_slots + a.n_split) * (D + 2) + c] = v;
     }
-    s = acc;
-  }
-  float v = s;
-  for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
-  if ((tid & 63) == 0) red[tid >> 6] = v;
-  __syncthreads();
-  const float m = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
-  const float p = (tid < n_tail) ? exp2f(s - m) : 0.f;
-  ps[tid] = p;
-  float l = p;
-  for (int o = 32; o > 0; o >>= 1) l += __shfl_xor(l, o);
-  if ((tid & 63) == 0) red[4 + (tid >> 6)] = l;
-  __syncthreads();
-  float* part = a.partials + ((long)bhq * a.n_slots + a.n_split) * (d + 2);
-  if (tid < d) {
-    float o = 0.f;
-    for (int t = 0; t < n_tail; ++t) o = fmaf(ps[t], h2f(vt[(long)t * d + tid]), o);
-    part[tid] = o;
-  }
-  if (tid == 0) {
-    part[d] = (n_tail > 0) ? m * m_unit : -INFINITY;
-    part[d + 1] = red[4] + red[5] + red[6] + red[7];
+    __syncthreads();
   }
 }
 
 int32_t launch_tail_partial(const DecodeArgs& a, float m_unit, hipStream_t st) {
-  hipLaunchKernelGGL(tail_partial_kernel, dim3(a.cache.batch * a.q_heads), dim3(256), 0, st, a, m_unit);
+  const dim3 grid(a.cache.batch * a.cache.kv_heads);
+  if (a.fmt.head_dim == 128) hipLaunchKernelGGL(tail_partial_kernel<128>, grid, dim3(256), 0, st, a, m_unit);
+  else hipLaunchKernelGGL(tail_partial_kernel<64>, grid, dim3(256), 0, st, a, m_unit);
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
 }

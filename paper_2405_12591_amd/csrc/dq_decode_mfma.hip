@@ -35,6 +35,7 @@
 #include <type_traits>
 
 #include "dq_decode.h"
+#include "dq_tail.h"
 
 namespace dq {
 
@@ -130,7 +131,13 @@ __device__ __forceinline__ float pow2i(int e) {
 
 // BITS: code width.  NG: step groups per token row (group = 128 / NG).  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
 // of one (sequence, kv head) are dealt round-robin to the NW waves of each of its n_split workgroups.
-template <int BITS, int NG, int R, int NW>
+// TM: what to do about the fp16 tail (tokens not yet compressed).  0: there is none.  1: the launch
+// has one workgroup per (sequence, kv head), which works the tail off while its first codes are on
+// their way.  2: the launch has several workgroups per (sequence, kv head); the one of split 0 does
+// the same and hands the tail's partial in with its own.  (A workgroup of its own for the tail was
+// tried: on a full chip its few dependent loads take tens of microseconds behind the streams, and
+// the workgroups queued behind it start that much later.)
+template <int BITS, int NG, int R, int NW, int TM>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
   typedef Codec<BITS> C;
   typedef typename C::chunk_t chunk_t;
@@ -147,6 +154,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   constexpr int WAVE_LDS = QS_BYTES + PS_BYTES + SS_BYTES;
   static_assert(WAVE_LDS >= NC * D * 4 + 2 * R * 4, "merge area must fit the wave's LDS");
   __shared__ __attribute__((aligned(16))) unsigned char smem[NW * WAVE_LDS];
+  // the fp16 tail's partial result (computed once per (sequence, kv head), by split 0, before the
+  // first tile; its scratch borrows the waves' areas, which are not in use yet)
+  typedef TailBlock<D, NW, R> Tail;
+  static_assert(sizeof(smem) >= Tail::kScratchFloats * sizeof(float), "tail scratch must fit the waves' LDS");
+  __shared__ float s_tail[R * (D + 2)];
+  __shared__ int s_last;
+  __shared__ float s_wgt[4][kMaxSplits + 1];
+  __shared__ float s_sum[4];
 
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, g = lane >> 4;
@@ -166,6 +181,73 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const bool spec_ok = first_tile * kTileTokens < a.max_seq_len;
   int S = 0;  // the sequence's real length, read after the speculative loads are on their way
 
+  // ---- the last workgroup of this (sequence, kv head) to finish merges the partial results ----
+  const long bhq0 = (long)b * a.q_heads + (long)h * R;
+  const int n_contrib = a.n_split;   // workgroups that hand in partials
+  auto ticket_and_merge = [&]() __attribute__((always_inline)) {
+    // The barrier waits for every thread's stores above to be acknowledged; only then does one
+    // thread take a ticket.  The merging workgroup reads the partials with device-scope loads.
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();
+    if (tid == 0) {
+      const int ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_last = (ticket == n_contrib - 1);
+      if (s_last) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next call
+    }
+    __syncthreads();
+    if (!s_last) return;
+    // Wave hd reads the maxima and sums of head hd's partials, one slot per lane (all loads in
+    // flight together), and leaves each slot's weight in LDS; then every thread adds up its output
+    // element over the slots, eight device-scope loads at a time.
+    const int ns = a.n_slots;   // <= kMaxSplits + 1 (the tail's slot included)
+    if (wave < R) {
+      const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
+      float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
+      if (lane < ns) {
+        m0 = __hip_atomic_load(base + lane * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        l0 = __hip_atomic_load(base + lane * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      if (lane + 64 < ns) {
+        m1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        l1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      }
+      const float M = wave_allmax(fmaxf(m0, m1));
+      const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m0 - M);
+      const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - M);
+      if (lane < ns) s_wgt[wave][lane] = w0;
+      if (lane + 64 < ns) s_wgt[wave][lane + 64] = w1;
+      const float L = wave_allsum(l0 * w0 + l1 * w1);
+      if (lane == 0) s_sum[wave] = L;
+    }
+    __syncthreads();
+    for (int idx = tid; idx < R * D; idx += 64 * NW) {
+      const int hd = idx / D, c = idx % D;
+      const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
+      float o = 0.f;
+      int sp = 0;
+      for (; sp + 8 <= ns; sp += 8) {
+        float v[8];
+#pragma unroll
+        for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+#pragma unroll
+        for (int k = 0; k < 8; ++k) {
+          const float wk = s_wgt[hd][sp + k];
+          o = (wk != 0.f) ? fmaf(v[k], wk, o) : o;   // an empty slot contributes nothing whatever it holds
+        }
+      }
+      for (; sp < ns; ++sp) {
+        const float wk = s_wgt[hd][sp];
+        const float vk = __hip_atomic_load(col + sp * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        o = (wk != 0.f) ? fmaf(vk, wk, o) : o;
+      }
+      const float L = s_sum[hd];
+      const float r = (L > 0.f) ? o / L : 0.f;
+      a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
+      if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
+    }
+  };
+
+
   unsigned char* wl = smem + wave * WAVE_LDS;
   unsigned char* Qs = wl;                                        // [NC][8 row pairs][16 slots] bytes
   unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 token groups][16 slots] bytes
@@ -181,20 +263,22 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   else if (BITS == 2) { tA = 16 * G16 + 8 * (pi & 1) + (pi >> 1); tB = tA + 4; }
   else { tA = 16 * G16 + 2 * pi; tB = tA + 1; }
 
-  // ---- loop-invariant B operands of the fold: q[k = b1][n' = (b2, head)] ----
+  // loop-invariant B operands of the fold, q[k = b1][n' = (b2, head)].  The loads go out first (the
+  // memory counter retires in issue order and q is needed before the first codes); the values are
+  // packed further down, after the first tile's codes have been requested, so that the wait for q
+  // does not sit in front of those requests.
   half4 bq[F];
+  uint32_t q_raw[F][4];
   {
     const int b2 = n & 7;
 #pragma unroll
     for (int f = 0; f < F; ++f) {
       const int hd = 2 * f + (n >> 3);
-      half4 v = {0, 0, 0, 0};
-      if (hd < R) {
-        const uint16_t* qp = a.q + ((long)b * a.q_heads + (long)h * R + hd) * D;
+      // no branch here (columns past the last head read head R - 1 and are zeroed when packed):
+      // across a branch the compiler loses count of the loads in flight and waits for all of them
+      const uint16_t* qp = a.q + ((long)b * a.q_heads + (long)h * R + min(hd, R - 1)) * D;
 #pragma unroll
-        for (int i = 0; i < 4; ++i) v[i] = __builtin_bit_cast(_Float16, qp[(4 * g + i) * J2 + b2]);
-      }
-      bq[f] = v;
+      for (int i = 0; i < 4; ++i) q_raw[f][i] = qp[(4 * g + i) * J2 + b2];
     }
   }
 
@@ -448,14 +532,39 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     __builtin_amdgcn_wave_barrier();
   };
 
-  if (spec_ok) issue_tile(first_tile);   // in bounds: max_seq_len <= block_capacity * block_tokens
+  // The first requests go out in one straight line of code, without a branch: across a branch the
+  // compiler loses count of the loads in flight and makes every later wait a wait for all of them.
+  // So a wave whose first tile lies past max_seq_len reads tile 0 instead (in bounds: the cache
+  // holds at least one block) and throws it away, and with TM == 1 every row of the tail below its
+  // capacity is requested whatever the tail's length.  The tail's rows go first: they are worked
+  // off while the codes are on their way.
+  Tail tb;
+  const bool do_tail = (TM == 1) || (TM == 2 && split == 0);   // TM == 2: a branch, and coarser waits
+  if (do_tail) tb.issue_keys(a, b, h, (long)h * R, R);
+  issue_tile(spec_ok ? first_tile : 0);
+  // Both lengths are requested only now (a scalar load that is still out holds up every wait on
+  // scalar data, the addresses of the loads above among them) and before the asm statements below
+  // (after them the compiler no longer treats memory as unchanged and would fetch these with vector
+  // loads, whose wait covers the requests above).
+  const int seq_len_raw = a.seq_lens[b];
+  const int tail_len_raw = do_tail ? a.tail.tail_lens[b] : 0;
+#pragma unroll
+  for (int f = 0; f < F; ++f) {
+    const bool head_live = (2 * f + (n >> 3)) < R;
+#pragma unroll
+    for (int i = 0; i < 4; ++i) {
+      asm volatile("" : "+v"(q_raw[f][i]));   // nothing derived from q may move above the requests
+      bq[f][i] = __builtin_bit_cast(_Float16, (uint16_t)(head_live ? q_raw[f][i] : 0u));
+    }
+  }
+  if (do_tail) tb.finish(tail_len_raw, R, reinterpret_cast<float*>(smem), s_tail);
 
-  S = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  S = min(max(seq_len_raw, 0), a.max_seq_len);
   const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
   {
     int tile = first_tile;
     if (tile < tiles_total) {
-      if (!spec_ok) issue_tile(tile);
+      if (!spec_ok) issue_tile(tile);   // cannot happen while seq_len <= max_seq_len; kept for safety
       for (; tile + tile_stride < tiles_total; tile += tile_stride) compute_tile(tile, std::true_type{});
       compute_tile(tile, std::false_type{});
     }
@@ -478,7 +587,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     for (int hd = 0; hd < R; ++hd) { Mml[hd] = m_run[hd]; Mml[R + hd] = l_run[hd]; }
   }
   __syncthreads();
-  const long bhq0 = (long)b * a.q_heads + (long)h * R;
   for (int idx = tid; idx < R * D; idx += 64 * NW) {
     const int hd = idx / D, c = idx % D;
     float M = -INFINITY;
@@ -500,8 +608,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
     if (a.n_split == 1) {   // this workgroup saw the whole sequence: finish here
-      if (a.tail.k_tail) {  // fold in the fp16 tail's partial (written by the kernel launched before this one)
-        const float* tp = a.partials + ((bhq0 + hd) * a.n_slots + 1) * (D + 2);
+      if (TM == 1) {  // fold in the fp16 tail's partial
+        const float* tp = s_tail + hd * (D + 2);
         const float mt = tp[D];
         const float Mn = fmaxf(M, mt);
         const float w0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
@@ -521,74 +629,20 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // M in log2 units
         __hip_atomic_store(part + D + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
+      if (TM == 2 && split == 0) {   // the tail's partial travels with split 0's, in the slot after the splits
+        float* tpart = a.partials + ((bhq0 + hd) * a.n_slots + a.n_split) * (D + 2);
+        const float* tp = s_tail + hd * (D + 2);
+        __hip_atomic_store(tpart + c, tp[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (c == 0) {
+          __hip_atomic_store(tpart + D, tp[D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(tpart + D + 1, tp[D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        }
+      }
     }
   }
   if (a.n_split == 1) return;
 
-  // ---- the last workgroup of this (sequence, kv head) to arrive merges the split partials ----
-  // The barrier waits for every thread's stores above to be acknowledged; only then does one
-  // thread take a ticket.  The merging workgroup reads the partials with device-scope loads.
-  __shared__ int s_last;
-  __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-  __syncthreads();
-  if (tid == 0) {
-    const int ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    s_last = (ticket == a.n_split - 1);
-    if (s_last) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next call
-  }
-  __syncthreads();
-  if (!s_last) return;
-  // Wave hd reads the maxima and sums of head hd's partials, one slot per lane (all loads in
-  // flight together), and leaves each slot's weight in LDS; then every thread adds up its output
-  // element over the slots, eight device-scope loads at a time.
-  __shared__ float s_wgt[4][kMaxSplits + 1];
-  __shared__ float s_sum[4];
-  const int ns = a.n_slots;   // <= kMaxSplits + 1 (the tail's slot included)
-  if (wave < R) {
-    const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
-    float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
-    if (lane < ns) {
-      m0 = __hip_atomic_load(base + lane * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      l0 = __hip_atomic_load(base + lane * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    if (lane + 64 < ns) {
-      m1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      l1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-    }
-    const float M = wave_allmax(fmaxf(m0, m1));
-    const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m0 - M);
-    const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - M);
-    if (lane < ns) s_wgt[wave][lane] = w0;
-    if (lane + 64 < ns) s_wgt[wave][lane + 64] = w1;
-    const float L = wave_allsum(l0 * w0 + l1 * w1);
-    if (lane == 0) s_sum[wave] = L;
-  }
-  __syncthreads();
-  for (int idx = tid; idx < R * D; idx += 64 * NW) {
-    const int hd = idx / D, c = idx % D;
-    const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
-    float o = 0.f;
-    int sp = 0;
-    for (; sp + 8 <= ns; sp += 8) {
-      float v[8];
-#pragma unroll
-      for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-      for (int k = 0; k < 8; ++k) {
-        const float wk = s_wgt[hd][sp + k];
-        o = (wk != 0.f) ? fmaf(v[k], wk, o) : o;   // an empty slot contributes nothing whatever it holds
-      }
-    }
-    for (; sp < ns; ++sp) {
-      const float wk = s_wgt[hd][sp];
-      const float vk = __hip_atomic_load(col + sp * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      o = (wk != 0.f) ? fmaf(vk, wk, o) : o;
-    }
-    const float L = s_sum[hd];
-    const float r = (L > 0.f) ? o / L : 0.f;
-    a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
-    if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
-  }
+  ticket_and_merge();
 }
 
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
@@ -602,14 +656,21 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   return false;
 }
 
-template <int BITS, int NG, int R>
-static void launch_r(const DecodeArgs& a, hipStream_t st) {
+template <int BITS, int NG, int R, int TM>
+static void launch_tm(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   // the events, when given, receive the kernel's own begin and end timestamps
   if (a.nw == 8)
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
   else
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+}
+
+template <int BITS, int NG, int R>
+static void launch_r(const DecodeArgs& a, hipStream_t st) {
+  if (!a.tail.k_tail) launch_tm<BITS, NG, R, 0>(a, st);
+  else if (a.n_split == 1) launch_tm<BITS, NG, R, 1>(a, st);
+  else launch_tm<BITS, NG, R, 2>(a, st);
 }
 
 template <int BITS>
@@ -633,10 +694,6 @@ static int32_t launch_bits(const DecodeArgs& a, hipStream_t st) {
 }
 
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
-  if (a.tail.k_tail) {   // the tail's partial, with its maximum in log2 units like this path's
-    const int32_t rc = launch_tail_partial(a, 1.0f, st);
-    if (rc != DQ_OK) return rc;
-  }
   const int32_t rc = (a.fmt.bits == 8) ? launch_bits<8>(a, st)
                      : (a.fmt.bits == 4) ? launch_bits<4>(a, st) : launch_bits<2>(a, st);
   if (rc != DQ_OK) return rc;
