@@ -138,8 +138,39 @@ def test_compress_kv_properties(name, t_new, n_valid):
     w = _small(name, batch=3 if n_valid else 2, q_heads=4, kv_heads=2 if name == "gqa_long" else 4)
     w = _small(name, batch=w.batch, q_heads=w.q_heads, kv_heads=w.kv_heads,
                n_outlier=min(w.n_outlier, 8))
-    fmt, ofmt = formats(w)
     _say("compress_kv %s t_new=%d n_valid=%s" % (name, t_new, n_valid))
+    _check_compress(w, t_new, n_valid)
+
+
+@pytest.mark.parametrize("seed", [21, 22])
+def test_compress_kv_random_cases(seed, monkeypatch):
+    """Seeded sweep: code widths, group sizes, head dimensions, ragged n_valid (1, a few, full),
+    short t_new, skipped sequences, and forced waves-per-block of the decomposition kernel."""
+    rng = np.random.default_rng(seed)
+    for case in range(8):
+        d = int(rng.choice([128, 128, 64]))
+        j1 = 16 if d == 128 and rng.integers(0, 4) else int(rng.choice([8, 16] if d == 64 else [8, 32]))
+        bits = int(rng.choice([2, 4, 8]))
+        group = int(rng.choice([g for g in (32, 64, 128) if g <= d and (g == d or g <= d // 2) and (g * bits) % 32 == 0]))
+        tb = int(rng.choice([128, 256]))
+        batch, kvh = int(rng.choice([2, 3])), int(rng.choice([1, 2, 5]))
+        t_new = int(rng.choice([tb, tb, int(rng.integers(1, tb + 1))]))
+        n_valid = None if rng.integers(0, 2) else [int(rng.choice([1, 2, t_new, int(rng.integers(1, t_new + 1))])) for _ in range(batch)]
+        waves = str(rng.choice(["", "1", "2", "4"]))
+        if waves:
+            monkeypatch.setenv("DQ_COMPRESS_WAVES", waves)
+        else:
+            monkeypatch.delenv("DQ_COMPRESS_WAVES", raising=False)
+        w = _small("llama7b_4bit", batch=batch, q_heads=kvh, kv_heads=kvh, head_dim=d, j1=j1, j2=d // j1, bits=bits,
+                   group=group, block_tokens=tb, max_seq=tb, min_seq=tb, seed=4000 + 100 * seed + case,
+                   n_outlier=int(rng.choice([0, 2, 6])))
+        _say("compress_kv random seed %d case %d: d=%d j1=%d bits=%d G=%d Tb=%d B=%d H=%d t_new=%d n_valid=%s waves=%r"
+             % (seed, case, d, j1, bits, group, tb, batch, kvh, t_new, n_valid, waves))
+        _check_compress(w, t_new, n_valid)
+
+
+def _check_compress(w, t_new, n_valid):
+    fmt, ofmt = formats(w)
     tb, d, j1, j2 = fmt.block_tokens, fmt.head_dim, fmt.j1, fmt.j2
     k = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[0] for h in range(w.kv_heads)]) for b in range(w.batch)])
     v = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[1] for h in range(w.kv_heads)]) for b in range(w.batch)])
