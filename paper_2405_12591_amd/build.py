@@ -20,18 +20,39 @@ def sources():
     return sorted(glob.glob(os.path.join(PKG_DIR, "csrc", "*.hip")))
 
 
-def build_library(verbose: bool = False) -> str:
-    """Compile every HIP source into one shared library; returns its path."""
-    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    cmd = [hipcc, *HIPCC_FLAGS, "-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG_DIR, "csrc"),
-           *sources(), "-o", LIB_PATH + ".tmp"]
+def _run(cmd):
     proc = subprocess.run(cmd, capture_output=True, text=True)
     log = "\n".join(l for l in (proc.stdout + proc.stderr).splitlines() if "packed-fp32-ops" not in l)
-    if proc.returncode != 0:
-        raise RuntimeError("hipcc failed:\n" + log)
+    return proc.returncode, log
+
+
+def build_library(verbose: bool = False) -> str:
+    """Compile every HIP source (in parallel, one hipcc per file) and link one shared library;
+    returns its path."""
+    from concurrent.futures import ThreadPoolExecutor
+    hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
+    obj_dir = os.path.join(PKG_DIR, "_build")
+    os.makedirs(obj_dir, exist_ok=True)
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    includes = ["-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG_DIR, "csrc")]
+    jobs = []
+    for src in sources():
+        obj = os.path.join(obj_dir, os.path.basename(src) + ".o")
+        jobs.append((src, obj, [hipcc, *flags, *includes, "-c", src, "-o", obj]))
+    workers = max(1, min(len(jobs), int(os.environ.get("MAX_JOBS", "8")), os.cpu_count() or 1))
+    with ThreadPoolExecutor(workers) as pool:
+        results = list(pool.map(lambda j: _run(j[2]), jobs))
+    logs = []
+    for (src, _, _), (rc, log) in zip(jobs, results):
+        if rc != 0:
+            raise RuntimeError("hipcc failed on %s:\n%s" % (os.path.basename(src), log))
+        logs.append(log)
+    rc, log = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[j[1] for j in jobs], "-o", LIB_PATH + ".tmp"])
+    if rc != 0:
+        raise RuntimeError("link failed:\n" + log)
     os.replace(LIB_PATH + ".tmp", LIB_PATH)
-    if verbose and log.strip():
-        print(log)
+    if verbose and any(l.strip() for l in logs + [log]):
+        print("\n".join(l for l in logs + [log] if l.strip()))
     return LIB_PATH
 
 

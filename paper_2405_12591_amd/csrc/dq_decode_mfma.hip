@@ -1,649 +1,9 @@
-// Matrix-core decode attention over the compressed cache for the formats
-//   bits in {2, 4, 8};  group = 128 with q_heads / kv_heads in {1, 2, 4},
-//                       group = 64  with q_heads / kv_heads in {1, 2}
-// with head_dim = 128, j1 = 16, j2 = 8, block_tokens % 128 == 0.
-//
-// This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
-// 2405.12591) carried through the attention that follows it.  The low-bit codes never become
-// floating point: a 32-bit word of codes is split into words of four bytes each
-// (4-bit: x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F; 2-bit: (x >> 2k) & 0x03030303; 8-bit: x ^ 0x80808080) and fed to the
-// int8 matrix cores; the other operand (the folded query, then the softmax weights times the
-// value steps) is expressed as three 7-bit integer limbs relative to a per-tile power of two,
-// one B column per limb, so the contraction is exact integer arithmetic.  Per 128-token tile,
-// one wavefront
-//   1. folds the keys' small tensor into the query,  q'[r, b2] = sum_b1 T_S^K[b1, r] q[b1, b2]
-//      (one 16x16x16 f16 MFMA per two heads; T_S and q are fp16, so the products are exact),
-//      and writes the limbs of q' * scale * log2(e) as B operands;
-//   2. streams the key codes: S[t][limb] = sum_c u[t, c] limb[c]  (16x16x64 i8 MFMA,
-//      u = code + 2^(bits-1); the offset is removed with a constant-A MFMA);
-//   3. online softmax with two tokens per lane (scores cross from the MFMA layout through
-//      wave-private LDS); w_t = p_t * step^V_t is cut into limbs, again B columns;
-//   4. streams the value codes (stored token-contiguous): o'[r, b2] = sum_t u[t, r, b2] limb[t];
-//   5. applies the values' small tensor with fp32 16x16x4 MFMAs,
-//      acc[b1, b2] = alpha * acc + sum_r T_S^V[b1, r] o'[r, b2].
-// With two step groups per token row (group = 64: rows r < 8 and r >= 8 of the large tensor)
-// every limb gets one B column per group: the key side zeroes the limbs of the other group's
-// channels, the value side keeps only the rows of its group when o' enters the epilogue.
-// A query head takes 4 (one group) or 8 (two groups) of the sixteen B columns.
-//
-// MFMA operand layouts (lane l: n = l % 16, g = l / 16):
-//   A[m][k]: lane holds row m = n, k = S*g + i (S values per lane);  B[k][n]: column n, same k;
-//   D[m][n]: lane holds column n, rows m = 4*g + i.
-#include <hip/hip_ext.h>
-
-#include <cstdlib>
-#include <type_traits>
-
+// Host side of the matrix-core decode path: which formats it takes, and the launch.  The kernel
+// template lives in dq_decode_mfma_kernel.h; its instantiations are spread over one source file per
+// code width so that they compile in parallel.
 #include "dq_decode.h"
-#include "dq_tail.h"
 
 namespace dq {
-
-typedef _Float16 half4 __attribute__((ext_vector_type(4)));
-typedef float f32x4 __attribute__((ext_vector_type(4)));
-typedef int i32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x4 __attribute__((ext_vector_type(4)));
-typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
-
-constexpr float kLog2e = 1.4426950408889634f;
-constexpr int kLimbBits = 7;
-constexpr int kMantBits = 3 * kLimbBits;  // 21-bit integers: limb0 * 2^14 + limb1 * 2^7 + limb2
-
-// ---- per-bit-width pieces -------------------------------------------------------------------
-// Chunk: what one lane loads of a 16-row piece of codes (32 bytes at 8 bits, 16 at 4, 8 at 2); it
-// feeds two int8 MFMAs of 16 codes per lane each.  `slot(e)` is the byte position, inside the 16
-// bytes a lane hands to one MFMA, of the e-th of its 16 consecutive codes.
-template <int BITS> struct Codec;
-template <> struct Codec<4> {
-  typedef u32x4 chunk_t;
-  static constexpr int kOffset = 8;
-  // first MFMA: words x, y (codes 0..15 of the lane's 32); second: words z, w
-  static __device__ __forceinline__ i32x4 half(const chunk_t& c, int which) {
-    const uint32_t M = 0x0F0F0F0Fu;
-    const uint32_t x0 = which ? c.z : c.x, x1 = which ? c.w : c.y;
-    i32x4 v;
-    v.x = (int)(x0 & M);          // codes 0, 2, 4, 6
-    v.y = (int)((x0 >> 4) & M);   // codes 1, 3, 5, 7
-    v.z = (int)(x1 & M);          // codes 8, 10, 12, 14
-    v.w = (int)((x1 >> 4) & M);   // codes 9, 11, 13, 15
-    return v;
-  }
-  static __device__ __forceinline__ int slot(int e) { return (e & 8) + (e & 1) * 4 + ((e & 7) >> 1); }
-};
-template <> struct Codec<2> {
-  typedef u32x2 chunk_t;
-  static constexpr int kOffset = 2;
-  static __device__ __forceinline__ i32x4 half(const chunk_t& c, int which) {
-    const uint32_t M = 0x03030303u;
-    const uint32_t x = which ? c.y : c.x;
-    i32x4 v;
-    v.x = (int)(x & M);           // codes 0, 4, 8, 12
-    v.y = (int)((x >> 2) & M);    // codes 1, 5, 9, 13
-    v.z = (int)((x >> 4) & M);    // codes 2, 6, 10, 14
-    v.w = (int)((x >> 6) & M);    // codes 3, 7, 11, 15
-    return v;
-  }
-  static __device__ __forceinline__ int slot(int e) { return (e & 3) * 4 + (e >> 2); }
-};
-
-template <> struct Codec<8> {
-  typedef uint32_t chunk_t __attribute__((ext_vector_type(8)));
-  static constexpr int kOffset = 0;   // the stored byte becomes the signed code by flipping its top bit
-  static __device__ __forceinline__ i32x4 half(const chunk_t& c, int which) {
-    const uint32_t F = 0x80808080u;
-    i32x4 v;
-    v.x = (int)((which ? c.s4 : c.s0) ^ F);
-    v.y = (int)((which ? c.s5 : c.s1) ^ F);
-    v.z = (int)((which ? c.s6 : c.s2) ^ F);
-    v.w = (int)((which ? c.s7 : c.s3) ^ F);
-    return v;
-  }
-  static __device__ __forceinline__ int slot(int e) { return e; }
-};
-
-template <int CTRL>
-__device__ __forceinline__ float dpp_f(float v) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, __builtin_bit_cast(int, v), CTRL, 0xF, 0xF, true));
-}
-__device__ __forceinline__ float lane_f(float v, int l) {
-  return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
-}
-// all-reduce over the 16 lanes of a row, then over the four rows
-__device__ __forceinline__ float wave_allmax(float v) {
-  v = fmaxf(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
-  v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
-  v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
-  v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror
-  return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
-}
-__device__ __forceinline__ float wave_allsum(float v) {
-  v += dpp_f<0xB1>(v);
-  v += dpp_f<0x4E>(v);
-  v += dpp_f<0x141>(v);
-  v += dpp_f<0x140>(v);
-  return (lane_f(v, 0) + lane_f(v, 16)) + (lane_f(v, 32) + lane_f(v, 48));
-}
-
-// 2^e as a float for -126 <= e <= 127
-__device__ __forceinline__ float pow2i(int e) {
-  return __builtin_bit_cast(float, (uint32_t)(e + 127) << 23);
-}
-
-// BITS: code width.  NG: step groups per token row (group = 128 / NG).  R: query heads per kv head.  NW: wavefronts per workgroup (4 or 8); the tiles
-// of one (sequence, kv head) are dealt round-robin to the NW waves of each of its n_split workgroups.
-// TM: what to do about the fp16 tail (tokens not yet compressed).  0: there is none.  1: the launch
-// has one workgroup per (sequence, kv head), which works the tail off while its first codes are on
-// their way.  2: the launch has several workgroups per (sequence, kv head); the one of split 0 does
-// the same and hands the tail's partial in with its own.  (A workgroup of its own for the tail was
-// tried: on a full chip its few dependent loads take tens of microseconds behind the streams, and
-// the workgroups queued behind it start that much later.)
-template <int BITS, int NG, int R, int NW, int TM>
-__global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
-  typedef Codec<BITS> C;
-  typedef typename C::chunk_t chunk_t;
-  constexpr int CPH = 4 * NG;                 // B columns per head: column CPH*head + 4*group + limb
-  constexpr int NC = CPH * R;
-  static_assert(NC <= 16, "too many heads for sixteen B columns");
-  constexpr int F = (R + 1) / 2;              // fold MFMAs (two heads each)
-  constexpr int D = 128, J1 = 16, J2 = 8;
-  constexpr int ROWB = D * BITS / 8;          // bytes of a key row
-  constexpr int VROWB = kTileTokens * BITS / 8;   // bytes of a value row (one r, one b2) in a tile
-  constexpr int CHUNKB = sizeof(chunk_t);
-  constexpr int SS = 132;                     // ints per column of the score staging (128 tokens + bias + pad)
-  constexpr int QS_BYTES = NC * 128, PS_BYTES = NC * 128, SS_BYTES = NC * SS * 4;
-  constexpr int WAVE_LDS = QS_BYTES + PS_BYTES + SS_BYTES;
-  static_assert(WAVE_LDS >= NC * D * 4 + 2 * R * 4, "merge area must fit the wave's LDS");
-  __shared__ __attribute__((aligned(16))) unsigned char smem[NW * WAVE_LDS];
-  // the fp16 tail's partial result (computed once per (sequence, kv head), by split 0, before the
-  // first tile; its scratch borrows the waves' areas, which are not in use yet)
-  typedef TailBlock<D, NW, R> Tail;
-  static_assert(sizeof(smem) >= Tail::kScratchFloats * sizeof(float), "tail scratch must fit the waves' LDS");
-  __shared__ float s_tail[R * (D + 2)];
-  __shared__ int s_last;
-  __shared__ float s_wgt[4][kMaxSplits + 1];
-  __shared__ float s_sum[4];
-
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
-  const int n = lane & 15, g = lane >> 4;
-  const int split = blockIdx.x;
-  const int bh = blockIdx.y;
-  const int H = a.cache.kv_heads, NB = a.cache.block_capacity;
-  const int b = bh / H, h = bh % H;
-  const int tpb = a.fmt.block_tokens / kTileTokens;
-  const long codes_per_block = (long)a.fmt.block_tokens * ROWB;
-  const long scales_per_block = (long)a.fmt.block_tokens * NG;
-
-  // The sequence length lives in device memory and takes a memory round trip to read.  Tiles are dealt round-robin over all waves of all splits of this (sequence, kv head), so a wave's
-  // first tile does not depend on the sequence length and its loads can start before the length is
-  // known; they are wasted only if the sequence is shorter than that tile.
-  const int first_tile = split * NW + wave;
-  const int tile_stride = a.n_split * NW;
-  const bool spec_ok = first_tile * kTileTokens < a.max_seq_len;
-  int S = 0;  // the sequence's real length, read after the speculative loads are on their way
-
-  // ---- the last workgroup of this (sequence, kv head) to finish merges the partial results ----
-  const long bhq0 = (long)b * a.q_heads + (long)h * R;
-  const int n_contrib = a.n_split;   // workgroups that hand in partials
-  auto ticket_and_merge = [&]() __attribute__((always_inline)) {
-    // The barrier waits for every thread's stores above to be acknowledged; only then does one
-    // thread take a ticket.  The merging workgroup reads the partials with device-scope loads.
-    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();
-    if (tid == 0) {
-      const int ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      s_last = (ticket == n_contrib - 1);
-      if (s_last) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next call
-    }
-    __syncthreads();
-    if (!s_last) return;
-    // Wave hd reads the maxima and sums of head hd's partials, one slot per lane (all loads in
-    // flight together), and leaves each slot's weight in LDS; then every thread adds up its output
-    // element over the slots, eight device-scope loads at a time.
-    const int ns = a.n_slots;   // <= kMaxSplits + 1 (the tail's slot included)
-    if (wave < R) {
-      const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
-      float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
-      if (lane < ns) {
-        m0 = __hip_atomic_load(base + lane * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        l0 = __hip_atomic_load(base + lane * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      if (lane + 64 < ns) {
-        m1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        l1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      const float M = wave_allmax(fmaxf(m0, m1));
-      const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m0 - M);
-      const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - M);
-      if (lane < ns) s_wgt[wave][lane] = w0;
-      if (lane + 64 < ns) s_wgt[wave][lane + 64] = w1;
-      const float L = wave_allsum(l0 * w0 + l1 * w1);
-      if (lane == 0) s_sum[wave] = L;
-    }
-    __syncthreads();
-    for (int idx = tid; idx < R * D; idx += 64 * NW) {
-      const int hd = idx / D, c = idx % D;
-      const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
-      float o = 0.f;
-      int sp = 0;
-      for (; sp + 8 <= ns; sp += 8) {
-        float v[8];
-#pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-#pragma unroll
-        for (int k = 0; k < 8; ++k) {
-          const float wk = s_wgt[hd][sp + k];
-          o = (wk != 0.f) ? fmaf(v[k], wk, o) : o;   // an empty slot contributes nothing whatever it holds
-        }
-      }
-      for (; sp < ns; ++sp) {
-        const float wk = s_wgt[hd][sp];
-        const float vk = __hip_atomic_load(col + sp * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        o = (wk != 0.f) ? fmaf(vk, wk, o) : o;
-      }
-      const float L = s_sum[hd];
-      const float r = (L > 0.f) ? o / L : 0.f;
-      a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
-      if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
-    }
-  };
-
-
-  unsigned char* wl = smem + wave * WAVE_LDS;
-  unsigned char* Qs = wl;                                        // [NC][8 row pairs][16 slots] bytes
-  unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 token groups][16 slots] bytes
-  int* Ss = reinterpret_cast<int*>(wl + QS_BYTES + PS_BYTES);    // [NC][SS] ints
-  const bool col_live = (n < NC) && ((n & 3) != 3);
-  const int col_grp = (n >> 2) & (NG - 1);                       // step group of this lane's B column
-
-  // softmax layout: lane = 8*G16 + pi owns the two tokens of token group G16 whose weights sit in
-  // B slots 2*pi and 2*pi + 1
-  const int G16 = lane >> 3, pi = lane & 7;
-  int tA, tB;
-  if (BITS == 4) { tA = 16 * G16 + 8 * (pi >> 2) + ((0x5140 >> (4 * (pi & 3))) & 7); tB = tA + 2; }
-  else if (BITS == 2) { tA = 16 * G16 + 8 * (pi & 1) + (pi >> 1); tB = tA + 4; }
-  else { tA = 16 * G16 + 2 * pi; tB = tA + 1; }
-
-  // loop-invariant B operands of the fold, q[k = b1][n' = (b2, head)].  The loads go out first (the
-  // memory counter retires in issue order and q is needed before the first codes); the values are
-  // packed further down, after the first tile's codes have been requested, so that the wait for q
-  // does not sit in front of those requests.
-  half4 bq[F];
-  uint32_t q_raw[F][4];
-  {
-    const int b2 = n & 7;
-#pragma unroll
-    for (int f = 0; f < F; ++f) {
-      const int hd = 2 * f + (n >> 3);
-      // no branch here (columns past the last head read head R - 1 and are zeroed when packed):
-      // across a branch the compiler loses count of the loads in flight and waits for all of them
-      const uint16_t* qp = a.q + ((long)b * a.q_heads + (long)h * R + min(hd, R - 1)) * D;
-#pragma unroll
-      for (int i = 0; i < 4; ++i) q_raw[f][i] = qp[(4 * g + i) * J2 + b2];
-    }
-  }
-
-  float m_run[R], l_run[R];
-#pragma unroll
-  for (int hd = 0; hd < R; ++hd) { m_run[hd] = -INFINITY; l_run[hd] = 0.f; }
-  f32x4 acc[J2];
-#pragma unroll
-  for (int b2 = 0; b2 < J2; ++b2) acc[b2] = (f32x4){0.f, 0.f, 0.f, 0.f};
-
-  const float qk_scale = a.scale * kLog2e;
-  constexpr int kPlusWord = C::kOffset * 0x01010101;                       // four bytes of +offset
-  constexpr int kMinusWord = (int)((uint32_t)((256 - C::kOffset) & 255) * 0x01010101u);  // four bytes of -offset
-  const i32x4 a_plus = {kPlusWord, kPlusWord, kPlusWord, kPlusWord};
-  const i32x4 a_minus = {kMinusWord, kMinusWord, kMinusWord, kMinusWord};
-  const i32x4 izero = {0, 0, 0, 0};
-
-  // ---- the code stream of one wave: 16 chunks per tile (keys j = 0..7 in slots 0..7, values
-  // b2 = 0..7 in slots 8..15) flow through a 16-slot register ring; a slot is refilled in place
-  // with the same chunk of the wave's next tile as soon as it has been unpacked, so one whole
-  // tile per wave is in flight at all times.  The memory counter retires loads in issue order,
-  // so everything is requested in the order it will be used: the next tile's small tensors and
-  // steps first (needed before its first key chunk), then the refills.
-  chunk_t ring[16];
-  struct Side { u32x2 ksm, vsm; uint32_t dkA, dkB, dvA, dvB; };   // small tensors + the lane's steps
-  Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0};
-
-  auto tile_ptrs = [&](int tile, const unsigned char*& kc, const unsigned char*& vc, long& blkid, int& tib) {
-    blkid = (long)bh * NB + tile / tpb;
-    tib = tile % tpb;
-    kc = a.cache.k_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + CHUNKB * g;
-    vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * VROWB + CHUNKB * g;
-  };
-  auto load_steps = [&](const uint16_t* p, int t) -> uint32_t {   // the NG fp16 steps of token t
-    if (NG == 1) return p[t];
-    return *reinterpret_cast<const uint32_t*>(p + 2 * t);
-  };
-  auto load_side = [&](Side& sd, long blkid, int tib) {
-    sd.ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + blkid * (J1 * J1) + n * J1 + 4 * g);
-    sd.vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
-    const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens * NG;
-    const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens * NG;
-    sd.dkA = load_steps(ksc, tA); sd.dkB = load_steps(ksc, tB);
-    sd.dvA = load_steps(vsc, tA); sd.dvB = load_steps(vsc, tB);
-  };
-  auto issue_tile = [&](int tile) {
-    const unsigned char *kc, *vc;
-    long blkid;
-    int tib;
-    tile_ptrs(tile, kc, vc, blkid, tib);
-    load_side(cur, blkid, tib);
-    __builtin_amdgcn_sched_barrier(0);
-#pragma unroll
-    for (int j = 0; j < 8; ++j) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc + j * (16 * ROWB)));
-#pragma unroll
-    for (int b2 = 0; b2 < 8; ++b2) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc + b2 * (J1 * VROWB)));
-  };
-  auto step_of = [&](uint32_t packed, int grp) -> float {   // fp16 step of group grp from the packed word
-    return h2f((uint16_t)(grp ? (packed >> 16) : (packed & 0xFFFFu)));
-  };
-
-  // One tile.  HAS_NEXT: the wave has another tile after this one.
-  auto compute_tile = [&](const int tile, auto has_next_tag) __attribute__((always_inline)) {
-    constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
-    const int tok0 = tile * kTileTokens;
-    const unsigned char *kc_next = nullptr, *vc_next = nullptr;
-    long blkid_next = 0;
-    int tib_next = 0;
-    if (HAS_NEXT) tile_ptrs(tile + tile_stride, kc_next, vc_next, blkid_next, tib_next);
-    Side nxt = cur;
-    if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
-    __builtin_amdgcn_sched_barrier(0);
-    const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
-    float dvA[NG], dvB[NG], dkA[NG], dkB[NG];
-#pragma unroll
-    for (int gr = 0; gr < NG; ++gr) {
-      dvA[gr] = okA ? step_of(cur.dvA, gr) : 0.f;
-      dvB[gr] = okB ? step_of(cur.dvB, gr) : 0.f;
-      dkA[gr] = step_of(cur.dkA, gr);
-      dkB[gr] = step_of(cur.dkB, gr);
-    }
-    const half4 vsm_h = __builtin_bit_cast(half4, cur.vsm);
-
-    // ---- 1. fold T_S^K into q; limbs of q' relative to 2^e >= max |q'| ----
-    float q_unscale;
-    {
-      const half4 aK = __builtin_bit_cast(half4, cur.ksm);
-      f32x4 fd[F];
-      float amax = 0.f;
-#pragma unroll
-      for (int f = 0; f < F; ++f) {
-        fd[f] = __builtin_amdgcn_mfma_f32_16x16x16f16(aK, bq[f], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
-#pragma unroll
-        for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(fd[f][i]));
-      }
-      amax = wave_allmax(amax) * qk_scale;
-      int e = 0;
-      if (amax > 0.f && amax < INFINITY) e = __builtin_amdgcn_frexp_expf(amax);  // amax = f * 2^e, f in [0.5, 1)
-      e = max(min(e, 100), -100);
-      const float qn = qk_scale * pow2i(kMantBits - 1 - e);   // |q' * qn| < 2^20
-      q_unscale = pow2i(e - (kMantBits - 1));
-      // the fold's D layout: lane (n' = b2 + 8*head, g) holds rows r = 4g + i.  Channel (r, b2) is
-      // code number (r & 1)*8 + b2 of the 16 codes that row pair r >> 1 contributes to one MFMA.
-#pragma unroll
-      for (int f = 0; f < F; ++f) {
-        const int hd = 2 * f + (n >> 3);
-        if (hd < R) {
-#pragma unroll
-          for (int i = 0; i < 4; ++i) {
-            const int vi = (int)__builtin_rintf(fd[f][i] * qn);
-            const int r = 4 * g + i;
-            const int grp = (NG == 2) ? (r >> 3) : 0;
-            const int pos = (r >> 1) * 16 + C::slot((r & 1) * 8 + (n & 7));
-            unsigned char* dst = Qs + (CPH * hd + 4 * grp) * 128 + pos;
-            dst[0] = (unsigned char)(vi >> (2 * kLimbBits));
-            dst[128] = (unsigned char)((vi >> kLimbBits) & 127);
-            dst[256] = (unsigned char)(vi & 127);
-            if (NG == 2) {   // this channel contributes nothing to the other group's columns
-              unsigned char* oth = Qs + (CPH * hd + 4 * (1 - grp)) * 128 + pos;
-              oth[0] = 0; oth[128] = 0; oth[256] = 0;
-            }
-          }
-        }
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-    i32x4 bqs[2];
-#pragma unroll
-    for (int w = 0; w < 2; ++w) {
-      i32x4 t = izero;
-      if (col_live) t = *reinterpret_cast<const i32x4*>(Qs + n * 128 + (2 * g + w) * 16);
-      bqs[w] = t;
-    }
-
-    // ---- 2. scores: S[t][col] = sum_c u[t, c] limb[col][c];  bias row: offset * sum_c limb[col][c] ----
-    {
-      i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[0], izero, 0, 0, 0);
-      bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[1], bias, 0, 0, 0);
-      if (col_live && g == 0) Ss[n * SS + 128] = bias[0];
-      i32x4 s_prev = izero;
-#pragma unroll
-      for (int j = 0; j < 8; ++j) {
-        const i32x4 a0 = C::half(ring[j], 0), a1 = C::half(ring[j], 1);
-        __builtin_amdgcn_sched_barrier(0);   // the slot is dead from here on: refill it in place
-        if (HAS_NEXT) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc_next + j * (16 * ROWB)));
-        __builtin_amdgcn_sched_barrier(0);
-        i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bqs[0], izero, 0, 0, 0);
-        s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bqs[1], s, 0, 0, 0);
-        // the previous chunk's scores are stored while this chunk's MFMAs run
-        if (j > 0 && col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * (j - 1) + 4 * g) = s_prev;
-        s_prev = s;
-      }
-      if (col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * 7 + 4 * g) = s_prev;
-    }
-    __builtin_amdgcn_wave_barrier();
-
-    // ---- 3. online softmax, tokens tA and tB per lane ----
-    float v_unscale, vs;
-    {
-      float dvm = fmaxf(dvA[0], dvB[0]);
-      if (NG == 2) dvm = fmaxf(dvm, fmaxf(dvA[NG - 1], dvB[NG - 1]));
-      const float dvmax = wave_allmax(dvm);
-      int e = 0;
-      if (dvmax > 0.f && dvmax < INFINITY) e = __builtin_amdgcn_frexp_expf(dvmax);
-      vs = pow2i(kMantBits - e);   // p * step * vs < 2^21
-      v_unscale = pow2i(e - kMantBits);
-    }
-    float alpha[R];
-#pragma unroll
-    for (int hd = 0; hd < R; ++hd) {
-      float sA = 0.f, sB = 0.f;
-#pragma unroll
-      for (int gr = 0; gr < NG; ++gr) {
-        const int* s0 = Ss + (CPH * hd + 4 * gr) * SS;
-        const int* s1 = s0 + SS;
-        const int* s2 = s1 + SS;
-        const int b0 = s0[128], b1 = s1[128], b2v = s2[128];
-        sA += ((float)(s0[tA] - b0) * 16384.f + (float)(s1[tA] - b1) * 128.f + (float)(s2[tA] - b2v)) * dkA[gr];
-        sB += ((float)(s0[tB] - b0) * 16384.f + (float)(s1[tB] - b1) * 128.f + (float)(s2[tB] - b2v)) * dkB[gr];
-      }
-      sA = okA ? sA * q_unscale : -INFINITY;
-      sB = okB ? sB * q_unscale : -INFINITY;
-      const float mt = wave_allmax(fmaxf(sA, sB));
-      const float m_new = fmaxf(m_run[hd], mt);          // finite: the tile has a valid token
-      alpha[hd] = __builtin_amdgcn_exp2f(m_run[hd] - m_new);
-      const float pA = __builtin_amdgcn_exp2f(sA - m_new);
-      const float pB = __builtin_amdgcn_exp2f(sB - m_new);
-      l_run[hd] = l_run[hd] * alpha[hd] + (pA + pB);
-      m_run[hd] = m_new;
-#pragma unroll
-      for (int gr = 0; gr < NG; ++gr) {
-        const float wA = okA ? pA * (dvA[gr] * vs) : 0.f;
-        const float wB = okB ? pB * (dvB[gr] * vs) : 0.f;
-        const uint32_t iA = min((uint32_t)(wA + 0.5f), (1u << kMantBits) - 1u);
-        const uint32_t iB = min((uint32_t)(wB + 0.5f), (1u << kMantBits) - 1u);
-        unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
-        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((iA >> 14) | ((iB >> 14) << 8));
-        *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127u) | (((iB >> 7) & 127u) << 8));
-        *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127u) | ((iB & 127u) << 8));
-      }
-    }
-    __builtin_amdgcn_wave_barrier();
-
-    // ---- 4 + 5. o' = sum_t u limb per b2, then the small-tensor epilogue ----
-    i32x4 bp[2];
-#pragma unroll
-    for (int v = 0; v < 2; ++v) {
-      i32x4 t = izero;
-      if (col_live) t = *reinterpret_cast<const i32x4*>(Ps + n * 128 + (2 * g + v) * 16);
-      bp[v] = t;
-    }
-    float alpha_col = 1.f;
-#pragma unroll
-    for (int hd = 0; hd < R; ++hd) alpha_col = ((n / CPH) == hd) ? alpha[hd] : alpha_col;
-    float aT[4];
-#pragma unroll
-    for (int i = 0; i < 4; ++i) aT[i] = (float)vsm_h[i] * v_unscale;
-    // with two step groups a column's weights carry the step of one group only: rows r = 4g + i
-    // of the other group (g >= 2 for group 0, g < 2 for group 1) are dropped on the way in
-    const bool keep = (NG == 1) || ((g >> 1) == col_grp);
-    i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[0], izero, 0, 0, 0);
-    cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[1], cinitv, 0, 0, 0);
-    if (__any(alpha_col != 1.f)) {   // the running maximum moved: rare after the first tiles
-#pragma unroll
-      for (int b2 = 0; b2 < J2; ++b2) acc[b2] *= alpha_col;
-    }
-    auto epilogue = [&](int b2, const i32x4& o) __attribute__((always_inline)) {
-      f32x4 c = acc[b2];
-#pragma unroll
-      for (int i = 0; i < 4; ++i) {
-        float of = (float)o[i];
-        if (NG == 2) of = keep ? of : 0.f;
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], of, c, 0, 0, 0);
-      }
-      acc[b2] = c;
-    };
-    i32x4 o_prev = izero;
-#pragma unroll
-    for (int b2 = 0; b2 < J2; ++b2) {
-      const i32x4 a0 = C::half(ring[8 + b2], 0), a1 = C::half(ring[8 + b2], 1);
-      __builtin_amdgcn_sched_barrier(0);
-      if (HAS_NEXT) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc_next + b2 * (J1 * VROWB)));
-      __builtin_amdgcn_sched_barrier(0);
-      i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bp[0], cinitv, 0, 0, 0);
-      o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bp[1], o, 0, 0, 0);
-      if (b2 > 0) epilogue(b2 - 1, o_prev);   // while this b2's integer MFMAs run
-      o_prev = o;
-    }
-    epilogue(J2 - 1, o_prev);
-    cur = nxt;
-    __builtin_amdgcn_wave_barrier();
-  };
-
-  // The first requests go out in one straight line of code, without a branch: across a branch the
-  // compiler loses count of the loads in flight and makes every later wait a wait for all of them.
-  // So a wave whose first tile lies past max_seq_len reads tile 0 instead (in bounds: the cache
-  // holds at least one block) and throws it away, and with TM == 1 every row of the tail below its
-  // capacity is requested whatever the tail's length.  The tail's rows go first: they are worked
-  // off while the codes are on their way.
-  Tail tb;
-  const bool do_tail = (TM == 1) || (TM == 2 && split == 0);   // TM == 2: a branch, and coarser waits
-  if (do_tail) tb.issue_keys(a, b, h, (long)h * R, R);
-  issue_tile(spec_ok ? first_tile : 0);
-  // Both lengths are requested only now (a scalar load that is still out holds up every wait on
-  // scalar data, the addresses of the loads above among them) and before the asm statements below
-  // (after them the compiler no longer treats memory as unchanged and would fetch these with vector
-  // loads, whose wait covers the requests above).
-  const int seq_len_raw = a.seq_lens[b];
-  const int tail_len_raw = do_tail ? a.tail.tail_lens[b] : 0;
-#pragma unroll
-  for (int f = 0; f < F; ++f) {
-    const bool head_live = (2 * f + (n >> 3)) < R;
-#pragma unroll
-    for (int i = 0; i < 4; ++i) {
-      asm volatile("" : "+v"(q_raw[f][i]));   // nothing derived from q may move above the requests
-      bq[f][i] = __builtin_bit_cast(_Float16, (uint16_t)(head_live ? q_raw[f][i] : 0u));
-    }
-  }
-  if (do_tail) tb.finish(tail_len_raw, R, reinterpret_cast<float*>(smem), s_tail);
-
-  S = min(max(seq_len_raw, 0), a.max_seq_len);
-  const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
-  {
-    int tile = first_tile;
-    if (tile < tiles_total) {
-      if (!spec_ok) issue_tile(tile);   // cannot happen while seq_len <= max_seq_len; kept for safety
-      for (; tile + tile_stride < tiles_total; tile += tile_stride) compute_tile(tile, std::true_type{});
-      compute_tile(tile, std::false_type{});
-    }
-  }
-
-  // ---- merge the waves of the workgroup ----
-  float* Macc = reinterpret_cast<float*>(wl);            // [NC][128] per wave (reuses the wave's LDS)
-  float* Mml = Macc + NC * D;                            // [R] m, [R] l
-#pragma unroll
-  for (int hd = 0; hd < R; ++hd) l_run[hd] = wave_allsum(l_run[hd]);
-  if (col_live) {
-#pragma unroll
-    for (int b2 = 0; b2 < J2; ++b2) {
-#pragma unroll
-      for (int i = 0; i < 4; ++i) Macc[n * D + (4 * g + i) * J2 + b2] = acc[b2][i];
-    }
-  }
-  if (lane == 0) {
-#pragma unroll
-    for (int hd = 0; hd < R; ++hd) { Mml[hd] = m_run[hd]; Mml[R + hd] = l_run[hd]; }
-  }
-  __syncthreads();
-  for (int idx = tid; idx < R * D; idx += 64 * NW) {
-    const int hd = idx / D, c = idx % D;
-    float M = -INFINITY;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) M = fmaxf(M, reinterpret_cast<const float*>(smem + w * WAVE_LDS)[NC * D + hd]);
-    float o = 0.f, L = 0.f;
-#pragma unroll
-    for (int w = 0; w < NW; ++w) {
-      const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
-      const float mw = base[NC * D + hd];
-      const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      float v = 0.f;
-#pragma unroll
-      for (int gr = 0; gr < NG; ++gr) {
-        const float* col = base + (CPH * hd + 4 * gr) * D + c;
-        v += col[0] * 16384.f + col[D] * 128.f + col[2 * D];
-      }
-      o = fmaf(v, wgt, o);
-      L = fmaf(base[NC * D + R + hd], wgt, L);
-    }
-    if (a.n_split == 1) {   // this workgroup saw the whole sequence: finish here
-      if (TM == 1) {  // fold in the fp16 tail's partial
-        const float* tp = s_tail + hd * (D + 2);
-        const float mt = tp[D];
-        const float Mn = fmaxf(M, mt);
-        const float w0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
-        const float w1 = (mt == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mt - Mn);
-        o = o * w0 + tp[c] * w1;
-        L = L * w0 + tp[D + 1] * w1;
-      }
-      const float r = (L > 0.f) ? o / L : 0.f;
-      a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
-      if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
-    } else {
-      // device-scope stores: they go through to memory, past the per-XCD L2, so that a workgroup
-      // on another XCD can read them without any cache write-back or invalidation
-      float* part = a.partials + ((bhq0 + hd) * a.n_slots + split) * (D + 2);
-      __hip_atomic_store(part + c, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      if (c == 0) {
-        __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // M in log2 units
-        __hip_atomic_store(part + D + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      }
-      if (TM == 2 && split == 0) {   // the tail's partial travels with split 0's, in the slot after the splits
-        float* tpart = a.partials + ((bhq0 + hd) * a.n_slots + a.n_split) * (D + 2);
-        const float* tp = s_tail + hd * (D + 2);
-        __hip_atomic_store(tpart + c, tp[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        if (c == 0) {
-          __hip_atomic_store(tpart + D, tp[D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(tpart + D + 1, tp[D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        }
-      }
-    }
-  }
-  if (a.n_split == 1) return;
-
-  ticket_and_merge();
-}
 
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads % kv_heads) return false;
@@ -656,46 +16,14 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   return false;
 }
 
-template <int BITS, int NG, int R, int TM>
-static void launch_tm(const DecodeArgs& a, hipStream_t st) {
-  const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
-  // the events, when given, receive the kernel's own begin and end timestamps
-  if (a.nw == 8)
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
-  else
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
-}
-
-template <int BITS, int NG, int R>
-static void launch_r(const DecodeArgs& a, hipStream_t st) {
-  if (!a.tail.k_tail) launch_tm<BITS, NG, R, 0>(a, st);
-  else if (a.n_split == 1) launch_tm<BITS, NG, R, 1>(a, st);
-  else launch_tm<BITS, NG, R, 2>(a, st);
-}
-
-template <int BITS>
-static int32_t launch_bits(const DecodeArgs& a, hipStream_t st) {
-  const int rep = a.q_heads / a.cache.kv_heads;
-  if (a.fmt.group == 128) {
-    switch (rep) {
-      case 1: launch_r<BITS, 1, 1>(a, st); break;
-      case 2: launch_r<BITS, 1, 2>(a, st); break;
-      case 4: launch_r<BITS, 1, 4>(a, st); break;
-      default: return DQ_EINVAL;
-    }
-  } else {
-    switch (rep) {
-      case 1: launch_r<BITS, 2, 1>(a, st); break;
-      case 2: launch_r<BITS, 2, 2>(a, st); break;
-      default: return DQ_EINVAL;
-    }
-  }
-  return DQ_OK;
-}
+// defined in dq_decode_mfma_b8.hip, _b4.hip, _b2.hip
+int32_t launch_decode_mfma_b8(const DecodeArgs& a, hipStream_t st);
+int32_t launch_decode_mfma_b4(const DecodeArgs& a, hipStream_t st);
+int32_t launch_decode_mfma_b2(const DecodeArgs& a, hipStream_t st);
 
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st) {
-  const int32_t rc = (a.fmt.bits == 8) ? launch_bits<8>(a, st)
-                     : (a.fmt.bits == 4) ? launch_bits<4>(a, st) : launch_bits<2>(a, st);
+  const int32_t rc = (a.fmt.bits == 8) ? launch_decode_mfma_b8(a, st)
+                     : (a.fmt.bits == 4) ? launch_decode_mfma_b4(a, st) : launch_decode_mfma_b2(a, st);
   if (rc != DQ_OK) return rc;
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
