@@ -87,7 +87,8 @@ int32_t dq_version(void);
 const char* dq_status_string(int32_t status);
 int32_t dq_last_hip_error(void);
 
-/* 1 if the matrix-core decode kernel supports (format, q_heads / kv_heads), else 0. */
+/* 1 if the matrix-core decode kernel supports (format, q_heads / kv_heads), else 0: head_dim 128,
+ * j1 16, any code width; group 128 with q_heads / kv_heads in {1, 2, 4} or group 64 with {1, 2}. */
 int32_t dq_decode_mfma_supported(const dq_format* fmt, int32_t q_heads, int32_t kv_heads);
 
 /* Bytes of workspace dq_attn_decode needs for these sizes (0 on invalid arguments).  The
@@ -146,8 +147,11 @@ typedef struct dq_tail {
 
 /*
  * dq_attn_decode over the compressed tokens t < seq_lens[b] followed by the fp16 tail tokens:
- * one softmax over the union.  A small kernel turns the tail into one more partial result,
- * which the streaming kernel's merge folds in.  `tail` may be NULL (then this is dq_attn_decode).
+ * one softmax over the union.  The tail becomes one more partial result of the merge (computed
+ * inside the matrix-core kernel while its first codes are on their way; by a small kernel of its
+ * own ahead of the plain kernel).  Rows >= tail_lens[b] are read but never used: they may hold
+ * anything, but all `capacity` rows must be readable.  `tail` may be NULL (then this is
+ * dq_attn_decode).
  */
 int32_t dq_attn_decode_tail(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
                             int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
