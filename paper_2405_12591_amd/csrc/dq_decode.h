@@ -20,9 +20,21 @@ struct DecodeArgs {
   int n_slots;             // partial slots per (b, head): n_split, plus one for the fp16 tail
   dq_tail tail;            // k_tail == nullptr: no tail
   int nw;                  // waves per workgroup of the matrix-core kernel (4 or 8)
+  int unit_map;            // which (sequence, kv head) a workgroup row takes: 0 = its own index, see unit_of_row()
   hipEvent_t ev_start;     // optional: recorded around the main kernel
   hipEvent_t ev_stop;
 };
+
+// Which (sequence, kv head) unit the workgroups with blockIdx.y == row work on.  Workgroups go to
+// the XCDs round-robin, so with the plain mapping an XCD only ever sees the units of one residue
+// class mod 8, whose data sit at a fixed offset pattern in memory; the other mappings (bijections on
+// [0, units) whenever units is a multiple of 8) give it a different class, or all of them.
+__host__ __device__ inline int unit_of_row(int row, int units, int unit_map) {
+  if (unit_map == 0 || (units & 7)) return row;
+  const int j = row >> 3, k = row & 7;
+  if (unit_map == 1) return 8 * j + ((5 * k) & 7);   // another class per XCD
+  return 8 * j + ((k + j) & 7);                        // every class on every XCD
+}
 
 // Workspace carve-up shared by the host entry points.
 inline size_t decode_counter_bytes(int batch, int kv_heads) {

@@ -168,7 +168,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   const int n = lane & 15, g = lane >> 4;
   const int split = blockIdx.x;
-  const int bh = blockIdx.y;
+  const int bh = unit_of_row(blockIdx.y, gridDim.y, a.unit_map);
   const int H = a.cache.kv_heads, NB = a.cache.block_capacity;
   const int b = bh / H, h = bh % H;
   const int tpb = a.fmt.block_tokens / kTileTokens;
