@@ -186,9 +186,11 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
   a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, cache->kv_heads));
   a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, &a.nw);
-  // every residue class of units on every XCD: measured 3 % faster on the 256-unit benchmark shape
-  // (the XCDs finish closer together), neutral elsewhere
-  a.unit_map = 2;
+  // With one workgroup per compute unit and equal shares, a launch ends with its slowest XCD.
+  // Dealing the units so that every XCD sees every residue class of them (mod 8) brings the XCDs
+  // closer together: measured 4 - 5 % faster on the 256-unit benchmark shapes (4- and 8-bit), neutral
+  // or within half a percent either way on the other workloads, where the plain order stays.
+  a.unit_map = (a.n_split == 1 && cache->batch * cache->kv_heads <= 256) ? 3 : 0;
   if (const char* env = getenv("DQ_DECODE_UNIT_MAP")) a.unit_map = atoi(env);   // tuning aid
   a.n_slots = a.n_split + (tail ? 1 : 0);
   if (tail) a.tail = *tail;

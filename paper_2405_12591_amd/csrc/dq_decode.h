@@ -28,12 +28,17 @@ struct DecodeArgs {
 // Which (sequence, kv head) unit the workgroups with blockIdx.y == row work on.  Workgroups go to
 // the XCDs round-robin, so with the plain mapping an XCD only ever sees the units of one residue
 // class mod 8, whose data sit at a fixed offset pattern in memory; the other mappings (bijections on
-// [0, units) whenever units is a multiple of 8) give it a different class, or all of them.
+// [0, units) whenever units is a multiple of 8) give it a different class, all of them, or a
+// contiguous range of units.  Measured on the 256-unit benchmark shape (us per step): 0: 27.0,
+// 2: 25.9, 3: 25.7, 4: 26.5, 5: 25.7.
 __host__ __device__ inline int unit_of_row(int row, int units, int unit_map) {
   if (unit_map == 0 || (units & 7)) return row;
   const int j = row >> 3, k = row & 7;
   if (unit_map == 1) return 8 * j + ((5 * k) & 7);   // another class per XCD
-  return 8 * j + ((k + j) & 7);                        // every class on every XCD
+  if (unit_map == 3) return 8 * j + ((k + 3 * j) & 7);   // every class on every XCD (the default where it is used)
+  if (unit_map == 4 && (units & (units - 1)) == 0) return (row * 37) & (units - 1);   // scattered
+  if (unit_map == 5) return k * (units >> 3) + j;    // a contiguous range of units per XCD
+  return 8 * j + ((k + j) & 7);                        // every class on every XCD, neighbours shifted by one
 }
 
 // Workspace carve-up shared by the host entry points.
