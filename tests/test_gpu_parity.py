@@ -442,6 +442,61 @@ def test_decode_under_graph_capture_replays_identically():
         del scratch
 
 
+def test_serving_step_under_graph_capture_replays_identically():
+    """One serving step as a graph: compress a full block of appended rows into the next slot, then
+    decode over blocks + fp16 tail.  Neither call allocates, records a memset or reads a host value
+    that changes, so every replay must give the bits of the eager run."""
+    w = _small("llama7b_4bit", batch=2, q_heads=8, kv_heads=4, max_seq=768, min_seq=768)
+    fmt, ofmt = formats(w)
+    nb = 8
+    k, v = workloads.kv_tensor(w, 768)
+    kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
+    cache = dq.alloc_cache(fmt, w.batch, w.kv_heads, nb, DEV)
+    cws = dq.compress_workspace(fmt, w.batch, w.kv_heads, DEV)
+    for blk in range(5):                                   # five blocks already compressed
+        sl = slice(blk * 128, (blk + 1) * 128)
+        dq.compress_kv(cache, kd[:, :, sl].contiguous(), vd[:, :, sl].contiguous(),
+                       torch.full((w.batch,), blk, dtype=torch.int32, device=DEV), None, cws)
+    new_k, new_v = kd[:, :, 640:768].contiguous(), vd[:, :, 640:768].contiguous()   # the block being compressed
+    slot = torch.full((w.batch,), 5, dtype=torch.int32, device=DEV)
+    r = np.random.default_rng(9)
+    kt = torch.from_numpy((r.standard_normal((w.batch, w.kv_heads, 128, 128)) * 2).astype(np.float16)).to(DEV)
+    vt = torch.from_numpy((r.standard_normal((w.batch, w.kv_heads, 128, 128)) * 2).astype(np.float16)).to(DEV)
+    tl = torch.tensor([3, 100], dtype=torch.int32, device=DEV)
+    lens = torch.tensor([768, 700], dtype=torch.int32, device=DEV)
+    q = torch.from_numpy(workloads.query(w)).to(DEV)
+    ws = dq.decode_workspace(fmt, w.batch, w.q_heads, w.kv_heads, 768, DEV)
+
+    def step(out):
+        dq.compress_kv(cache, new_k, new_v, slot, None, cws)
+        dq.attn_decode(cache, q, lens, 768, ws, out=out, tail=(kt, vt, tl))
+
+    eager = torch.empty_like(q)
+    step(eager)
+    torch.cuda.synchronize()
+    eager_cache = {n: t.clone() for n, t in cache.t.items()}
+    out = torch.empty_like(q)
+    stream = torch.cuda.Stream()
+    graph = torch.cuda.CUDAGraph()
+    with torch.cuda.stream(stream):
+        step(out)                                            # warm-up on the capture stream
+        stream.synchronize()
+        with torch.cuda.graph(graph, stream=stream):
+            step(out)
+    torch.cuda.synchronize()
+    for rep in range(3):
+        out.fill_(float("nan"))
+        for t in cache.t.values():                           # the replay must rewrite slot 5 itself
+            t[:, :, 5].zero_()
+        scratch = torch.randn(1 << 20, device=DEV).sum()     # eager work between replays
+        graph.replay()
+        torch.cuda.synchronize()
+        assert torch.equal(out, eager), rep
+        for n, t in cache.t.items():
+            assert torch.equal(t, eager_cache[n]), (rep, n)
+        del scratch
+
+
 # ------------------------------------------------------------------------------------------
 # fp16 residual tail: tokens generated since the last compression (Section 3.2)
 # ------------------------------------------------------------------------------------------
