@@ -23,7 +23,7 @@
 //      acc[b1, b2] = alpha * acc + sum_r T_S^V[b1, r] o'[r, b2].
 // With two step groups per token row (group = 64: rows r < 8 and r >= 8 of the large tensor)
 // every limb gets one B column per group: the key side zeroes the limbs of the other group's
-// channels, the value side keeps only the rows of its group when o' enters the epilogue.
+// channels, the value side takes each row of o' from the column of that row's group.
 // A query head takes 4 (one group) or 8 (two groups) of the sixteen B columns.
 //
 // MFMA operand layouts (lane l: n = l % 16, g = l / 16):
@@ -148,6 +148,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   static_assert(NC <= 16, "too many heads for sixteen B columns");
   constexpr int F = (R + 1) / 2;              // fold MFMAs (two heads each)
   constexpr int D = 128, J1 = 16, J2 = 8;
+  // The epilogue multiplies o'[r][column] by the values' small tensor, sixteen columns at a time,
+  // but one b2 fills only 3 R of them (one limb triple per head, once the two step groups' columns
+  // have been merged): the columns of PK = 4 / R successive b2 are packed side by side first.
+  constexpr int PK = 4 / R, NSET = J2 / PK;
   constexpr int ROWB = D * BITS / 8;          // bytes of a key row
   constexpr int VROWB = kTileTokens * BITS / 8;   // bytes of a value row (one r, one b2) in a tile
   constexpr int CHUNKB = sizeof(chunk_t);
@@ -255,7 +259,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 token groups][16 slots] bytes
   int* Ss = reinterpret_cast<int*>(wl + QS_BYTES + PS_BYTES);    // [NC][SS] ints
   const bool col_live = (n < NC) && ((n & 3) != 3);
-  const int col_grp = (n >> 2) & (NG - 1);                       // step group of this lane's B column
+  // the epilogue's packed columns (see PK): column n holds head packed_head, slot packed_slot of its set
+  const int packed_head = (R == 1) ? 0 : (R == 4) ? (n >> 2) : (NG == 1) ? ((n >> 2) & 1) : (n >> 3);
+  const int packed_slot = (R == 1) ? (n >> 2) : (R == 4) ? 0 : (NG == 1) ? (n >> 3) : ((n >> 2) & 1);
 
   // softmax layout: lane = 8*G16 + pi owns the two tokens of token group G16 whose weights sit in
   // B slots 2*pi and 2*pi + 1
@@ -287,9 +293,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   float m_run[R], l_run[R];
 #pragma unroll
   for (int hd = 0; hd < R; ++hd) { m_run[hd] = -INFINITY; l_run[hd] = 0.f; }
-  f32x4 acc[J2];
+  f32x4 acc[NSET];
 #pragma unroll
-  for (int b2 = 0; b2 < J2; ++b2) acc[b2] = (f32x4){0.f, 0.f, 0.f, 0.f};
+  for (int st = 0; st < NSET; ++st) acc[st] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const float qk_scale = a.scale * kLog2e;
   constexpr int kPlusWord = C::kOffset * 0x01010101;                       // four bytes of +offset
@@ -398,10 +404,6 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
             dst[0] = (unsigned char)(vi >> (2 * kLimbBits));
             dst[128] = (unsigned char)((vi >> kLimbBits) & 127);
             dst[256] = (unsigned char)(vi & 127);
-            if (NG == 2) {   // this channel contributes nothing to the other group's columns
-              unsigned char* oth = Qs + (CPH * hd + 4 * (1 - grp)) * 128 + pos;
-              oth[0] = 0; oth[128] = 0; oth[256] = 0;
-            }
           }
         }
       }
@@ -494,30 +496,44 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     }
     float alpha_col = 1.f;
 #pragma unroll
-    for (int hd = 0; hd < R; ++hd) alpha_col = ((n / CPH) == hd) ? alpha[hd] : alpha_col;
+    for (int hd = 0; hd < R; ++hd) alpha_col = (packed_head == hd) ? alpha[hd] : alpha_col;
     float aT[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) aT[i] = (float)vsm_h[i] * v_unscale;
-    // with two step groups a column's weights carry the step of one group only: rows r = 4g + i
-    // of the other group (g >= 2 for group 0, g < 2 for group 1) are dropped on the way in
-    const bool keep = (NG == 1) || ((g >> 1) == col_grp);
     i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[0], izero, 0, 0, 0);
     cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[1], cinitv, 0, 0, 0);
     if (__any(alpha_col != 1.f)) {   // the running maximum moved: rare after the first tiles
 #pragma unroll
-      for (int b2 = 0; b2 < J2; ++b2) acc[b2] *= alpha_col;
+      for (int st = 0; st < NSET; ++st) acc[st] *= alpha_col;
     }
-    auto epilogue = [&](int b2, const i32x4& o) __attribute__((always_inline)) {
-      f32x4 c = acc[b2];
+    // o' of one b2 arrives with column 4*(NG*head + group) + limb.  pack() puts it into the
+    // set's B operand: with two step groups a column's weights carry the step of one group only,
+    // so rows r = 4g + i < 8 are taken from the first group's column and rows >= 8 from the second
+    // group's (four lanes further on), which leaves one limb triple per head; then the triple
+    // moves to the bank of four columns that slot k = b2 % PK owns.
+    auto pack = [&](i32x4& pk, i32x4 o, auto k_tag) __attribute__((always_inline)) {
+      constexpr int K = decltype(k_tag)::value % PK;
 #pragma unroll
       for (int i = 0; i < 4; ++i) {
-        float of = (float)o[i];
-        if (NG == 2) of = keep ? of : 0.f;
-        c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], of, c, 0, 0, 0);
+        int v = o[i];
+        if (NG == 2) v = __builtin_amdgcn_update_dpp(v, v, 0x104 /* row_shl:4 */, 0xC, 0x5, false);
+        if (K == 0) {
+          pk[i] = v;
+        } else {
+          // live banks after the merge: R = 1: {0};  R = 2: {0, 1} (one group), {0, 2} (two groups)
+          constexpr int kShift = (R == 2 && NG == 1) ? 8 * K : 4 * K;
+          constexpr int kBanks = ((R == 1) ? 0x1 : (NG == 1) ? 0x3 : 0x5) << (kShift / 4);
+          pk[i] = __builtin_amdgcn_update_dpp(pk[i], v, 0x110 + kShift /* row_shr */, 0xF, kBanks, false);
+        }
       }
-      acc[b2] = c;
     };
-    i32x4 o_prev = izero;
+    auto epilogue = [&](int st, const i32x4& pk) __attribute__((always_inline)) {
+      f32x4 c = acc[st];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)pk[i], c, 0, 0, 0);
+      acc[st] = c;
+    };
+    i32x4 pk_cur = izero, pk_done = izero;
 #pragma unroll
     for (int b2 = 0; b2 < J2; ++b2) {
       const i32x4 a0 = C::half(ring[8 + b2], 0), a1 = C::half(ring[8 + b2], 1);
@@ -526,10 +542,15 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       __builtin_amdgcn_sched_barrier(0);
       i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bp[0], cinitv, 0, 0, 0);
       o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bp[1], o, 0, 0, 0);
-      if (b2 > 0) epilogue(b2 - 1, o_prev);   // while this b2's integer MFMAs run
-      o_prev = o;
+      // the previous set's epilogue runs while this b2's integer MFMAs do
+      if (b2 > 0 && b2 % PK == 0) epilogue(b2 / PK - 1, pk_done);
+      if (b2 % PK == 0) pack(pk_cur, o, std::integral_constant<int, 0>{});
+      else if (b2 % PK == 1) pack(pk_cur, o, std::integral_constant<int, 1>{});
+      else if (b2 % PK == 2) pack(pk_cur, o, std::integral_constant<int, 2>{});
+      else pack(pk_cur, o, std::integral_constant<int, 3>{});
+      if (b2 % PK == PK - 1) pk_done = pk_cur;
     }
-    epilogue(J2 - 1, o_prev);
+    epilogue(NSET - 1, pk_done);
     cur = nxt;
     __builtin_amdgcn_wave_barrier();
   };
@@ -561,6 +582,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   }
   if (do_tail) tb.finish(tail_len_raw, R, reinterpret_cast<float*>(smem), s_tail);
 
+  if (NG == 2) {
+    // A channel contributes nothing to the other group's columns: those bytes of the query limbs
+    // are the same in every tile and are zeroed once (the fold writes only its own group's).
+    static_assert(QS_BYTES % 16 == 0, "");
+    for (int o = lane * 16; o < QS_BYTES; o += 64 * 16) *reinterpret_cast<i32x4*>(Qs + o) = izero;
+    __builtin_amdgcn_wave_barrier();
+  }
   S = min(max(seq_len_raw, 0), a.max_seq_len);
   const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
   {
@@ -577,11 +605,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   float* Mml = Macc + NC * D;                            // [R] m, [R] l
 #pragma unroll
   for (int hd = 0; hd < R; ++hd) l_run[hd] = wave_allsum(l_run[hd]);
-  if (col_live) {
+  if ((n & 3) != 3) {   // [head][limb][channel b1 * 8 + b2]
 #pragma unroll
-    for (int b2 = 0; b2 < J2; ++b2) {
+    for (int st = 0; st < NSET; ++st) {
 #pragma unroll
-      for (int i = 0; i < 4; ++i) Macc[n * D + (4 * g + i) * J2 + b2] = acc[b2][i];
+      for (int i = 0; i < 4; ++i) Macc[(4 * packed_head + (n & 3)) * D + (4 * g + i) * J2 + st * PK + packed_slot] = acc[st][i];
     }
   }
   if (lane == 0) {
@@ -600,12 +628,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
       const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      float v = 0.f;
-#pragma unroll
-      for (int gr = 0; gr < NG; ++gr) {
-        const float* col = base + (CPH * hd + 4 * gr) * D + c;
-        v += col[0] * 16384.f + col[D] * 128.f + col[2 * D];
-      }
+      const float* col = base + 4 * hd * D + c;
+      const float v = col[0] * 16384.f + col[D] * 128.f + col[2 * D];
       o = fmaf(v, wgt, o);
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
