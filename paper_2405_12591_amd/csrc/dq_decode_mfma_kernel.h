@@ -169,7 +169,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   __shared__ float s_wgt[4][kMaxSplits + 1];
   __shared__ float s_sum[4];
 
-  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  const int tid = threadIdx.x, lane = tid & 63;
+  // the wave's number as a scalar: everything derived from it (its tiles, their addresses) is then
+  // computed once per wave on the scalar unit instead of once per lane
+  const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
   const int split = blockIdx.x;
   const int bh = unit_of_row(blockIdx.y, gridDim.y, a.unit_map);
