@@ -20,13 +20,20 @@ What follows which passage of the paper
                                    ordinary attention); "Kernel Fusion for Dequantization"
                                    (scale x integer, then the product of T_L and T_S)
   * compression ratio mu           Section 3.3, Eq. 4
+  * n = 3 variant (T_1 x T_2 x T_3, middle tensor quantized)
+                                   Preliminary, Eq. 2 with n = 3; Section 4.3 "Analysis of
+                                   Length of Local Tensors"
 
 Readings taken where the paper is silent (each is listed in the design notes of
 the repository): per-head blocks of `block_tokens` rows; i_1 = 1 so the small
 tensor mixes only channels; no bond truncation; singular values kept in the
 small tensor; per-group fp16 steps with groups of `group` consecutive elements
 inside one token row of the large tensor; ties round to even; 2-bit uses the
-literal Eq. 1 levels {-1, 0, +1}; codes stored offset-binary.
+literal Eq. 1 levels {-1, 0, +1}; codes stored offset-binary.  Three local tensors
+(`i3` > 1): factors I = 1 * (T_b/i3) * i3, J = j1 * j2 * 1, so the third tensor mixes
+the i3 tokens of a run of consecutive tokens; the singular values of the first cut stay in
+T_1 and those of the second cut in T_3, which leaves the quantized middle tensor T_2 with
+orthonormal columns.
 
 Parity pins (tests/test_oracle_*.py): exact reconstruction <= 1e-10, orthonormal
 rows of T_L, textbook SVD special cases, exact-rational brute force of the
@@ -53,6 +60,7 @@ class Format:
     j1: int
     j2: int
     block_tokens: int
+    i3: int = 1   # 1: two local tensors; > 1: three, the third one i3 x i3 on the token side
 
     def check(self) -> None:
         if self.bits not in (2, 4, 8):
@@ -63,6 +71,8 @@ class Format:
             raise ValueError("group must divide head_dim")
         if self.block_tokens % TILE_TOKENS:
             raise ValueError("block_tokens must be a multiple of %d" % TILE_TOKENS)
+        if self.i3 < 1 or self.block_tokens % self.i3:
+            raise ValueError("i3 must divide block_tokens")
 
     @property
     def qmax(self) -> int:
@@ -167,6 +177,51 @@ def as_local_tensors(t_s: np.ndarray, t_l: np.ndarray, i1: int, j1: int, i2: int
     """View (T_S, T_L) of `mpo_split` as the two 4-index local tensors of Eq. 2."""
     d = t_s.shape[1]
     return [t_s.reshape(1, i1, j1, d), t_l.reshape(d, i2, j2, 1)]
+
+
+def mpo3_split(x: np.ndarray, j1: int, i3: int) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
+    """Three-site MPO of X[T_b, d] (Eq. 2 with n = 3) for the factor shapes
+    I = 1 * i2 * i3, J = j1 * j2 * 1:  X[(a2, a3), (b1, b2)] = sum_{r, e} T_1[b1, r] T_2[r, a2, b2, e] T_3[e, a3].
+
+    Two SVDs, no truncation.  The first is `mpo_split` (T_1 = U S, bond r of size j1); its right
+    factor, regrouped as A[(r, a2, b2), a3], is cut again: A = U' S' V'^T, T_2 = U' (orthonormal
+    columns, the large tensor), T_3 = S' V'^T (i3 x i3, bond e first).  Returns
+    (T_1 [j1, j1], T_2 [j1, i2, j2, i3], T_3 [i3, i3]).  Each (column of T_2, row of T_3) pair is
+    sign-flipped so that the largest-magnitude entry of the T_3 row is positive (reproducibility
+    only).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    n_tok, d = x.shape
+    j2, i2 = d // j1, n_tok // i3
+    if i2 * i3 != n_tok:
+        raise ValueError("i3 must divide the number of rows")
+    t_1, right = mpo_split(x, j1)                       # right[r, (t, b2)], t = a2*i3 + a3
+    a = right.reshape(j1, i2, i3, j2).transpose(0, 1, 3, 2).reshape(j1 * i2 * j2, i3)
+    u, s, vt = np.linalg.svd(a, full_matrices=False)
+    t_3 = s[:, None] * vt
+    piv = np.argmax(np.abs(t_3), axis=1)
+    sign = np.where(t_3[np.arange(t_3.shape[0]), piv] < 0, -1.0, 1.0)
+    return t_1, (u * sign[None, :]).reshape(j1, i2, j2, i3), t_3 * sign[:, None]
+
+
+def mpo3_contract(t_1: np.ndarray, t_2: np.ndarray, t_3: np.ndarray) -> np.ndarray:
+    """X[(a2, a3), (b1, b2)] from the three local tensors of `mpo3_split`, term by term."""
+    j1, i2, j2, i3 = t_2.shape
+    x = np.einsum("br,racd,de->aebc", t_1, t_2, t_3)    # [a2, a3, b1, b2]
+    return x.reshape(i2 * i3, j1 * j2)
+
+
+def middle_to_token_major(t_2: np.ndarray) -> np.ndarray:
+    """T_2[r, a2, b2, e] -> rows (a2, e), elements r*j2 + b2, rounded to fp32: the same row layout
+    as the two-tensor large tensor, with the bond index e in the place of the token a3."""
+    j1, i2, j2, i3 = t_2.shape
+    return np.ascontiguousarray(t_2.transpose(1, 3, 0, 2).reshape(i2 * i3, j1 * j2)).astype(np.float32)
+
+
+def token_major_to_middle(kp: np.ndarray, j1: int, j2: int, i3: int) -> np.ndarray:
+    """Inverse layout change of `middle_to_token_major` (values untouched)."""
+    i2 = kp.shape[0] // i3
+    return kp.reshape(i2, i3, j1, j2).transpose(2, 0, 3, 1)
 
 
 # --------------------------------------------------------------------------------------
@@ -289,6 +344,7 @@ class Block:
     steps: np.ndarray    # fp16 [block_tokens, head_dim/group]
     codes: np.ndarray    # int32 [block_tokens, head_dim], element index r*j2 + b2
     large32: np.ndarray  # fp32 [block_tokens, head_dim], the unquantized large tensor, token-major
+    small3: Optional[np.ndarray] = None   # fp16 [i3 (bond e), i3 (token a3)]   T_3, three tensors only
 
 
 def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
@@ -304,35 +360,59 @@ def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
     n = x.shape[0] if n_valid is None else n_valid
     xb = np.zeros((tb, d), np.float64)
     xb[:n] = np.asarray(x[:n], dtype=np.float64)
-    if identity_small:
-        t_s = np.eye(fmt.j1)
-        t_l = matricise(xb, 1, fmt.j1)
+    small3 = None
+    if fmt.i3 > 1:
+        if identity_small or sigma_in != "small":
+            raise ValueError("the three-tensor form has no identity / sigma-in-large variant")
+        t_s, t_2, t_3 = mpo3_split(xb, fmt.j1, fmt.i3)
+        kp = middle_to_token_major(t_2)
+        with np.errstate(over="ignore"):
+            small3 = t_3.astype(np.float16)
     else:
-        t_s, t_l = mpo_split(xb, fmt.j1, 1, sigma_in)
-    kp = large_to_token_major(t_l, tb, fmt.j2)
+        if identity_small:
+            t_s = np.eye(fmt.j1)
+            t_l = matricise(xb, 1, fmt.j1)
+        else:
+            t_s, t_l = mpo_split(xb, fmt.j1, 1, sigma_in)
+        kp = large_to_token_major(t_l, tb, fmt.j2)
     steps = group_steps(kp, fmt.group, fmt.qmax)
     codes = quantize_codes(kp, steps, fmt.group, fmt.qmax)
     with np.errstate(over="ignore"):
         small = t_s.astype(np.float16)
-    return Block(small=small, steps=steps, codes=codes, large32=kp)
+    return Block(small=small, steps=steps, codes=codes, large32=kp, small3=small3)
 
 
-def reconstruct_block(small: np.ndarray, steps: np.ndarray, codes: np.ndarray, fmt: Format
-                      ) -> np.ndarray:
-    """X_hat[block_tokens, head_dim] = un-matricise(T_S16 @ (Delta * c)) in fp64, no rounding."""
+def reconstruct_block(small: np.ndarray, steps: np.ndarray, codes: np.ndarray, fmt: Format,
+                      small3: Optional[np.ndarray] = None) -> np.ndarray:
+    """X_hat[block_tokens, head_dim] = un-matricise(T_S16 @ (Delta * c)) in fp64, no rounding.
+    Three tensors: the dequantized middle tensor is first multiplied by T_3 (fp16 values) over
+    the bond e, which gives the right factor of the first cut back."""
     # rows past the valid tokens of a partly filled block may hold anything (NaN steps included)
     with np.errstate(invalid="ignore", over="ignore"):
-        t_l_hat = token_major_to_large(dequantize(codes, steps, fmt.group), fmt.j1, fmt.j2)
+        deq = dequantize(codes, steps, fmt.group)
+        if fmt.i3 > 1:
+            t_2_hat = token_major_to_middle(deq, fmt.j1, fmt.j2, fmt.i3)          # [r, a2, b2, e]
+            right = np.einsum("racd,de->raec", t_2_hat, small3.astype(np.float64))  # [r, a2, a3, b2]
+            t_l_hat = right.reshape(fmt.j1, fmt.block_tokens * fmt.j2)
+        else:
+            t_l_hat = token_major_to_large(deq, fmt.j1, fmt.j2)
         m_hat = small.astype(np.float64) @ t_l_hat
     return unmatricise(m_hat, fmt.block_tokens, fmt.head_dim, 1, fmt.j1)
 
 
-def reconstruction_bound(small: np.ndarray, steps: np.ndarray, fmt: Format) -> np.ndarray:
+def reconstruction_bound(small: np.ndarray, steps: np.ndarray, fmt: Format,
+                         small3: Optional[np.ndarray] = None) -> np.ndarray:
     """Elementwise bound on |X_hat - T_S16 @ T_L| from the Delta/2 code error:
-    0.5 * sum_r |T_S16[b1, r]| * Delta[t, group(r*j2 + b2)], shape [block_tokens, head_dim]."""
+    0.5 * sum_r |T_S16[b1, r]| * Delta[t, group(r*j2 + b2)], shape [block_tokens, head_dim].
+    Three tensors: Delta[t, .] is replaced by sum_e |T_3[e, a3]| * Delta[(a2, e), .]."""
     tb, d = fmt.block_tokens, fmt.head_dim
     delta = np.repeat(steps.astype(np.float64), fmt.group, axis=1)      # [t, r*j2+b2]
-    delta_l = token_major_to_large(delta, fmt.j1, fmt.j2)               # [r, (t, b2)]
+    if fmt.i3 > 1:
+        dm = token_major_to_middle(delta, fmt.j1, fmt.j2, fmt.i3)       # [r, a2, b2, e]
+        right = np.einsum("racd,de->raec", dm, np.abs(small3.astype(np.float64)))
+        delta_l = right.reshape(fmt.j1, tb * fmt.j2)
+    else:
+        delta_l = token_major_to_large(delta, fmt.j1, fmt.j2)           # [r, (t, b2)]
     m_bound = 0.5 * np.abs(small.astype(np.float64)) @ delta_l
     return unmatricise(m_bound, tb, d, 1, fmt.j1)
 
@@ -349,11 +429,19 @@ def empty_cache(fmt: Format, batch: int, kv_heads: int, block_capacity: int) -> 
       v_codes  u8  [B, H, NB, T_b/128, j2, j1, 128*bits/8] token-contiguous inside 128-token tiles
       v_scales f16 [B, H, NB, T_b, d/G]
       v_small  f16 [B, H, NB, j1 (b1), j1 (r)]             T_S of values, natural
+    and, with three local tensors,
+      k_small3 f16 [B, H, NB, i3 (token a3), i3 (bond e)]  T_3 of keys, TRANSPOSED (token first)
+      v_small3 f16 [B, H, NB, i3 (bond e), i3 (token a3)]  T_3 of values, natural
     """
     fmt.check()
     b, h, nb, tb, d = batch, kv_heads, block_capacity, fmt.block_tokens, fmt.head_dim
     tiles = tb // TILE_TOKENS
+    extra = {}
+    if fmt.i3 > 1:
+        extra = {"k_small3": np.zeros((b, h, nb, fmt.i3, fmt.i3), np.float16),
+                 "v_small3": np.zeros((b, h, nb, fmt.i3, fmt.i3), np.float16)}
     return {
+        **extra,
         "k_codes": np.zeros((b, h, nb, tb, fmt.row_bytes), np.uint8),
         "k_scales": np.zeros((b, h, nb, tb, fmt.groups_per_row), np.float16),
         "k_small": np.zeros((b, h, nb, fmt.j1, fmt.j1), np.float16),
@@ -372,16 +460,22 @@ def store_block(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: int, blk: 
     cache["v_codes"][b, h, blk] = pack_rows(value_codes_to_tiles(vblock.codes, fmt.j1, fmt.j2), fmt.bits)
     cache["v_scales"][b, h, blk] = vblock.steps
     cache["v_small"][b, h, blk] = vblock.small
+    if fmt.i3 > 1:
+        cache["k_small3"][b, h, blk] = kblock.small3.T
+        cache["v_small3"][b, h, blk] = vblock.small3
 
 
 def load_block(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: int, blk: int, which: str
-               ) -> Tuple[np.ndarray, np.ndarray, np.ndarray]:
-    """Read (small [b1, r] fp16, steps, signed codes [t, r*j2+b2]) of a key ('k') or value ('v') block."""
+               ) -> Tuple:
+    """Read (small [b1, r] fp16, steps, signed codes [t, r*j2+b2]) of a key ('k') or value ('v')
+    block; with three local tensors a fourth item, T_3 [e, a3] fp16, follows."""
     if which == "k":
         codes = unpack_rows(cache["k_codes"][b, h, blk], fmt.bits)
-        return cache["k_small"][b, h, blk].T, cache["k_scales"][b, h, blk], codes
+        out = (cache["k_small"][b, h, blk].T, cache["k_scales"][b, h, blk], codes)
+        return out + ((cache["k_small3"][b, h, blk].T,) if fmt.i3 > 1 else ())
     codes = value_tiles_to_codes(unpack_rows(cache["v_codes"][b, h, blk], fmt.bits))
-    return cache["v_small"][b, h, blk], cache["v_scales"][b, h, blk], codes
+    out = (cache["v_small"][b, h, blk], cache["v_scales"][b, h, blk], codes)
+    return out + ((cache["v_small3"][b, h, blk],) if fmt.i3 > 1 else ())
 
 
 def compress_sequence(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: int,
@@ -404,8 +498,9 @@ def reconstruct_sequence(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: i
     k_hat = np.zeros((n_blk * tb, d))
     v_hat = np.zeros((n_blk * tb, d))
     for blk in range(n_blk):
-        k_hat[blk * tb:(blk + 1) * tb] = reconstruct_block(*load_block(cache, fmt, b, h, blk, "k"), fmt)
-        v_hat[blk * tb:(blk + 1) * tb] = reconstruct_block(*load_block(cache, fmt, b, h, blk, "v"), fmt)
+        kb, vb = load_block(cache, fmt, b, h, blk, "k"), load_block(cache, fmt, b, h, blk, "v")
+        k_hat[blk * tb:(blk + 1) * tb] = reconstruct_block(kb[0], kb[1], kb[2], fmt, *kb[3:])
+        v_hat[blk * tb:(blk + 1) * tb] = reconstruct_block(vb[0], vb[1], vb[2], fmt, *vb[3:])
     return k_hat[:n_tok], v_hat[:n_tok]
 
 
@@ -468,7 +563,7 @@ def compression_ratio(fmt: Format, step_bits: int = 16) -> float:
     """mu = (#T_L * B + #T_S * 16 + bits of the steps) / (#W * 16) for one block (Eq. 4)."""
     n_w = fmt.block_tokens * fmt.head_dim
     n_l = fmt.j1 * fmt.block_tokens * fmt.j2
-    n_s = fmt.j1 * fmt.j1
+    n_s = fmt.j1 * fmt.j1 + (fmt.i3 * fmt.i3 if fmt.i3 > 1 else 0)
     n_delta = fmt.block_tokens * fmt.groups_per_row
     return (n_l * fmt.bits + n_s * 16 + n_delta * step_bits) / (n_w * 16.0)
 
@@ -476,4 +571,4 @@ def compression_ratio(fmt: Format, step_bits: int = 16) -> float:
 def cache_bytes_per_block(fmt: Format) -> int:
     """Bytes one key (or value) block occupies in the storage arrays."""
     return (fmt.block_tokens * fmt.row_bytes + fmt.block_tokens * fmt.groups_per_row * 2
-            + fmt.j1 * fmt.j1 * 2)
+            + fmt.j1 * fmt.j1 * 2 + (fmt.i3 * fmt.i3 * 2 if fmt.i3 > 1 else 0))
