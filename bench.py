@@ -52,7 +52,7 @@ def _cpu_worker(rank, n_workers, wname, pairs, barrier, queue):
         pass
     from oracle import decoquant_oracle as O
     w = workloads.get_workload(wname)
-    fmt = O.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens)
+    fmt = O.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3)
     mine = pairs[rank::n_workers]
     lens = workloads.seq_lens(w)
     q = workloads.query(w)
@@ -115,7 +115,7 @@ def cpu_baseline(wname: str, n_pairs: int):
 # --------------------------------------------------------------------------------------------
 def build_cache(dq, torch, w, dev):
     """Host-generate the layer's K/V, upload, compress every block on the GPU."""
-    fmt = dq.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens)
+    fmt = dq.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3)
     tb = w.block_tokens
     total = w.max_seq + w.append_tokens
     nb = -(-total // tb)
@@ -167,7 +167,8 @@ def build_cache(dq, torch, w, dev):
 def algorithmic_bytes(w, lens) -> float:
     """Bytes the method itself must read per step: codes + steps + small tensors of every cached
     token of every kv head (keys and values), plus q and out."""
-    per_tok = 2 * (w.head_dim * w.bits / 8 + 2 * w.head_dim / w.group) + 2 * (2 * w.j1 * w.j1) / w.block_tokens
+    small = 2 * w.j1 * w.j1 + (2 * w.i3 * w.i3 if w.i3 > 1 else 0)     # bytes of fp16 small tensors per block
+    per_tok = 2 * (w.head_dim * w.bits / 8 + 2 * w.head_dim / w.group) + 2 * small / w.block_tokens
     toks = float(np.sum(lens.astype(np.int64))) * w.kv_heads
     return per_tok * toks + w.batch * w.q_heads * w.head_dim * 4
 

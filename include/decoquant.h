@@ -34,6 +34,20 @@
  *   v_scales f16  [B, H, NB, T_b, d/G]        same grouping (by c') as keys
  *   v_small  f16  [B, H, NB, j1, j1]          T_S of values, entry [b1][r]
  * Token t of sequence b lives in block t / T_b, row t % T_b.
+ *
+ * Three local tensors (format field i3 = 8; Eq. 2 with n = 3, which Section 4.3 "Analysis of
+ * Length of Local Tensors" reports as the more accurate, costlier variant): the row index is
+ * factored as 1 * (T_b / 8) * 8 and the column index as j1 * j2 * 1,
+ *   X[(a2, a3), (b1, b2)] = sum_{r, e} T_1[b1, r] T_2[r, a2, b2, e] T_3[e, a3],
+ * T_1 = T_S as above, T_2 (orthonormal columns over (r, a2, b2)) is the quantized large tensor and
+ * T_3 (8 x 8, fp16, carries the second cut's singular values) mixes the 8 tokens of a run of
+ * consecutive tokens.  The codes and steps keep the layouts above with the bond index e in the
+ * place of the token's low three bits (row a2*8 + e holds T_2[., a2, ., e]); two more arrays:
+ *   k_small3 f16  [B, H, NB, 8, 8]            T_3 of keys TRANSPOSED: entry [a3][e] = T_3[e][a3]
+ *   v_small3 f16  [B, H, NB, 8, 8]            T_3 of values, entry [e][a3]
+ * A real token a2*8 + a3 then depends on all eight rows a2*8 + e: in the last, partly valid block
+ * of a sequence every row of a run that contains a valid token must hold what dq_compress_kv
+ * wrote (it writes whole blocks); runs wholly past seq_lens[b] may hold anything.
  */
 #ifndef DECOQUANT_H
 #define DECOQUANT_H
@@ -54,7 +68,7 @@ typedef enum dq_status {
 
 /* Format of a compressed cache.  Constraints: bits in {2, 4, 8}; head_dim == j1*j2;
  * head_dim in {64, 128}; j1 in {8, 16, 32}; group divides head_dim and group >= head_dim/2
- * or group divides head_dim/2; block_tokens is a positive multiple of 128. */
+ * or group divides head_dim/2; block_tokens is a positive multiple of 128; i3 in {1, 8}. */
 typedef struct dq_format {
   int32_t bits;         /* m of Eq. 1; qmax = 2^(m-1) - 1                         */
   int32_t group;        /* G: elements per step, consecutive inside one token row  */
@@ -62,10 +76,13 @@ typedef struct dq_format {
   int32_t j1;           /* side of the small tensor T_S (Eq. 2: j_1)               */
   int32_t j2;           /* d / j1 (Eq. 2: j_2)                                     */
   int32_t block_tokens; /* T_b: tokens per decomposed block (Eq. 2: i_2; i_1 = 1)  */
+  int32_t i3;           /* 1: two local tensors; 8: three, T_3 is 8 x 8 on the token side
+                           (then i_2 = T_b / 8, i_3 = 8, j_3 = 1)                  */
 } dq_format;
 
-/* Device pointers to the six arrays described above; shapes are fixed by (format, batch,
- * kv_heads, block_capacity). */
+/* Device pointers to the arrays described above; shapes are fixed by (format, batch,
+ * kv_heads, block_capacity).  k_small3 / v_small3 are read only when format.i3 == 8 (NULL
+ * otherwise). */
 typedef struct dq_cache {
   uint8_t* k_codes;
   uint16_t* k_scales;
@@ -73,6 +90,8 @@ typedef struct dq_cache {
   uint8_t* v_codes;
   uint16_t* v_scales;
   uint16_t* v_small;
+  uint16_t* k_small3;
+  uint16_t* v_small3;
   int32_t batch;
   int32_t kv_heads;
   int32_t block_capacity; /* NB */
@@ -179,6 +198,10 @@ size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t 
  * of (b, h) at index 2*(b*H+h), V block next), then one status word per block.
  * The factors are not unique (signs, order of equal singular values): only their product and
  * the orthonormality of T_L's rows are defined.
+ * With format.i3 == 8 a second cut follows: the 8 x 8 Gram matrix over the token index a3 of the
+ * first cut's right factor is diagonalised the same way, T_3 = diag(sigma') V'^T goes to
+ * k_small3 / v_small3 and the fp32 workspace rows are replaced by T_2 (row a2*8 + e) before they
+ * are quantized; t_new < T_b and n_valid keep their meaning (missing rows are zero).
  */
 int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
                        const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,

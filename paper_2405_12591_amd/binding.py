@@ -27,7 +27,7 @@ class DQError(RuntimeError):
 
 class _CFormat(C.Structure):
     _fields_ = [("bits", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
-                ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32)]
+                ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32), ("i3", C.c_int32)]
 
 
 class _CTail(C.Structure):
@@ -37,6 +37,7 @@ class _CTail(C.Structure):
 class _CCache(C.Structure):
     _fields_ = [("k_codes", C.c_void_p), ("k_scales", C.c_void_p), ("k_small", C.c_void_p),
                 ("v_codes", C.c_void_p), ("v_scales", C.c_void_p), ("v_small", C.c_void_p),
+                ("k_small3", C.c_void_p), ("v_small3", C.c_void_p),
                 ("batch", C.c_int32), ("kv_heads", C.c_int32), ("block_capacity", C.c_int32)]
 
 
@@ -107,9 +108,10 @@ class Format:
     j1: int
     j2: int
     block_tokens: int
+    i3: int = 1   # 8: three local tensors (T_3 is 8 x 8 on the token side)
 
     def c(self) -> _CFormat:
-        return _CFormat(self.bits, self.group, self.head_dim, self.j1, self.j2, self.block_tokens)
+        return _CFormat(self.bits, self.group, self.head_dim, self.j1, self.j2, self.block_tokens, self.i3)
 
     @property
     def row_bytes(self) -> int:
@@ -130,9 +132,10 @@ class Cache:
         for name, ten in tensors.items():
             if not (ten.is_cuda and ten.is_contiguous()):
                 raise DQError("cache tensor %s must be a contiguous device tensor" % name)
+        small3 = [tensors[n].data_ptr() if n in tensors else None for n in ("k_small3", "v_small3")]
         self.c = _CCache(*(tensors[n].data_ptr() for n in
                            ("k_codes", "k_scales", "k_small", "v_codes", "v_scales", "v_small")),
-                         batch, kv_heads, block_capacity)
+                         *small3, batch, kv_heads, block_capacity)
 
     def nbytes(self) -> int:
         return sum(t.numel() * t.element_size() for t in self.t.values())
@@ -144,7 +147,12 @@ class Cache:
 
 def _shapes(fmt: Format, b: int, h: int, nb: int):
     tiles = fmt.block_tokens // 128
+    extra = {}
+    if fmt.i3 > 1:
+        extra = {"k_small3": ((b, h, nb, fmt.i3, fmt.i3), torch.float16),
+                 "v_small3": ((b, h, nb, fmt.i3, fmt.i3), torch.float16)}
     return {
+        **extra,
         "k_codes": ((b, h, nb, fmt.block_tokens, fmt.row_bytes), torch.uint8),
         "k_scales": ((b, h, nb, fmt.block_tokens, fmt.groups), torch.float16),
         "k_small": ((b, h, nb, fmt.j1, fmt.j1), torch.float16),
@@ -156,7 +164,7 @@ def _shapes(fmt: Format, b: int, h: int, nb: int):
 
 def alloc_cache(fmt: Format, batch: int, kv_heads: int, block_capacity: int, device="cuda:0",
                 fill: Optional[int] = 0) -> Cache:
-    """Allocate the six cache arrays.  fill=None leaves them uninitialised."""
+    """Allocate the cache arrays.  fill=None leaves them uninitialised."""
     tensors = {}
     for name, (shape, dtype) in _shapes(fmt, batch, kv_heads, block_capacity).items():
         t = torch.empty(shape, dtype=dtype, device=device)

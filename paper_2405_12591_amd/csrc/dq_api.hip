@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 
 using namespace dq;
 
-extern "C" int32_t dq_version(void) { return 1; }
+extern "C" int32_t dq_version(void) { return 2; }
 
 extern "C" const char* dq_status_string(int32_t status) {
   switch (status) {
@@ -159,6 +159,7 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
       !cache->v_small)
     return DQ_EINVAL;
+  if (fmt->i3 != 1 && (!cache->k_small3 || !cache->v_small3)) return DQ_EINVAL;
   if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
   if (q_heads <= 0 || q_heads % cache->kv_heads) return DQ_EINVAL;
   if (max_seq_len < 0 || (long)max_seq_len > (long)cache->block_capacity * fmt->block_tokens) return DQ_EINVAL;

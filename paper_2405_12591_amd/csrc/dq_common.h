@@ -11,6 +11,7 @@ namespace dq {
 constexpr int kTileTokens = 128;   // tokens per value-code tile and per decode work tile
 constexpr int kMaxSplits = 64;     // upper bound on split-sequence partials per (b, head)
 constexpr int kWsHeaderBytes = 256;
+constexpr int kRun = 8;            // side of the third local tensor: tokens per run it mixes
 
 // Record a failed HIP runtime call for dq_last_hip_error().
 void set_last_hip_error(hipError_t e);
@@ -35,6 +36,7 @@ inline bool format_ok(const dq_format* f) {
   if (!(f->group == f->head_dim || (f->group <= seg && seg % f->group == 0))) return false;
   if ((f->group * f->bits) % 32) return false;  // a group covers whole 32-bit words
   if (f->block_tokens <= 0 || f->block_tokens % kTileTokens) return false;
+  if (f->i3 != 1 && f->i3 != kRun) return false;
   return true;
 }
 

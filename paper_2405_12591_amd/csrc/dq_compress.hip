@@ -707,6 +707,159 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   }
 }
 
+// ------------------------------------------------------------------------------------------
+// Second cut of the three-tensor form (Eq. 2 with n = 3; factor shapes 1 * (T_b/8) * 8 by
+// j1 * j2 * 1).  The first cut left its right factor R[(a2, a3), c'] (orthonormal over r) as fp32
+// rows in the workspace.  Regrouped as A[(a2, c'), a3] it is cut again,
+//   A = T_2 diag(sigma') V'^T,   T_3[e, a3] = sigma'_e V'[a3, e],   T_2 = A V' diag(1/sigma'),
+// through the 8 x 8 Gram matrix A^T A (fp64; the fp32 inputs make every product exact), the same
+// Jacobi iteration as the first cut, and a projection that overwrites the eight rows of every run
+// a2 in place: row a2*8 + e becomes T_2[., a2, ., e].  One workgroup of four waves per block.
+// ------------------------------------------------------------------------------------------
+template <int DD>
+__global__ __launch_bounds__(256) void split3_kernel(dq_format fmt, dq_cache cache,
+                                                     const int32_t* __restrict__ blk_idx,
+                                                     float* __restrict__ large_ws) {
+  constexpr int N = kRun, LD = N + 1;
+  const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
+  const int unit = blockIdx.x;  // (b*H + h)*2 + which
+  const int which = unit & 1;
+  const int bh = unit >> 1;
+  const int slot = blk_idx[bh / g.H];
+  if (slot < 0 || slot >= g.NB) return;
+  const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
+  float* blk = large_ws + (long)unit * g.Tb * DD;
+  const int runs = g.Tb / N;
+
+  __shared__ double gpart[4][16 * 16];
+  __shared__ double A0[N * LD], A1[N * LD], V0[N * LD], V1[N * LD], W3[N * N];
+  __shared__ double rc[N], rs[N], lam[N], sigma[N];
+  __shared__ int partner[N], is_p[N], order[N], any_big;
+
+  // ---- Gram matrix on the fp64 matrix cores: a 16 x 16 product of two runs side by side, whose
+  // two diagonal 8 x 8 blocks are the runs' contributions.  Lane (n, k): row a2 = 2*pair + n/8,
+  // token a3 = n % 8, elements c' = 16*S + 4*k + j for the j-th of four successive products.
+  {
+    const int n = lane & 15, k = lane >> 4;
+    f64x4 acc = {0.0, 0.0, 0.0, 0.0};
+    for (int pair = wave; pair < runs / 2; pair += 4) {
+      const float* row = blk + (long)((2 * pair + (n >> 3)) * N + (n & 7)) * DD + 4 * k;
+      float4 v[DD / 16];
+#pragma unroll
+      for (int S = 0; S < DD / 16; ++S) v[S] = *reinterpret_cast<const float4*>(row + 16 * S);
+#pragma unroll
+      for (int S = 0; S < DD / 16; ++S) {
+        const double x0 = v[S].x, x1 = v[S].y, x2 = v[S].z, x3 = v[S].w;
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x0, x0, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x1, x1, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x2, x2, acc, 0, 0, 0);
+        acc = __builtin_amdgcn_mfma_f64_16x16x4f64(x3, x3, acc, 0, 0, 0);
+      }
+    }
+#pragma unroll
+    for (int i = 0; i < 4; ++i) gpart[wave][(k + 4 * i) * 16 + n] = acc[i];
+  }
+  __syncthreads();
+  if (tid < N * N) {
+    const int p = tid >> 3, q = tid & 7;
+    double s = 0.0;
+#pragma unroll
+    for (int w = 0; w < 4; ++w) s += gpart[w][p * 16 + q] + gpart[w][(p + 8) * 16 + q + 8];   // fixed order
+    A0[p * LD + q] = s;
+    V0[p * LD + q] = (p == q) ? 1.0 : 0.0;
+  }
+  __syncthreads();
+  double trace = 0.0;
+#pragma unroll
+  for (int i = 0; i < N; ++i) trace += A0[i * LD + i];
+  const double floor_abs = 1e-17 * trace;
+
+  // ---- parallel cyclic Jacobi: 7 rounds of 4 disjoint rotations per sweep ----
+  double* Ac = A0; double* An = A1; double* Vc = V0; double* Vn = V1;
+  constexpr int NM1 = N - 1;
+  for (int sweep = 0; sweep < 16; ++sweep) {
+    if (tid == 0) any_big = 0;
+    __syncthreads();
+    for (int round = 0; round < NM1; ++round) {
+      if (tid < N / 2) {
+        int p, q;
+        if (tid == 0) { p = NM1; q = round; }
+        else { p = (round + tid) % NM1; q = (round - tid + NM1) % NM1; }
+        if (p > q) { const int t = p; p = q; q = t; }
+        double c, sn;
+        bool big;
+        jacobi_rotation(Ac[p * LD + p], Ac[q * LD + q], Ac[p * LD + q], floor_abs, c, sn, big);
+        if (big) any_big = 1;
+        rc[p] = c; rs[p] = sn; rc[q] = c; rs[q] = sn;
+        partner[p] = q; partner[q] = p;
+        is_p[p] = 1; is_p[q] = 0;
+      }
+      __syncthreads();
+      // J[p][p] = c, J[p][q] = s, J[q][p] = -s, J[q][q] = c per pair;  A' = J^T A J,  V' = V J
+      if (tid < N * N) {
+        const int i = tid >> 3, j = tid & 7;
+        const int pi = partner[i], pj = partner[j];
+        const double cj = rc[j], sj = is_p[j] ? -rs[j] : rs[j];
+        const double ci = rc[i], si = is_p[i] ? -rs[i] : rs[i];
+        const double aj_i = Ac[i * LD + j] * cj + Ac[i * LD + pj] * sj;
+        const double aj_pi = Ac[pi * LD + j] * cj + Ac[pi * LD + pj] * sj;
+        An[i * LD + j] = ci * aj_i + si * aj_pi;
+        Vn[i * LD + j] = Vc[i * LD + j] * cj + Vc[i * LD + pj] * sj;
+      }
+      __syncthreads();
+      double* t = Ac; Ac = An; An = t;
+      t = Vc; Vc = Vn; Vn = t;
+    }
+    const int again = any_big;
+    __syncthreads();
+    if (!again) break;   // no rotated entry was above 3e-5 of its diagonal pair: this sweep finished them
+  }
+
+  // ---- singular values in descending order, T_3, and W3[e][a3] = V'[a3, e] / sigma'_e ----
+  if (tid < N) lam[tid] = Ac[tid * LD + tid];
+  __syncthreads();
+  if (tid < N) {
+    int rank = 0;
+    const double me = lam[tid];
+    for (int s2 = 0; s2 < N; ++s2) rank += (lam[s2] > me) || (lam[s2] == me && s2 < tid);
+    order[rank] = tid;
+  }
+  __syncthreads();
+  if (tid < N) {
+    const double lmax = fmax(lam[order[0]], 0.0);
+    const double l = lam[order[tid]];
+    sigma[tid] = (l > 1e-12 * lmax && l > 0.0) ? sqrt(l) : 0.0;
+  }
+  __syncthreads();
+  if (tid < N * N) {
+    const int e = tid >> 3, a3 = tid & 7;
+    const double v = Vc[a3 * LD + order[e]];
+    const double sg = sigma[e];
+    W3[e * N + a3] = sg > 0.0 ? v / sg : 0.0;
+    const long b3 = ((long)bh * g.NB + slot) * (N * N);
+    const uint16_t hb = f64_to_f16_rne(v * sg, true, nullptr);   // |T_3| <= sqrt(j1): far inside fp16
+    if (which) cache.v_small3[b3 + e * N + a3] = hb;   // values: natural [e][a3]
+    else cache.k_small3[b3 + a3 * N + e] = hb;         // keys: transposed [a3][e]
+  }
+  __syncthreads();
+
+  // ---- projection in place: a thread owns one (a2, c') column of eight rows ----
+  for (int idx = tid; idx < runs * DD; idx += 256) {
+    const int a2 = idx / DD, c = idx % DD;
+    float* col = blk + (long)a2 * N * DD + c;
+    double x[N];
+#pragma unroll
+    for (int a3 = 0; a3 < N; ++a3) x[a3] = (double)col[a3 * DD];
+#pragma unroll
+    for (int e = 0; e < N; ++e) {
+      double y = 0.0;
+#pragma unroll
+      for (int a3 = 0; a3 < N; ++a3) y = fma(W3[e * N + a3], x[a3], y);
+      col[e * DD] = (float)y;
+    }
+  }
+}
+
 }  // namespace dq
 
 // ------------------------------------------------------------------------------------------
@@ -757,6 +910,7 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
       !cache->v_small)
     return DQ_EINVAL;
+  if (fmt->i3 != 1 && (!cache->k_small3 || !cache->v_small3)) return DQ_EINVAL;
   if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
   if (t_new < 1 || t_new > fmt->block_tokens) return DQ_EINVAL;
   const size_t need = dq_compress_workspace_bytes(fmt, cache->batch, cache->kv_heads);
@@ -794,6 +948,13 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   }
 #undef DQ_LAUNCH_DECOMPOSE
   DQ_HIP_CHECK(hipGetLastError());
+  if (fmt->i3 == kRun) {   // three local tensors: cut the right factor again before it is quantized
+    if (fmt->head_dim == 128)
+      hipLaunchKernelGGL((split3_kernel<128>), dim3(units), dim3(256), 0, st, *fmt, *cache, blk_idx, large_ws);
+    else
+      hipLaunchKernelGGL((split3_kernel<64>), dim3(units), dim3(256), 0, st, *fmt, *cache, blk_idx, large_ws);
+    DQ_HIP_CHECK(hipGetLastError());
+  }
   const int tiles = units * (fmt->block_tokens / kTileTokens);
   const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
 #define DQ_LAUNCH_QTILES(B_, D_)                                                                       \

@@ -5,7 +5,10 @@
 //   s_t        = sum_g step^K[t, g] * sum_{c' in g} code^K[t, c'] q'[c']
 //   o'[c']     = sum_t p_t step^V[t, g(c')] code^V[t, c']          (per 128-token tile)
 //   acc[b1,b2] = alpha * acc[b1, b2] + sum_r T_S^V[b1, r] o'[r, b2]
-// followed by a log-sum-exp merge of the splits.
+// followed by a log-sum-exp merge of the splits.  With three local tensors (format.i3 == 8) row
+// a2*8 + e of the codes belongs to the bond index e, not to a token: the scores of the eight tokens
+// of a run are s[a2*8 + a3] = sum_e T_3^K[e, a3] y[a2*8 + e] (y: the row sums above), and the values
+// are weighted with p'[a2*8 + e] = sum_a3 T_3^V[e, a3] p[a2*8 + a3].
 #include <hip/hip_ext.h>
 
 #include "dq_decode.h"
@@ -52,6 +55,9 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
   __shared__ float opart[4][128];
   __shared__ float sK[32 * 32];    // T_S^K as stored: [r][b1]
   __shared__ float sV[32 * 32];    // T_S^V as stored: [b1][r]
+  __shared__ float sK3[kRun * kRun];   // T_3^K as stored: [a3][e]
+  __shared__ float sV3[kRun * kRun];   // T_3^V as stored: [e][a3]
+  const bool three = a.fmt.i3 == kRun;
 
   if (tid < d) qs[tid] = h2f(a.q[(long)bhq * d + tid]);
   float acc = 0.f;                 // thread c < d owns output channel c = b1*j2 + b2
@@ -71,6 +77,10 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
       const uint16_t* ks = a.cache.k_small + blkid * g.small_per_block;
       const uint16_t* vs = a.cache.v_small + blkid * g.small_per_block;
       for (int i = tid; i < j1 * j1; i += blockDim.x) { sK[i] = h2f(ks[i]); sV[i] = h2f(vs[i]); }
+      if (three && tid < kRun * kRun) {
+        sK3[tid] = h2f(a.cache.k_small3[blkid * (kRun * kRun) + tid]);
+        sV3[tid] = h2f(a.cache.v_small3[blkid * (kRun * kRun) + tid]);
+      }
       __syncthreads();
       if (tid < d) {
         const int r = tid / j2, b2 = tid % j2;
@@ -86,7 +96,9 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
       const int t = tile * kTileTokens + tt;
       const int row = tib * kTileTokens + tt;
       float s = 0.f;
-      if (t < S) {
+      // three tensors: a row is needed as soon as its run of eight holds a valid token
+      const bool row_live = three ? (t - (tt & (kRun - 1))) < S : t < S;
+      if (row_live) {
         const uint8_t* rowp = a.cache.k_codes + blkid * g.codes_per_block + (long)row * g.row_bytes;
         const uint16_t* scp = a.cache.k_scales + blkid * g.scales_per_block + (long)row * g.groups;
         const uint32_t* words = reinterpret_cast<const uint32_t*>(rowp) + half * seg * BITS / 32;
@@ -101,9 +113,21 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
         }
       }
       s += __shfl_xor(s, 1);
-      if (half == 0) sc[tt] = (t < S) ? s : -INFINITY;
+      if (half == 0) sc[tt] = three ? (row_live ? s : 0.f) : ((t < S) ? s : -INFINITY);
     }
     __syncthreads();
+    if (three) {   // rows -> tokens: s[a2*8 + a3] = sum_e T_3^K[e, a3] y[a2*8 + e]
+      float s = -INFINITY;
+      if (tid < kTileTokens && tile * kTileTokens + tid < S) {
+        const int run0 = tid & ~(kRun - 1), a3 = tid & (kRun - 1);
+        s = 0.f;
+#pragma unroll
+        for (int e = 0; e < kRun; ++e) s = fmaf(sK3[a3 * kRun + e], sc[run0 + e], s);
+      }
+      __syncthreads();
+      if (tid < kTileTokens) sc[tid] = s;
+      __syncthreads();
+    }
     // ---- tile max ----
     float v = (tid < kTileTokens) ? sc[tid] : -INFINITY;
     for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
@@ -124,6 +148,17 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
     __syncthreads();
     l_run = l_run * alpha + (red[4] + red[5] + red[6] + red[7]);
     m_run = m_new;
+    if (three) {   // tokens -> rows: p'[a2*8 + e] = sum_a3 T_3^V[e, a3] p[a2*8 + a3]
+      float pw = 0.f;
+      if (tid < kTileTokens) {
+        const int run0 = tid & ~(kRun - 1), e = tid & (kRun - 1);
+#pragma unroll
+        for (int a3 = 0; a3 < kRun; ++a3) pw = fmaf(sV3[e * kRun + a3], sc[run0 + a3], pw);
+      }
+      __syncthreads();
+      if (tid < kTileTokens) sc[tid] = pw;
+      __syncthreads();
+    }
     // ---- values: thread (c', part) accumulates its share of the tile's tokens ----
     {
       const int cp = tid % d, part = tid / d;

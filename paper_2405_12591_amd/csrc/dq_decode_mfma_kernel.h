@@ -139,7 +139,13 @@ __device__ __forceinline__ float pow2i(int e) {
 // the same and hands the tail's partial in with its own.  (A workgroup of its own for the tail was
 // tried: on a full chip its few dependent loads take tens of microseconds behind the streams, and
 // the workgroups queued behind it start that much later.)
-template <int BITS, int NG, int R, int NW, int TM>
+// N3: three local tensors (format.i3 == 8).  Row a2*8 + e of the codes then belongs to the bond
+// index e of the third tensor instead of a token: the tile's 128 row sums y are computed as
+// before, the scores of the eight tokens of a run are s[a3] = sum_e T_3^K[e, a3] y[e], and the
+// value rows are weighted with p'[e] = sum_a3 T_3^V[e, a3] p[a3] (signed, so these weights get a
+// signed top limb like the query's).  The lanes that hold the eight rows of a run form a quad,
+// so both products are quad broadcasts and fused multiply-adds.
+template <int BITS, int NG, int R, int NW, int TM, bool N3>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
   typedef Codec<BITS> C;
   typedef typename C::chunk_t chunk_t;
@@ -268,7 +274,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 
   // softmax layout: lane = 8*G16 + pi owns the two tokens of token group G16 whose weights sit in
   // B slots 2*pi and 2*pi + 1
-  const int G16 = lane >> 3, pi = lane & 7;
+  // (with three tensors and 2-bit codes the low lane bits are dealt the other way round, which
+  // puts the eight rows of a run into one quad of lanes)
+  const int G16 = lane >> 3, pi = (N3 && BITS == 2) ? (((lane & 3) << 1) | ((lane >> 2) & 1)) : (lane & 7);
   int tA, tB;
   if (BITS == 4) { tA = 16 * G16 + 8 * (pi >> 2) + ((0x5140 >> (4 * (pi & 3))) & 7); tB = tA + 2; }
   else if (BITS == 2) { tA = 16 * G16 + 8 * (pi & 1) + (pi >> 1); tB = tA + 4; }
@@ -314,8 +322,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // so everything is requested in the order it will be used: the next tile's small tensors and
   // steps first (needed before its first key chunk), then the refills.
   chunk_t ring[16];
-  struct Side { u32x2 ksm, vsm; uint32_t dkA, dkB, dvA, dvB; };   // small tensors + the lane's steps
-  Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0};
+  // small tensors + the lane's steps; three tensors: the columns of T_3^K of the lane's two tokens
+  // and the rows of T_3^V of its two rows, eight fp16 each
+  struct Side { u32x2 ksm, vsm; uint32_t dkA, dkB, dvA, dvB; u32x4 k3A, k3B, v3A, v3B; };
+  Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
 
   auto tile_ptrs = [&](int tile, const unsigned char*& kc, const unsigned char*& vc, long& blkid, int& tib) {
     blkid = (long)bh * NB + tile / tpb;
@@ -334,6 +344,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens * NG;
     sd.dkA = load_steps(ksc, tA); sd.dkB = load_steps(ksc, tB);
     sd.dvA = load_steps(vsc, tA); sd.dvB = load_steps(vsc, tB);
+    if (N3) {
+      const uint16_t* k3 = a.cache.k_small3 + blkid * (kRun * kRun);   // [a3][e]
+      const uint16_t* v3 = a.cache.v_small3 + blkid * (kRun * kRun);   // [e][a3]
+      sd.k3A = *reinterpret_cast<const u32x4*>(k3 + (tA & 7) * kRun);
+      sd.k3B = *reinterpret_cast<const u32x4*>(k3 + (tB & 7) * kRun);
+      sd.v3A = *reinterpret_cast<const u32x4*>(v3 + (tA & 7) * kRun);
+      sd.v3B = *reinterpret_cast<const u32x4*>(v3 + (tB & 7) * kRun);
+    }
   };
   auto issue_tile = [&](int tile) {
     const unsigned char *kc, *vc;
@@ -351,6 +369,31 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     return h2f((uint16_t)(grp ? (packed >> 16) : (packed & 0xFFFFu)));
   };
 
+  // Three tensors: outA = sum over the run of coefA[row] * x[row] (and outB with coefB), where the
+  // eight values x of a run sit in a quad of lanes, two per lane (xA, xB), and the coefficient
+  // vectors hold one fp16 per row of the run.  Quad lane k holds the rows offA(k) and offB(k).
+  auto quad_mix = [&](float xA, float xB, const u32x4& coefA, const u32x4& coefB, float& outA, float& outB)
+                      __attribute__((always_inline)) {
+    typedef _Float16 half8 __attribute__((ext_vector_type(8)));
+    const half8 cA = __builtin_bit_cast(half8, coefA), cB = __builtin_bit_cast(half8, coefB);
+#pragma unroll
+    for (int k = 0; k < 4; ++k) {
+      const int offA = (BITS == 4) ? ((0x5140 >> (4 * k)) & 7) : (BITS == 2) ? k : 2 * k;
+      const int offB = (BITS == 4) ? offA + 2 : (BITS == 2) ? k + 4 : 2 * k + 1;
+      float a_k, b_k;
+      switch (k) {   // the DPP control must be a literal
+        case 0: a_k = dpp_f<0x00>(xA); b_k = dpp_f<0x00>(xB); break;
+        case 1: a_k = dpp_f<0x55>(xA); b_k = dpp_f<0x55>(xB); break;
+        case 2: a_k = dpp_f<0xAA>(xA); b_k = dpp_f<0xAA>(xB); break;
+        default: a_k = dpp_f<0xFF>(xA); b_k = dpp_f<0xFF>(xB); break;
+      }
+      outA = fmaf((float)cA[offA], a_k, outA);
+      outA = fmaf((float)cA[offB], b_k, outA);
+      outB = fmaf((float)cB[offA], a_k, outB);
+      outB = fmaf((float)cB[offB], b_k, outB);
+    }
+  };
+
   // One tile.  HAS_NEXT: the wave has another tile after this one.
   auto compute_tile = [&](const int tile, auto has_next_tag) __attribute__((always_inline)) {
     constexpr bool HAS_NEXT = decltype(has_next_tag)::value;
@@ -363,11 +406,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
     __builtin_amdgcn_sched_barrier(0);
     const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
+    // three tensors: a row counts as soon as its run of eight holds a valid token
+    const bool rowA = N3 ? (tok0 + (tA & ~7)) < S : okA, rowB = N3 ? (tok0 + (tB & ~7)) < S : okB;
     float dvA[NG], dvB[NG], dkA[NG], dkB[NG];
 #pragma unroll
     for (int gr = 0; gr < NG; ++gr) {
-      dvA[gr] = okA ? step_of(cur.dvA, gr) : 0.f;
-      dvB[gr] = okB ? step_of(cur.dvB, gr) : 0.f;
+      dvA[gr] = rowA ? step_of(cur.dvA, gr) : 0.f;
+      dvB[gr] = rowB ? step_of(cur.dvB, gr) : 0.f;
       dkA[gr] = step_of(cur.dkA, gr);
       dkB[gr] = step_of(cur.dkB, gr);
     }
@@ -443,8 +488,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     __builtin_amdgcn_wave_barrier();
 
     // ---- 3. online softmax, tokens tA and tB per lane ----
-    float v_unscale, vs;
-    {
+    float v_unscale, vs = 0.f;
+    if (!N3) {
       float dvm = fmaxf(dvA[0], dvB[0]);
       if (NG == 2) dvm = fmaxf(dvm, fmaxf(dvA[NG - 1], dvB[NG - 1]));
       const float dvmax = wave_allmax(dvm);
@@ -454,6 +499,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       v_unscale = pow2i(e - kMantBits);
     }
     float alpha[R];
+    float wA[R][NG], wB[R][NG];   // three tensors: the weights, kept until their common scale is known
+    float wmax = 0.f;
 #pragma unroll
     for (int hd = 0; hd < R; ++hd) {
       float sA = 0.f, sB = 0.f;
@@ -466,6 +513,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         sA += ((float)(s0[tA] - b0) * 16384.f + (float)(s1[tA] - b1) * 128.f + (float)(s2[tA] - b2v)) * dkA[gr];
         sB += ((float)(s0[tB] - b0) * 16384.f + (float)(s1[tB] - b1) * 128.f + (float)(s2[tB] - b2v)) * dkB[gr];
       }
+      if (N3) {   // rows -> tokens with T_3^K
+        const float yA = sA, yB = sB;
+        sA = 0.f; sB = 0.f;
+        quad_mix(yA, yB, cur.k3A, cur.k3B, sA, sB);
+      }
       sA = okA ? sA * q_unscale : -INFINITY;
       sB = okB ? sB * q_unscale : -INFINITY;
       const float mt = wave_allmax(fmaxf(sA, sB));
@@ -475,16 +527,47 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const float pB = __builtin_amdgcn_exp2f(sB - m_new);
       l_run[hd] = l_run[hd] * alpha[hd] + (pA + pB);
       m_run[hd] = m_new;
+      if (N3) {   // tokens -> rows with T_3^V; the weights are signed
+        float qA = 0.f, qB = 0.f;
+        quad_mix(pA, pB, cur.v3A, cur.v3B, qA, qB);
 #pragma unroll
-      for (int gr = 0; gr < NG; ++gr) {
-        const float wA = okA ? pA * (dvA[gr] * vs) : 0.f;
-        const float wB = okB ? pB * (dvB[gr] * vs) : 0.f;
-        const uint32_t iA = min((uint32_t)(wA + 0.5f), (1u << kMantBits) - 1u);
-        const uint32_t iB = min((uint32_t)(wB + 0.5f), (1u << kMantBits) - 1u);
-        unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
-        *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((iA >> 14) | ((iB >> 14) << 8));
-        *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127u) | (((iB >> 7) & 127u) << 8));
-        *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127u) | ((iB & 127u) << 8));
+        for (int gr = 0; gr < NG; ++gr) {
+          wA[hd][gr] = rowA ? qA * dvA[gr] : 0.f;
+          wB[hd][gr] = rowB ? qB * dvB[gr] : 0.f;
+          wmax = fmaxf(wmax, fmaxf(fabsf(wA[hd][gr]), fabsf(wB[hd][gr])));
+        }
+      } else {
+#pragma unroll
+        for (int gr = 0; gr < NG; ++gr) {
+          const float wa = okA ? pA * (dvA[gr] * vs) : 0.f;
+          const float wb = okB ? pB * (dvB[gr] * vs) : 0.f;
+          const uint32_t iA = min((uint32_t)(wa + 0.5f), (1u << kMantBits) - 1u);
+          const uint32_t iB = min((uint32_t)(wb + 0.5f), (1u << kMantBits) - 1u);
+          unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
+          *reinterpret_cast<uint16_t*>(dst) = (uint16_t)((iA >> 14) | ((iB >> 14) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127u) | (((iB >> 7) & 127u) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127u) | ((iB & 127u) << 8));
+        }
+      }
+    }
+    if (N3) {
+      // limbs relative to the largest weight of the tile: |w * vs| < 2^20, top limb signed
+      wmax = wave_allmax(wmax);
+      int e = 0;
+      if (wmax > 0.f && wmax < INFINITY) e = __builtin_amdgcn_frexp_expf(wmax);
+      e = max(min(e, 100), -100);
+      vs = pow2i(kMantBits - 1 - e);
+      v_unscale = pow2i(e - (kMantBits - 1));
+#pragma unroll
+      for (int hd = 0; hd < R; ++hd) {
+#pragma unroll
+        for (int gr = 0; gr < NG; ++gr) {
+          const int iA = (int)__builtin_rintf(wA[hd][gr] * vs), iB = (int)__builtin_rintf(wB[hd][gr] * vs);
+          unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
+          *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(((iA >> 14) & 255) | (((iB >> 14) & 255) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127) | (((iB >> 7) & 127) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127) | ((iB & 127) << 8));
+        }
       }
     }
     __builtin_amdgcn_wave_barrier();
@@ -673,21 +756,27 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 
   ticket_and_merge();
 }
-template <int BITS, int NG, int R, int TM>
+template <int BITS, int NG, int R, int TM, bool N3>
 inline void launch_tm(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   // the events, when given, receive the kernel's own begin and end timestamps
   if (a.nw == 8)
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM, N3>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
   else
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM, N3>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+}
+
+template <int BITS, int NG, int R, bool N3>
+inline void launch_n3(const DecodeArgs& a, hipStream_t st) {
+  if (!a.tail.k_tail) launch_tm<BITS, NG, R, 0, N3>(a, st);
+  else if (a.n_split == 1) launch_tm<BITS, NG, R, 1, N3>(a, st);
+  else launch_tm<BITS, NG, R, 2, N3>(a, st);
 }
 
 template <int BITS, int NG, int R>
 inline void launch_r(const DecodeArgs& a, hipStream_t st) {
-  if (!a.tail.k_tail) launch_tm<BITS, NG, R, 0>(a, st);
-  else if (a.n_split == 1) launch_tm<BITS, NG, R, 1>(a, st);
-  else launch_tm<BITS, NG, R, 2>(a, st);
+  if (a.fmt.i3 == kRun) launch_n3<BITS, NG, R, true>(a, st);
+  else launch_n3<BITS, NG, R, false>(a, st);
 }
 
 template <int BITS>

@@ -9,7 +9,7 @@ DEV = "cuda:0"
 
 
 def formats(w):
-    args = (w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens)
+    args = (w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3)
     return dq.Format(*args), O.Format(*args)
 
 
@@ -41,6 +41,7 @@ def _poison_tail(cache, ofmt, b, h, n, r):
     """Overwrite the rows >= n of the last block (codes and steps) with garbage."""
     tb = ofmt.block_tokens
     blk, row = (n - 1) // tb, (n - 1) % tb + 1
+    row = -(-row // ofmt.i3) * ofmt.i3   # three tensors: the rows of a run with a valid token all count
     if row >= tb:
         return
     cache["k_codes"][b, h, blk, row:] = r.integers(0, 256, size=cache["k_codes"][b, h, blk, row:].shape, dtype=np.uint8)

@@ -25,7 +25,7 @@ def test_library_exports_every_declared_symbol(dq):
 
 
 def test_status_strings_and_version(dq):
-    assert dq.version() >= 1
+    assert dq.version() >= 2
     assert dq.status_string(0) == "ok"
     assert "workspace" in dq.status_string(-2)
     assert "invalid" in dq.status_string(-1)
@@ -38,7 +38,7 @@ def test_workspace_queries_validate_the_format(dq):
     assert dq.lib.dq_compress_workspace_bytes(C.byref(good), 4, 40) == 256 + 4 * 40 * 2 * 128 * 128 * 4 + 1280
     for bad in [dq.Format(3, 128, 128, 16, 8, 128), dq.Format(4, 128, 128, 16, 4, 128),
                 dq.Format(4, 96, 128, 16, 8, 128), dq.Format(4, 128, 128, 16, 8, 100),
-                dq.Format(4, 128, 256, 16, 16, 128)]:
+                dq.Format(4, 128, 256, 16, 16, 128), dq.Format(4, 128, 128, 16, 8, 128, 4)]:
         c = bad.c()
         assert dq.lib.dq_decode_workspace_bytes(C.byref(c), 8, 32, 32, 4096) == 0
         assert dq.lib.dq_compress_workspace_bytes(C.byref(c), 4, 40) == 0
@@ -62,10 +62,10 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     good = dq.Format(4, 128, 128, 16, 8, 128).c()
 
     class FakeCache(C.Structure):
-        _fields_ = [("p", C.c_void_p * 6), ("batch", C.c_int32), ("kv_heads", C.c_int32), ("cap", C.c_int32)]
+        _fields_ = [("p", C.c_void_p * 8), ("batch", C.c_int32), ("kv_heads", C.c_int32), ("cap", C.c_int32)]
 
     fake = FakeCache()
-    for i in range(6):
+    for i in range(8):
         fake.p[i] = 0x1000          # never dereferenced: the checks below fail first
     fake.batch, fake.kv_heads, fake.cap = 2, 4, 8
     need = dq.lib.dq_decode_workspace_bytes(C.byref(good), 2, 4, 4, 1024)

@@ -41,6 +41,7 @@ class Workload:
     n_outlier: int          # outlier channels per head (or per layer for layer_outliers)
     outlier_scale: float
     append_tokens: int = 0  # tokens appended (and compressed) before the decode step
+    i3: int = 1             # 8: three local tensors (the third one 8 x 8 on the token side)
 
 
 WORKLOADS = {
@@ -57,6 +58,9 @@ WORKLOADS = {
     # the 8-bit variant of the benchmark shape (the paper's fused kernel covers 2, 4 and 8 bits)
     "llama7b_8bit": Workload("llama7b_8bit", 1006, 8, 32, 32, 128, 4096, 4096, 8, 128, 16, 8, 128,
                              "lognormal_tokens", 4, 20.0),
+    # the benchmark shape with three local tensors (the paper's n = 3 variant)
+    "llama7b_4bit_n3": Workload("llama7b_4bit_n3", 1007, 8, 32, 32, 128, 4096, 4096, 4, 128, 16, 8, 128,
+                                "lognormal_tokens", 4, 20.0, i3=8),
 }
 
 
