@@ -734,7 +734,7 @@ __global__ __launch_bounds__(256) void split3_kernel(dq_format fmt, dq_cache cac
   __shared__ double gpart[4][16 * 16];
   __shared__ double A0[N * LD], A1[N * LD], V0[N * LD], V1[N * LD], W3[N * N];
   __shared__ double rc[N], rs[N], lam[N], sigma[N];
-  __shared__ int partner[N], is_p[N], order[N], any_big;
+  __shared__ int partner[N], is_p[N], order[N];
 
   // ---- Gram matrix on the fp64 matrix cores: a 16 x 16 product of two runs side by side, whose
   // two diagonal 8 x 8 blocks are the runs' contributions.  Lane (n, k): row a2 = 2*pair + n/8,
@@ -769,77 +769,77 @@ __global__ __launch_bounds__(256) void split3_kernel(dq_format fmt, dq_cache cac
     V0[p * LD + q] = (p == q) ? 1.0 : 0.0;
   }
   __syncthreads();
-  double trace = 0.0;
+  // ---- wave 0 alone: Jacobi, ordering, T_3.  A wave's LDS operations execute in order, so
+  // inside it a compiler barrier (no hardware one) separates the steps. ----
+  if (wave == 0) {
+    double trace = 0.0;
 #pragma unroll
-  for (int i = 0; i < N; ++i) trace += A0[i * LD + i];
-  const double floor_abs = 1e-17 * trace;
-
-  // ---- parallel cyclic Jacobi: 7 rounds of 4 disjoint rotations per sweep ----
-  double* Ac = A0; double* An = A1; double* Vc = V0; double* Vn = V1;
-  constexpr int NM1 = N - 1;
-  for (int sweep = 0; sweep < 16; ++sweep) {
-    if (tid == 0) any_big = 0;
-    __syncthreads();
-    for (int round = 0; round < NM1; ++round) {
-      if (tid < N / 2) {
-        int p, q;
-        if (tid == 0) { p = NM1; q = round; }
-        else { p = (round + tid) % NM1; q = (round - tid + NM1) % NM1; }
-        if (p > q) { const int t = p; p = q; q = t; }
-        double c, sn;
-        bool big;
-        jacobi_rotation(Ac[p * LD + p], Ac[q * LD + q], Ac[p * LD + q], floor_abs, c, sn, big);
-        if (big) any_big = 1;
-        rc[p] = c; rs[p] = sn; rc[q] = c; rs[q] = sn;
-        partner[p] = q; partner[q] = p;
-        is_p[p] = 1; is_p[q] = 0;
+    for (int i = 0; i < N; ++i) trace += A0[i * LD + i];
+    const double floor_abs = 1e-17 * trace;
+    // parallel cyclic Jacobi: 7 rounds of 4 disjoint rotations per sweep
+    double* Ac = A0; double* An = A1; double* Vc = V0; double* Vn = V1;
+    constexpr int NM1 = N - 1;
+    for (int sweep = 0; sweep < 16; ++sweep) {
+      bool any_big = false;
+      for (int round = 0; round < NM1; ++round) {
+        bool big = false;
+        if (lane < N / 2) {
+          int p, q;
+          if (lane == 0) { p = NM1; q = round; }
+          else { p = (round + lane) % NM1; q = (round - lane + NM1) % NM1; }
+          if (p > q) { const int t = p; p = q; q = t; }
+          double c, sn;
+          jacobi_rotation(Ac[p * LD + p], Ac[q * LD + q], Ac[p * LD + q], floor_abs, c, sn, big);
+          rc[p] = c; rs[p] = sn; rc[q] = c; rs[q] = sn;
+          partner[p] = q; partner[q] = p;
+          is_p[p] = 1; is_p[q] = 0;
+        }
+        any_big = any_big || __any(big);
+        __builtin_amdgcn_wave_barrier();
+        // J[p][p] = c, J[p][q] = s, J[q][p] = -s, J[q][q] = c per pair;  A' = J^T A J,  V' = V J
+        {
+          const int i = lane >> 3, j = lane & 7;
+          const int pi = partner[i], pj = partner[j];
+          const double cj = rc[j], sj = is_p[j] ? -rs[j] : rs[j];
+          const double ci = rc[i], si = is_p[i] ? -rs[i] : rs[i];
+          const double aj_i = Ac[i * LD + j] * cj + Ac[i * LD + pj] * sj;
+          const double aj_pi = Ac[pi * LD + j] * cj + Ac[pi * LD + pj] * sj;
+          An[i * LD + j] = ci * aj_i + si * aj_pi;
+          Vn[i * LD + j] = Vc[i * LD + j] * cj + Vc[i * LD + pj] * sj;
+        }
+        __builtin_amdgcn_wave_barrier();
+        double* t = Ac; Ac = An; An = t;
+        t = Vc; Vc = Vn; Vn = t;
       }
-      __syncthreads();
-      // J[p][p] = c, J[p][q] = s, J[q][p] = -s, J[q][q] = c per pair;  A' = J^T A J,  V' = V J
-      if (tid < N * N) {
-        const int i = tid >> 3, j = tid & 7;
-        const int pi = partner[i], pj = partner[j];
-        const double cj = rc[j], sj = is_p[j] ? -rs[j] : rs[j];
-        const double ci = rc[i], si = is_p[i] ? -rs[i] : rs[i];
-        const double aj_i = Ac[i * LD + j] * cj + Ac[i * LD + pj] * sj;
-        const double aj_pi = Ac[pi * LD + j] * cj + Ac[pi * LD + pj] * sj;
-        An[i * LD + j] = ci * aj_i + si * aj_pi;
-        Vn[i * LD + j] = Vc[i * LD + j] * cj + Vc[i * LD + pj] * sj;
-      }
-      __syncthreads();
-      double* t = Ac; Ac = An; An = t;
-      t = Vc; Vc = Vn; Vn = t;
+      if (!any_big) break;   // no rotated entry was above 3e-5 of its diagonal pair: this sweep finished them
     }
-    const int again = any_big;
-    __syncthreads();
-    if (!again) break;   // no rotated entry was above 3e-5 of its diagonal pair: this sweep finished them
-  }
 
-  // ---- singular values in descending order, T_3, and W3[e][a3] = V'[a3, e] / sigma'_e ----
-  if (tid < N) lam[tid] = Ac[tid * LD + tid];
-  __syncthreads();
-  if (tid < N) {
-    int rank = 0;
-    const double me = lam[tid];
-    for (int s2 = 0; s2 < N; ++s2) rank += (lam[s2] > me) || (lam[s2] == me && s2 < tid);
-    order[rank] = tid;
-  }
-  __syncthreads();
-  if (tid < N) {
-    const double lmax = fmax(lam[order[0]], 0.0);
-    const double l = lam[order[tid]];
-    sigma[tid] = (l > 1e-12 * lmax && l > 0.0) ? sqrt(l) : 0.0;
-  }
-  __syncthreads();
-  if (tid < N * N) {
-    const int e = tid >> 3, a3 = tid & 7;
-    const double v = Vc[a3 * LD + order[e]];
-    const double sg = sigma[e];
-    W3[e * N + a3] = sg > 0.0 ? v / sg : 0.0;
-    const long b3 = ((long)bh * g.NB + slot) * (N * N);
-    const uint16_t hb = f64_to_f16_rne(v * sg, true, nullptr);   // |T_3| <= sqrt(j1): far inside fp16
-    if (which) cache.v_small3[b3 + e * N + a3] = hb;   // values: natural [e][a3]
-    else cache.k_small3[b3 + a3 * N + e] = hb;         // keys: transposed [a3][e]
+    // singular values in descending order, T_3, and W3[e][a3] = V'[a3, e] / sigma'_e
+    if (lane < N) lam[lane] = Ac[lane * LD + lane];
+    __builtin_amdgcn_wave_barrier();
+    if (lane < N) {
+      int rank = 0;
+      const double me = lam[lane];
+      for (int s2 = 0; s2 < N; ++s2) rank += (lam[s2] > me) || (lam[s2] == me && s2 < lane);
+      order[rank] = lane;
+    }
+    __builtin_amdgcn_wave_barrier();
+    if (lane < N) {
+      const double lmax = fmax(lam[order[0]], 0.0);
+      const double l = lam[order[lane]];
+      sigma[lane] = (l > 1e-12 * lmax && l > 0.0) ? sqrt(l) : 0.0;
+    }
+    __builtin_amdgcn_wave_barrier();
+    {
+      const int e = lane >> 3, a3 = lane & 7;
+      const double v = Vc[a3 * LD + order[e]];
+      const double sg = sigma[e];
+      W3[e * N + a3] = sg > 0.0 ? v / sg : 0.0;
+      const long b3 = ((long)bh * g.NB + slot) * (N * N);
+      const uint16_t hb = f64_to_f16_rne(v * sg, true, nullptr);   // |T_3| <= sqrt(j1): far inside fp16
+      if (which) cache.v_small3[b3 + e * N + a3] = hb;   // values: natural [e][a3]
+      else cache.k_small3[b3 + a3 * N + e] = hb;         // keys: transposed [a3][e]
+    }
   }
   __syncthreads();
 

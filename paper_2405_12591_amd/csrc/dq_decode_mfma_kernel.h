@@ -322,10 +322,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // so everything is requested in the order it will be used: the next tile's small tensors and
   // steps first (needed before its first key chunk), then the refills.
   chunk_t ring[16];
-  // small tensors + the lane's steps; three tensors: the columns of T_3^K of the lane's two tokens
-  // and the rows of T_3^V of its two rows, eight fp16 each
-  struct Side { u32x2 ksm, vsm; uint32_t dkA, dkB, dvA, dvB; u32x4 k3A, k3B, v3A, v3B; };
-  Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+  struct Side { u32x2 ksm, vsm; uint32_t dkA, dkB, dvA, dvB; };   // small tensors + the lane's steps
+  Side cur = {{0, 0}, {0, 0}, 0, 0, 0, 0};
+  // three tensors: the columns of T_3^K of the lane's two tokens and the rows of T_3^V of its two
+  // rows, eight fp16 each (kept apart from Side so that the other instances carry nothing of it)
+  struct Side3 { u32x4 k3A, k3B, v3A, v3B; };
+  Side3 cur3 = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
 
   auto tile_ptrs = [&](int tile, const unsigned char*& kc, const unsigned char*& vc, long& blkid, int& tib) {
     blkid = (long)bh * NB + tile / tpb;
@@ -344,14 +346,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens * NG;
     sd.dkA = load_steps(ksc, tA); sd.dkB = load_steps(ksc, tB);
     sd.dvA = load_steps(vsc, tA); sd.dvB = load_steps(vsc, tB);
-    if (N3) {
-      const uint16_t* k3 = a.cache.k_small3 + blkid * (kRun * kRun);   // [a3][e]
-      const uint16_t* v3 = a.cache.v_small3 + blkid * (kRun * kRun);   // [e][a3]
-      sd.k3A = *reinterpret_cast<const u32x4*>(k3 + (tA & 7) * kRun);
-      sd.k3B = *reinterpret_cast<const u32x4*>(k3 + (tB & 7) * kRun);
-      sd.v3A = *reinterpret_cast<const u32x4*>(v3 + (tA & 7) * kRun);
-      sd.v3B = *reinterpret_cast<const u32x4*>(v3 + (tB & 7) * kRun);
-    }
+  };
+  auto load_side3 = [&](Side3& sd, long blkid) {
+    const uint16_t* k3 = a.cache.k_small3 + blkid * (kRun * kRun);   // [a3][e]
+    const uint16_t* v3 = a.cache.v_small3 + blkid * (kRun * kRun);   // [e][a3]
+    sd.k3A = *reinterpret_cast<const u32x4*>(k3 + (tA & 7) * kRun);
+    sd.k3B = *reinterpret_cast<const u32x4*>(k3 + (tB & 7) * kRun);
+    sd.v3A = *reinterpret_cast<const u32x4*>(v3 + (tA & 7) * kRun);
+    sd.v3B = *reinterpret_cast<const u32x4*>(v3 + (tB & 7) * kRun);
   };
   auto issue_tile = [&](int tile) {
     const unsigned char *kc, *vc;
@@ -359,6 +361,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     int tib;
     tile_ptrs(tile, kc, vc, blkid, tib);
     load_side(cur, blkid, tib);
+    if (N3) load_side3(cur3, blkid);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc + j * (16 * ROWB)));
@@ -404,6 +407,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     if (HAS_NEXT) tile_ptrs(tile + tile_stride, kc_next, vc_next, blkid_next, tib_next);
     Side nxt = cur;
     if (HAS_NEXT) load_side(nxt, blkid_next, tib_next);
+    Side3 nxt3;
+    if (N3) {
+      nxt3 = cur3;
+      if (HAS_NEXT) load_side3(nxt3, blkid_next);
+    }
     __builtin_amdgcn_sched_barrier(0);
     const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
     // three tensors: a row counts as soon as its run of eight holds a valid token
@@ -516,7 +524,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       if (N3) {   // rows -> tokens with T_3^K
         const float yA = sA, yB = sB;
         sA = 0.f; sB = 0.f;
-        quad_mix(yA, yB, cur.k3A, cur.k3B, sA, sB);
+        quad_mix(yA, yB, cur3.k3A, cur3.k3B, sA, sB);
       }
       sA = okA ? sA * q_unscale : -INFINITY;
       sB = okB ? sB * q_unscale : -INFINITY;
@@ -529,7 +537,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       m_run[hd] = m_new;
       if (N3) {   // tokens -> rows with T_3^V; the weights are signed
         float qA = 0.f, qB = 0.f;
-        quad_mix(pA, pB, cur.v3A, cur.v3B, qA, qB);
+        quad_mix(pA, pB, cur3.v3A, cur3.v3B, qA, qB);
 #pragma unroll
         for (int gr = 0; gr < NG; ++gr) {
           wA[hd][gr] = rowA ? qA * dvA[gr] : 0.f;
@@ -638,6 +646,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     }
     epilogue(NSET - 1, pk_done);
     cur = nxt;
+    if (N3) cur3 = nxt3;
     __builtin_amdgcn_wave_barrier();
   };
 
@@ -760,10 +769,15 @@ template <int BITS, int NG, int R, int TM, bool N3>
 inline void launch_tm(const DecodeArgs& a, hipStream_t st) {
   const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
   // the events, when given, receive the kernel's own begin and end timestamps
-  if (a.nw == 8)
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM, N3>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
-  else
-    hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM, N3>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+  // (8-bit codes: a wave's ring of chunks is twice as large and an 8-wave workgroup runs out of
+  // registers, so that width always takes 4 waves)
+  if constexpr (BITS < 8) {
+    if (a.nw == 8) {
+      hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM, N3>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+      return;
+    }
+  }
+  hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM, N3>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
 }
 
 template <int BITS, int NG, int R, bool N3>

@@ -16,8 +16,9 @@ from gpu_util import DEV, formats, oracle_cache_for_pairs, tolerance
 pytestmark = pytest.mark.gpu
 
 
-@pytest.mark.parametrize("seed", [11, 12, 13])
-def test_random_decode_cases(seed, monkeypatch):
+@pytest.mark.parametrize("seed,i3", [(11, 1), (12, 1), (13, 1), (21, 8), (22, 8), (23, 8)])
+def test_random_decode_cases(seed, i3, monkeypatch):
+    """i3 = 8: the same sweep over caches in the three-tensor form."""
     rng = np.random.default_rng(seed)
     for case in range(16):
         bits = int(rng.choice([2, 4, 8]))
@@ -28,7 +29,7 @@ def test_random_decode_cases(seed, monkeypatch):
         max_seq = int(rng.choice([128, 300, 640, 1100, 2100]))
         w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=kvh * rep, kv_heads=kvh,
                                 max_seq=-(-max_seq // tb) * tb, min_seq=-(-max_seq // tb) * tb, bits=bits, group=group,
-                                block_tokens=tb, seed=3000 + 100 * seed + case)
+                                block_tokens=tb, seed=3000 + 100 * seed + case, i3=i3)
         fmt, ofmt = formats(w)
         lens = np.array([int(rng.choice([0, 1, 127, 128, 129, max_seq, int(rng.integers(0, max_seq + 1))]))
                          for _ in range(batch)], np.int32)
@@ -42,8 +43,8 @@ def test_random_decode_cases(seed, monkeypatch):
                 monkeypatch.setenv(key, val)
             else:
                 monkeypatch.delenv(key, raising=False)
-        print("seed %d case %d: bits=%d G=%d rep=%d kvh=%d B=%d Tb=%d max_seq=%d lens=%s tail=%s cap=%d tl=%s splits=%r waves=%r"
-              % (seed, case, bits, group, rep, kvh, batch, tb, max_seq, lens.tolist(), use_tail, cap, tl.tolist(), splits, waves),
+        print("seed %d i3=%d case %d: bits=%d G=%d rep=%d kvh=%d B=%d Tb=%d max_seq=%d lens=%s tail=%s cap=%d tl=%s splits=%r waves=%r"
+              % (seed, i3, case, bits, group, rep, kvh, batch, tb, max_seq, lens.tolist(), use_tail, cap, tl.tolist(), splits, waves),
               flush=True)
         pairs = [(b, h) for b in range(batch) for h in range(kvh)]
         cache = oracle_cache_for_pairs(w, ofmt, pairs, lens, seed=case)

@@ -89,6 +89,16 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     assert st == -1
     st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, None)
     assert st == -2
+    # three local tensors need the two extra arrays
+    three = dq.Format(4, 128, 128, 16, 8, 128, 8).c()
+    fake.p[6] = 0
+    fake.p[7] = 0
+    need3 = dq.lib.dq_decode_workspace_bytes(C.byref(three), 2, 4, 4, 1024)
+    assert need3 == need
+    st = dq.lib.dq_attn_decode(C.byref(three), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need3, 0, None)
+    assert st == -1
+    st = dq.lib.dq_compress_kv(C.byref(three), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed, None)
+    assert st == -1
     # quantize_pack: rows not a multiple of 128
     st = dq.lib.dq_quantize_pack(C.byref(good), ptr, 100, 0, ptr, ptr, None)
     assert st == -1
