@@ -38,6 +38,7 @@ PROFILED_TRAFFIC_BYTES = {
     ("llama7b_8bit", "mfma"): (137580 + 64) * 1.9994 * 1024,
     ("llama13b_mixed", "mfma"): (152210 + 352) * 2.0150 * 1024,
     ("gqa_long", "mfma"): (287270 + 764) * 1.9997 * 1024,
+    ("llama7b_4bit_n3", "mfma"): (72851 + 64) * 1.9988 * 1024,
 }
 
 
@@ -271,7 +272,8 @@ def main():
         "data": "synthetic",
         "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "seq_len": [int(lens.min()), int(lens.max())], "bits": w.bits,
-                   "group": w.group, "block_tokens": w.block_tokens, "j1": w.j1, "kernel_path": path,
+                   "group": w.group, "block_tokens": w.block_tokens, "j1": w.j1, "local_tensors": 3 if w.i3 > 1 else 2,
+                   "kernel_path": path,
                    "cache_copies_rotated": n_layers, "cache_bytes_per_layer": cache0.nbytes()},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": PROFILED_TRAFFIC_BYTES.get((w.name, path)),
