@@ -540,13 +540,15 @@ def test_decode_with_fp16_tail(name, kw, lens, tail_lens, flags):
     assert (np.abs(out_plain.cpu().numpy().astype(np.float64) - want_plain) <= tolerance(want_plain)).all()
 
 
-def test_kv_cache_layer_policy_prefill_then_decode_steps():
+@pytest.mark.parametrize("i3", [1, 8])
+def test_kv_cache_layer_policy_prefill_then_decode_steps(i3):
     """Section 3.2 end to end: a ragged prefill goes through the tail, whole blocks are compressed
     as they fill, then single tokens are appended step by step and every decode attends to blocks +
-    tail.  Checked against the oracle reading the GPU's own compressed arrays."""
-    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=400, min_seq=400)
+    tail.  Checked against the oracle reading the GPU's own compressed arrays.  i3 = 8: the same
+    with three local tensors per block."""
+    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=400, min_seq=400, i3=i3)
     fmt, ofmt = formats(w)
-    _say("KVCacheLayer policy")
+    _say("KVCacheLayer policy, i3=%d" % i3)
     layer = dq.KVCacheLayer(fmt, w.batch, w.q_heads, w.kv_heads, 512, DEV)
     k, v = workloads.kv_tensor(w)                      # [2, 2, 400, 128]
     kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
