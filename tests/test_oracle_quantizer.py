@@ -158,3 +158,24 @@ def test_compression_ratio_closed_form_and_storage_bytes():
     # bytes per cached token per kv head, keys + values (the benchmark's algorithmic bytes)
     assert 2 * O.cache_bytes_per_block(fmt) / 128 == 140
     assert 2 * O.cache_bytes_per_block(O.Format(2, 64, 128, 16, 8, 128)) / 128 == 80
+
+
+def test_compression_ratio_against_the_sizes_the_paper_prints():
+    # Section 4.2, main results table, column "Size (MB)": 46.7 at 16 bits, 23.3 / 11.7 / 5.8 at
+    # 8 / 4 / 2 bits, i.e. B/16 of the fp16 cache to the table's rounding.  Eq. 4 adds the small
+    # tensor and the steps on top: a few percent of the fp16 size, never less than B/16.
+    import os
+    rows = {}
+    with open(os.path.join(os.path.dirname(__file__), "golden", "table_sizes.txt")) as f:
+        for line in f:
+            if line.strip() and not line.startswith("#"):
+                bits, mb = line.split()
+                rows[int(bits)] = float(mb)
+    for bits in (8, 4, 2):
+        printed = rows[bits] / rows[16]
+        assert abs(printed - bits / 16) <= 0.06 / rows[16] + 1e-12          # one unit of the last printed digit
+        for group in (128, 64):
+            mu = O.compression_ratio(O.Format(bits, group, 128, 16, 8, 128))
+            overhead = (16 * 16 * 16 + 128 * (128 // group) * 16) / (128 * 128 * 16.0)
+            assert abs(mu - (bits / 16 + overhead)) < 1e-15
+            assert printed - 0.002 <= mu <= printed + 0.04
