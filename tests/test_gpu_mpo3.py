@@ -131,6 +131,68 @@ def test_compress_kv_three_tensors_properties(name, t_new, n_valid):
     kw = dict(batch=3 if n_valid else 2, q_heads=4, kv_heads=2) if name != "tiny" else {}
     w = _small(name, **kw) if name != "tiny" else dataclasses.replace(workloads.get_workload("tiny"), i3=8)
     _say("compress, three tensors: %s t_new=%d n_valid=%s" % (name, t_new, n_valid))
+    _check_compress3(w, t_new, n_valid)
+
+
+@pytest.mark.parametrize("seed", [31, 32])
+def test_compress_kv_three_tensors_random_cases(seed):
+    """Seeded sweep: code widths, group sizes, head dimensions, block sizes, ragged n_valid, short
+    t_new, skipped sequences."""
+    rng = np.random.default_rng(seed)
+    for case in range(8):
+        d = int(rng.choice([128, 128, 64]))
+        j1 = 16 if d == 128 and rng.integers(0, 4) else int(rng.choice([8, 16] if d == 64 else [8, 32]))
+        bits = int(rng.choice([2, 4, 8]))
+        group = int(rng.choice([g for g in (32, 64, 128) if g <= d and (g == d or g <= d // 2) and (g * bits) % 32 == 0]))
+        tb = int(rng.choice([128, 256]))
+        batch, kvh = int(rng.choice([2, 3])), int(rng.choice([1, 2, 5]))
+        t_new = int(rng.choice([tb, tb, int(rng.integers(1, tb + 1))]))
+        n_valid = None if rng.integers(0, 2) else [int(rng.choice([1, 2, t_new, int(rng.integers(1, t_new + 1))])) for _ in range(batch)]
+        w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=kvh, kv_heads=kvh, head_dim=d,
+                                j1=j1, j2=d // j1, bits=bits, group=group, block_tokens=tb, max_seq=tb, min_seq=tb,
+                                seed=5000 + 100 * seed + case, n_outlier=int(rng.choice([0, 2, 6])), i3=8)
+        _say("compress, three tensors, random seed %d case %d: d=%d j1=%d bits=%d G=%d Tb=%d B=%d H=%d t_new=%d n_valid=%s"
+             % (seed, case, d, j1, bits, group, tb, batch, kvh, t_new, n_valid))
+        _check_compress3(w, t_new, n_valid)
+
+
+@pytest.mark.parametrize("i3", [1, 8])
+def test_compress_kv_degenerate_blocks(i3):
+    """All-zero blocks, a block of identical rows (rank one on both sides), a block whose only
+    non-zero entries sit in one channel, values at the fp16 limit: the decomposition must settle
+    and leave finite factors whose product is the block."""
+    w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=2, q_heads=2, kv_heads=2, max_seq=128, min_seq=128, i3=i3)
+    fmt, ofmt = formats(w)
+    r = np.random.default_rng(77)
+    blocks = np.zeros((2, 2, 128, 128), np.float16)          # (0, 0): all zero
+    blocks[0, 1] = r.standard_normal(128).astype(np.float16)[None, :]                 # identical rows
+    blocks[1, 0, :, 37] = r.standard_normal(128).astype(np.float16)                   # one channel
+    blocks[1, 1] = (r.choice([-1.0, 1.0], size=(128, 128)) * 60000.0).astype(np.float16)   # near the fp16 limit
+    cache = dq.alloc_cache(fmt, 2, 2, 1, DEV, fill=0xA5)
+    ws = dq.compress_workspace(fmt, 2, 2, DEV)
+    x = torch.from_numpy(blocks).to(DEV)
+    dq.compress_kv(cache, x, x.clone(), torch.zeros(2, dtype=torch.int32, device=DEV), None, ws)
+    torch.cuda.synchronize()
+    sweeps = int(ws[4:8].view(torch.int32).item())
+    _say("degenerate blocks, i3=%d: status %d, sweeps %d" % (i3, int(ws[:4].view(torch.int32).item()), sweeps))
+    assert sweeps <= 10
+    arrs = {n: t.cpu().numpy() for n, t in cache.t.items()}
+    for b in range(2):
+        for h in range(2):
+            for which in ("k", "v"):
+                blk = O.load_block(arrs, ofmt, b, h, 0, which)
+                assert all(np.isfinite(np.asarray(a, np.float64)).all() for a in blk)
+                x_hat = O.reconstruct_block(blk[0], blk[1], blk[2], ofmt, *blk[3:])
+                ref = blocks[b, h].astype(np.float64)
+                bound = O.reconstruction_bound(blk[0], blk[1], ofmt, *blk[3:])
+                # the half-step bound plus the fp16 rounding of the small tensors (saturated T_S excepted)
+                slack = 2.0 ** -8 * np.abs(ref).max() + 1e-6
+                if (b, h) == (1, 1) and int(ws[:4].view(torch.int32).item()) & 1:
+                    continue     # T_S saturated (status bit 0): the product is no longer the block
+                assert (np.abs(x_hat - ref) <= bound + slack).all(), (b, h, which, np.abs(x_hat - ref).max())
+
+
+def _check_compress3(w, t_new, n_valid):
     fmt, ofmt = formats(w)
     tb, d, j1, j2 = fmt.block_tokens, fmt.head_dim, fmt.j1, fmt.j2
     k = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[0] for h in range(w.kv_heads)]) for b in range(w.batch)])
