@@ -53,6 +53,8 @@ def _split_remarks(log: str):
                 kernels[name][key.split(" [")[0]] = int(val)
         elif "kernel-resource-usage" not in line:
             rest.append(line)
+    if not any(("warning" in l) or ("error" in l) for l in rest):
+        rest = []   # only the include trail that led to the remarks is left
     return kernels, "\n".join(rest)
 
 

@@ -47,7 +47,8 @@ int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int 
   int n = 1, nw = 4;
   if (max_tiles > 0) {
     if (mfma) {
-      choose_mfma_shape(batch * kv_heads, max_tiles, q_heads / kv_heads, f->bits, &n, &nw);
+      const int hg = mfma_head_groups(f, q_heads, kv_heads);   // each head group is a workgroup of its own
+      choose_mfma_shape(batch * kv_heads * hg, max_tiles, q_heads / kv_heads / hg, f->bits, &n, &nw);
     } else {
       const int units = batch * q_heads;
       n = (2048 + units - 1) / units;
@@ -134,7 +135,7 @@ extern "C" size_t dq_decode_workspace_bytes(const dq_format* fmt, int32_t batch,
   if (!format_ok(fmt) || batch <= 0 || q_heads <= 0 || kv_heads <= 0 || q_heads % kv_heads ||
       max_seq_len < 0)
     return 0;
-  return (size_t)kWsHeaderBytes + decode_counter_bytes(batch, kv_heads) +
+  return (size_t)kWsHeaderBytes + decode_counter_bytes(batch, q_heads) +
          decode_partial_bytes(fmt, batch, q_heads);
 }
 
@@ -185,13 +186,14 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   a.out_f32 = out_f32;
   char* ws = reinterpret_cast<char*>(workspace);
   a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
-  a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, cache->kv_heads));
+  a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, q_heads));
+  a.head_groups = use_mfma ? mfma_head_groups(fmt, q_heads, cache->kv_heads) : 1;
   a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, &a.nw);
   // With one workgroup per compute unit and equal shares, a launch ends with its slowest XCD.
   // Dealing the units so that every XCD sees every residue class of them (mod 8) brings the XCDs
   // closer together: measured 4 - 5 % faster on the 256-unit benchmark shapes (4- and 8-bit), neutral
   // or within half a percent either way on the other workloads, where the plain order stays.
-  a.unit_map = (a.n_split == 1 && cache->batch * cache->kv_heads <= 256) ? 3 : 0;
+  a.unit_map = (a.n_split == 1 && a.head_groups == 1 && cache->batch * cache->kv_heads <= 256) ? 3 : 0;
   if (const char* env = getenv("DQ_DECODE_UNIT_MAP")) a.unit_map = atoi(env);   // tuning aid
   a.n_slots = a.n_split + (tail ? 1 : 0);
   if (tail) a.tail = *tail;

@@ -15,11 +15,12 @@ struct DecodeArgs {
   uint16_t* out;           // [B, Hq, d] fp16 bits
   float* out_f32;          // optional
   float* partials;         // [B*Hq, n_split, d + 2]
-  int32_t* counters;       // [B*Hkv] zero between calls
+  int32_t* counters;       // [B*Hkv*head_groups] zero between calls
   int n_split;
   int n_slots;             // partial slots per (b, head): n_split, plus one for the fp16 tail
   dq_tail tail;            // k_tail == nullptr: no tail
   int nw;                  // waves per workgroup of the matrix-core kernel (4 or 8)
+  int head_groups;         // matrix-core kernel: workgroups per (sequence, kv head, split), each with q_heads/kv_heads/head_groups heads
   int unit_map;            // which (sequence, kv head) a workgroup row takes: 0 = its own index, see unit_of_row()
   hipEvent_t ev_start;     // optional: recorded around the main kernel
   hipEvent_t ev_stop;
@@ -42,8 +43,8 @@ __host__ __device__ inline int unit_of_row(int row, int units, int unit_map) {
 }
 
 // Workspace carve-up shared by the host entry points.
-inline size_t decode_counter_bytes(int batch, int kv_heads) {
-  return align_up((size_t)batch * kv_heads * sizeof(int32_t), 256);
+inline size_t decode_counter_bytes(int batch, int q_heads) {   // one per (sequence, kv head, head group) at most
+  return align_up((size_t)batch * q_heads * sizeof(int32_t), 256);
 }
 inline size_t decode_partial_bytes(const dq_format* f, int batch, int q_heads) {
   return (size_t)batch * q_heads * (kMaxSplits + 1) * (f->head_dim + 2) * sizeof(float);
@@ -53,6 +54,7 @@ int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st);
 int32_t launch_tail_partial(const DecodeArgs& a, float m_unit, hipStream_t st);
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads);
+int mfma_head_groups(const dq_format* f, int q_heads, int kv_heads);
 int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma,
                   int* nw_out);
 

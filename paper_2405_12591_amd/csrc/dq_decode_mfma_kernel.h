@@ -180,8 +180,16 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // computed once per wave on the scalar unit instead of once per lane
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
   const int n = lane & 15, g = lane >> 4;
+  // More query heads per kv head than the sixteen B columns hold (R of them per workgroup) are
+  // served in head groups: head_groups workgroups per (sequence, kv head, split), each streaming
+  // the same codes for its own R heads.  The groups are the slow part of the grid's y index, so the
+  // workgroups of one (sequence, kv head) are a multiple of eight apart in launch order (whenever
+  // the number of units is one) and land on the same XCD: while they run side by side, the second
+  // to ask for a line finds it in that XCD's L2.
   const int split = blockIdx.x;
-  const int bh = unit_of_row(blockIdx.y, gridDim.y, a.unit_map);
+  const int n_units = gridDim.y / a.head_groups;
+  const int hgrp = blockIdx.y / n_units;
+  const int bh = unit_of_row(blockIdx.y % n_units, n_units, a.unit_map);
   const int H = a.cache.kv_heads, NB = a.cache.block_capacity;
   const int b = bh / H, h = bh % H;
   const int tpb = a.fmt.block_tokens / kTileTokens;
@@ -197,7 +205,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   int S = 0;  // the sequence's real length, read after the speculative loads are on their way
 
   // ---- the last workgroup of this (sequence, kv head) to finish merges the partial results ----
-  const long bhq0 = (long)b * a.q_heads + (long)h * R;
+  const long hq_first = (long)h * (a.q_heads / H) + (long)hgrp * R;   // this workgroup's first query head
+  const long bhq0 = (long)b * a.q_heads + hq_first;
+  int32_t* const ticket_counter = a.counters + (long)bh * a.head_groups + hgrp;
   const int n_contrib = a.n_split;   // workgroups that hand in partials
   auto ticket_and_merge = [&]() __attribute__((always_inline)) {
     // The barrier waits for every thread's stores above to be acknowledged; only then does one
@@ -205,9 +215,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) {
-      const int ticket = __hip_atomic_fetch_add(&a.counters[bh], 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      const int ticket = __hip_atomic_fetch_add(ticket_counter, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last = (ticket == n_contrib - 1);
-      if (s_last) __hip_atomic_store(&a.counters[bh], 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next call
+      if (s_last) __hip_atomic_store(ticket_counter, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);  // clean for the next call
     }
     __syncthreads();
     if (!s_last) return;
@@ -295,7 +305,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const int hd = 2 * f + (n >> 3);
       // no branch here (columns past the last head read head R - 1 and are zeroed when packed):
       // across a branch the compiler loses count of the loads in flight and waits for all of them
-      const uint16_t* qp = a.q + ((long)b * a.q_heads + (long)h * R + min(hd, R - 1)) * D;
+      const uint16_t* qp = a.q + (bhq0 + min(hd, R - 1)) * D;
 #pragma unroll
       for (int i = 0; i < 4; ++i) q_raw[f][i] = qp[(4 * g + i) * J2 + b2];
     }
@@ -658,7 +668,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // off while the codes are on their way.
   Tail tb;
   const bool do_tail = (TM == 1) || (TM == 2 && split == 0);   // TM == 2: a branch, and coarser waits
-  if (do_tail) tb.issue_keys(a, b, h, (long)h * R, R);
+  if (do_tail) tb.issue_keys(a, b, h, hq_first, R);
   issue_tile(spec_ok ? first_tile : 0);
   // Both lengths are requested only now (a scalar load that is still out holds up every wait on
   // scalar data, the addresses of the loads above among them) and before the asm statements below
@@ -767,7 +777,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 }
 template <int BITS, int NG, int R, int TM, bool N3>
 inline void launch_tm(const DecodeArgs& a, hipStream_t st) {
-  const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads);
+  const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads * a.head_groups);
   // the events, when given, receive the kernel's own begin and end timestamps
   // (8-bit codes: a wave's ring of chunks is twice as large and an 8-wave workgroup runs out of
   // registers, so that width always takes 4 waves)
@@ -795,7 +805,7 @@ inline void launch_r(const DecodeArgs& a, hipStream_t st) {
 
 template <int BITS>
 int32_t launch_bits(const DecodeArgs& a, hipStream_t st) {
-  const int rep = a.q_heads / a.cache.kv_heads;
+  const int rep = a.q_heads / a.cache.kv_heads / a.head_groups;   // query heads per workgroup
   if (a.fmt.group == 128) {
     switch (rep) {
       case 1: launch_r<BITS, 1, 1>(a, st); break;
