@@ -47,8 +47,9 @@ int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int 
   int n = 1, nw = 4;
   if (max_tiles > 0) {
     if (mfma) {
-      const int hg = mfma_head_groups(f, q_heads, kv_heads);   // each head group is a workgroup of its own
-      choose_mfma_shape(batch * kv_heads * hg, max_tiles, q_heads / kv_heads / hg, f->bits, &n, &nw);
+      int per_group = 1;
+      const int hg = mfma_head_groups(f, q_heads, kv_heads, &per_group);   // each head group is a workgroup of its own
+      choose_mfma_shape(batch * kv_heads * hg, max_tiles, per_group, f->bits, &n, &nw);
     } else {
       const int units = batch * q_heads;
       n = (2048 + units - 1) / units;
@@ -187,7 +188,8 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   char* ws = reinterpret_cast<char*>(workspace);
   a.counters = reinterpret_cast<int32_t*>(ws + kWsHeaderBytes);
   a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, q_heads));
-  a.head_groups = use_mfma ? mfma_head_groups(fmt, q_heads, cache->kv_heads) : 1;
+  a.heads_per_group = q_heads / cache->kv_heads;
+  a.head_groups = use_mfma ? mfma_head_groups(fmt, q_heads, cache->kv_heads, &a.heads_per_group) : 1;
   a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, &a.nw);
   // With one workgroup per compute unit and equal shares, a launch ends with its slowest XCD.
   // Dealing the units so that every XCD sees every residue class of them (mod 8) brings the XCDs

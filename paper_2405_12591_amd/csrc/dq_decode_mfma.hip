@@ -6,26 +6,29 @@
 namespace dq {
 
 // Query heads per kv head that one workgroup takes: four B columns per head and step group of the
-// sixteen, so at most 4 (one step group) or 2 (two); the kernel is built for 1, 2 and 4.  More heads,
-// or a number that is none of these, are served in equal groups of the largest size that divides it.
+// sixteen, so at most 4 (one step group) or 2 (two); the kernel is built for 1, 2 and 4.  More heads
+// are served in groups of that many, the last group taking what is left (7 = 4 + 3); a number that
+// is not a power of two takes the next size up (3 heads run in a workgroup built for 4).
 static int heads_per_workgroup(const dq_format* f, int rep) {
   const int most = (f->group == 128) ? 4 : 2;
-  for (int r = most; r >= 1; r >>= 1)
-    if (rep % r == 0) return (rep / r <= kMaxHeadGroups) ? r : 0;
-  return 0;
+  int r = 1;
+  while (r < rep && r < most) r <<= 1;
+  return ((rep + r - 1) / r <= kMaxHeadGroups) ? r : 0;
 }
 
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
-  if (!format_ok(f) || kv_heads <= 0 || q_heads % kv_heads) return false;
+  if (!format_ok(f) || kv_heads <= 0 || q_heads <= 0 || q_heads % kv_heads) return false;
   if (f->head_dim != 128 || f->j1 != 16 || f->j2 != 8) return false;
   if (f->bits != 8 && f->bits != 4 && f->bits != 2) return false;
   if (f->group != 128 && f->group != 64) return false;
   return heads_per_workgroup(f, q_heads / kv_heads) > 0;
 }
 
-int mfma_head_groups(const dq_format* f, int q_heads, int kv_heads) {
+int mfma_head_groups(const dq_format* f, int q_heads, int kv_heads, int* heads_per_group) {
   const int rep = q_heads / kv_heads;
-  return rep / heads_per_workgroup(f, rep);
+  const int r = heads_per_workgroup(f, rep);
+  if (heads_per_group) *heads_per_group = r;
+  return (rep + r - 1) / r;
 }
 
 // defined in dq_decode_mfma_b8.hip, _b4.hip, _b2.hip

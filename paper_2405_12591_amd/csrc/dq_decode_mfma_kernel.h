@@ -206,6 +206,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 
   // ---- the last workgroup of this (sequence, kv head) to finish merges the partial results ----
   const long hq_first = (long)h * (a.q_heads / H) + (long)hgrp * R;   // this workgroup's first query head
+  // the last group may hold fewer than R heads (3 = 3, 7 = 4 + 3 query heads per kv head): the columns
+  // of the missing ones compute on a zero query and are never written out
+  const int nh = min(R, a.q_heads / H - hgrp * R);
   const long bhq0 = (long)b * a.q_heads + hq_first;
   int32_t* const ticket_counter = a.counters + (long)bh * a.head_groups + hgrp;
   const int n_contrib = a.n_split;   // workgroups that hand in partials
@@ -225,7 +228,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     // flight together), and leaves each slot's weight in LDS; then every thread adds up its output
     // element over the slots, eight device-scope loads at a time.
     const int ns = a.n_slots;   // <= kMaxSplits + 1 (the tail's slot included)
-    if (wave < R) {
+    if (wave < nh) {
       const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
       float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
       if (lane < ns) {
@@ -245,7 +248,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       if (lane == 0) s_sum[wave] = L;
     }
     __syncthreads();
-    for (int idx = tid; idx < R * D; idx += 64 * NW) {
+    for (int idx = tid; idx < nh * D; idx += 64 * NW) {
       const int hd = idx / D, c = idx % D;
       const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
       float o = 0.f;
@@ -303,9 +306,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 #pragma unroll
     for (int f = 0; f < F; ++f) {
       const int hd = 2 * f + (n >> 3);
-      // no branch here (columns past the last head read head R - 1 and are zeroed when packed):
+      // no branch here (columns past the last head read head nh - 1 and are zeroed when packed):
       // across a branch the compiler loses count of the loads in flight and waits for all of them
-      const uint16_t* qp = a.q + (bhq0 + min(hd, R - 1)) * D;
+      const uint16_t* qp = a.q + (bhq0 + min(hd, nh - 1)) * D;
 #pragma unroll
       for (int i = 0; i < 4; ++i) q_raw[f][i] = qp[(4 * g + i) * J2 + b2];
     }
@@ -668,7 +671,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // off while the codes are on their way.
   Tail tb;
   const bool do_tail = (TM == 1) || (TM == 2 && split == 0);   // TM == 2: a branch, and coarser waits
-  if (do_tail) tb.issue_keys(a, b, h, hq_first, R);
+  if (do_tail) tb.issue_keys(a, b, h, hq_first, nh);
   issue_tile(spec_ok ? first_tile : 0);
   // Both lengths are requested only now (a scalar load that is still out holds up every wait on
   // scalar data, the addresses of the loads above among them) and before the asm statements below
@@ -678,14 +681,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const int tail_len_raw = do_tail ? a.tail.tail_lens[b] : 0;
 #pragma unroll
   for (int f = 0; f < F; ++f) {
-    const bool head_live = (2 * f + (n >> 3)) < R;
+    const bool head_live = (2 * f + (n >> 3)) < nh;
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       asm volatile("" : "+v"(q_raw[f][i]));   // nothing derived from q may move above the requests
       bq[f][i] = __builtin_bit_cast(_Float16, (uint16_t)(head_live ? q_raw[f][i] : 0u));
     }
   }
-  if (do_tail) tb.finish(tail_len_raw, R, reinterpret_cast<float*>(smem), s_tail);
+  if (do_tail) tb.finish(tail_len_raw, nh, reinterpret_cast<float*>(smem), s_tail);
 
   if (NG == 2) {
     // A channel contributes nothing to the other group's columns: those bytes of the query limbs
@@ -722,7 +725,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     for (int hd = 0; hd < R; ++hd) { Mml[hd] = m_run[hd]; Mml[R + hd] = l_run[hd]; }
   }
   __syncthreads();
-  for (int idx = tid; idx < R * D; idx += 64 * NW) {
+  for (int idx = tid; idx < nh * D; idx += 64 * NW) {
     const int hd = idx / D, c = idx % D;
     float M = -INFINITY;
 #pragma unroll
@@ -805,7 +808,7 @@ inline void launch_r(const DecodeArgs& a, hipStream_t st) {
 
 template <int BITS>
 int32_t launch_bits(const DecodeArgs& a, hipStream_t st) {
-  const int rep = a.q_heads / a.cache.kv_heads / a.head_groups;   // query heads per workgroup
+  const int rep = a.heads_per_group;   // query heads per workgroup (the last group may hold fewer)
   if (a.fmt.group == 128) {
     switch (rep) {
       case 1: launch_r<BITS, 1, 1>(a, st); break;

@@ -286,8 +286,9 @@ def test_stream_read_runs():
     ("llama7b_2bit", dict(batch=2, q_heads=8, kv_heads=2, max_seq=900, min_seq=900, group=128), [900, 385]),
     # more query heads per kv head than one workgroup takes: head groups
     ("gqa_long", dict(batch=2, q_heads=16, kv_heads=2, max_seq=900, min_seq=900), [900, 130]),       # 2 groups of 4
-    ("gqa_long", dict(batch=2, q_heads=6, kv_heads=2, max_seq=700, min_seq=700), [700, 1]),          # 3 groups of 1
-    ("gqa_long", dict(batch=1, q_heads=12, kv_heads=2, max_seq=2300, min_seq=2300), [2300]),         # 3 groups of 2
+    ("gqa_long", dict(batch=2, q_heads=6, kv_heads=2, max_seq=700, min_seq=700), [700, 1]),          # 3 heads in a group of 4
+    ("gqa_long", dict(batch=1, q_heads=14, kv_heads=2, max_seq=2300, min_seq=2300), [2300]),         # 7 = 4 + 3
+    ("llama7b_2bit", dict(batch=2, q_heads=6, kv_heads=2, max_seq=640, min_seq=640), [640, 200]),    # G64: 3 = 2 + 1
     ("llama7b_2bit", dict(batch=2, q_heads=8, kv_heads=2, max_seq=900, min_seq=900), [900, 385]),    # G64: 2 groups of 2
     # 8-bit codes
     ("llama7b_8bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=1000, min_seq=1000), [1000, 257]),
@@ -311,8 +312,9 @@ def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
     assert dq.decode_mfma_supported(dq.Format(2, 128, 128, 16, 8, 128), 32, 8)
     assert dq.decode_mfma_supported(dq.Format(4, 64, 128, 16, 8, 128), 32, 16)
     assert dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 64, 8)     # two head groups of four
-    assert dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 24, 8)     # three groups of one
-    assert not dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 34, 2)  # seventeen groups
+    assert dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 24, 8)     # three heads in a workgroup built for four
+    assert dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 34, 2)     # 17 = 4 + 4 + 4 + 4 + 1
+    assert not dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 130, 2)  # seventeen groups
     assert not dq.decode_mfma_supported(dq.Format(4, 32, 128, 16, 8, 128), 32, 32)
     assert dq.decode_mfma_supported(dq.Format(8, 128, 128, 16, 8, 128), 32, 32)
     assert not dq.decode_mfma_supported(dq.Format(8, 32, 128, 16, 8, 128), 32, 32)

@@ -23,7 +23,7 @@ def test_random_decode_cases(seed, i3, monkeypatch):
     for case in range(16):
         bits = int(rng.choice([2, 4, 8]))
         group = int(rng.choice([64, 128]))
-        rep = int(rng.choice([1, 2, 4, 8, 3] if group == 128 else [1, 2, 4]))
+        rep = int(rng.choice([1, 2, 4, 8, 3, 7] if group == 128 else [1, 2, 4, 3]))
         kvh, batch = int(rng.choice([1, 2, 3])), int(rng.choice([1, 2, 3]))
         tb = int(rng.choice([128, 256]))
         max_seq = int(rng.choice([128, 300, 640, 1100, 2100]))
