@@ -224,13 +224,21 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     }
     __syncthreads();
     if (!s_last) return;
-    // Wave hd reads the maxima and sums of head hd's partials, one slot per lane (all loads in
-    // flight together), and leaves each slot's weight in LDS; then every thread adds up its output
-    // element over the slots, eight device-scope loads at a time.
+    // Wave hd requests the maxima and sums of head hd's partials, one slot per lane, and every
+    // thread the first eight slots of its output element, all in flight together; wave hd leaves
+    // each slot's weight in LDS; then every thread adds up
+    // its element over the slots, eight device-scope loads at a time (slots past the last one are
+    // not read and weigh nothing).
     const int ns = a.n_slots;   // <= kMaxSplits + 1 (the tail's slot included)
+    auto load_slots = [&](const float* col, int sp, float (&v)[8]) __attribute__((always_inline)) {
+#pragma unroll
+      for (int k = 0; k < 8; ++k)
+        v[k] = (sp + k < ns) ? __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+    };
+    float v_first[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
+    float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
     if (wave < nh) {
       const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
-      float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
       if (lane < ns) {
         m0 = __hip_atomic_load(base + lane * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         l0 = __hip_atomic_load(base + lane * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
@@ -239,6 +247,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         m1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         l1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
+    }
+    if (tid < nh * D) load_slots(a.partials + (bhq0 + tid / D) * ns * (D + 2) + tid % D, 0, v_first);
+    if (wave < nh) {
       const float M = wave_allmax(fmaxf(m0, m1));
       const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m0 - M);
       const float w1 = (m1 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m1 - M);
@@ -252,21 +263,19 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const int hd = idx / D, c = idx % D;
       const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
       float o = 0.f;
-      int sp = 0;
-      for (; sp + 8 <= ns; sp += 8) {
+      for (int sp = 0; sp < ns; sp += 8) {
         float v[8];
+        if (idx == tid && sp == 0) {
 #pragma unroll
-        for (int k = 0; k < 8; ++k) v[k] = __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          for (int k = 0; k < 8; ++k) v[k] = v_first[k];
+        } else {
+          load_slots(col, sp, v);
+        }
 #pragma unroll
         for (int k = 0; k < 8; ++k) {
-          const float wk = s_wgt[hd][sp + k];
+          const float wk = (sp + k < ns) ? s_wgt[hd][sp + k] : 0.f;
           o = (wk != 0.f) ? fmaf(v[k], wk, o) : o;   // an empty slot contributes nothing whatever it holds
         }
-      }
-      for (; sp < ns; ++sp) {
-        const float wk = s_wgt[hd][sp];
-        const float vk = __hip_atomic_load(col + sp * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        o = (wk != 0.f) ? fmaf(vk, wk, o) : o;
       }
       const float L = s_sum[hd];
       const float r = (L > 0.f) ? o / L : 0.f;
