@@ -1,7 +1,8 @@
 // Matrix-core decode attention over the compressed cache for the formats
-//   bits in {2, 4, 8};  group = 128 with q_heads / kv_heads in {1, 2, 4},
-//                       group = 64  with q_heads / kv_heads in {1, 2}
-// with head_dim = 128, j1 = 16, j2 = 8, block_tokens % 128 == 0.
+//   bits in {2, 4, 8};  group = 128 with 1, 2 or 4 query heads of a kv head per workgroup,
+//                       group = 64  with 1 or 2
+// with head_dim = 128, j1 = 16, j2 = 8, block_tokens % 128 == 0, two or three local tensors.
+// More query heads per kv head are served by several workgroups (head groups) over the same codes.
 //
 // This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
 // 2405.12591) carried through the attention that follows it.  The low-bit codes never become
@@ -20,7 +21,9 @@
 //      wave-private LDS); w_t = p_t * step^V_t is cut into limbs, again B columns;
 //   4. streams the value codes (stored token-contiguous): o'[r, b2] = sum_t u[t, r, b2] limb[t];
 //   5. applies the values' small tensor with fp32 16x16x4 MFMAs,
-//      acc[b1, b2] = alpha * acc + sum_r T_S^V[b1, r] o'[r, b2].
+//      acc[b1, b2] = alpha * acc + sum_r T_S^V[b1, r] o'[r, b2]
+//      (the limb columns of several b2 packed side by side first, so that the sixteen columns
+//      of these MFMAs are all in use).
 // With two step groups per token row (group = 64: rows r < 8 and r >= 8 of the large tensor)
 // every limb gets one B column per group: the key side zeroes the limbs of the other group's
 // channels, the value side takes each row of o' from the column of that row's group.
