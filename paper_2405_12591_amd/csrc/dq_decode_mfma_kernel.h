@@ -113,13 +113,31 @@ __device__ __forceinline__ float dpp_f(float v) {
 __device__ __forceinline__ float lane_f(float v, int l) {
   return __builtin_bit_cast(float, __builtin_amdgcn_readlane(__builtin_bit_cast(int, v), l));
 }
-// all-reduce over the 16 lanes of a row, then over the four rows
-__device__ __forceinline__ float wave_allmax(float v) {
-  v = fmaxf(v, dpp_f<0xB1>(v));   // quad_perm [1,0,3,2]
-  v = fmaxf(v, dpp_f<0x4E>(v));   // quad_perm [2,3,0,1]
-  v = fmaxf(v, dpp_f<0x141>(v));  // row_half_mirror
-  v = fmaxf(v, dpp_f<0x140>(v));  // row_mirror
-  return fmaxf(fmaxf(lane_f(v, 0), lane_f(v, 16)), fmaxf(lane_f(v, 32), lane_f(v, 48)));
+template <int CTRL>
+__device__ __forceinline__ int dpp_i(int v) {
+  return __builtin_amdgcn_update_dpp(0, v, CTRL, 0xF, 0xF, true);
+}
+// Maximum over the wave, taken on integer keys that order like the floats (for v >= 0 the bit
+// pattern itself; otherwise the low 31 bits of negative values are flipped): an integer maximum
+// takes its partner lane's value straight from the DPP operand, where a floating-point one needs
+// the value copied and quieted first.  All-reduce over the 16 lanes of a row, then over the four rows.
+__device__ __forceinline__ int wave_allmax_key(int x) {
+  x = max(x, dpp_i<0xB1>(x));    // quad_perm [1,0,3,2]
+  x = max(x, dpp_i<0x4E>(x));    // quad_perm [2,3,0,1]
+  x = max(x, dpp_i<0x141>(x));   // row_half_mirror
+  x = max(x, dpp_i<0x140>(x));   // row_mirror
+  return max(max(__builtin_amdgcn_readlane(x, 0), __builtin_amdgcn_readlane(x, 16)),
+             max(__builtin_amdgcn_readlane(x, 32), __builtin_amdgcn_readlane(x, 48)));
+}
+__device__ __forceinline__ float wave_allmax(float v) {          // any finite values and -inf
+  int x = __builtin_bit_cast(int, v);
+  x ^= (x >> 31) & 0x7FFFFFFF;
+  x = wave_allmax_key(x);
+  x ^= (x >> 31) & 0x7FFFFFFF;
+  return __builtin_bit_cast(float, x);
+}
+__device__ __forceinline__ float wave_allmax_nonneg(float v) {   // v >= 0 (+0 only)
+  return __builtin_bit_cast(float, wave_allmax_key(__builtin_bit_cast(int, v)));
 }
 __device__ __forceinline__ float wave_allsum(float v) {
   v += dpp_f<0xB1>(v);
@@ -463,7 +481,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 #pragma unroll
         for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(fd[f][i]));
       }
-      amax = wave_allmax(amax) * qk_scale;
+      amax = wave_allmax_nonneg(amax) * qk_scale;
       int e = 0;
       if (amax > 0.f && amax < INFINITY) e = __builtin_amdgcn_frexp_expf(amax);  // amax = f * 2^e, f in [0.5, 1)
       e = max(min(e, 100), -100);
@@ -525,7 +543,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     if (!N3) {
       float dvm = fmaxf(dvA[0], dvB[0]);
       if (NG == 2) dvm = fmaxf(dvm, fmaxf(dvA[NG - 1], dvB[NG - 1]));
-      const float dvmax = wave_allmax(dvm);
+      const float dvmax = wave_allmax_nonneg(dvm);
       int e = 0;
       if (dvmax > 0.f && dvmax < INFINITY) e = __builtin_amdgcn_frexp_expf(dvmax);
       vs = pow2i(kMantBits - e);   // p * step * vs < 2^21
@@ -585,7 +603,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     }
     if (N3) {
       // limbs relative to the largest weight of the tile: |w * vs| < 2^20, top limb signed
-      wmax = wave_allmax(wmax);
+      wmax = wave_allmax_nonneg(wmax);
       int e = 0;
       if (wmax > 0.f && wmax < INFINITY) e = __builtin_amdgcn_frexp_expf(wmax);
       e = max(min(e, 100), -100);
