@@ -190,7 +190,8 @@ size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t 
  * applied when a block of appended tokens has accumulated; Section 3.1 for the two steps).
  *   k_new, v_new  f16 [B, H, t_new, d], 1 <= t_new <= T_b (host integer)
  *   blk_idx       i32 [B] device, 0 <= blk_idx[b] < block_capacity; negative skips sequence b
- *   n_valid       i32 [B] device, rows >= n_valid[b] (and rows >= t_new) count as zero; may be NULL
+ *   n_valid       i32 [B] device, rows >= n_valid[b] (and rows >= t_new) count as zero; may be NULL;
+ *                 a sequence with no valid row is skipped like one with a negative blk_idx
  * The decomposition is an eigen-decomposition of the fp64 Gram matrix M M^T (j1 x j1) by
  * cyclic Jacobi rotations: T_S = U diag(sigma), T_L = diag(1/sigma) U^T M; directions with
  * sigma <= 1e-6 sigma_max are dropped (T_S column and T_L row zero).  T_S saturates to the
@@ -210,6 +211,24 @@ int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const uint16_t* k_
                        const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
                        const int32_t* n_valid, void* workspace, size_t workspace_bytes,
                        void* hip_stream);
+
+/*
+ * dq_compress_kv for a run of blocks per (sequence, kv head), as a prompt leaves it (Section 3.2:
+ * the cache is quantized block by block; every block is decomposed on its own): t_new >= 1 rows,
+ * cut into ceil(t_new / T_b) blocks of T_b rows, block j going to slot blk_idx[b] + j.  Same
+ * arguments and results as dq_compress_kv, whose kernels it shares (a block's bits do not depend on
+ * the call that wrote it), with these differences: the workspace holds the fp32 large tensors of
+ * all blocks ([B*H*blocks*2, T_b, d], K block j of (b, h) at index 2*((b*H+h)*blocks + j)) and is
+ * sized by dq_compress_blocks_workspace_bytes; a block whose slot falls outside the cache or none
+ * of whose rows is valid (rows >= n_valid[b]) is not written.  At most 2^22 blocks per call, keys
+ * and values counted apart.
+ */
+size_t dq_compress_blocks_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads,
+                                          int32_t t_new);
+int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                              const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                              const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                              void* hip_stream);
 
 /*
  * Quantize and pack a caller-supplied large tensor (Preliminary, Eq. 1 per group; Section 3.1

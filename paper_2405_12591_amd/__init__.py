@@ -22,6 +22,7 @@ from .binding import (  # noqa: F401
     workspace_init,
     attn_decode,
     compress_kv,
+    compress_kv_blocks,
     quantize_pack,
     stream_read,
     decode_mfma_supported,

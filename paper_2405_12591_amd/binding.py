@@ -17,7 +17,8 @@ DECODE_FORCE_MFMA = 2
 EXPORTED_SYMBOLS = [
     "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
     "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed", "dq_attn_decode_tail",
-    "dq_compress_workspace_bytes", "dq_compress_kv", "dq_quantize_pack", "dq_stream_read",
+    "dq_compress_workspace_bytes", "dq_compress_kv", "dq_compress_blocks_workspace_bytes", "dq_compress_kv_blocks",
+    "dq_quantize_pack", "dq_stream_read",
 ]
 
 
@@ -73,6 +74,10 @@ def _load() -> C.CDLL:
     l.dq_compress_kv.restype = C.c_int32
     l.dq_compress_kv.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_int32,
                                  C.c_void_p, C.c_void_p, C.c_void_p, C.c_size_t, C.c_void_p]
+    l.dq_compress_blocks_workspace_bytes.restype = C.c_size_t
+    l.dq_compress_blocks_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32, C.c_int32]
+    l.dq_compress_kv_blocks.restype = C.c_int32
+    l.dq_compress_kv_blocks.argtypes = l.dq_compress_kv.argtypes
     l.dq_quantize_pack.restype = C.c_int32
     l.dq_quantize_pack.argtypes = [C.POINTER(_CFormat), C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
@@ -204,11 +209,16 @@ def decode_workspace(fmt: Format, batch: int, q_heads: int, kv_heads: int, max_s
     return ws
 
 
-def compress_workspace(fmt: Format, batch: int, kv_heads: int, device="cuda:0") -> torch.Tensor:
+def compress_workspace(fmt: Format, batch: int, kv_heads: int, device="cuda:0",
+                       t_new: Optional[int] = None) -> torch.Tensor:
+    """Workspace of compress_kv; with t_new, of compress_kv_blocks for that many rows per sequence."""
     cf = fmt.c()
-    n = lib.dq_compress_workspace_bytes(C.byref(cf), batch, kv_heads)
+    if t_new is None:
+        n = lib.dq_compress_workspace_bytes(C.byref(cf), batch, kv_heads)
+    else:
+        n = lib.dq_compress_blocks_workspace_bytes(C.byref(cf), batch, kv_heads, t_new)
     if n == 0:
-        raise DQError("dq_compress_workspace_bytes rejected the arguments")
+        raise DQError("the compression workspace query rejected the arguments")
     return torch.empty((n + 15) // 16 * 16, dtype=torch.uint8, device=device)
 
 
@@ -264,6 +274,20 @@ def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx:
                             blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
                             workspace.data_ptr(), workspace.numel(), _stream_ptr(k_new.device))
     _check(st, "dq_compress_kv")
+
+
+def compress_kv_blocks(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
+                       n_valid: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+    """Compress k_new, v_new [B, H, t_new, d], any t_new >= 1, into the block slots from blk_idx[b]
+    on (dq_compress_kv_blocks)."""
+    for t in (k_new, v_new):
+        if t.dtype != torch.float16 or not t.is_contiguous():
+            raise DQError("k_new/v_new must be contiguous fp16")
+    cf = cache.fmt.c()
+    st = lib.dq_compress_kv_blocks(C.byref(cf), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
+                                   k_new.shape[2], blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
+                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(k_new.device))
+    _check(st, "dq_compress_kv_blocks")
 
 
 def quantize_pack(fmt: Format, t_large: torch.Tensor, value_layout: bool):

@@ -11,6 +11,7 @@ namespace dq {
 constexpr int kTileTokens = 128;   // tokens per value-code tile and per decode work tile
 constexpr int kMaxSplits = 64;     // upper bound on split-sequence partials per (b, head)
 constexpr int kWsHeaderBytes = 256;
+constexpr int kMaxCompressUnits = 1 << 22;   // blocks (keys and values counted apart) one compression call takes
 constexpr int kMaxHeadGroups = 16; // matrix-core decode: groups of query heads per kv head
 constexpr int kRun = 8;            // side of the third local tensor: tokens per run it mixes
 

@@ -10,6 +10,40 @@
 
 namespace dq {
 
+// What one dq_compress_kv call works on: t_new rows per (sequence, kv head), cut into n_blocks
+// blocks of T_b rows (the last one may be short); block j of sequence b goes to slot blk_idx[b] + j.
+struct CompressJob {
+  const uint16_t* k_new;     // [B, H, t_new, d] fp16 bits
+  const uint16_t* v_new;
+  int t_new;
+  int n_blocks;              // ceil(t_new / T_b)
+  const int32_t* blk_idx;    // [B]
+  const int32_t* n_valid;    // [B] or null
+};
+
+// Work unit `unit` = (((b * H + h) * n_blocks) + j) * 2 + which.  slot < 0: nothing to do (sequence
+// skipped, slot past the cache's capacity, or a block none of whose rows is valid).
+struct UnitRef {
+  int which, b, slot, nv;    // nv: valid rows of this block (the rest count as zero)
+  long bh;                   // b * H + h
+  const uint16_t* X;         // the block's first row
+};
+__device__ __forceinline__ UnitRef unit_ref(const Geometry& g, const CompressJob& job, int unit) {
+  UnitRef u;
+  u.which = unit & 1;
+  const int ub = unit >> 1;
+  const int j = ub % job.n_blocks;
+  u.bh = ub / job.n_blocks;
+  u.b = (int)(u.bh / g.H);
+  const int first = job.blk_idx[u.b];
+  int rows = job.t_new;
+  if (job.n_valid) rows = min(max(job.n_valid[u.b], 0), job.t_new);
+  u.nv = min(max(rows - j * g.Tb, 0), g.Tb);
+  u.slot = (first < 0 || first + j >= g.NB || u.nv == 0) ? -1 : first + j;
+  u.X = (u.which ? job.v_new : job.k_new) + (u.bh * job.t_new + (long)j * g.Tb) * g.d;
+  return u;
+}
+
 // ------------------------------------------------------------------------------------------
 // Quantize + pack one tile of 128 token rows (Eq. 1 per group).  256 threads.
 // ------------------------------------------------------------------------------------------
@@ -195,11 +229,11 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restr
                          codes + tile * tile_code_bytes, scales + tile * kTileTokens * (D / G), lds_u);
 }
 
-// Compress path: tile `blockIdx.x` of block (b, h, which) goes to cache slot blk_idx[b].
+// Compress path: tile `blockIdx.x % tiles_per_block` of work unit `blockIdx.x / tiles_per_block`.
 template <int BITS, int D>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __restrict__ large_ws,
                                                              dq_format fmt, dq_cache cache,
-                                                             const int32_t* __restrict__ blk_idx,
+                                                             CompressJob job,
                                                              const int32_t* __restrict__ unit_status,
                                                              int n_units, int32_t* __restrict__ status) {
   extern __shared__ uint8_t lds_u[];
@@ -221,13 +255,11 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __rest
     if (threadIdx.x < 2) status[threadIdx.x] = red[threadIdx.x];
   }
   const int tile = blockIdx.x % g.tiles_per_block;
-  const int unit = blockIdx.x / g.tiles_per_block;  // (b*H + h)*2 + which
-  const int which = unit & 1;
-  const int bh = unit >> 1;
-  const int b = bh / g.H;
-  const int slot = blk_idx[b];
-  if (slot < 0 || slot >= g.NB) return;
-  const long blk = (long)bh * g.NB + slot;
+  const int unit = blockIdx.x / g.tiles_per_block;
+  const UnitRef ur = unit_ref(g, job, unit);
+  const int which = ur.which, slot = ur.slot;
+  if (slot < 0) return;
+  const long blk = ur.bh * g.NB + slot;
   const float* src = large_ws + ((long)unit * g.Tb + (long)tile * kTileTokens) * D;
   uint8_t* codes = (which ? cache.v_codes : cache.k_codes) + blk * g.codes_per_block +
                    (long)tile * kTileTokens * g.row_bytes;
@@ -266,31 +298,23 @@ __host__ __device__ inline size_t decompose_lds_bytes(int j1, int d) {
 }
 
 template <int J1, int DD>
-__global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache cache,
-                                                       const uint16_t* __restrict__ k_new,
-                                                       const uint16_t* __restrict__ v_new,
-                                                       int t_new,
-                                                       const int32_t* __restrict__ blk_idx,
-                                                       const int32_t* __restrict__ n_valid,
+__global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                        float* __restrict__ large_ws,
                                                        int32_t* __restrict__ unit_status) {
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
-  const int unit = blockIdx.x;  // (b*H + h)*2 + which
-  const int which = unit & 1;
-  const int bh = unit >> 1;
-  const int b = bh / g.H;
-  const int slot = blk_idx[b];
-  if (slot < 0 || slot >= g.NB) {
+  const int unit = blockIdx.x;
+  const UnitRef ur = unit_ref(g, job, unit);
+  const int which = ur.which, slot = ur.slot, nv = ur.nv;
+  const long bh = ur.bh;
+  if (slot < 0) {
     if (threadIdx.x == 0) unit_status[unit] = 0;
     return;
   }
-  int nv = t_new;
-  if (n_valid) nv = min(max(n_valid[b], 0), t_new);
   const int tid = threadIdx.x;
   constexpr int j1 = J1, d = DD, j2 = DD / J1;   // compile-time shapes: loops unroll, no divisions
   constexpr int ld = j1 + 1;             // padded leading dimension of the small matrices
   constexpr int nent = j1 * j1;
-  const uint16_t* X = (which ? v_new : k_new) + (long)bh * t_new * d;  // [t_new, d] fp16 bits
+  const uint16_t* X = ur.X;  // [nv, d] fp16 bits
 
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
   double* A0 = reinterpret_cast<double*>(lds_raw);   // Gram matrix, double buffered
@@ -501,29 +525,22 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
 // NWV waves per block: the two contractions are split over the waves by token, the eigen-solver
 // runs in one of them.  The host picks NWV so that the launch has about one wave per SIMD.
 template <int NWV>
-__global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq_cache cache,
-                                                               const uint16_t* __restrict__ k_new,
-                                                               const uint16_t* __restrict__ v_new, int t_new,
-                                                               const int32_t* __restrict__ blk_idx,
-                                                               const int32_t* __restrict__ n_valid,
+__global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                                float* __restrict__ large_ws,
                                                                int32_t* __restrict__ unit_status) {
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
-  const int unit = blockIdx.x;  // (b*H + h)*2 + which
-  const int which = unit & 1;
-  const int bh = unit >> 1;
-  const int b = bh / g.H;
-  const int slot = blk_idx[b];
-  if (slot < 0 || slot >= g.NB) {
+  const int unit = blockIdx.x;
+  const UnitRef ur = unit_ref(g, job, unit);
+  const int which = ur.which, slot = ur.slot, nv = ur.nv;
+  const long bh = ur.bh;
+  if (slot < 0) {
     if (threadIdx.x == 0) unit_status[unit] = 0;
     return;
   }
-  int nv = t_new;
-  if (n_valid) nv = min(max(n_valid[b], 0), t_new);
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
   const int solver = unit % NWV;   // the wave that runs the eigen-solver (spread over the SIMDs)
   constexpr int j1 = 16, d = 128, ld = 17;
-  const uint16_t* X = (which ? v_new : k_new) + (long)bh * t_new * d;  // [t_new, d] fp16 bits
+  const uint16_t* X = ur.X;  // [nv, d] fp16 bits
 
   __shared__ double A[j1 * ld], V[j1 * ld], W[j1 * ld];
   __shared__ double P[(NWV > 1 ? NWV - 1 : 1) * j1 * ld];   // Gram partials of the other waves
@@ -717,16 +734,15 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
 // a2 in place: row a2*8 + e becomes T_2[., a2, ., e].  One workgroup of four waves per block.
 // ------------------------------------------------------------------------------------------
 template <int DD>
-__global__ __launch_bounds__(256) void split3_kernel(dq_format fmt, dq_cache cache,
-                                                     const int32_t* __restrict__ blk_idx,
+__global__ __launch_bounds__(256) void split3_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                      float* __restrict__ large_ws) {
   constexpr int N = kRun, LD = N + 1;
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
-  const int unit = blockIdx.x;  // (b*H + h)*2 + which
-  const int which = unit & 1;
-  const int bh = unit >> 1;
-  const int slot = blk_idx[bh / g.H];
-  if (slot < 0 || slot >= g.NB) return;
+  const int unit = blockIdx.x;
+  const UnitRef ur = unit_ref(g, job, unit);
+  const int which = ur.which, slot = ur.slot;
+  const long bh = ur.bh;
+  if (slot < 0) return;
   const int tid = threadIdx.x, lane = tid & 63, wave = tid >> 6;
   float* blk = large_ws + (long)unit * g.Tb * DD;
   const int runs = g.Tb / N;
@@ -867,12 +883,24 @@ __global__ __launch_bounds__(256) void split3_kernel(dq_format fmt, dq_cache cac
 // ------------------------------------------------------------------------------------------
 using namespace dq;
 
+static size_t compress_workspace_bytes(const dq_format* fmt, int batch, int kv_heads, int n_blocks) {
+  // header (status words), the fp32 large tensors, one status word per block
+  const size_t units = (size_t)batch * kv_heads * 2 * n_blocks;
+  return (size_t)kWsHeaderBytes + units * fmt->block_tokens * fmt->head_dim * sizeof(float) +
+         align_up(units * sizeof(int32_t), 256);
+}
+
 extern "C" size_t dq_compress_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads) {
   if (!format_ok(fmt) || batch <= 0 || kv_heads <= 0) return 0;
-  // header (status words), the fp32 large tensors, one status word per block
-  return (size_t)kWsHeaderBytes +
-         (size_t)batch * kv_heads * 2 * fmt->block_tokens * fmt->head_dim * sizeof(float) +
-         align_up((size_t)batch * kv_heads * 2 * sizeof(int32_t), 256);
+  return compress_workspace_bytes(fmt, batch, kv_heads, 1);
+}
+
+extern "C" size_t dq_compress_blocks_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads,
+                                                     int32_t t_new) {
+  if (!format_ok(fmt) || batch <= 0 || kv_heads <= 0 || t_new < 1) return 0;
+  const int n_blocks = (t_new + fmt->block_tokens - 1) / fmt->block_tokens;
+  if ((long)batch * kv_heads * 2 * n_blocks > (long)kMaxCompressUnits) return 0;
+  return compress_workspace_bytes(fmt, batch, kv_heads, n_blocks);
 }
 
 extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, int64_t n_rows,
@@ -902,35 +930,35 @@ extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, 
   return DQ_OK;
 }
 
-extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
-                                  const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
-                                  const int32_t* n_valid, void* workspace, size_t workspace_bytes,
-                                  void* hip_stream) {
-  if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
+static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                             const uint16_t* v_new, int32_t t_new, int n_blocks, const int32_t* blk_idx,
+                             const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                             void* hip_stream) {
   if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
       !cache->v_small)
     return DQ_EINVAL;
   if (fmt->i3 != 1 && (!cache->k_small3 || !cache->v_small3)) return DQ_EINVAL;
   if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
-  if (t_new < 1 || t_new > fmt->block_tokens) return DQ_EINVAL;
-  const size_t need = dq_compress_workspace_bytes(fmt, cache->batch, cache->kv_heads);
+  if ((long)cache->batch * cache->kv_heads * 2 * n_blocks > (long)kMaxCompressUnits) return DQ_EINVAL;
+  const size_t need = compress_workspace_bytes(fmt, cache->batch, cache->kv_heads, n_blocks);
   if (workspace_bytes < need) return DQ_ENOSPACE;
   hipStream_t st = (hipStream_t)hip_stream;
   int32_t* status = reinterpret_cast<int32_t*>(workspace);
   float* large_ws = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kWsHeaderBytes);
-  const int units = cache->batch * cache->kv_heads * 2;
+  const int units = cache->batch * cache->kv_heads * 2 * n_blocks;
   int32_t* unit_status = reinterpret_cast<int32_t*>(large_ws + (size_t)units * fmt->block_tokens * fmt->head_dim);
+  const CompressJob job = {k_new, v_new, t_new, n_blocks, blk_idx, n_valid};
   const size_t dlds = decompose_lds_bytes(fmt->j1, fmt->head_dim);
-#define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                   \
-  hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, k_new, \
-                     v_new, t_new, blk_idx, n_valid, large_ws, unit_status)
+#define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                      \
+  hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, job, large_ws, \
+                     unit_status)
   static const bool force_general = getenv("DQ_COMPRESS_GENERAL") != nullptr;   // for A/B timing
   if (fmt->head_dim == 128 && fmt->j1 == 16 && !force_general) {
     // At most one workgroup per compute unit (256 on the chip) gets more waves per block: the
     // eigen-solver wave is issue-bound and slows down when two of them share a SIMD.
-#define DQ_LAUNCH_D16(N_)                                                                                \
-  hipLaunchKernelGGL((decompose16_kernel<N_>), dim3(units), dim3(64 * N_), 0, st, *fmt, *cache, k_new, \
-                     v_new, t_new, blk_idx, n_valid, large_ws, unit_status)
+#define DQ_LAUNCH_D16(N_)                                                                                  \
+  hipLaunchKernelGGL((decompose16_kernel<N_>), dim3(units), dim3(64 * N_), 0, st, *fmt, *cache, job, large_ws, \
+                     unit_status)
     int nwv = units <= 256 ? 4 : units <= 512 ? 2 : 1;
     if (const char* e = getenv("DQ_COMPRESS_WAVES")) nwv = atoi(e);   // for sweeps
     if (nwv >= 4) DQ_LAUNCH_D16(4);
@@ -950,16 +978,16 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   DQ_HIP_CHECK(hipGetLastError());
   if (fmt->i3 == kRun) {   // three local tensors: cut the right factor again before it is quantized
     if (fmt->head_dim == 128)
-      hipLaunchKernelGGL((split3_kernel<128>), dim3(units), dim3(256), 0, st, *fmt, *cache, blk_idx, large_ws);
+      hipLaunchKernelGGL((split3_kernel<128>), dim3(units), dim3(256), 0, st, *fmt, *cache, job, large_ws);
     else
-      hipLaunchKernelGGL((split3_kernel<64>), dim3(units), dim3(256), 0, st, *fmt, *cache, blk_idx, large_ws);
+      hipLaunchKernelGGL((split3_kernel<64>), dim3(units), dim3(256), 0, st, *fmt, *cache, job, large_ws);
     DQ_HIP_CHECK(hipGetLastError());
   }
   const int tiles = units * (fmt->block_tokens / kTileTokens);
   const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
 #define DQ_LAUNCH_QTILES(B_, D_)                                                                       \
   hipLaunchKernelGGL((quantize_tiles_kernel<B_, D_>), dim3(tiles), dim3(256), lds, st, large_ws, *fmt, \
-                     *cache, blk_idx, unit_status, units, status)
+                     *cache, job, unit_status, units, status)
   if (fmt->head_dim == 128) {
     if (fmt->bits == 2) DQ_LAUNCH_QTILES(2, 128);
     else if (fmt->bits == 4) DQ_LAUNCH_QTILES(4, 128);
@@ -972,4 +1000,26 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
 #undef DQ_LAUNCH_QTILES
   DQ_HIP_CHECK(hipGetLastError());
   return DQ_OK;
+}
+
+extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                                  const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                                  const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                                  void* hip_stream) {
+  if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
+  if (t_new < 1 || t_new > fmt->block_tokens) return DQ_EINVAL;
+  return compress_impl(fmt, cache, k_new, v_new, t_new, 1, blk_idx, n_valid, workspace, workspace_bytes,
+                       hip_stream);
+}
+
+extern "C" int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                                         const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                                         const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                                         void* hip_stream) {
+  if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
+  if (t_new < 1) return DQ_EINVAL;
+  const int n_blocks = (t_new + fmt->block_tokens - 1) / fmt->block_tokens;
+  if (n_blocks > cache->block_capacity) return DQ_EINVAL;
+  return compress_impl(fmt, cache, k_new, v_new, t_new, n_blocks, blk_idx, n_valid, workspace,
+                       workspace_bytes, hip_stream);
 }

@@ -591,3 +591,48 @@ def test_kv_cache_layer_policy_prefill_then_decode_steps(i3):
                     nt = layer.n_tail[b]
                     assert np.array_equal(layer.k_tail[b, h, :nt].cpu().numpy(), k[b, h, lens[b]:lens[b] + nt])
     assert layer.n_blocks == [3, 1] and layer.n_tail == [6, 92]
+
+
+@pytest.mark.parametrize("i3,bits,tb", [(1, 4, 128), (8, 4, 128), (1, 2, 256), (8, 8, 128)])
+def test_compress_kv_blocks_writes_what_block_by_block_calls_write(i3, bits, tb):
+    """A prompt's worth of rows in one call (dq_compress_kv_blocks): every block must come out with
+    the very bits that compressing it alone gives, ragged lengths and all; blocks past a sequence's
+    rows or past the cache's capacity stay untouched."""
+    group = 64 if bits == 2 else 128
+    w = _small("llama7b_4bit", batch=3, q_heads=2, kv_heads=2, bits=bits, group=group, block_tokens=tb,
+               max_seq=4 * tb, min_seq=4 * tb, i3=i3)
+    fmt, ofmt = formats(w)
+    t_new = 3 * tb + 37                                   # three whole blocks and a short one
+    k, v = workloads.kv_tensor(w, t_new)
+    kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
+    n_valid = [t_new, tb + 5, 0]                          # full, ragged, nothing
+    first = [0, 1, 2]
+    nb = 4                                                # sequence 1: blocks 1, 2 fit; its others have no rows
+    _say("compress_kv_blocks i3=%d bits=%d Tb=%d t_new=%d n_valid=%s" % (i3, bits, tb, t_new, n_valid))
+    bulk = dq.alloc_cache(fmt, w.batch, w.kv_heads, nb, DEV, fill=0xA5)
+    ws = dq.compress_workspace(fmt, w.batch, w.kv_heads, DEV, t_new=t_new)
+    dq.compress_kv_blocks(bulk, kd, vd, torch.tensor(first, dtype=torch.int32, device=DEV),
+                          torch.tensor(n_valid, dtype=torch.int32, device=DEV), ws)
+    torch.cuda.synchronize()
+    assert int(ws[:4].view(torch.int32).item()) == 0
+    single = dq.alloc_cache(fmt, w.batch, w.kv_heads, nb, DEV, fill=0xA5)
+    ws1 = dq.compress_workspace(fmt, w.batch, w.kv_heads, DEV)
+    for j in range(4):
+        rows = min(tb, t_new - j * tb)
+        slots = [first[b] + j if (n_valid[b] - j * tb > 0 and first[b] + j < nb) else -1 for b in range(w.batch)]
+        nv = [max(0, min(n_valid[b] - j * tb, rows)) for b in range(w.batch)]
+        dq.compress_kv(single, kd[:, :, j * tb:j * tb + rows].contiguous(), vd[:, :, j * tb:j * tb + rows].contiguous(),
+                       torch.tensor(slots, dtype=torch.int32, device=DEV), torch.tensor(nv, dtype=torch.int32, device=DEV), ws1)
+    torch.cuda.synchronize()
+    for name in bulk.t:
+        assert torch.equal(bulk.t[name], single.t[name]), name
+    # sequence 2 (no valid rows) and the slots nothing was sent to still hold the fill pattern
+    assert (bulk.t["k_codes"][2] == 0xA5).all() and (bulk.t["k_codes"][1, :, 0] == 0xA5).all()
+    assert (bulk.t["k_codes"][1, :, 3] == 0xA5).all()
+    # and the blocks decode like the oracle's reading of them
+    arrs = {n: t.cpu().numpy() for n, t in bulk.t.items()}
+    q = workloads.query(w)
+    lens = np.array([t_new, 0, 0], np.int32)
+    want = O.attention_decode(arrs, ofmt, q, lens, pairs=[(0, 0), (0, 1)])
+    got16, _ = run_decode(fmt, arrs, q, lens, 4 * tb, dq.DECODE_AUTO)
+    assert (np.abs(got16[0].astype(np.float64) - want[0]) <= tolerance(want[0])).all()

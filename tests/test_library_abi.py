@@ -89,6 +89,15 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     assert st == -1
     st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, None)
     assert st == -2
+    # several blocks per call: the workspace grows with the number of blocks; more blocks than the cache holds
+    assert dq.lib.dq_compress_blocks_workspace_bytes(C.byref(good), 2, 4, 128) == cneed
+    bneed = dq.lib.dq_compress_blocks_workspace_bytes(C.byref(good), 2, 4, 300)
+    assert bneed == 256 + 2 * 4 * 3 * 2 * 128 * 128 * 4 + 256
+    st = dq.lib.dq_compress_kv_blocks(C.byref(good), cache_p, ptr, ptr, 300, ptr, None, ptr, bneed - 1, None)
+    assert st == -2
+    st = dq.lib.dq_compress_kv_blocks(C.byref(good), cache_p, ptr, ptr, 8 * 128 + 1, ptr, None, ptr, 1 << 40, None)
+    assert st == -1
+    assert dq.lib.dq_compress_blocks_workspace_bytes(C.byref(good), 2, 4, 0) == 0
     # three local tensors need the two extra arrays
     three = dq.Format(4, 128, 128, 16, 8, 128, 8).c()
     fake.p[6] = 0
