@@ -358,6 +358,34 @@ class KVCacheLayer:
                 self._compress(full)
         self.tail_lens.copy_(torch.tensor(self.n_tail, dtype=torch.int32))
 
+    def prefill(self, k_new: torch.Tensor, v_new: torch.Tensor, counts=None) -> None:
+        """Append the rows of a prompt, k_new, v_new [B, H_kv, n, d], to empty sequences; sequence b
+        takes the first counts[b] rows (default: all n).  The whole blocks of all sequences are
+        compressed by one dq_compress_kv_blocks call, the rest goes to the tails."""
+        if any(self.n_blocks) or any(self.n_tail):
+            raise DQError("prefill needs empty sequences; use append")
+        tb = self.fmt.block_tokens
+        n = k_new.shape[2]
+        counts = [n] * self.batch if counts is None else list(counts)
+        whole = [c // tb for c in counts]
+        if max(whole) > self.capacity_blocks:
+            raise DQError("the prompt exceeds the cache capacity")
+        if max(whole) > 0:
+            rows = max(whole) * tb
+            ws = compress_workspace(self.fmt, self.batch, self.kv_heads, self.device, t_new=rows)
+            first = torch.tensor([0 if w else -1 for w in whole], dtype=torch.int32, device=self.device)
+            valid = torch.tensor([w * tb for w in whole], dtype=torch.int32, device=self.device)
+            compress_kv_blocks(self.cache, k_new[:, :, :rows].contiguous(), v_new[:, :, :rows].contiguous(),
+                               first, valid, ws)
+        for b in range(self.batch):
+            rest = counts[b] - whole[b] * tb
+            if rest:
+                self.k_tail[b, :, :rest] = k_new[b, :, whole[b] * tb:counts[b]]
+                self.v_tail[b, :, :rest] = v_new[b, :, whole[b] * tb:counts[b]]
+            self.n_blocks[b], self.n_tail[b] = whole[b], rest
+        self.seq_lens.copy_(torch.tensor([nb * tb for nb in self.n_blocks], dtype=torch.int32))
+        self.tail_lens.copy_(torch.tensor(self.n_tail, dtype=torch.int32))
+
     def _compress(self, seqs) -> None:
         idx = [-1] * self.batch
         for b in seqs:

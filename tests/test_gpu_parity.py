@@ -636,3 +636,23 @@ def test_compress_kv_blocks_writes_what_block_by_block_calls_write(i3, bits, tb)
     want = O.attention_decode(arrs, ofmt, q, lens, pairs=[(0, 0), (0, 1)])
     got16, _ = run_decode(fmt, arrs, q, lens, 4 * tb, dq.DECODE_AUTO)
     assert (np.abs(got16[0].astype(np.float64) - want[0]) <= tolerance(want[0])).all()
+
+
+def test_kv_cache_layer_prefill_in_one_call_equals_appending():
+    w = _small("llama7b_4bit", batch=3, q_heads=4, kv_heads=2, max_seq=700, min_seq=700)
+    fmt, _ = formats(w)
+    k, v = workloads.kv_tensor(w)
+    kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
+    counts = [700, 130, 90]
+    a = dq.KVCacheLayer(fmt, w.batch, w.q_heads, w.kv_heads, 768, DEV)
+    b = dq.KVCacheLayer(fmt, w.batch, w.q_heads, w.kv_heads, 768, DEV)
+    a.append(kd, vd, counts=counts)
+    b.prefill(kd, vd, counts=counts)
+    torch.cuda.synchronize()
+    assert a.n_blocks == b.n_blocks == [5, 1, 0] and a.n_tail == b.n_tail == [60, 2, 90]
+    for name in a.cache.t:
+        assert torch.equal(a.cache.t[name], b.cache.t[name]), name
+    for bb in range(3):
+        assert torch.equal(a.k_tail[bb, :, :a.n_tail[bb]], b.k_tail[bb, :, :b.n_tail[bb]])
+    q = torch.from_numpy(workloads.query(w)).to(DEV)
+    assert torch.equal(a.decode(q), b.decode(q))
