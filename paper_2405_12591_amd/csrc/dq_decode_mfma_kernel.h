@@ -9,7 +9,7 @@
 // floating point: a 32-bit word of codes is split into words of four bytes each
 // (4-bit: x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F; 2-bit: (x >> 2k) & 0x03030303; 8-bit: x ^ 0x80808080) and fed to the
 // int8 matrix cores; the other operand (the folded query, then the softmax weights times the
-// value steps) is expressed as three 7-bit integer limbs relative to a per-tile power of two,
+// value steps) is expressed as 7-bit integer limbs (four and three) relative to a per-tile power of two,
 // one B column per limb, so the contraction is exact integer arithmetic.  Per 128-token tile,
 // one wavefront
 //   1. folds the keys' small tensor into the query,  q'[r, b2] = sum_b1 T_S^K[b1, r] q[b1, b2]
@@ -52,7 +52,11 @@ typedef uint32_t u32x2 __attribute__((ext_vector_type(2)));
 
 constexpr float kLog2e = 1.4426950408889634f;
 constexpr int kLimbBits = 7;
-constexpr int kMantBits = 3 * kLimbBits;  // 21-bit integers: limb0 * 2^14 + limb1 * 2^7 + limb2
+constexpr int kMantBits = 3 * kLimbBits;  // weights: 21-bit integers, limb0 * 2^14 + limb1 * 2^7 + limb2
+// The folded query takes all four columns of its group of four: 28 bits relative to the tile's
+// largest |q'|.  With three limbs the rounding of the small entries of q' (2^-21 of the largest one,
+// times 128 channels) was the largest error of the whole kernel on peaked softmaxes.
+constexpr int kQueryBits = 4 * kLimbBits;
 
 // ---- per-bit-width pieces -------------------------------------------------------------------
 // Chunk: what one lane loads of a 16-row piece of codes (32 bytes at 8 bits, 16 at 4, 8 at 2); it
@@ -310,7 +314,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   unsigned char* Qs = wl;                                        // [NC][8 row pairs][16 slots] bytes
   unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 token groups][16 slots] bytes
   int* Ss = reinterpret_cast<int*>(wl + QS_BYTES + PS_BYTES);    // [NC][SS] ints
-  const bool col_live = (n < NC) && ((n & 3) != 3);
+  const bool col_live = (n < NC) && ((n & 3) != 3);   // value side: three limbs per group of four columns
+  const bool col_live_k = n < NC;                      // key side: four
   // the epilogue's packed columns (see PK): column n holds head packed_head, slot packed_slot of its set
   const int packed_head = (R == 1) ? 0 : (R == 4) ? (n >> 2) : (NG == 1) ? ((n >> 2) & 1) : (n >> 3);
   const int packed_slot = (R == 1) ? (n >> 2) : (R == 4) ? 0 : (NG == 1) ? (n >> 3) : ((n >> 2) & 1);
@@ -485,8 +490,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       int e = 0;
       if (amax > 0.f && amax < INFINITY) e = __builtin_amdgcn_frexp_expf(amax);  // amax = f * 2^e, f in [0.5, 1)
       e = max(min(e, 100), -100);
-      const float qn = qk_scale * pow2i(kMantBits - 1 - e);   // |q' * qn| < 2^20
-      q_unscale = pow2i(e - (kMantBits - 1));
+      const float qn = qk_scale * pow2i(kQueryBits - 1 - e);   // |q' * qn| < 2^27
+      q_unscale = pow2i(e - (kQueryBits - 1));
       // the fold's D layout: lane (n' = b2 + 8*head, g) holds rows r = 4g + i.  Channel (r, b2) is
       // code number (r & 1)*8 + b2 of the 16 codes that row pair r >> 1 contributes to one MFMA.
 #pragma unroll
@@ -500,9 +505,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
             const int grp = (NG == 2) ? (r >> 3) : 0;
             const int pos = (r >> 1) * 16 + C::slot((r & 1) * 8 + (n & 7));
             unsigned char* dst = Qs + (CPH * hd + 4 * grp) * 128 + pos;
-            dst[0] = (unsigned char)(vi >> (2 * kLimbBits));
-            dst[128] = (unsigned char)((vi >> kLimbBits) & 127);
-            dst[256] = (unsigned char)(vi & 127);
+            dst[0] = (unsigned char)(vi >> (3 * kLimbBits));
+            dst[128] = (unsigned char)((vi >> (2 * kLimbBits)) & 127);
+            dst[256] = (unsigned char)((vi >> kLimbBits) & 127);
+            dst[384] = (unsigned char)(vi & 127);
           }
         }
       }
@@ -512,7 +518,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 #pragma unroll
     for (int w = 0; w < 2; ++w) {
       i32x4 t = izero;
-      if (col_live) t = *reinterpret_cast<const i32x4*>(Qs + n * 128 + (2 * g + w) * 16);
+      if (col_live_k) t = *reinterpret_cast<const i32x4*>(Qs + n * 128 + (2 * g + w) * 16);
       bqs[w] = t;
     }
 
@@ -520,7 +526,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     {
       i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[0], izero, 0, 0, 0);
       bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[1], bias, 0, 0, 0);
-      if (col_live && g == 0) Ss[n * SS + 128] = bias[0];
+      if (col_live_k && g == 0) Ss[n * SS + 128] = bias[0];
       i32x4 s_prev = izero;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -531,10 +537,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bqs[0], izero, 0, 0, 0);
         s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bqs[1], s, 0, 0, 0);
         // the previous chunk's scores are stored while this chunk's MFMAs run
-        if (j > 0 && col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * (j - 1) + 4 * g) = s_prev;
+        if (j > 0 && col_live_k) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * (j - 1) + 4 * g) = s_prev;
         s_prev = s;
       }
-      if (col_live) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * 7 + 4 * g) = s_prev;
+      if (col_live_k) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * 7 + 4 * g) = s_prev;
     }
     __builtin_amdgcn_wave_barrier();
 
@@ -560,9 +566,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         const int* s0 = Ss + (CPH * hd + 4 * gr) * SS;
         const int* s1 = s0 + SS;
         const int* s2 = s1 + SS;
-        const int b0 = s0[128], b1 = s1[128], b2v = s2[128];
-        sA += ((float)(s0[tA] - b0) * 16384.f + (float)(s1[tA] - b1) * 128.f + (float)(s2[tA] - b2v)) * dkA[gr];
-        sB += ((float)(s0[tB] - b0) * 16384.f + (float)(s1[tB] - b1) * 128.f + (float)(s2[tB] - b2v)) * dkB[gr];
+        const int* s3 = s2 + SS;
+        const int b0 = s0[128], b1 = s1[128], b2v = s2[128], b3 = s3[128];
+        sA += (((float)(s0[tA] - b0) * 128.f + (float)(s1[tA] - b1)) * 16384.f +
+               ((float)(s2[tA] - b2v) * 128.f + (float)(s3[tA] - b3))) * dkA[gr];
+        sB += (((float)(s0[tB] - b0) * 128.f + (float)(s1[tB] - b1)) * 16384.f +
+               ((float)(s2[tB] - b2v) * 128.f + (float)(s3[tB] - b3))) * dkB[gr];
       }
       if (N3) {   // rows -> tokens with T_3^K
         const float yA = sA, yB = sB;
