@@ -451,11 +451,13 @@ def test_decode_under_graph_capture_replays_identically():
         del scratch
 
 
-def test_serving_step_under_graph_capture_replays_identically():
+@pytest.mark.parametrize("i3,q_heads", [(1, 8), (8, 8), (1, 32)])
+def test_serving_step_under_graph_capture_replays_identically(i3, q_heads):
     """One serving step as a graph: compress a full block of appended rows into the next slot, then
     decode over blocks + fp16 tail.  Neither call allocates, records a memset or reads a host value
-    that changes, so every replay must give the bits of the eager run."""
-    w = _small("llama7b_4bit", batch=2, q_heads=8, kv_heads=4, max_seq=768, min_seq=768)
+    that changes, so every replay must give the bits of the eager run.  Also with three local
+    tensors, and with eight query heads per kv head (two head groups)."""
+    w = _small("llama7b_4bit", batch=2, q_heads=q_heads, kv_heads=4, max_seq=768, min_seq=768, i3=i3)
     fmt, ofmt = formats(w)
     nb = 8
     k, v = workloads.kv_tensor(w, 768)
