@@ -111,3 +111,15 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     # quantize_pack: rows not a multiple of 128
     st = dq.lib.dq_quantize_pack(C.byref(good), ptr, 100, 0, ptr, ptr, None)
     assert st == -1
+
+
+def test_library_depends_on_the_hip_runtime_only(dq):
+    """The boundary is a plain C ABI: the shared library must not pull in torch, Python or any
+    other framework (PyTorch only provides device memory and streams on the caller's side)."""
+    import subprocess
+    from paper_2405_12591_amd import build as B
+    out = subprocess.run(["readelf", "-d", B.LIB_PATH], capture_output=True, text=True, check=True).stdout
+    needed = [line.split("[")[1].split("]")[0] for line in out.splitlines() if "NEEDED" in line]
+    assert any("amdhip64" in n for n in needed), needed
+    for n in needed:
+        assert not any(bad in n.lower() for bad in ("torch", "python", "c10", "caffe", "rccl", "nccl")), needed
