@@ -283,6 +283,7 @@ def main():
         "kv_tokens_streamed_per_s": float(np.sum(lens.astype(np.int64))) * w.kv_heads / (ms_per_step * 1e-3),
         "whole_call_GBps": alg / (ms_per_step * 1e-3) / 1e9,
         "stream_read_ceiling_GBps": stream_gbps,
+        "frac_of_stream_read_ceiling": achieved / stream_gbps if stream_gbps > 0 else None,
         "compress_kv": {"ms_per_call": compress_ms, "blocks_per_call": 2 * w.batch * w.kv_heads,
                         "rows_per_block": w.block_tokens},
         "host_wall_s_timed_region": wall,
