@@ -58,6 +58,9 @@ WORKLOADS = {
     # the 8-bit variant of the benchmark shape (the paper's fused kernel covers 2, 4 and 8 bits)
     "llama7b_8bit": Workload("llama7b_8bit", 1006, 8, 32, 32, 128, 4096, 4096, 8, 128, 16, 8, 128,
                              "lognormal_tokens", 4, 20.0),
+    # eight query heads per kv head (the head grouping of the 70B-class LLaMA models) on the long-context shape
+    "gqa8_long": Workload("gqa8_long", 1008, 16, 64, 8, 128, 32768, 32768, 4, 128, 16, 8, 128,
+                          "student_t", 4, 10.0),
     # the benchmark shape with three local tensors (the paper's n = 3 variant)
     "llama7b_4bit_n3": Workload("llama7b_4bit_n3", 1007, 8, 32, 32, 128, 4096, 4096, 4, 128, 16, 8, 128,
                                 "lognormal_tokens", 4, 20.0, i3=8),
