@@ -164,6 +164,8 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   if (fmt->i3 != 1 && (!cache->k_small3 || !cache->v_small3)) return DQ_EINVAL;
   if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
   if (q_heads <= 0 || q_heads % cache->kv_heads) return DQ_EINVAL;
+  // (sequence, head) pairs are the y index of every grid here
+  if ((long)cache->batch * q_heads > kMaxGridY) return DQ_EINVAL;
   if (max_seq_len < 0 || (long)max_seq_len > (long)cache->block_capacity * fmt->block_tokens) return DQ_EINVAL;
   if ((flags & DQ_DECODE_FORCE_GENERIC) && (flags & DQ_DECODE_FORCE_MFMA)) return DQ_EINVAL;
   const size_t need = dq_decode_workspace_bytes(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len);
