@@ -15,8 +15,9 @@
 //   1. folds the keys' small tensor into the query,  q'[r, b2] = sum_b1 T_S^K[b1, r] q[b1, b2]
 //      (one 16x16x16 f16 MFMA per two heads; T_S and q are fp16, so the products are exact),
 //      and writes the limbs of q' * scale * log2(e) as B operands;
-//   2. streams the key codes: S[t][limb] = sum_c u[t, c] limb[c]  (16x16x64 i8 MFMA,
-//      u = code + 2^(bits-1); the offset is removed with a constant-A MFMA);
+//   2. streams the key codes: S[t][limb] = sum_c (u[t, c] - offset) limb[c]  (16x16x64 i8 MFMA,
+//      u = code + offset as stored; the offset's share comes from a constant-A MFMA and is the
+//      accumulators' starting value);
 //   3. online softmax with two tokens per lane (scores cross from the MFMA layout through
 //      wave-private LDS); w_t = p_t * step^V_t is cut into limbs, again B columns;
 //   4. streams the value codes (stored token-contiguous): o'[r, b2] = sum_t u[t, r, b2] limb[t];
@@ -186,7 +187,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   constexpr int ROWB = D * BITS / 8;          // bytes of a key row
   constexpr int VROWB = kTileTokens * BITS / 8;   // bytes of a value row (one r, one b2) in a tile
   constexpr int CHUNKB = sizeof(chunk_t);
-  constexpr int SS = 132;                     // ints per column of the score staging (128 tokens + bias + pad)
+  constexpr int SS = 132;                     // ints per column of the score staging (128 tokens + pad)
   constexpr int QS_BYTES = NC * 128, PS_BYTES = NC * 128, SS_BYTES = NC * SS * 4;
   constexpr int WAVE_LDS = QS_BYTES + PS_BYTES + SS_BYTES;
   static_assert(WAVE_LDS >= NC * D * 4 + 2 * R * 4, "merge area must fit the wave's LDS");
@@ -357,9 +358,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   for (int st = 0; st < NSET; ++st) acc[st] = (f32x4){0.f, 0.f, 0.f, 0.f};
 
   const float qk_scale = a.scale * kLog2e;
-  constexpr int kPlusWord = C::kOffset * 0x01010101;                       // four bytes of +offset
   constexpr int kMinusWord = (int)((uint32_t)((256 - C::kOffset) & 255) * 0x01010101u);  // four bytes of -offset
-  const i32x4 a_plus = {kPlusWord, kPlusWord, kPlusWord, kPlusWord};
   const i32x4 a_minus = {kMinusWord, kMinusWord, kMinusWord, kMinusWord};
   const i32x4 izero = {0, 0, 0, 0};
 
@@ -522,11 +521,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       bqs[w] = t;
     }
 
-    // ---- 2. scores: S[t][col] = sum_c u[t, c] limb[col][c];  bias row: offset * sum_c limb[col][c] ----
+    // ---- 2. scores: S[t][col] = sum_c (u[t, c] - offset) limb[col][c] ----
+    // (the offset's share, the same for every token, is the accumulators' starting value)
     {
-      i32x4 bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[0], izero, 0, 0, 0);
-      bias = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_plus, bqs[1], bias, 0, 0, 0);
-      if (col_live_k && g == 0) Ss[n * SS + 128] = bias[0];
+      i32x4 cinitk = izero;
+      if (C::kOffset != 0) {
+        cinitk = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bqs[0], izero, 0, 0, 0);
+        cinitk = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bqs[1], cinitk, 0, 0, 0);
+      }
       i32x4 s_prev = izero;
 #pragma unroll
       for (int j = 0; j < 8; ++j) {
@@ -534,7 +536,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         __builtin_amdgcn_sched_barrier(0);   // the slot is dead from here on: refill it in place
         if (HAS_NEXT) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc_next + j * (16 * ROWB)));
         __builtin_amdgcn_sched_barrier(0);
-        i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bqs[0], izero, 0, 0, 0);
+        i32x4 s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bqs[0], cinitk, 0, 0, 0);
         s = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bqs[1], s, 0, 0, 0);
         // the previous chunk's scores are stored while this chunk's MFMAs run
         if (j > 0 && col_live_k) *reinterpret_cast<i32x4*>(Ss + n * SS + 16 * (j - 1) + 4 * g) = s_prev;
@@ -567,11 +569,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         const int* s1 = s0 + SS;
         const int* s2 = s1 + SS;
         const int* s3 = s2 + SS;
-        const int b0 = s0[128], b1 = s1[128], b2v = s2[128], b3 = s3[128];
-        sA += (((float)(s0[tA] - b0) * 128.f + (float)(s1[tA] - b1)) * 16384.f +
-               ((float)(s2[tA] - b2v) * 128.f + (float)(s3[tA] - b3))) * dkA[gr];
-        sB += (((float)(s0[tB] - b0) * 128.f + (float)(s1[tB] - b1)) * 16384.f +
-               ((float)(s2[tB] - b2v) * 128.f + (float)(s3[tB] - b3))) * dkB[gr];
+        sA += (((float)s0[tA] * 128.f + (float)s1[tA]) * 16384.f + ((float)s2[tA] * 128.f + (float)s3[tA])) * dkA[gr];
+        sB += (((float)s0[tB] * 128.f + (float)s1[tB]) * 16384.f + ((float)s2[tB] * 128.f + (float)s3[tB])) * dkB[gr];
       }
       if (N3) {   // rows -> tokens with T_3^K
         const float yA = sA, yB = sB;
@@ -646,8 +645,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     float aT[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) aT[i] = (float)vsm_h[i] * v_unscale;
-    i32x4 cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[0], izero, 0, 0, 0);
-    cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[1], cinitv, 0, 0, 0);
+    i32x4 cinitv = izero;
+    if (C::kOffset != 0) {
+      cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[0], izero, 0, 0, 0);
+      cinitv = __builtin_amdgcn_mfma_i32_16x16x64_i8(a_minus, bp[1], cinitv, 0, 0, 0);
+    }
     if (__any(alpha_col != 1.f)) {   // the running maximum moved: rare after the first tiles
 #pragma unroll
       for (int st = 0; st < NSET; ++st) acc[st] *= alpha_col;
