@@ -579,9 +579,15 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       }
       sA = okA ? sA * q_unscale : -INFINITY;
       sB = okB ? sB * q_unscale : -INFINITY;
-      const float mt = wave_allmax(fmaxf(sA, sB));
-      const float m_new = fmaxf(m_run[hd], mt);          // finite: the tile has a valid token
-      alpha[hd] = __builtin_amdgcn_exp2f(m_run[hd] - m_new);
+      // the running maximum moves in a sequence's first tiles and rarely afterwards: the wave-wide
+      // reduction runs only when some lane holds a score above it
+      const float mt_lane = fmaxf(sA, sB);
+      float m_new = m_run[hd];                           // finite after the first tile (it has a valid token)
+      alpha[hd] = 1.f;
+      if (__any(mt_lane > m_new)) {
+        m_new = wave_allmax(mt_lane);
+        alpha[hd] = __builtin_amdgcn_exp2f(m_run[hd] - m_new);
+      }
       const float pA = __builtin_amdgcn_exp2f(sA - m_new);
       const float pB = __builtin_amdgcn_exp2f(sB - m_new);
       l_run[hd] = l_run[hd] * alpha[hd] + (pA + pB);
