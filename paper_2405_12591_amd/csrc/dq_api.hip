@@ -49,7 +49,10 @@ int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int 
     if (mfma) {
       int per_group = 1;
       const int hg = mfma_head_groups(f, q_heads, kv_heads, &per_group);   // each head group is a workgroup of its own
-      choose_mfma_shape(batch * kv_heads * hg, max_tiles, per_group, f->bits, &n, &nw);
+      if (mfma_pair_heads(f, q_heads, kv_heads))   // two kv heads, one query head each, per workgroup
+        choose_mfma_shape(batch * kv_heads / 2, max_tiles, 2, f->bits, &n, &nw);
+      else
+        choose_mfma_shape(batch * kv_heads * hg, max_tiles, per_group, f->bits, &n, &nw);
     } else {
       const int units = batch * q_heads;
       n = (2048 + units - 1) / units;
@@ -197,7 +200,9 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   // Dealing the units so that every XCD sees every residue class of them (mod 8) brings the XCDs
   // closer together: measured 4 - 5 % faster on the 256-unit benchmark shapes (4- and 8-bit), neutral
   // or within half a percent either way on the other workloads, where the plain order stays.
-  a.unit_map = (a.n_split == 1 && a.head_groups == 1 && cache->batch * cache->kv_heads <= 256) ? 3 : 0;
+  a.pair_heads = (use_mfma && mfma_pair_heads(fmt, q_heads, cache->kv_heads)) ? 1 : 0;
+  const int units = cache->batch * cache->kv_heads / (a.pair_heads ? 2 : 1);
+  a.unit_map = (a.n_split == 1 && a.head_groups == 1 && units <= 256) ? 3 : 0;
   if (const char* env = getenv("DQ_DECODE_UNIT_MAP")) a.unit_map = atoi(env);   // tuning aid
   a.n_slots = a.n_split + (tail ? 1 : 0);
   if (tail) a.tail = *tail;

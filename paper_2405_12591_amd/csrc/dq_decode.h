@@ -22,6 +22,7 @@ struct DecodeArgs {
   int nw;                  // waves per workgroup of the matrix-core kernel (4 or 8)
   int head_groups;         // matrix-core kernel: workgroups per (sequence, kv head, split) ...
   int heads_per_group;     // ... each with this many query heads (1, 2 or 4; the last one what is left)
+  int pair_heads;          // matrix-core kernel: 1 = two kv heads of 64 channels per workgroup (one query head each)
   int unit_map;            // which (sequence, kv head) a workgroup row takes: 0 = its own index, see unit_of_row()
   hipEvent_t ev_start;     // optional: recorded around the main kernel
   hipEvent_t ev_stop;
@@ -55,6 +56,7 @@ int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st);
 int32_t launch_tail_partial(const DecodeArgs& a, float m_unit, hipStream_t st);
 int32_t launch_decode_mfma(const DecodeArgs& a, hipStream_t st);
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads);
+bool mfma_pair_heads(const dq_format* f, int q_heads, int kv_heads);
 int mfma_head_groups(const dq_format* f, int q_heads, int kv_heads, int* heads_per_group);
 int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma,
                   int* nw_out);

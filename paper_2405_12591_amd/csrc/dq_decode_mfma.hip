@@ -16,8 +16,17 @@ static int heads_per_workgroup(const dq_format* f, int rep) {
   return ((rep + r - 1) / r <= kMaxHeadGroups) ? r : 0;
 }
 
+// Heads of 64 channels are worked in pairs of neighbouring kv heads (as one head of 128 channels and
+// two step groups): j1 = j2 = 8, one step per row, one query head per kv head, an even number of
+// heads, two local tensors.
+bool mfma_pair_heads(const dq_format* f, int q_heads, int kv_heads) {
+  if (!format_ok(f) || kv_heads <= 0 || q_heads != kv_heads || (kv_heads & 1)) return false;
+  return f->head_dim == 64 && f->j1 == 8 && f->j2 == 8 && f->group == 64 && f->i3 == 1;
+}
+
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads <= 0 || q_heads % kv_heads) return false;
+  if (mfma_pair_heads(f, q_heads, kv_heads)) return true;
   if (f->head_dim != 128 || f->j1 != 16 || f->j2 != 8) return false;
   if (f->bits != 8 && f->bits != 4 && f->bits != 2) return false;
   if (f->group != 128 && f->group != 64) return false;
@@ -25,6 +34,10 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
 }
 
 int mfma_head_groups(const dq_format* f, int q_heads, int kv_heads, int* heads_per_group) {
+  if (mfma_pair_heads(f, q_heads, kv_heads)) {
+    if (heads_per_group) *heads_per_group = 1;
+    return 1;
+  }
   const int rep = q_heads / kv_heads;
   const int r = heads_per_workgroup(f, rep);
   if (heads_per_group) *heads_per_group = r;

@@ -3,6 +3,9 @@
 //                       group = 64  with 1 or 2
 // with head_dim = 128, j1 = 16, j2 = 8, block_tokens % 128 == 0, two or three local tensors.
 // More query heads per kv head are served by several workgroups (head groups) over the same codes.
+// Heads of 64 channels (j1 = 8, j2 = 8, group = 64, one query head per kv head) ride in pairs: two
+// neighbouring kv heads are worked as one head of 128 channels whose small tensors are block-diagonal
+// and whose two query heads are the real ones padded with zeros (see P2 below).
 //
 // This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
 // 2405.12591) carried through the attention that follows it.  The low-bit codes never become
@@ -171,8 +174,18 @@ __device__ __forceinline__ float pow2i(int e) {
 // value rows are weighted with p'[e] = sum_a3 T_3^V[e, a3] p[a3] (signed, so these weights get a
 // signed top limb like the query's).  The lanes that hold the eight rows of a run form a quad,
 // so both products are quad broadcasts and fused multiply-adds.
-template <int BITS, int NG, int R, int NW, int TM, bool N3>
+// P2: a pair of kv heads of 64 channels each (j1 = 8), one query head per kv head, as one virtual
+// head of 128 channels and two step groups (NG = 2, R = 2).  Virtual row r of the large tensors is row
+// r % 8 of head r / 8, a virtual token row is the two heads' rows side by side, virtual query head hd
+// is real head hd's query in its own 64 channels and zero in the other's, and the small tensors are
+// the heads' 8 x 8 ones on the diagonal of a 16 x 16 one.  Scores, softmax and the epilogue then run
+// unchanged: head hd's scores come from its own channels only, and its output sits in virtual
+// channels [64 hd, 64 hd + 64) (the other half, the other head's values under this head's weights,
+// is dropped).  Only addresses (each lane reads its own head's arrays), the masks that realise the
+// zeros, and the mapping of the output differ.
+template <int BITS, int NG, int R, int NW, int TM, bool N3, bool P2>
 __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode_mfma_kernel(DecodeArgs a) {
+  static_assert(!P2 || (NG == 2 && R == 2 && !N3), "a pair of heads is two step groups and two query heads");
   typedef Codec<BITS> C;
   typedef typename C::chunk_t chunk_t;
   constexpr int CPH = 4 * NG;                 // B columns per head: column CPH*head + 4*group + limb
@@ -184,7 +197,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // but one b2 fills only 3 R of them (one limb triple per head, once the two step groups' columns
   // have been merged): the columns of PK = 4 / R successive b2 are packed side by side first.
   constexpr int PK = 4 / R, NSET = J2 / PK;
-  constexpr int ROWB = D * BITS / 8;          // bytes of a key row
+  constexpr int RD = P2 ? 64 : D;             // channels of a real head (output, partials, cache rows)
+  constexpr int RJ1 = P2 ? 8 : J1;            // rows of a real head's large tensors
+  constexpr int ROWB = RD * BITS / 8;         // bytes of a key row in memory
   constexpr int VROWB = kTileTokens * BITS / 8;   // bytes of a value row (one r, one b2) in a tile
   constexpr int CHUNKB = sizeof(chunk_t);
   constexpr int SS = 132;                     // ints per column of the score staging (128 tokens + pad)
@@ -194,7 +209,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   __shared__ __attribute__((aligned(16))) unsigned char smem[NW * WAVE_LDS];
   // the fp16 tail's partial result (computed once per (sequence, kv head), by split 0, before the
   // first tile; its scratch borrows the waves' areas, which are not in use yet)
-  typedef TailBlock<D, NW, R> Tail;
+  typedef TailBlock<D, NW, R, P2> Tail;
   static_assert(sizeof(smem) >= Tail::kScratchFloats * sizeof(float), "tail scratch must fit the waves' LDS");
   __shared__ float s_tail[R * (D + 2)];
   __shared__ int s_last;
@@ -217,10 +232,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const int hgrp = blockIdx.y / n_units;
   const int bh = unit_of_row(blockIdx.y % n_units, n_units, a.unit_map);
   const int H = a.cache.kv_heads, NB = a.cache.block_capacity;
-  const int b = bh / H, h = bh % H;
+  constexpr int HPU = P2 ? 2 : 1;              // kv heads per unit
+  const int b = bh / (H / HPU), h = (bh % (H / HPU)) * HPU;
+  const long bh0 = (long)b * H + h;            // the unit's (first) kv head among all (sequence, kv head) pairs
   const int tpb = a.fmt.block_tokens / kTileTokens;
   const long codes_per_block = (long)a.fmt.block_tokens * ROWB;
-  const long scales_per_block = (long)a.fmt.block_tokens * NG;
+  constexpr int MG = P2 ? 1 : NG;              // step groups per row in memory
+  const long scales_per_block = (long)a.fmt.block_tokens * MG;
 
   // The sequence length lives in device memory and takes a memory round trip to read.  Tiles are dealt round-robin over all waves of all splits of this (sequence, kv head), so a wave's
   // first tile does not depend on the sequence length and its loads can start before the length is
@@ -234,7 +252,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const long hq_first = (long)h * (a.q_heads / H) + (long)hgrp * R;   // this workgroup's first query head
   // the last group may hold fewer than R heads (3 = 3, 7 = 4 + 3 query heads per kv head): the columns
   // of the missing ones compute on a zero query and are never written out
-  const int nh = min(R, a.q_heads / H - hgrp * R);
+  const int nh = P2 ? 2 : min(R, a.q_heads / H - hgrp * R);
   const long bhq0 = (long)b * a.q_heads + hq_first;
   int32_t* const ticket_counter = a.counters + (long)bh * a.head_groups + hgrp;
   const int n_contrib = a.n_split;   // workgroups that hand in partials
@@ -259,22 +277,22 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     auto load_slots = [&](const float* col, int sp, float (&v)[8]) __attribute__((always_inline)) {
 #pragma unroll
       for (int k = 0; k < 8; ++k)
-        v[k] = (sp + k < ns) ? __hip_atomic_load(col + (sp + k) * (D + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
+        v[k] = (sp + k < ns) ? __hip_atomic_load(col + (sp + k) * (RD + 2), __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT) : 0.f;
     };
     float v_first[8] = {0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f, 0.f};
     float m0 = -INFINITY, l0 = 0.f, m1 = -INFINITY, l1 = 0.f;
     if (wave < nh) {
-      const float* base = a.partials + (bhq0 + wave) * ns * (D + 2);
+      const float* base = a.partials + (bhq0 + wave) * ns * (RD + 2);
       if (lane < ns) {
-        m0 = __hip_atomic_load(base + lane * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        l0 = __hip_atomic_load(base + lane * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        m0 = __hip_atomic_load(base + lane * (RD + 2) + RD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        l0 = __hip_atomic_load(base + lane * (RD + 2) + RD + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       if (lane + 64 < ns) {
-        m1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-        l1 = __hip_atomic_load(base + (lane + 64) * (D + 2) + D + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        m1 = __hip_atomic_load(base + (lane + 64) * (RD + 2) + RD, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        l1 = __hip_atomic_load(base + (lane + 64) * (RD + 2) + RD + 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
     }
-    if (tid < nh * D) load_slots(a.partials + (bhq0 + tid / D) * ns * (D + 2) + tid % D, 0, v_first);
+    if (tid < nh * RD) load_slots(a.partials + (bhq0 + tid / RD) * ns * (RD + 2) + tid % RD, 0, v_first);
     if (wave < nh) {
       const float M = wave_allmax(fmaxf(m0, m1));
       const float w0 = (m0 == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(m0 - M);
@@ -285,9 +303,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       if (lane == 0) s_sum[wave] = L;
     }
     __syncthreads();
-    for (int idx = tid; idx < nh * D; idx += 64 * NW) {
-      const int hd = idx / D, c = idx % D;
-      const float* col = a.partials + (bhq0 + hd) * ns * (D + 2) + c;
+    for (int idx = tid; idx < nh * RD; idx += 64 * NW) {
+      const int hd = idx / RD, c = idx % RD;
+      const float* col = a.partials + (bhq0 + hd) * ns * (RD + 2) + c;
       float o = 0.f;
       for (int sp = 0; sp < ns; sp += 8) {
         float v[8];
@@ -305,8 +323,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       }
       const float L = s_sum[hd];
       const float r = (L > 0.f) ? o / L : 0.f;
-      a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
-      if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
+      a.out[(bhq0 + hd) * RD + c] = f2h_rne(r);
+      if (a.out_f32) a.out_f32[(bhq0 + hd) * RD + c] = r;
     }
   };
 
@@ -344,9 +362,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const int hd = 2 * f + (n >> 3);
       // no branch here (columns past the last head read head nh - 1 and are zeroed when packed):
       // across a branch the compiler loses count of the loads in flight and waits for all of them
-      const uint16_t* qp = a.q + (bhq0 + min(hd, nh - 1)) * D;
+      // (a pair of heads: virtual row b1 = 4g + i of virtual head hd is row b1 % 8 of the real head;
+      // the rows of the other head's half are zeroed when packed)
+      const uint16_t* qp = a.q + (bhq0 + min(hd, nh - 1)) * RD;
 #pragma unroll
-      for (int i = 0; i < 4; ++i) q_raw[f][i] = qp[(4 * g + i) * J2 + b2];
+      for (int i = 0; i < 4; ++i) q_raw[f][i] = qp[((4 * g + i) & (RJ1 - 1)) * J2 + b2];
     }
   }
 
@@ -375,24 +395,49 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // rows, eight fp16 each (kept apart from Side so that the other instances carry nothing of it)
   struct Side3 { u32x4 k3A, k3B, v3A, v3B; };
   Side3 cur3 = {{0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}, {0, 0, 0, 0}};
+  // a pair of heads: the second head's steps of the lane's two tokens (its step group 1)
+  struct SideP { uint32_t dkA, dkB, dvA, dvB; };
+  SideP curP = {0, 0, 0, 0};
+  // the lane's part of a block-diagonal small tensor lies on the diagonal
+  const bool small_live = !P2 || (g >> 1) == (n >> 3);
 
   auto tile_ptrs = [&](int tile, const unsigned char*& kc, const unsigned char*& vc, long& blkid, int& tib) {
-    blkid = (long)bh * NB + tile / tpb;
+    blkid = bh0 * NB + tile / tpb;
     tib = tile % tpb;
-    kc = a.cache.k_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + CHUNKB * g;
-    vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * VROWB + CHUNKB * g;
+    if (P2) {
+      // keys: a virtual row is the two heads' rows side by side, two chunks each; values: virtual
+      // row r of a b2 is row r % 8 of head r / 8 (the second head's blocks lie NB blocks further on)
+      kc = a.cache.k_codes + (blkid + (g >> 1) * NB) * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + CHUNKB * (g & 1);
+      vc = a.cache.v_codes + (blkid + (n >> 3) * NB) * codes_per_block + (long)tib * kTileTokens * ROWB + (n & 7) * VROWB + CHUNKB * g;
+    } else {
+      kc = a.cache.k_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * ROWB + CHUNKB * g;
+      vc = a.cache.v_codes + blkid * codes_per_block + (long)tib * kTileTokens * ROWB + n * VROWB + CHUNKB * g;
+    }
   };
-  auto load_steps = [&](const uint16_t* p, int t) -> uint32_t {   // the NG fp16 steps of token t
-    if (NG == 1) return p[t];
+  auto load_steps = [&](const uint16_t* p, int t) -> uint32_t {   // the fp16 steps of token t as stored
+    if (MG == 1) return p[t];
     return *reinterpret_cast<const uint32_t*>(p + 2 * t);
   };
   auto load_side = [&](Side& sd, long blkid, int tib) {
-    sd.ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + blkid * (J1 * J1) + n * J1 + 4 * g);
-    sd.vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
-    const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens * NG;
-    const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens * NG;
+    if (P2) {
+      // the lane's row of its own head's 8 x 8 small tensor (used only where small_live)
+      const long sb = (blkid + (n >> 3) * NB) * (RJ1 * RJ1) + (n & 7) * RJ1 + 4 * (g & 1);
+      sd.ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + sb);
+      sd.vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + sb);
+    } else {
+      sd.ksm = *reinterpret_cast<const u32x2*>(a.cache.k_small + blkid * (J1 * J1) + n * J1 + 4 * g);
+      sd.vsm = *reinterpret_cast<const u32x2*>(a.cache.v_small + blkid * (J1 * J1) + n * J1 + 4 * g);
+    }
+    const uint16_t* ksc = a.cache.k_scales + blkid * scales_per_block + tib * kTileTokens * MG;
+    const uint16_t* vsc = a.cache.v_scales + blkid * scales_per_block + tib * kTileTokens * MG;
     sd.dkA = load_steps(ksc, tA); sd.dkB = load_steps(ksc, tB);
     sd.dvA = load_steps(vsc, tA); sd.dvB = load_steps(vsc, tB);
+  };
+  auto load_sideP = [&](SideP& sd, long blkid, int tib) {   // the same steps of the pair's second head
+    const uint16_t* ksc = a.cache.k_scales + (blkid + NB) * scales_per_block + tib * kTileTokens;
+    const uint16_t* vsc = a.cache.v_scales + (blkid + NB) * scales_per_block + tib * kTileTokens;
+    sd.dkA = ksc[tA]; sd.dkB = ksc[tB];
+    sd.dvA = vsc[tA]; sd.dvB = vsc[tB];
   };
   auto load_side3 = [&](Side3& sd, long blkid) {
     const uint16_t* k3 = a.cache.k_small3 + blkid * (kRun * kRun);   // [a3][e]
@@ -409,13 +454,16 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     tile_ptrs(tile, kc, vc, blkid, tib);
     load_side(cur, blkid, tib);
     if (N3) load_side3(cur3, blkid);
+    if (P2) load_sideP(curP, blkid, tib);
     __builtin_amdgcn_sched_barrier(0);
 #pragma unroll
     for (int j = 0; j < 8; ++j) ring[j] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(kc + j * (16 * ROWB)));
 #pragma unroll
-    for (int b2 = 0; b2 < 8; ++b2) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc + b2 * (J1 * VROWB)));
+    for (int b2 = 0; b2 < 8; ++b2) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc + b2 * (RJ1 * VROWB)));
   };
-  auto step_of = [&](uint32_t packed, int grp) -> float {   // fp16 step of group grp from the packed word
+  // fp16 step of group grp: from the packed word, or (a pair of heads) from the second head's word
+  auto step_of = [&](uint32_t packed, uint32_t second, int grp) -> float {
+    if (P2) return h2f((uint16_t)(grp ? second : packed));
     return h2f((uint16_t)(grp ? (packed >> 16) : (packed & 0xFFFFu)));
   };
 
@@ -459,6 +507,11 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       nxt3 = cur3;
       if (HAS_NEXT) load_side3(nxt3, blkid_next);
     }
+    SideP nxtP;
+    if (P2) {
+      nxtP = curP;
+      if (HAS_NEXT) load_sideP(nxtP, blkid_next, tib_next);
+    }
     __builtin_amdgcn_sched_barrier(0);
     const bool okA = (tok0 + tA) < S, okB = (tok0 + tB) < S;
     // three tensors: a row counts as soon as its run of eight holds a valid token
@@ -466,17 +519,17 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     float dvA[NG], dvB[NG], dkA[NG], dkB[NG];
 #pragma unroll
     for (int gr = 0; gr < NG; ++gr) {
-      dvA[gr] = rowA ? step_of(cur.dvA, gr) : 0.f;
-      dvB[gr] = rowB ? step_of(cur.dvB, gr) : 0.f;
-      dkA[gr] = step_of(cur.dkA, gr);
-      dkB[gr] = step_of(cur.dkB, gr);
+      dvA[gr] = rowA ? step_of(cur.dvA, curP.dvA, gr) : 0.f;
+      dvB[gr] = rowB ? step_of(cur.dvB, curP.dvB, gr) : 0.f;
+      dkA[gr] = step_of(cur.dkA, curP.dkA, gr);
+      dkB[gr] = step_of(cur.dkB, curP.dkB, gr);
     }
-    const half4 vsm_h = __builtin_bit_cast(half4, cur.vsm);
+    const half4 vsm_h = __builtin_bit_cast(half4, small_live ? cur.vsm : u32x2{0u, 0u});
 
     // ---- 1. fold T_S^K into q; limbs of q' relative to 2^e >= max |q'| ----
     float q_unscale;
     {
-      const half4 aK = __builtin_bit_cast(half4, cur.ksm);
+      const half4 aK = __builtin_bit_cast(half4, small_live ? cur.ksm : u32x2{0u, 0u});
       f32x4 fd[F];
       float amax = 0.f;
 #pragma unroll
@@ -692,7 +745,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     for (int b2 = 0; b2 < J2; ++b2) {
       const i32x4 a0 = C::half(ring[8 + b2], 0), a1 = C::half(ring[8 + b2], 1);
       __builtin_amdgcn_sched_barrier(0);
-      if (HAS_NEXT) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc_next + b2 * (J1 * VROWB)));
+      if (HAS_NEXT) ring[8 + b2] = __builtin_nontemporal_load(reinterpret_cast<const chunk_t*>(vc_next + b2 * (RJ1 * VROWB)));
       __builtin_amdgcn_sched_barrier(0);
       i32x4 o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a0, bp[0], cinitv, 0, 0, 0);
       o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bp[1], o, 0, 0, 0);
@@ -707,6 +760,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     epilogue(NSET - 1, pk_done);
     cur = nxt;
     if (N3) cur3 = nxt3;
+    if (P2) curP = nxtP;
     __builtin_amdgcn_wave_barrier();
   };
 
@@ -728,7 +782,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const int tail_len_raw = do_tail ? a.tail.tail_lens[b] : 0;
 #pragma unroll
   for (int f = 0; f < F; ++f) {
-    const bool head_live = (2 * f + (n >> 3)) < nh;
+    const bool head_live = (2 * f + (n >> 3)) < nh && (!P2 || (g >> 1) == (n >> 3));
 #pragma unroll
     for (int i = 0; i < 4; ++i) {
       asm volatile("" : "+v"(q_raw[f][i]));   // nothing derived from q may move above the requests
@@ -772,8 +826,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     for (int hd = 0; hd < R; ++hd) { Mml[hd] = m_run[hd]; Mml[R + hd] = l_run[hd]; }
   }
   __syncthreads();
-  for (int idx = tid; idx < nh * D; idx += 64 * NW) {
-    const int hd = idx / D, c = idx % D;
+  for (int idx = tid; idx < nh * RD; idx += 64 * NW) {
+    // c: the real head's channel; cv: where it sits among the 128 channels the waves worked on
+    const int hd = idx / RD, c = idx % RD, cv = P2 ? c + RD * hd : c;
     float M = -INFINITY;
 #pragma unroll
     for (int w = 0; w < NW; ++w) M = fmaxf(M, reinterpret_cast<const float*>(smem + w * WAVE_LDS)[NC * D + hd]);
@@ -783,7 +838,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const float* base = reinterpret_cast<const float*>(smem + w * WAVE_LDS);
       const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
-      const float* col = base + 4 * hd * D + c;
+      const float* col = base + 4 * hd * D + cv;
       const float v = col[0] * 16384.f + col[D] * 128.f + col[2 * D];
       o = fmaf(v, wgt, o);
       L = fmaf(base[NC * D + R + hd], wgt, L);
@@ -795,28 +850,28 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         const float Mn = fmaxf(M, mt);
         const float w0 = (M == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(M - Mn);
         const float w1 = (mt == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mt - Mn);
-        o = o * w0 + tp[c] * w1;
+        o = o * w0 + tp[cv] * w1;
         L = L * w0 + tp[D + 1] * w1;
       }
       const float r = (L > 0.f) ? o / L : 0.f;
-      a.out[(bhq0 + hd) * D + c] = f2h_rne(r);
-      if (a.out_f32) a.out_f32[(bhq0 + hd) * D + c] = r;
+      a.out[(bhq0 + hd) * RD + c] = f2h_rne(r);
+      if (a.out_f32) a.out_f32[(bhq0 + hd) * RD + c] = r;
     } else {
       // device-scope stores: they go through to memory, past the per-XCD L2, so that a workgroup
       // on another XCD can read them without any cache write-back or invalidation
-      float* part = a.partials + ((bhq0 + hd) * a.n_slots + split) * (D + 2);
+      float* part = a.partials + ((bhq0 + hd) * a.n_slots + split) * (RD + 2);
       __hip_atomic_store(part + c, o, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       if (c == 0) {
-        __hip_atomic_store(part + D, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // M in log2 units
-        __hip_atomic_store(part + D + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(part + RD, M, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);   // M in log2 units
+        __hip_atomic_store(part + RD + 1, L, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       }
       if (TM == 2 && split == 0) {   // the tail's partial travels with split 0's, in the slot after the splits
-        float* tpart = a.partials + ((bhq0 + hd) * a.n_slots + a.n_split) * (D + 2);
+        float* tpart = a.partials + ((bhq0 + hd) * a.n_slots + a.n_split) * (RD + 2);
         const float* tp = s_tail + hd * (D + 2);
-        __hip_atomic_store(tpart + c, tp[c], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        __hip_atomic_store(tpart + c, tp[cv], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         if (c == 0) {
-          __hip_atomic_store(tpart + D, tp[D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-          __hip_atomic_store(tpart + D + 1, tp[D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(tpart + RD, tp[D], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+          __hip_atomic_store(tpart + RD + 1, tp[D + 1], __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
         }
       }
     }
@@ -825,26 +880,27 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 
   ticket_and_merge();
 }
-template <int BITS, int NG, int R, int TM, bool N3>
+template <int BITS, int NG, int R, int TM, bool N3, bool P2>
 inline void launch_tm(const DecodeArgs& a, hipStream_t st) {
-  const dim3 grid(a.n_split, a.cache.batch * a.cache.kv_heads * a.head_groups);
+  const int units = a.cache.batch * a.cache.kv_heads / (P2 ? 2 : 1);
+  const dim3 grid(a.n_split, units * a.head_groups);
   // the events, when given, receive the kernel's own begin and end timestamps
   // (8-bit codes: a wave's ring of chunks is twice as large and an 8-wave workgroup runs out of
   // registers, so that width always takes 4 waves)
   if constexpr (BITS < 8) {
     if (a.nw == 8) {
-      hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM, N3>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
+      hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 8, TM, N3, P2>), grid, dim3(512), 0, st, a.ev_start, a.ev_stop, 0, a);
       return;
     }
   }
-  hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM, N3>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
+  hipExtLaunchKernelGGL((decode_mfma_kernel<BITS, NG, R, 4, TM, N3, P2>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a);
 }
 
-template <int BITS, int NG, int R, bool N3>
+template <int BITS, int NG, int R, bool N3, bool P2 = false>
 inline void launch_n3(const DecodeArgs& a, hipStream_t st) {
-  if (!a.tail.k_tail) launch_tm<BITS, NG, R, 0, N3>(a, st);
-  else if (a.n_split == 1) launch_tm<BITS, NG, R, 1, N3>(a, st);
-  else launch_tm<BITS, NG, R, 2, N3>(a, st);
+  if (!a.tail.k_tail) launch_tm<BITS, NG, R, 0, N3, P2>(a, st);
+  else if (a.n_split == 1) launch_tm<BITS, NG, R, 1, N3, P2>(a, st);
+  else launch_tm<BITS, NG, R, 2, N3, P2>(a, st);
 }
 
 template <int BITS, int NG, int R>
@@ -855,6 +911,10 @@ inline void launch_r(const DecodeArgs& a, hipStream_t st) {
 
 template <int BITS>
 int32_t launch_bits(const DecodeArgs& a, hipStream_t st) {
+  if (a.pair_heads) {   // two kv heads of 64 channels per workgroup
+    launch_n3<BITS, 2, 2, false, true>(a, st);
+    return DQ_OK;
+  }
   const int rep = a.heads_per_group;   // query heads per workgroup (the last group may hold fewer)
   if (a.fmt.group == 128) {
     switch (rep) {

@@ -26,8 +26,14 @@ __device__ __forceinline__ float tail_dpp(float v) {
 
 // D: head dimension.  NWV: waves in the workgroup (all of them must call both functions).
 // HEADS: query heads handled together (every row read serves all of them).
-template <int D, int NWV, int HEADS>
+// PAIR: D = 128 stands for two neighbouring kv heads of 64 channels, each with its own query head
+// (HEADS = 2): a row is the two heads' rows side by side (the lanes of each half read their own
+// head's array), query head hd is zero outside its own half, and so result[hd] is head hd's
+// partial in channels [64 hd, 64 hd + 64); the other half of it means nothing.
+template <int D, int NWV, int HEADS, bool PAIR = false>
 struct TailBlock {
+  static_assert(!PAIR || (D == 128 && HEADS == 2), "a pair is two heads of 64 channels");
+  static constexpr int RD = PAIR ? D / 2 : D;   // halves per row in memory
   static constexpr int LPR = D / 8;      // lanes per row
   static constexpr int RPI = 64 / LPR;   // rows per wave-wide load
   static constexpr int HB = HEADS;
@@ -54,21 +60,24 @@ struct TailBlock {
     chunk = lane % LPR; rsub = lane / LPR;
     cap = a.tail.capacity;
     const int H = a.cache.kv_heads;
-    kt = a.tail.k_tail + ((long)b * H + h) * cap * D;
-    vt = a.tail.v_tail + ((long)b * H + h) * cap * D;
+    // the lane's 8 halves of a row: kt + row * RD
+    const int own = PAIR ? chunk / (LPR / 2) : 0;          // which head of the pair the lane reads
+    const int part = PAIR ? chunk % (LPR / 2) : chunk;
+    kt = a.tail.k_tail + ((long)b * H + h + own) * cap * RD + 8 * part;
+    vt = a.tail.v_tail + ((long)b * H + h + own) * cap * RD + 8 * part;
     qk = a.scale * 1.4426950408889634f;
 #pragma unroll
     for (int hd = 0; hd < HB; ++hd)
-      qraw[hd] = *reinterpret_cast<const tail_u4*>(a.q + ((long)b * a.q_heads + hq0 + min(hd, nh - 1)) * D + 8 * chunk);
+      qraw[hd] = *reinterpret_cast<const tail_u4*>(a.q + ((long)b * a.q_heads + hq0 + min(hd, nh - 1)) * RD + 8 * part);
     // Rows below the capacity are readable whatever the tail's length, which is not known yet; rows
     // past the capacity read the last row instead.  No branches: the caller may have other loads in
     // flight whose count the compiler has to keep.
 #pragma unroll
     for (int it = 0; it < BATCH; ++it)
-      kreg[it] = *reinterpret_cast<const tail_u4*>(kt + (long)min(batch_row(0, it), cap - 1) * D + 8 * chunk);
+      kreg[it] = *reinterpret_cast<const tail_u4*>(kt + (long)min(batch_row(0, it), cap - 1) * RD);
 #pragma unroll
     for (int it = 0; it < BATCH; ++it)
-      vreg[it] = *reinterpret_cast<const tail_u4*>(vt + (long)min(batch_row(0, it), cap - 1) * D + 8 * chunk);
+      vreg[it] = *reinterpret_cast<const tail_u4*>(vt + (long)min(batch_row(0, it), cap - 1) * RD);
   }
 
   __device__ __forceinline__ void score_rows(const tail_u4 (&rows)[BATCH], int batch, int n_tail, float* sc) {
@@ -110,7 +119,7 @@ struct TailBlock {
       asm volatile("" : "+v"(qraw[hd].x), "+v"(qraw[hd].y), "+v"(qraw[hd].z), "+v"(qraw[hd].w));
       const tail_h8 qv = __builtin_bit_cast(tail_h8, qraw[hd]);
 #pragma unroll
-      for (int i = 0; i < 8; ++i) qreg[hd][i] = (hd < nh) ? (float)qv[i] * qk : 0.f;
+      for (int i = 0; i < 8; ++i) qreg[hd][i] = (hd < nh && (!PAIR || chunk / (LPR / 2) == hd)) ? (float)qv[i] * qk : 0.f;
     }
     const int n_batches = (n_tail + ROWS_PER_BATCH - 1) / ROWS_PER_BATCH;
     // ---- scores ----
@@ -121,7 +130,7 @@ struct TailBlock {
       for (int it = 0; it < BATCH; ++it) {
         const int row = batch_row(batch, it);
         rows[it] = tail_u4{0u, 0u, 0u, 0u};
-        if (row < n_tail) rows[it] = *reinterpret_cast<const tail_u4*>(kt + (long)row * D + 8 * chunk);
+        if (row < n_tail) rows[it] = *reinterpret_cast<const tail_u4*>(kt + (long)row * RD);
       }
       score_rows(rows, batch, n_tail, sc);
     }
@@ -166,7 +175,7 @@ struct TailBlock {
         // batch 0 was requested by issue_keys() for every row below the capacity: rows past the
         // tail's length hold whatever the caller left there and are dropped here
         rows[it] = (row < n_tail) ? vreg[it] : tail_u4{0u, 0u, 0u, 0u};
-        if (batch > 0 && row < n_tail) rows[it] = *reinterpret_cast<const tail_u4*>(vt + (long)row * D + 8 * chunk);
+        if (batch > 0 && row < n_tail) rows[it] = *reinterpret_cast<const tail_u4*>(vt + (long)row * RD);
       }
 #pragma unroll
       for (int it = 0; it < BATCH; ++it) {

@@ -318,12 +318,12 @@ def test_mfma_path_is_the_default_where_supported_and_rejected_elsewhere():
     assert not dq.decode_mfma_supported(dq.Format(4, 32, 128, 16, 8, 128), 32, 32)
     assert dq.decode_mfma_supported(dq.Format(8, 128, 128, 16, 8, 128), 32, 32)
     assert not dq.decode_mfma_supported(dq.Format(8, 32, 128, 16, 8, 128), 32, 32)
-    assert not dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 4, 4)
-    w = workloads.get_workload("tiny")
-    fmt, ofmt = formats(w)
-    cache = dq.alloc_cache(fmt, 1, 4, 1, DEV)
-    ws = dq.decode_workspace(fmt, 1, 4, 4, 256, DEV)
-    q = torch.zeros((1, 4, 64), dtype=torch.float16, device=DEV)
+    assert dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 4, 4)          # 64-channel heads ride in pairs
+    assert not dq.decode_mfma_supported(dq.Format(4, 64, 64, 8, 8, 256), 3, 3)      # an odd head is left over
+    fmt = dq.Format(4, 64, 64, 8, 8, 256)
+    cache = dq.alloc_cache(fmt, 1, 3, 1, DEV)
+    ws = dq.decode_workspace(fmt, 1, 3, 3, 256, DEV)
+    q = torch.zeros((1, 3, 64), dtype=torch.float16, device=DEV)
     with pytest.raises(dq.DQError):
         dq.attn_decode(cache, q, torch.zeros(1, dtype=torch.int32, device=DEV), 256, ws, flags=dq.DECODE_FORCE_MFMA)
 

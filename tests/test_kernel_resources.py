@@ -17,7 +17,7 @@ def _resources():
 def test_no_scratch_in_the_streaming_kernels():
     res = _resources()
     decode = {k: v for k, v in res.items() if "decode_mfma_kernel" in k}
-    assert len(decode) >= 100            # every (bits, groups, heads, waves, tail mode, tensors) instance
+    assert len(decode) >= 100            # every (bits, groups, heads, waves, tail mode, tensors, head pairing) instance
     for name, r in res.items():
         if any(s in name for s in ("decode_mfma_kernel", "decompose16_kernel", "quantize_tiles_kernel",
                                    "quantize_pack_kernel", "split3_kernel", "stream_read_kernel")):
@@ -29,11 +29,11 @@ def test_occupancy_the_launch_shapes_count_on():
     res = _resources()
     seen = 0
     for name, r in res.items():
-        m = re.search(r"decode_mfma_kernelILi(\d)ELi(\d)ELi(\d)ELi(\d)ELi(\d)ELb([01])E", name)
+        m = re.search(r"decode_mfma_kernelILi(\d)ELi(\d)ELi(\d)ELi(\d)ELi(\d)ELb([01])ELb([01])E", name)
         if not m:
             continue
         seen += 1
-        bits, _, _, waves, _, _ = (int(x) for x in m.groups())
+        bits, _, _, waves, _, _, _ = (int(x) for x in m.groups())
         assert r["LDS Size"] <= 160 * 1024, (name, r)
         if bits < 8 and waves == 4:
             # these workgroups run two to a compute unit: two waves per SIMD share its 512 registers

@@ -61,6 +61,10 @@ WORKLOADS = {
     # eight query heads per kv head (the head grouping of the 70B-class LLaMA models) on the long-context shape
     "gqa8_long": Workload("gqa8_long", 1008, 16, 64, 8, 128, 32768, 32768, 4, 128, 16, 8, 128,
                           "student_t", 4, 10.0),
+    # heads of 64 channels (the head size of the smaller OPT models the paper evaluates): same cached
+    # tokens per sequence and about the same bytes per launch as the benchmark shape
+    "opt_d64_4bit": Workload("opt_d64_4bit", 1009, 16, 32, 32, 64, 4096, 4096, 4, 64, 8, 8, 128,
+                             "lognormal_tokens", 2, 20.0),
     # the benchmark shape with three local tensors (the paper's n = 3 variant)
     "llama7b_4bit_n3": Workload("llama7b_4bit_n3", 1007, 8, 32, 32, 128, 4096, 4096, 4, 128, 16, 8, 128,
                                 "lognormal_tokens", 4, 20.0, i3=8),
