@@ -39,6 +39,7 @@ PROFILED_TRAFFIC_BYTES = {
     ("llama13b_mixed", "mfma"): (152210 + 352) * 2.0150 * 1024,
     ("gqa_long", "mfma"): (287270 + 764) * 1.9997 * 1024,
     ("gqa8_long", "mfma"): (349035 + 256) * 1.9997 * 1024,
+    ("opt_d64_4bit", "mfma"): (71851 + 64) * 1.9988 * 1024,
     ("llama7b_4bit_n3", "mfma"): (72851 + 64) * 1.9988 * 1024,
 }
 

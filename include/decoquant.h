@@ -110,7 +110,9 @@ int32_t dq_last_hip_error(void);
  * j1 16, any code width, group 128 or 64.  One workgroup serves up to 4 (group 128) or 2 (group 64)
  * query heads of a kv head from one pass over its codes; more heads per kv head are served in head
  * groups of that many (the last one takes what is left: 7 = 4 + 3), each its own workgroup reading
- * the same codes (at most 16 groups). */
+ * the same codes (at most 16 groups).  Heads of 64 channels are also taken when j1 = j2 = 8,
+ * group = 64, two local tensors, q_heads == kv_heads and kv_heads is even: two neighbouring kv
+ * heads are then worked by one workgroup as one head of 128 channels. */
 int32_t dq_decode_mfma_supported(const dq_format* fmt, int32_t q_heads, int32_t kv_heads);
 
 /* Bytes of workspace dq_attn_decode needs for these sizes (0 on invalid arguments).  The
