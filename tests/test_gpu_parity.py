@@ -551,17 +551,23 @@ def test_decode_with_fp16_tail(name, kw, lens, tail_lens, flags):
     assert (np.abs(out_plain.cpu().numpy().astype(np.float64) - want_plain) <= tolerance(want_plain)).all()
 
 
-@pytest.mark.parametrize("i3", [1, 8])
-def test_kv_cache_layer_policy_prefill_then_decode_steps(i3):
+@pytest.mark.parametrize("i3,d", [(1, 128), (8, 128), (1, 64)])
+def test_kv_cache_layer_policy_prefill_then_decode_steps(i3, d):
     """Section 3.2 end to end: a ragged prefill goes through the tail, whole blocks are compressed
     as they fill, then single tokens are appended step by step and every decode attends to blocks +
     tail.  Checked against the oracle reading the GPU's own compressed arrays.  i3 = 8: the same
-    with three local tensors per block."""
-    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=400, min_seq=400, i3=i3)
+    with three local tensors per block.  d = 64: heads of 64 channels (worked in pairs by the
+    matrix-core kernel, tail included)."""
+    if d == 128:
+        w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=400, min_seq=400, i3=i3)
+    else:
+        w = _small("llama7b_4bit", batch=2, q_heads=2, kv_heads=2, max_seq=400, min_seq=400, i3=i3,
+                   head_dim=64, j1=8, j2=8, group=64)
     fmt, ofmt = formats(w)
-    _say("KVCacheLayer policy, i3=%d" % i3)
+    assert dq.decode_mfma_supported(fmt, w.q_heads, w.kv_heads)
+    _say("KVCacheLayer policy, i3=%d d=%d" % (i3, d))
     layer = dq.KVCacheLayer(fmt, w.batch, w.q_heads, w.kv_heads, 512, DEV)
-    k, v = workloads.kv_tensor(w)                      # [2, 2, 400, 128]
+    k, v = workloads.kv_tensor(w)                      # [2, 2, 400, d]
     kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
     prefill = [300, 130]
     layer.append(kd[:, :, :300].contiguous(), vd[:, :, :300].contiguous(), counts=prefill)
