@@ -528,6 +528,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 
     // ---- 1. fold T_S^K into q; limbs of q' relative to 2^e >= max |q'| ----
     float q_unscale;
+    float q_unscale_second = 0.f;   // a pair of heads: each head's query gets a scale of its own
     {
       const half4 aK = __builtin_bit_cast(half4, small_live ? cur.ksm : u32x2{0u, 0u});
       f32x4 fd[F];
@@ -535,15 +536,30 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 #pragma unroll
       for (int f = 0; f < F; ++f) {
         fd[f] = __builtin_amdgcn_mfma_f32_16x16x16f16(aK, bq[f], (f32x4){0.f, 0.f, 0.f, 0.f}, 0, 0, 0);
+        // a pair of heads: rows r = 4g + i of the other head's half are zero by construction; they
+        // are set to zero outright so that nothing the other head holds (a NaN, say) gets across
+        if (P2 && !small_live) fd[f] = (f32x4){0.f, 0.f, 0.f, 0.f};
 #pragma unroll
         for (int i = 0; i < 4; ++i) amax = fmaxf(amax, fabsf(fd[f][i]));
       }
-      amax = wave_allmax_nonneg(amax) * qk_scale;
-      int e = 0;
-      if (amax > 0.f && amax < INFINITY) e = __builtin_amdgcn_frexp_expf(amax);  // amax = f * 2^e, f in [0.5, 1)
-      e = max(min(e, 100), -100);
+      auto exponent_of = [&](float m) -> int {
+        int e = 0;
+        if (m > 0.f && m < INFINITY) e = __builtin_amdgcn_frexp_expf(m);  // m = f * 2^e, f in [0.5, 1)
+        return max(min(e, 100), -100);
+      };
+      int e;
+      if (P2) {
+        // the lane's column belongs to head n / 8: one maximum per head
+        const int e_first = exponent_of(wave_allmax_nonneg((n >> 3) ? 0.f : amax) * qk_scale);
+        const int e_second = exponent_of(wave_allmax_nonneg((n >> 3) ? amax : 0.f) * qk_scale);
+        e = (n >> 3) ? e_second : e_first;
+        q_unscale = pow2i(e_first - (kQueryBits - 1));
+        q_unscale_second = pow2i(e_second - (kQueryBits - 1));
+      } else {
+        e = exponent_of(wave_allmax_nonneg(amax) * qk_scale);
+        q_unscale = pow2i(e - (kQueryBits - 1));
+      }
       const float qn = qk_scale * pow2i(kQueryBits - 1 - e);   // |q' * qn| < 2^27
-      q_unscale = pow2i(e - (kQueryBits - 1));
       // the fold's D layout: lane (n' = b2 + 8*head, g) holds rows r = 4g + i.  Channel (r, b2) is
       // code number (r & 1)*8 + b2 of the 16 codes that row pair r >> 1 contributes to one MFMA.
 #pragma unroll
@@ -601,14 +617,23 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 
     // ---- 3. online softmax, tokens tA and tB per lane ----
     float v_unscale, vs = 0.f;
+    float vs_second = 0.f;   // a pair of heads: the second head's steps get a scale of their own
     if (!N3) {
       float dvm = fmaxf(dvA[0], dvB[0]);
-      if (NG == 2) dvm = fmaxf(dvm, fmaxf(dvA[NG - 1], dvB[NG - 1]));
+      if (NG == 2 && !P2) dvm = fmaxf(dvm, fmaxf(dvA[NG - 1], dvB[NG - 1]));
       const float dvmax = wave_allmax_nonneg(dvm);
       int e = 0;
       if (dvmax > 0.f && dvmax < INFINITY) e = __builtin_amdgcn_frexp_expf(dvmax);
       vs = pow2i(kMantBits - e);   // p * step * vs < 2^21
       v_unscale = pow2i(e - kMantBits);
+      if (P2) {
+        const float dvmax2 = wave_allmax_nonneg(fmaxf(dvA[NG - 1], dvB[NG - 1]));
+        int e2 = 0;
+        if (dvmax2 > 0.f && dvmax2 < INFINITY) e2 = __builtin_amdgcn_frexp_expf(dvmax2);
+        vs_second = pow2i(kMantBits - e2);
+        // the epilogue's rows b1 = n of the second head (n >= 8) undo the second head's scale
+        if (n >> 3) v_unscale = pow2i(e2 - kMantBits);
+      }
     }
     float alpha[R];
     float wA[R][NG], wB[R][NG];   // three tensors: the weights, kept until their common scale is known
@@ -618,6 +643,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       float sA = 0.f, sB = 0.f;
 #pragma unroll
       for (int gr = 0; gr < NG; ++gr) {
+        if (P2 && gr != hd) continue;   // a head of a pair has its channels in its own step group only
         const int* s0 = Ss + (CPH * hd + 4 * gr) * SS;
         const int* s1 = s0 + SS;
         const int* s2 = s1 + SS;
@@ -630,8 +656,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         sA = 0.f; sB = 0.f;
         quad_mix(yA, yB, cur3.k3A, cur3.k3B, sA, sB);
       }
-      sA = okA ? sA * q_unscale : -INFINITY;
-      sB = okB ? sB * q_unscale : -INFINITY;
+      const float unscale = (P2 && hd) ? q_unscale_second : q_unscale;
+      sA = okA ? sA * unscale : -INFINITY;
+      sB = okB ? sB * unscale : -INFINITY;
       // the running maximum moves in a sequence's first tiles and rarely afterwards: the wave-wide
       // reduction runs only when some lane holds a score above it
       const float mt_lane = fmaxf(sA, sB);
@@ -657,8 +684,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       } else {
 #pragma unroll
         for (int gr = 0; gr < NG; ++gr) {
-          const float wa = okA ? pA * (dvA[gr] * vs) : 0.f;
-          const float wb = okB ? pB * (dvB[gr] * vs) : 0.f;
+          // a pair of heads: only the head's own rows are kept, so only their column gets weights
+          // (the other one stays zero from the start)
+          if (P2 && gr != hd) continue;
+          const float vsg = (P2 && gr) ? vs_second : vs;
+          const float wa = okA ? pA * (dvA[gr] * vsg) : 0.f;
+          const float wb = okB ? pB * (dvB[gr] * vsg) : 0.f;
           const uint32_t iA = min((uint32_t)(wa + 0.5f), (1u << kMantBits) - 1u);
           const uint32_t iB = min((uint32_t)(wb + 0.5f), (1u << kMantBits) - 1u);
           unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
@@ -796,6 +827,10 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
     // are the same in every tile and are zeroed once (the fold writes only its own group's).
     static_assert(QS_BYTES % 16 == 0, "");
     for (int o = lane * 16; o < QS_BYTES; o += 64 * 16) *reinterpret_cast<i32x4*>(Qs + o) = izero;
+    if (P2) {   // the weight columns of the other head's step group are never written: zero for good
+      static_assert(PS_BYTES % 16 == 0, "");
+      for (int o = lane * 16; o < PS_BYTES; o += 64 * 16) *reinterpret_cast<i32x4*>(Ps + o) = izero;
+    }
     __builtin_amdgcn_wave_barrier();
   }
   S = min(max(seq_len_raw, 0), a.max_seq_len);

@@ -97,6 +97,9 @@ struct TailBlock {
 #pragma unroll
       for (int hd = 0; hd < HB; ++hd) {
         float v = part[hd];
+        // a pair: the lanes on the other head's half of the row add an outright zero (their query is
+        // zero, but zero times whatever that head's row holds need not be)
+        if (PAIR && chunk / (LPR / 2) != hd) v = 0.f;
         v += tail_dpp<0xB1>(v);                    // lane ^ 1
         v += tail_dpp<0x4E>(v);                    // lane ^ 2
         v += tail_dpp<0x141>(v);                   // 7 - lane within 8

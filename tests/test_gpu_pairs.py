@@ -110,3 +110,21 @@ def test_random_pair_cases(seed, monkeypatch):
         assert torch.equal(out, again), (seed, case)
         assert (np.abs(g16 - want) <= tolerance(want)).all(), (seed, case, np.nanmax(np.abs(g16 - want)))
         assert (np.abs(g32 - want) <= np.maximum(2e-3, 1e-4 * np.abs(want))).all(), (seed, case)
+
+
+@pytest.mark.parametrize("bits", [2, 4, 8])
+def test_a_head_does_not_depend_on_its_partner(bits):
+    """Only one head of each pair holds a cache; its partner's arrays are garbage bytes with NaN and
+    Inf among the steps and small tensors.  The valid heads must come out as if they were alone."""
+    w = _w64(batch=2, q_heads=4, kv_heads=4, max_seq=640, block_tokens=128, bits=bits)
+    from test_gpu_parity import _decode_case
+    _say("pairs with a garbage partner, %d-bit" % bits)
+    _decode_case(w, [640, 300], dq.DECODE_FORCE_MFMA, pairs=[(0, 0), (0, 3), (1, 1), (1, 2)])
+
+
+def test_decode_full_size_64_channel_heads():
+    """The opt_d64_4bit bench configuration (batch 16, 32 heads, 4096 tokens, default launch shape):
+    sampled (sequence, head) pairs are oracle-compressed and checked element by element; every other
+    head, the partners of three of the sampled ones among them, holds garbage bytes."""
+    from test_gpu_parity import _full_size_case
+    _full_size_case("opt_d64_4bit", [(0, 0), (15, 31), (7, 12), (7, 13), (3, 17)])
