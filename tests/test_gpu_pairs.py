@@ -119,7 +119,17 @@ def test_a_head_does_not_depend_on_its_partner(bits):
     w = _w64(batch=2, q_heads=4, kv_heads=4, max_seq=640, block_tokens=128, bits=bits)
     from test_gpu_parity import _decode_case
     _say("pairs with a garbage partner, %d-bit" % bits)
-    _decode_case(w, [640, 300], dq.DECODE_FORCE_MFMA, pairs=[(0, 0), (0, 3), (1, 1), (1, 2)])
+    kept = [(0, 0), (0, 3), (1, 1), (1, 2)]
+    _decode_case(w, [640, 300], dq.DECODE_FORCE_MFMA, pairs=kept)
+    # and bit for bit what they are when the partners hold caches of their own
+    fmt, ofmt = formats(w)
+    lens = np.array([640, 300], np.int32)
+    q = workloads.query(w)
+    everyone = [(b, h) for b in range(w.batch) for h in range(w.kv_heads)]
+    alone, _ = run_decode(fmt, oracle_cache_for_pairs(w, ofmt, kept, lens), q, lens, int(w.max_seq), dq.DECODE_FORCE_MFMA)
+    full, _ = run_decode(fmt, oracle_cache_for_pairs(w, ofmt, everyone, lens), q, lens, int(w.max_seq), dq.DECODE_FORCE_MFMA)
+    for b, h in kept:
+        assert np.array_equal(alone[b, h].view(np.uint16), full[b, h].view(np.uint16)), (b, h)
 
 
 def test_decode_full_size_64_channel_heads():
