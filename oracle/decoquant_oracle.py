@@ -29,7 +29,10 @@ the repository): per-head blocks of `block_tokens` rows; i_1 = 1 so the small
 tensor mixes only channels; no bond truncation; singular values kept in the
 small tensor; per-group fp16 steps with groups of `group` consecutive elements
 inside one token row of the large tensor; ties round to even; 2-bit uses the
-literal Eq. 1 levels {-1, 0, +1}; codes stored offset-binary.  Three local tensors
+literal Eq. 1 levels {-1, 0, +1}; codes stored offset-binary.  Non-default level set
+(`levels` = 1, not the paper's: Eq. 1 is symmetric): all 2^m codes, c in
+[-2^(m-1), 2^(m-1) - 1] ({-2, -1, 0, +1} at 2 bits), with the step sized so that neither end
+clips, Delta = fp16(max(max(x) / (2^(m-1) - 1), max(-x) / 2^(m-1))).  Three local tensors
 (`i3` > 1): factors I = 1 * (T_b/i3) * i3, J = j1 * j2 * 1, so the third tensor mixes
 the i3 tokens of a run of consecutive tokens; the singular values of the first cut stay in
 T_1 and those of the second cut in T_3, which leaves the quantized middle tensor T_2 with
@@ -61,6 +64,7 @@ class Format:
     j2: int
     block_tokens: int
     i3: int = 1   # 1: two local tensors; > 1: three, the third one i3 x i3 on the token side
+    levels: int = 0   # 0: Eq. 1's symmetric codes [-qmax, qmax]; 1: all 2^bits codes [-qmax - 1, qmax]
 
     def check(self) -> None:
         if self.bits not in (2, 4, 8):
@@ -73,10 +77,16 @@ class Format:
             raise ValueError("block_tokens must be a multiple of %d" % TILE_TOKENS)
         if self.i3 < 1 or self.block_tokens % self.i3:
             raise ValueError("i3 must divide block_tokens")
+        if self.levels not in (0, 1):
+            raise ValueError("levels must be 0 (symmetric) or 1 (all codes)")
 
     @property
     def qmax(self) -> int:
         return (1 << (self.bits - 1)) - 1
+
+    @property
+    def full_range(self) -> bool:
+        return self.levels == 1
 
     @property
     def row_bytes(self) -> int:
@@ -245,27 +255,36 @@ def token_major_to_large(kp: np.ndarray, j1: int, j2: int) -> np.ndarray:
 # Eq. 1 per group: step, code, dequantized value
 # --------------------------------------------------------------------------------------
 
-def group_steps(kp: np.ndarray, group: int, qmax: int) -> np.ndarray:
+def group_steps(kp: np.ndarray, group: int, qmax: int, full_range: bool = False) -> np.ndarray:
     """Delta[t, g] = fp16(max|x| over group / qmax), the quotient rounded once to fp16.
 
     The fp64 quotient of a 24-bit numerator by qmax <= 127 cannot land within
     fp64 rounding distance of an fp16 rounding boundary without being on it, so
     fp64-divide-then-cast equals a single rounding of the exact quotient.
+
+    full_range (codes [-qmax - 1, qmax]): the smallest step under which neither end clips,
+    Delta = fp16(max(max(x) / qmax, max(-x) / (qmax + 1))); rounding is monotonic, so the larger of
+    the two rounded quotients is the rounded larger quotient.
     """
     n_tok, d = kp.shape
-    a = np.abs(kp.astype(np.float64)).reshape(n_tok, d // group, group).max(axis=2)
+    x = kp.astype(np.float64).reshape(n_tok, d // group, group)
     with np.errstate(over="ignore"):
-        return (a / float(qmax)).astype(np.float16)
+        if not full_range:
+            return (np.abs(x).max(axis=2) / float(qmax)).astype(np.float16)
+        up = (np.maximum(x, 0.0).max(axis=2) / float(qmax)).astype(np.float16)
+        down = (np.maximum(-x, 0.0).max(axis=2) / float(qmax + 1)).astype(np.float16)
+        return np.maximum(up, down)
 
 
-def quantize_codes(kp: np.ndarray, steps: np.ndarray, group: int, qmax: int) -> np.ndarray:
-    """c[t, e] = clamp(round_half_even(x / Delta), -qmax, qmax); all-zero where Delta == 0."""
+def quantize_codes(kp: np.ndarray, steps: np.ndarray, group: int, qmax: int, full_range: bool = False) -> np.ndarray:
+    """c[t, e] = clamp(round_half_even(x / Delta), lo, qmax), lo = -qmax (or -qmax - 1 with
+    full_range); all-zero where Delta == 0."""
     n_tok, d = kp.shape
     delta = np.repeat(steps.astype(np.float64), group, axis=1)
     x = kp.astype(np.float64)
     safe = np.where(delta > 0, delta, 1.0)
     c = np.rint(x / safe)
-    c = np.clip(c, -qmax, qmax)
+    c = np.clip(c, -qmax - (1 if full_range else 0), qmax)
     c = np.where(delta > 0, c, 0.0)
     return c.astype(np.int32)
 
@@ -375,8 +394,8 @@ def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
         else:
             t_s, t_l = mpo_split(xb, fmt.j1, 1, sigma_in)
         kp = large_to_token_major(t_l, tb, fmt.j2)
-    steps = group_steps(kp, fmt.group, fmt.qmax)
-    codes = quantize_codes(kp, steps, fmt.group, fmt.qmax)
+    steps = group_steps(kp, fmt.group, fmt.qmax, fmt.full_range)
+    codes = quantize_codes(kp, steps, fmt.group, fmt.qmax, fmt.full_range)
     with np.errstate(over="ignore"):
         small = t_s.astype(np.float16)
     return Block(small=small, steps=steps, codes=codes, large32=kp, small3=small3)
