@@ -55,7 +55,7 @@ def _cpu_worker(rank, n_workers, wname, pairs, barrier, queue):
         pass
     from oracle import decoquant_oracle as O
     w = workloads.get_workload(wname)
-    fmt = O.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3)
+    fmt = O.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels)
     mine = pairs[rank::n_workers]
     lens = workloads.seq_lens(w)
     q = workloads.query(w)
@@ -118,7 +118,7 @@ def cpu_baseline(wname: str, n_pairs: int):
 # --------------------------------------------------------------------------------------------
 def build_cache(dq, torch, w, dev):
     """Host-generate the layer's K/V, upload, compress every block on the GPU."""
-    fmt = dq.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3)
+    fmt = dq.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels)
     tb = w.block_tokens
     total = w.max_seq + w.append_tokens
     nb = -(-total // tb)

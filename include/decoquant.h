@@ -68,7 +68,8 @@ typedef enum dq_status {
 
 /* Format of a compressed cache.  Constraints: bits in {2, 4, 8}; head_dim == j1*j2;
  * head_dim in {64, 128}; j1 in {8, 16, 32}; group divides head_dim and group >= head_dim/2
- * or group divides head_dim/2; block_tokens is a positive multiple of 128; i3 in {1, 8}. */
+ * or group divides head_dim/2; block_tokens is a positive multiple of 128; i3 in {1, 8};
+ * levels in {0, 1}. */
 typedef struct dq_format {
   int32_t bits;         /* m of Eq. 1; qmax = 2^(m-1) - 1                         */
   int32_t group;        /* G: elements per step, consecutive inside one token row  */
@@ -78,6 +79,11 @@ typedef struct dq_format {
   int32_t block_tokens; /* T_b: tokens per decomposed block (Eq. 2: i_2; i_1 = 1)  */
   int32_t i3;           /* 1: two local tensors; 8: three, T_3 is 8 x 8 on the token side
                            (then i_2 = T_b / 8, i_3 = 8, j_3 = 1)                  */
+  int32_t levels;       /* 0: the symmetric codes of Eq. 1, c in [-qmax, qmax];
+                           1 (not the paper's): all 2^m codes, c in [-qmax - 1, qmax], with
+                           step = fp16(max(max(x) / qmax, max(-x) / (qmax + 1))) so that neither
+                           end clips.  Only the quantizer differs; decoding reads the stored
+                           field c + 2^(m-1) the same way.                          */
 } dq_format;
 
 /* Device pointers to the arrays described above; shapes are fixed by (format, batch,

@@ -8,6 +8,7 @@ from .binding import (  # noqa: F401
     Format,
     Cache,
     KVCacheLayer,
+    ABI_VERSION,
     DECODE_AUTO,
     DECODE_FORCE_GENERIC,
     DECODE_FORCE_MFMA,

@@ -11,6 +11,7 @@ import torch
 from . import build as _build
 
 DECODE_AUTO = 0
+ABI_VERSION = 3   # dq_version() of the library whose struct layouts this file mirrors
 DECODE_FORCE_GENERIC = 1
 DECODE_FORCE_MFMA = 2
 
@@ -28,7 +29,8 @@ class DQError(RuntimeError):
 
 class _CFormat(C.Structure):
     _fields_ = [("bits", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
-                ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32), ("i3", C.c_int32)]
+                ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32), ("i3", C.c_int32),
+                ("levels", C.c_int32)]
 
 
 class _CTail(C.Structure):
@@ -50,6 +52,8 @@ def _load() -> C.CDLL:
         raise DQError("libdecoquant.so is missing and could not be built")
     l = C.CDLL(path)
     l.dq_version.restype = C.c_int32
+    if int(l.dq_version()) != ABI_VERSION:   # the structs below would not match the library's
+        raise DQError("%s is version %d, this binding needs %d: rebuild it" % (path, int(l.dq_version()), ABI_VERSION))
     l.dq_status_string.restype = C.c_char_p
     l.dq_status_string.argtypes = [C.c_int32]
     l.dq_last_hip_error.restype = C.c_int32
@@ -114,9 +118,11 @@ class Format:
     j2: int
     block_tokens: int
     i3: int = 1   # 8: three local tensors (T_3 is 8 x 8 on the token side)
+    levels: int = 0   # 1: the quantizer uses all 2^bits codes (not the paper's symmetric range)
 
     def c(self) -> _CFormat:
-        return _CFormat(self.bits, self.group, self.head_dim, self.j1, self.j2, self.block_tokens, self.i3)
+        return _CFormat(self.bits, self.group, self.head_dim, self.j1, self.j2, self.block_tokens, self.i3,
+                        self.levels)
 
     @property
     def row_bytes(self) -> int:

@@ -40,6 +40,7 @@ inline bool format_ok(const dq_format* f) {
   if ((f->group * f->bits) % 32) return false;  // a group covers whole 32-bit words
   if (f->block_tokens <= 0 || f->block_tokens % kTileTokens) return false;
   if (f->i3 != 1 && f->i3 != kRun) return false;
+  if (f->levels != 0 && f->levels != 1) return false;
   return true;
 }
 

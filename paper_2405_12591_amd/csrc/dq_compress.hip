@@ -84,13 +84,17 @@ __device__ __forceinline__ int settle_code(float x, float c0, float step, double
   return c;
 }
 
-template <int BITS, int D>
+// FULL: the non-default level set (format.levels == 1): codes in [-QMAX - 1, QMAX], and the step is
+// the larger of max(x) / QMAX and max(-x) / (QMAX + 1), each rounded once to fp16 (rounding is
+// monotonic, so that is the rounded larger quotient; the second divisor is a power of two).
+template <int BITS, int D, bool FULL>
 __device__ __forceinline__ void quantize_tile(const float* __restrict__ src,  // [128, D] fp32
                               int G, int j1, int j2, int value_layout,
                               uint8_t* __restrict__ codes_out,    // tile's code bytes
                               uint16_t* __restrict__ scales_out,  // [128, D/G]
                               uint8_t* __restrict__ lds_u) {      // [128 * D] stored fields (+ value staging)
   constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  constexpr int QMIN = FULL ? -QMAX - 1 : -QMAX;
   constexpr int BIAS = 1 << (BITS - 1);
   constexpr int d = D;
   constexpr int LPR = D / 4;                 // lanes per row, 4 elements each: 32 or 16
@@ -107,35 +111,52 @@ __device__ __forceinline__ void quantize_tile(const float* __restrict__ src,  //
 #pragma unroll
   for (int ps = 0; ps < PASSES; ++ps)
     v[ps] = *reinterpret_cast<const float4*>(src + (long)(ps * ROWS_PER_PASS + rp) * d + 4 * li);
-  float amax[PASSES];
+  // amax: max |x| of the group (FULL: max x, at least 0); amin (FULL only): max -x, at least 0
+  float amax[PASSES], amin[PASSES];
 #pragma unroll
-  for (int ps = 0; ps < PASSES; ++ps)
-    amax[ps] = fmaxf(fmaxf(fabsf(v[ps].x), fabsf(v[ps].y)), fmaxf(fabsf(v[ps].z), fabsf(v[ps].w)));
+  for (int ps = 0; ps < PASSES; ++ps) {
+    if (FULL) {
+      amax[ps] = fmaxf(fmaxf(fmaxf(v[ps].x, v[ps].y), fmaxf(v[ps].z, v[ps].w)), 0.f);
+      amin[ps] = fmaxf(fmaxf(fmaxf(-v[ps].x, -v[ps].y), fmaxf(-v[ps].z, -v[ps].w)), 0.f);
+    } else {
+      amax[ps] = fmaxf(fmaxf(fabsf(v[ps].x), fabsf(v[ps].y)), fmaxf(fabsf(v[ps].z), fabsf(v[ps].w)));
+      amin[ps] = 0.f;
+    }
+  }
   // group maximum over gl lanes: lane exchanges inside a row of 16 lanes, then across the two rows
-  if (gl > 1) {
+  auto group_max = [&](float (&m)[PASSES]) __attribute__((always_inline)) {
+    if (gl > 1) {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0xB1>(amax[ps]));    // i ^ 1
-  }
-  if (gl > 2) {
+      for (int ps = 0; ps < PASSES; ++ps) m[ps] = fmaxf(m[ps], lane_exchange<0xB1>(m[ps]));    // i ^ 1
+    }
+    if (gl > 2) {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0x4E>(amax[ps]));    // i ^ 2
-  }
-  if (gl > 4) {
+      for (int ps = 0; ps < PASSES; ++ps) m[ps] = fmaxf(m[ps], lane_exchange<0x4E>(m[ps]));    // i ^ 2
+    }
+    if (gl > 4) {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0x141>(amax[ps]));   // 7 - i in 8
-  }
-  if (gl > 8) {
+      for (int ps = 0; ps < PASSES; ++ps) m[ps] = fmaxf(m[ps], lane_exchange<0x141>(m[ps]));   // 7 - i in 8
+    }
+    if (gl > 8) {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], lane_exchange<0x140>(amax[ps]));   // 15 - i in 16
-  }
-  if (LPR > 16 && gl > 16) {
+      for (int ps = 0; ps < PASSES; ++ps) m[ps] = fmaxf(m[ps], lane_exchange<0x140>(m[ps]));   // 15 - i in 16
+    }
+    if (LPR > 16 && gl > 16) {
 #pragma unroll
-    for (int ps = 0; ps < PASSES; ++ps) amax[ps] = fmaxf(amax[ps], __shfl_xor(amax[ps], 16));
-  }
+      for (int ps = 0; ps < PASSES; ++ps) m[ps] = fmaxf(m[ps], __shfl_xor(m[ps], 16));
+    }
+  };
+  group_max(amax);
+  if (FULL) group_max(amin);
   float step[PASSES], inv[PASSES];
 #pragma unroll
   for (int ps = 0; ps < PASSES; ++ps) {
-    const uint16_t sbits = group_step_bits<QMAX>(amax[ps]);
+    uint16_t sbits = group_step_bits<QMAX>(amax[ps]);
+    if (FULL) {
+      // both are bit patterns of non-negative fp16 values (or +inf), which order like integers
+      const uint16_t down = f2h_rne(amin[ps] * (1.0f / (float)(QMAX + 1)));   // exact: a power of two
+      sbits = sbits > down ? sbits : down;
+    }
     step[ps] = h2f(sbits);
     inv[ps] = step[ps] > 0.f ? __builtin_amdgcn_rcpf(step[ps]) : 0.f;   // step 0 (and inf): every code 0
     if ((li & (gl - 1)) == 0) scales_out[(ps * ROWS_PER_PASS + rp) * groups + li / gl] = sbits;
@@ -151,7 +172,7 @@ __device__ __forceinline__ void quantize_tile(const float* __restrict__ src,  //
       const float q = xs[e] * inv[ps];
       const float cf = __builtin_rintf(q);
       near |= fabsf(q - cf) > kNearTie;
-      fields |= (uint32_t)(min(max((int)cf, -QMAX), QMAX) + BIAS) << (8 * e);
+      fields |= (uint32_t)(min(max((int)cf, QMIN), QMAX) + BIAS) << (8 * e);
     }
     near_mask |= (near ? 1u : 0u) << ps;
     *reinterpret_cast<uint32_t*>(lds_u + (ps * ROWS_PER_PASS + rp) * d + 4 * li) = fields;
@@ -166,7 +187,7 @@ __device__ __forceinline__ void quantize_tile(const float* __restrict__ src,  //
 #pragma unroll
         for (int e = 0; e < 4; ++e) {
           const int c = settle_code(xs[e], __builtin_rintf(xs[e] * inv[ps]), step[ps], hs);
-          fields |= (uint32_t)(min(max(c, -QMAX), QMAX) + BIAS) << (8 * e);
+          fields |= (uint32_t)(min(max(c, QMIN), QMAX) + BIAS) << (8 * e);
         }
         *reinterpret_cast<uint32_t*>(lds_u + (ps * ROWS_PER_PASS + rp) * d + 4 * li) = fields;
       }
@@ -217,7 +238,7 @@ __host__ __device__ inline size_t quantize_lds_bytes(int d, int bits) {
 }
 
 // Stand-alone entry: contiguous input rows, contiguous outputs (dq_quantize_pack).
-template <int BITS, int D>
+template <int BITS, int D, bool FULL>
 __global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restrict__ t_large, int G, int j1,
                                                             int j2, int value_layout,
                                                             uint8_t* __restrict__ codes,
@@ -225,12 +246,12 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restr
   extern __shared__ uint8_t lds_u[];
   const long tile = blockIdx.x;
   const long tile_code_bytes = (long)kTileTokens * D * BITS / 8;
-  quantize_tile<BITS, D>(t_large + tile * kTileTokens * D, G, j1, j2, value_layout,
+  quantize_tile<BITS, D, FULL>(t_large + tile * kTileTokens * D, G, j1, j2, value_layout,
                          codes + tile * tile_code_bytes, scales + tile * kTileTokens * (D / G), lds_u);
 }
 
 // Compress path: tile `blockIdx.x % tiles_per_block` of work unit `blockIdx.x / tiles_per_block`.
-template <int BITS, int D>
+template <int BITS, int D, bool FULL>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __restrict__ large_ws,
                                                              dq_format fmt, dq_cache cache,
                                                              CompressJob job,
@@ -265,7 +286,7 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __rest
                    (long)tile * kTileTokens * g.row_bytes;
   uint16_t* scales = (which ? cache.v_scales : cache.k_scales) + blk * g.scales_per_block +
                      (long)tile * kTileTokens * g.groups;
-  quantize_tile<BITS, D>(src, g.G, g.j1, g.j2, which, codes, scales, lds_u);
+  quantize_tile<BITS, D, FULL>(src, g.G, g.j1, g.j2, which, codes, scales, lds_u);
 }
 
 // ------------------------------------------------------------------------------------------
@@ -913,9 +934,15 @@ extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, 
   const int tiles = (int)(n_rows / kTileTokens);
   const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
   const int d = fmt->head_dim, G = fmt->group, j1 = fmt->j1, j2 = fmt->j2;
-#define DQ_LAUNCH_QPACK(B_, D_)                                                                          \
-  hipLaunchKernelGGL((quantize_pack_kernel<B_, D_>), dim3(tiles), dim3(256), lds, st, t_large, G, j1, j2, \
-                     value_layout, codes, scales)
+#define DQ_LAUNCH_QPACK(B_, D_)                                                                                  \
+  do {                                                                                                           \
+    if (fmt->levels)                                                                                             \
+      hipLaunchKernelGGL((quantize_pack_kernel<B_, D_, true>), dim3(tiles), dim3(256), lds, st, t_large, G, j1,  \
+                         j2, value_layout, codes, scales);                                                       \
+    else                                                                                                         \
+      hipLaunchKernelGGL((quantize_pack_kernel<B_, D_, false>), dim3(tiles), dim3(256), lds, st, t_large, G, j1, \
+                         j2, value_layout, codes, scales);                                                       \
+  } while (0)
   if (d == 128) {
     if (fmt->bits == 2) DQ_LAUNCH_QPACK(2, 128);
     else if (fmt->bits == 4) DQ_LAUNCH_QPACK(4, 128);
@@ -985,9 +1012,15 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   }
   const int tiles = units * (fmt->block_tokens / kTileTokens);
   const size_t lds = quantize_lds_bytes(fmt->head_dim, fmt->bits);
-#define DQ_LAUNCH_QTILES(B_, D_)                                                                       \
-  hipLaunchKernelGGL((quantize_tiles_kernel<B_, D_>), dim3(tiles), dim3(256), lds, st, large_ws, *fmt, \
-                     *cache, job, unit_status, units, status)
+#define DQ_LAUNCH_QTILES(B_, D_)                                                                              \
+  do {                                                                                                        \
+    if (fmt->levels)                                                                                          \
+      hipLaunchKernelGGL((quantize_tiles_kernel<B_, D_, true>), dim3(tiles), dim3(256), lds, st, large_ws,    \
+                         *fmt, *cache, job, unit_status, units, status);                                      \
+    else                                                                                                      \
+      hipLaunchKernelGGL((quantize_tiles_kernel<B_, D_, false>), dim3(tiles), dim3(256), lds, st, large_ws,   \
+                         *fmt, *cache, job, unit_status, units, status);                                      \
+  } while (0)
   if (fmt->head_dim == 128) {
     if (fmt->bits == 2) DQ_LAUNCH_QTILES(2, 128);
     else if (fmt->bits == 4) DQ_LAUNCH_QTILES(4, 128);

@@ -9,7 +9,7 @@ DEV = "cuda:0"
 
 
 def formats(w):
-    args = (w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3)
+    args = (w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels)
     return dq.Format(*args), O.Format(*args)
 
 
