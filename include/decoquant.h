@@ -242,7 +242,9 @@ int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint1
  * Quantize and pack a caller-supplied large tensor (Preliminary, Eq. 1 per group; Section 3.1
  * step 2).  step = fp16(max|x| / qmax), the exact quotient rounded once, ties to even;
  * code = clamp(nearest integer of the exact x / step, ties to even, +-qmax); step == 0 gives
- * codes 0.  Results are bit-exact functions of the input.
+ * codes 0.  With format.levels == 1 the clamp is [-qmax - 1, qmax] and
+ * step = fp16(max(max(x) / qmax, max(-x) / (qmax + 1))), each quotient rounded once.  Results are
+ * bit-exact functions of the input.
  *   t_large  f32 [n_rows, d], token-major rows (element c' = r*j2 + b2); n_rows % 128 == 0
  *   value_layout  0: write key layout (codes [n_rows, d*bits/8]);
  *                 1: write value layout (codes [n_rows/128, j2, j1, 128*bits/8])
