@@ -8,8 +8,8 @@
  * values and the outliers) stays in fp16; T_L (j1 x T_b*j2, orthonormal rows, narrow range) is
  * quantized to `bits`-bit integers with one fp16 step per group (Preliminary, Eq. 1; Section
  * 3.1 "Local Tensor Quantization").  Decode attention reads the codes directly and applies
- * T_S by folding it into the query and into the P.V epilogue, which is the fused
- * "dequantize + multiply the local tensors" of Section 3.2 ("Kernel Fusion for
+ * T_S by folding it into the query and into the P.V epilogue, which is the fusion of
+ * dequantization with the product of the local tensors of Section 3.2 ("Kernel Fusion for
  * Dequantization") carried through the attention that follows it.
  *
  * Conventions for every entry point

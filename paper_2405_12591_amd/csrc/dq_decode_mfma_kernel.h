@@ -7,7 +7,7 @@
 // neighbouring kv heads are worked as one head of 128 channels whose small tensors are block-diagonal
 // and whose two query heads are the real ones padded with zeros (see P2 below).
 //
-// This is the fused "dequantize + multiply the local tensors" of Section 3.2 (arXiv
+// This is the fusion of dequantization with the product of the local tensors of Section 3.2 (arXiv
 // 2405.12591) carried through the attention that follows it.  The low-bit codes never become
 // floating point: a 32-bit word of codes is split into words of four bytes each
 // (4-bit: x & 0x0F0F0F0F, (x >> 4) & 0x0F0F0F0F; 2-bit: (x >> 2k) & 0x03030303; 8-bit: x ^ 0x80808080) and fed to the

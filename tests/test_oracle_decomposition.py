@@ -36,7 +36,7 @@ def test_split_is_exact(sigma_in, shape):
     assert t_s.shape == (j1, j1) and t_l.shape == (j1, n_tok * d // j1)
     rel = np.linalg.norm(t_s @ t_l - m) / np.linalg.norm(m)
     assert rel <= 1e-10
-    # parameter count is "slightly larger" than the matrix (Section 3.3): by exactly j1^2
+    # the local tensors hold a few more parameters than the matrix (Section 3.3): exactly j1^2 more
     assert t_s.size + t_l.size == x.size + j1 * j1
     if sigma_in == "small":
         assert np.abs(t_l @ t_l.T - np.eye(j1)).max() <= 1e-12
