@@ -545,23 +545,42 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
 
 // NWV waves per block: the two contractions are split over the waves by token, the eigen-solver
 // runs in one of them.  The host picks NWV so that the launch has about one wave per SIMD.
-template <int NWV>
+// PAIR: heads of 64 channels with j1 = 8.  The same block (keys or values, same sequence and block
+// position) of two neighbouring kv heads is worked as one block of 128 channels: the two 8 x T_b*8
+// regrouped matrices on top of each other.  The 16 x 16 Gram matrix then holds the heads' own 8 x 8
+// Gram matrices on its diagonal; the blocks off the diagonal (products across heads) are set to
+// zero, after which every rotation between the two halves is the identity and the iteration solves
+// the two 8 x 8 problems side by side (the rotations, their order and the stopping rule are those of
+// the 16 x 16 case).  Ordering, small tensors, projection and outputs are per head.
+template <int NWV, bool PAIR>
 __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                                float* __restrict__ large_ws,
                                                                int32_t* __restrict__ unit_status) {
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
-  const int unit = blockIdx.x;
+  // the work unit (of the pair's first head); the second head's unit lies `unit_gap` further on
+  int unit = blockIdx.x;
+  const int unit_gap = 2 * job.n_blocks;
+  if (PAIR) {
+    const int pb = blockIdx.x >> 1, j = pb % job.n_blocks, hp = pb / job.n_blocks;   // hp = b * (H/2) + head pair
+    const int half_h = g.H >> 1;
+    unit = (((hp / half_h) * g.H + 2 * (hp % half_h)) * job.n_blocks + j) * 2 + (blockIdx.x & 1);
+  }
   const UnitRef ur = unit_ref(g, job, unit);
   const int which = ur.which, slot = ur.slot, nv = ur.nv;
   const long bh = ur.bh;
   if (slot < 0) {
-    if (threadIdx.x == 0) unit_status[unit] = 0;
+    if (threadIdx.x == 0) {
+      unit_status[unit] = 0;
+      if (PAIR) unit_status[unit + unit_gap] = 0;
+    }
     return;
   }
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
-  const int solver = unit % NWV;   // the wave that runs the eigen-solver (spread over the SIMDs)
-  constexpr int j1 = 16, d = 128, ld = 17;
+  const int solver = blockIdx.x % NWV;   // the wave that runs the eigen-solver (spread over the SIMDs)
+  constexpr int j1 = 16, ld = 17;
+  constexpr int d = PAIR ? 64 : 128;     // halves per row in memory
   const uint16_t* X = ur.X;  // [nv, d] fp16 bits
+  const long head_gap = (long)job.t_new * d;   // PAIR: from a row of the first head to the same row of the second
 
   __shared__ double A[j1 * ld], V[j1 * ld], W[j1 * ld];
   __shared__ double P[(NWV > 1 ? NWV - 1 : 1) * j1 * ld];   // Gram partials of the other waves
@@ -585,7 +604,9 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
       for (int u = 0; u < NG; ++u) {
         const int t = t0 + 4 * (u * NWV + wv) + tk;
         x[u] = u32x4{0u, 0u, 0u, 0u};
-        if (t < nv) x[u] = *reinterpret_cast<const u32x4*>(X + (long)t * d + b1 * 8);
+        if (t < nv)
+          x[u] = *reinterpret_cast<const u32x4*>(PAIR ? X + (b1 >> 3) * head_gap + (long)t * d + (b1 & 7) * 8
+                                                      : X + (long)t * d + b1 * 8);
       }
 #pragma unroll
       for (int u = 0; u < NG; ++u) {
@@ -599,8 +620,11 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     }
     double* dst = wv == 0 ? A : P + (wv - 1) * j1 * ld;
 #pragma unroll
-    for (int i = 0; i < 4; ++i)
-      dst[((l >> 4) + 4 * i) * ld + (l & 15)] = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
+    for (int i = 0; i < 4; ++i) {
+      const int row = (l >> 4) + 4 * i, col = l & 15;
+      const double sum = (acc[0][i] + acc[1][i]) + (acc[2][i] + acc[3][i]);
+      dst[row * ld + col] = (PAIR && (row >> 3) != (col >> 3)) ? 0.0 : sum;   // no products across heads
+    }
     for (int idx = threadIdx.x; idx < j1 * j1; idx += 64 * NWV)
       V[(idx >> 4) * ld + (idx & 15)] = ((idx >> 4) == (idx & 15)) ? 1.0 : 0.0;
   }
@@ -622,10 +646,12 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     // {2I, 2I+1} x columns(pair J) of the accumulated rotations; it derives the rotation of pair I
     // from that pair's three entries and takes the one of pair J from lane (J, I).
     const int I = l >> 3, J = l & 7;
-    double floor_abs = 0.0;
+    // (a pair: each head's entries are measured against its own trace)
+    double trace_lo = 0.0, trace_hi = 0.0;
 #pragma unroll
-    for (int i = 0; i < j1; ++i) floor_abs += A[i * ld + i];
-    floor_abs = fmax(floor_abs * 1e-17, 1e-300);
+    for (int i = 0; i < j1 / 2; ++i) { trace_lo += A[i * ld + i]; trace_hi += A[(i + 8) * ld + i + 8]; }
+    const double floor_lo = fmax((PAIR ? trace_lo : trace_lo + trace_hi) * 1e-17, 1e-300);
+    const double floor_hi = PAIR ? fmax(trace_hi * 1e-17, 1e-300) : floor_lo;
     int sweeps = 0;
     for (int sweep = 0; sweep < 16; ++sweep) {
       ++sweeps;
@@ -644,7 +670,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
         // rotation of the transposed lane (J, I)
         double cI, sI;
         bool big;
-        jacobi_rotation(app, aqq, apq, floor_abs, cI, sI, big);
+        jacobi_rotation(app, aqq, apq, (PAIR && (p >> 3)) ? floor_hi : floor_lo, cI, sI, big);
         const double cJ = __shfl(cI, 8 * J + I), sJ = __shfl(sI, 8 * J + I);
         unsettled |= big;
         // Jm has Jm[p][p] = c, Jm[p][q] = s, Jm[q][p] = -s, Jm[q][q] = c;  A' = Jm^T A Jm,  V' = V Jm
@@ -671,14 +697,16 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     if (l < j1) lam[l] = A[l * ld + l];
     __builtin_amdgcn_wave_barrier();
     if (l < j1) {
+      // (a pair: every head's eigenvalues are ranked among themselves and stay in its half)
       int rank = 0;
       const double me = lam[l];
-      for (int s = 0; s < j1; ++s) rank += (lam[s] > me) || (lam[s] == me && s < l);
-      order[rank] = l;
+      for (int s = 0; s < j1; ++s)
+        rank += (!PAIR || (s >> 3) == (l >> 3)) && ((lam[s] > me) || (lam[s] == me && s < l));
+      order[(PAIR ? (l & 8) : 0) + rank] = l;
     }
     __builtin_amdgcn_wave_barrier();
     if (l < j1) {
-      const double lmax = fmax(lam[order[0]], 0.0);
+      const double lmax = fmax(lam[order[PAIR ? (l & 8) : 0]], 0.0);
       const double lv = lam[order[l]];
       sigma[l] = (lv > 1e-12 * lmax && lv > 0.0) ? sqrt(lv) : 0.0;
     }
@@ -691,13 +719,27 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
       const double uv = V[b1 * ld + order[r]];
       const double sg = sigma[r];
       W[r * ld + b1] = sg > 0.0 ? uv / sg : 0.0;
-      const uint16_t hb = f64_to_f16_rne(uv * sg, true, &sat);
-      if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
-      else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
+      if (PAIR) {
+        // the heads' 8 x 8 small tensors are the diagonal blocks (the second head's blocks lie NB
+        // blocks further on in the cache); the entries off the diagonal are zero and go nowhere
+        if ((b1 >> 3) == (r >> 3)) {
+          const uint16_t hb = f64_to_f16_rne(uv * sg, true, &sat);
+          uint16_t* sm = small + (long)(b1 >> 3) * g.NB * g.small_per_block;
+          if (which) sm[(b1 & 7) * 8 + (r & 7)] = hb;
+          else sm[(r & 7) * 8 + (b1 & 7)] = hb;
+        }
+      } else {
+        const uint16_t hb = f64_to_f16_rne(uv * sg, true, &sat);
+        if (which) small[b1 * j1 + r] = hb;   // values: natural [b1][r]
+        else small[r * j1 + b1] = hb;         // keys: transposed [r][b1]
+      }
     }
     // this block's status word: bit 0 = T_S saturated, bits 8.. = Jacobi sweeps used
     const bool any_sat = __any(sat);
-    if (l == 0) unit_status[unit] = (any_sat ? 1 : 0) | (sweeps << 8);
+    if (l == 0) {
+      unit_status[unit] = (any_sat ? 1 : 0) | (sweeps << 8);
+      if (PAIR) unit_status[unit + unit_gap] = (any_sat ? 1 : 0) | (sweeps << 8);   // one word for both heads
+    }
   }
   __syncthreads();
 
@@ -710,6 +752,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
 #pragma unroll
     for (int s = 0; s < 4; ++s) wreg[s] = W[(l & 15) * ld + 4 * s + (l >> 4)];
     float* out = large_ws + (long)unit * g.Tb * d;
+    const long out_gap = (long)unit_gap * g.Tb * d;   // PAIR: to the second head's rows in the workspace
     for (int t0 = 0; t0 < g.Tb; t0 += 128) {
       u32x4 x[NT][4];
 #pragma unroll
@@ -718,7 +761,10 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
           x[tg][s] = u32x4{0u, 0u, 0u, 0u};
-          if (t < nv) x[tg][s] = *reinterpret_cast<const u32x4*>(X + (long)t * d + (4 * s + (l >> 4)) * 8);
+          // b1 = 4 s + l / 16 (a pair: row b1 % 8 of head b1 / 8 = s / 2)
+          if (t < nv)
+            x[tg][s] = *reinterpret_cast<const u32x4*>(PAIR ? X + (s >> 1) * head_gap + (long)t * d + ((4 * s + (l >> 4)) & 7) * 8
+                                                            : X + (long)t * d + (4 * s + (l >> 4)) * 8);
         }
       }
 #pragma unroll
@@ -736,7 +782,9 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
         }
 #pragma unroll
         for (int i = 0; i < 4; ++i) {
-          float* dst = out + (long)t * d + ((l >> 4) + 4 * i) * 8;
+          // row r = l / 16 + 4 i of the large tensor (a pair: row r % 8 of head r / 8 = i / 2)
+          float* dst = PAIR ? out + (i >> 1) * out_gap + (long)t * d + (((l >> 4) + 4 * i) & 7) * 8
+                            : out + (long)t * d + ((l >> 4) + 4 * i) * 8;
           *reinterpret_cast<float4*>(dst) = make_float4((float)acc[0][i], (float)acc[1][i], (float)acc[2][i], (float)acc[3][i]);
           *reinterpret_cast<float4*>(dst + 4) = make_float4((float)acc[4][i], (float)acc[5][i], (float)acc[6][i], (float)acc[7][i]);
         }
@@ -980,13 +1028,22 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, job, large_ws, \
                      unit_status)
   static const bool force_general = getenv("DQ_COMPRESS_GENERAL") != nullptr;   // for A/B timing
-  if (fmt->head_dim == 128 && fmt->j1 == 16 && !force_general) {
+  // heads of 64 channels with j1 = 8 go through the same kernel two at a time
+  const bool pair_heads = fmt->head_dim == 64 && fmt->j1 == 8 && (cache->kv_heads & 1) == 0;
+  if (((fmt->head_dim == 128 && fmt->j1 == 16) || pair_heads) && !force_general) {
     // At most one workgroup per compute unit (256 on the chip) gets more waves per block: the
     // eigen-solver wave is issue-bound and slows down when two of them share a SIMD.
-#define DQ_LAUNCH_D16(N_)                                                                                  \
-  hipLaunchKernelGGL((decompose16_kernel<N_>), dim3(units), dim3(64 * N_), 0, st, *fmt, *cache, job, large_ws, \
-                     unit_status)
-    int nwv = units <= 256 ? 4 : units <= 512 ? 2 : 1;
+#define DQ_LAUNCH_D16(N_)                                                                                     \
+  do {                                                                                                        \
+    if (pair_heads)                                                                                           \
+      hipLaunchKernelGGL((decompose16_kernel<N_, true>), dim3(units / 2), dim3(64 * N_), 0, st, *fmt, *cache, \
+                         job, large_ws, unit_status);                                                         \
+    else                                                                                                      \
+      hipLaunchKernelGGL((decompose16_kernel<N_, false>), dim3(units), dim3(64 * N_), 0, st, *fmt, *cache,    \
+                         job, large_ws, unit_status);                                                         \
+  } while (0)
+    const int groups16 = pair_heads ? units / 2 : units;
+    int nwv = groups16 <= 256 ? 4 : groups16 <= 512 ? 2 : 1;
     if (const char* e = getenv("DQ_COMPRESS_WAVES")) nwv = atoi(e);   // for sweeps
     if (nwv >= 4) DQ_LAUNCH_D16(4);
     else if (nwv >= 2) DQ_LAUNCH_D16(2);

@@ -138,3 +138,47 @@ def test_decode_full_size_64_channel_heads():
     head, the partners of three of the sampled ones among them, holds garbage bytes."""
     from test_gpu_parity import _full_size_case
     _full_size_case("opt_d64_4bit", [(0, 0), (15, 31), (7, 12), (7, 13), (3, 17)])
+
+
+# ------------------------------------------------------------------------------------------
+# compression of 64-channel heads: two heads per workgroup of the tuned decomposition kernel
+# ------------------------------------------------------------------------------------------
+@pytest.mark.parametrize("bits,kvh,tb,waves", [(4, 2, 128, ""), (2, 6, 256, "1"), (8, 4, 128, "2"), (4, 4, 256, "4")])
+def test_compress_pairs_properties(bits, kvh, tb, waves, monkeypatch):
+    """Exact product, orthonormal rows of the large tensor, codes and steps equal to the oracle's
+    quantizer on the GPU's large tensor, untouched neighbours: the checks every compression test
+    runs, on shapes that go through the paired kernel, full and ragged."""
+    from test_gpu_parity import _check_compress
+    if waves:
+        monkeypatch.setenv("DQ_COMPRESS_WAVES", waves)
+    else:
+        monkeypatch.delenv("DQ_COMPRESS_WAVES", raising=False)
+    w = _w64(batch=3, q_heads=kvh, kv_heads=kvh, max_seq=tb, block_tokens=tb, bits=bits, n_outlier=2)
+    _say("compress_kv, pairs of 64-channel heads: bits=%d H=%d Tb=%d waves=%r" % (bits, kvh, tb, waves))
+    _check_compress(w, tb, [tb, 37, 1])
+    _check_compress(w, tb - 5, None)
+
+
+def test_compress_pairs_heads_of_very_different_size():
+    """A head a hundred thousand times smaller than its partner is decomposed as well as alone: the
+    rows of its large tensor are orthonormal and the product gives the block back."""
+    fmt, ofmt = dq.Format(4, 64, 64, 8, 8, 128), O.Format(4, 64, 64, 8, 8, 128)
+    r = np.random.default_rng(77)
+    k = r.standard_normal((1, 2, 128, 64)).astype(np.float32)
+    k[0, 1] *= 1e-5 * 3                                        # fp16 values around 3e-5: subnormal steps and all
+    k[0, 0, :, 5] *= 20
+    k = k.astype(np.float16)
+    cache = dq.alloc_cache(fmt, 1, 2, 1, DEV)
+    ws = dq.compress_workspace(fmt, 1, 2, DEV)
+    kd = torch.from_numpy(k).to(DEV)
+    dq.compress_kv(cache, kd, kd, torch.zeros(1, dtype=torch.int32, device=DEV), None, ws)
+    torch.cuda.synchronize()
+    large = ws[256:256 + 4 * 4 * 128 * 64].view(torch.float32).cpu().numpy().reshape(4, 128, 64)
+    small = cache.t["k_small"].cpu().numpy()
+    for h in range(2):
+        t_l = O.token_major_to_large(large[2 * h].astype(np.float64), 8, 8)        # [8, 128 * 8]
+        gram = t_l @ t_l.T
+        assert np.abs(gram - np.eye(8)).max() <= 1e-5, (h, np.abs(gram - np.eye(8)).max())
+        m = O.matricise(k[0, h].astype(np.float64), 1, 8)
+        t_s = small[0, h, 0].astype(np.float64).T                                   # keys are stored transposed
+        assert np.linalg.norm(t_s @ t_l - m) <= 2e-3 * np.linalg.norm(m), h         # fp16 small tensor, fp32 large
