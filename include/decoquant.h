@@ -166,7 +166,7 @@ int32_t dq_attn_decode_timed(const dq_format* fmt, const dq_cache* cache, const 
  * are buffered and DecoQuant runs only once a block's worth has accumulated).  They follow the
  * compressed tokens of their sequence.
  *   k_tail, v_tail  f16 [B, kv_heads, capacity, d]
- *   tail_lens       i32 [B] device, 0 <= tail_lens[b] <= capacity; capacity <= 256 (host integer)
+ *   tail_lens       i32 [B] device, 0 <= tail_lens[b] <= capacity; capacity <= 1024 (host integer)
  */
 typedef struct dq_tail {
   const uint16_t* k_tail;

@@ -174,7 +174,7 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   const size_t need = dq_decode_workspace_bytes(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len);
   if (need == 0) return DQ_EINVAL;
   if (workspace_bytes < need) return DQ_ENOSPACE;
-  if (tail && (!tail->k_tail || !tail->v_tail || !tail->tail_lens || tail->capacity < 1 || tail->capacity > 256))
+  if (tail && (!tail->k_tail || !tail->v_tail || !tail->tail_lens || tail->capacity < 1 || tail->capacity > kMaxTailRows))
     return DQ_EINVAL;
   const bool can_mfma = mfma_supported(fmt, q_heads, cache->kv_heads);
   if ((flags & DQ_DECODE_FORCE_MFMA) && !can_mfma) return DQ_EINVAL;

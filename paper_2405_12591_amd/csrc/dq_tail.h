@@ -1,6 +1,6 @@
 // The fp16 tail of a sequence (tokens appended since the last compressed block, Section 3.2 of
 // arXiv 2405.12591) as one more partial result of the decode step: plain fp32 attention of the
-// query heads of one kv head over at most 256 rows, computed by one workgroup.
+// query heads of one kv head over at most kMaxTailRows rows, computed by one workgroup.
 //
 // A row of D halves is read by D/8 lanes, 16 bytes each, so a wave covers 4 (D = 128) or 8 (D = 64)
 // whole rows per load; the query heads of the group share every row that is read.  The work comes in
@@ -40,7 +40,7 @@ struct TailBlock {
   static constexpr int BATCH = 8;        // row loads a lane keeps in flight
   static constexpr int ROWS_PER_BATCH = BATCH * RPI * NWV;
   // floats of LDS scratch finish() needs, and of the result it leaves
-  static constexpr int kScratchFloats = HB * 256 + NWV * HB * D + 2 * HB * NWV;
+  static constexpr int kScratchFloats = HB * kMaxTailRows + NWV * HB * D + 2 * HB * NWV;
   static constexpr int kResultFloats = HB * (D + 2);
 
   tail_u4 kreg[BATCH], vreg[BATCH], qraw[HB];
@@ -104,15 +104,15 @@ struct TailBlock {
         v += tail_dpp<0x4E>(v);                    // lane ^ 2
         v += tail_dpp<0x141>(v);                   // 7 - lane within 8
         if (LPR == 16) v += tail_dpp<0x140>(v);    // 15 - lane within 16
-        if (chunk == 0 && row < n_tail) sc[hd * 256 + row] = v;
+        if (chunk == 0 && row < n_tail) sc[hd * kMaxTailRows + row] = v;
       }
     }
   }
 
   // tail_len: the caller's read of tail_lens[b] (requested early, so that it has arrived by now)
   __device__ __forceinline__ void finish(int tail_len, int nh, float* scratch, float* result) {
-    float* sc = scratch;                       // [HB][256] scores, then weights
-    float* red = scratch + HB * 256;           // [NWV][HB][D]
+    float* sc = scratch;                       // [HB][kMaxTailRows] scores, then weights
+    float* red = scratch + HB * kMaxTailRows;  // [NWV][HB][D]
     float* stat = red + NWV * HB * D;          // [2][HB][NWV]
     const int tid = threadIdx.x;
     const int n_tail = min(max(tail_len, 0), cap);
@@ -143,7 +143,7 @@ struct TailBlock {
 #pragma unroll
     for (int hd = 0; hd < HB; ++hd) {
       float v = -INFINITY;
-      for (int t = tid; t < n_tail; t += 64 * NWV) v = fmaxf(v, sc[hd * 256 + t]);
+      for (int t = tid; t < n_tail; t += 64 * NWV) v = fmaxf(v, sc[hd * kMaxTailRows + t]);
       for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
       if (lane == 0) stat[hd * NWV + wave] = v;
     }
@@ -156,8 +156,8 @@ struct TailBlock {
       m[hd] = mm;
       float v = 0.f;
       for (int t = tid; t < n_tail; t += 64 * NWV) {
-        const float p = __builtin_amdgcn_exp2f(sc[hd * 256 + t] - mm);
-        sc[hd * 256 + t] = p;
+        const float p = __builtin_amdgcn_exp2f(sc[hd * kMaxTailRows + t] - mm);
+        sc[hd * kMaxTailRows + t] = p;
         v += p;
       }
       for (int o = 32; o > 0; o >>= 1) v += __shfl_xor(v, o);
@@ -186,7 +186,7 @@ struct TailBlock {
         const tail_h8 vv = __builtin_bit_cast(tail_h8, rows[it]);
         float w[HB];
 #pragma unroll
-        for (int hd = 0; hd < HB; ++hd) w[hd] = (row < n_tail) ? sc[hd * 256 + row] : 0.f;
+        for (int hd = 0; hd < HB; ++hd) w[hd] = (row < n_tail) ? sc[hd * kMaxTailRows + row] : 0.f;
 #pragma unroll
         for (int i = 0; i < 8; ++i) {
           const float vf = (float)vv[i];

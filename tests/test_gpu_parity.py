@@ -517,13 +517,20 @@ def test_serving_step_under_graph_capture_replays_identically(i3, q_heads):
     ("gqa_long", dict(batch=2, q_heads=8, kv_heads=2, max_seq=8192, min_seq=8192), [8192, 4096], [100, 1], 0),
     ("llama7b_2bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=640, min_seq=640), [640, 256], [64, 127], 0),
     ("tiny", dict(), [256], [200], 0),
+    # blocks of 512 and 1024 tokens: tails of up to that many rows (one workgroup per pair, and splits)
+    ("llama7b_4bit", dict(batch=3, q_heads=4, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=512), [1024, 512, 0], [511, 300, 512], 0),
+    ("llama7b_4bit", dict(batch=3, q_heads=4, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=512), [1024, 512, 0], [511, 300, 512], 1),
+    ("gqa_long", dict(batch=2, q_heads=8, kv_heads=2, max_seq=8192, min_seq=8192, block_tokens=1024), [8192, 1024], [1023, 700], 0),
+    ("llama7b_2bit", dict(batch=2, q_heads=2, kv_heads=2, max_seq=2048, min_seq=2048, block_tokens=1024), [2048, 1024], [1024, 1], 0),
+    ("llama7b_4bit", dict(batch=2, q_heads=4, kv_heads=4, max_seq=1024, min_seq=1024, block_tokens=512,
+                          head_dim=64, j1=8, j2=8, group=64), [1024, 512], [400, 512], 0),
 ])
 def test_decode_with_fp16_tail(name, kw, lens, tail_lens, flags):
     w = _small(name, **kw)
     fmt, ofmt = formats(w)
     lens = np.asarray(lens, np.int32)
     tl = np.asarray(tail_lens, np.int32)
-    cap = int(min(w.block_tokens, 256))
+    cap = int(w.block_tokens)
     _say("decode with tail %s lens=%s tail=%s flags=%d" % (name, list(lens), list(tl), flags))
     pairs = [(b, h) for b in range(w.batch) for h in range(w.kv_heads)]
     cache = oracle_cache_for_pairs(w, ofmt, pairs, lens)

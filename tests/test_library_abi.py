@@ -87,6 +87,13 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, big, 0, None)
     assert st == -1
     fake.batch = 2
+    # an fp16 tail of more rows than a call takes
+    tail_t = dq.Cache.__init__.__globals__["_CTail"]
+    for cap, want in ((1024, -2), (1025, -1), (0, -1)):      # a fitting one gets as far as the workspace check
+        tail = tail_t(0x1000, 0x1000, 0x1000, cap)
+        st = dq.lib.dq_attn_decode_tail(C.byref(good), cache_p, ptr, 4, ptr, 1024, C.byref(tail), 0.0, ptr, None,
+                                        ptr, need - 1 if want == -2 else need, 0, None)
+        assert st == want, (cap, st)
     # both force flags
     st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need, 3, None)
     assert st == -1
