@@ -608,13 +608,15 @@ def test_kv_cache_layer_policy_prefill_then_decode_steps(i3, d):
     assert layer.n_blocks == [3, 1] and layer.n_tail == [6, 92]
 
 
-@pytest.mark.parametrize("i3,bits,tb", [(1, 4, 128), (8, 4, 128), (1, 2, 256), (8, 8, 128)])
-def test_compress_kv_blocks_writes_what_block_by_block_calls_write(i3, bits, tb):
+@pytest.mark.parametrize("i3,bits,tb,d", [(1, 4, 128, 128), (8, 4, 128, 128), (1, 2, 256, 128), (8, 8, 128, 128),
+                                          (1, 4, 128, 64), (8, 2, 256, 64)])
+def test_compress_kv_blocks_writes_what_block_by_block_calls_write(i3, bits, tb, d):
     """A prompt's worth of rows in one call (dq_compress_kv_blocks): every block must come out with
     the very bits that compressing it alone gives, ragged lengths and all; blocks past a sequence's
     rows or past the cache's capacity stay untouched."""
-    group = 64 if bits == 2 else 128
+    group = 64 if (bits == 2 or d == 64) else 128
     w = _small("llama7b_4bit", batch=3, q_heads=2, kv_heads=2, bits=bits, group=group, block_tokens=tb,
+               head_dim=d, j1=d // 8, j2=8,
                max_seq=4 * tb, min_seq=4 * tb, i3=i3)
     fmt, ofmt = formats(w)
     t_new = 3 * tb + 37                                   # three whole blocks and a short one
