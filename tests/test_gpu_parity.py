@@ -384,6 +384,11 @@ def test_decode_full_size_llama7b_2bit():
     _full_size_case("llama7b_2bit", [(0, 0), (15, 31)])
 
 
+def test_decode_full_size_gqa8_long():
+    """Eight query heads per kv head at the bench shape: two head groups per (sequence, kv head)."""
+    _full_size_case("gqa8_long", [(0, 0), (15, 7)])
+
+
 # ------------------------------------------------------------------------------------------
 # widening: 8-bit codes, identity small tensor (plain group round-to-nearest), graph replay
 # ------------------------------------------------------------------------------------------
