@@ -137,3 +137,16 @@ def test_library_depends_on_the_hip_runtime_only(dq):
     assert any("amdhip64" in n for n in needed), needed
     for n in needed:
         assert not any(bad in n.lower() for bad in ("torch", "python", "c10", "caffe", "rccl", "nccl")), needed
+
+
+def test_public_header_is_plain_c():
+    """include/decoquant.h must be usable from C: no C++ in the declarations."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    header = os.path.join(os.path.dirname(os.path.dirname(os.path.abspath(__file__))), "include", "decoquant.h")
+    proc = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c", header],
+                          capture_output=True, text=True)
+    assert proc.returncode == 0, proc.stderr
