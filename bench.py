@@ -154,12 +154,13 @@ def build_cache(dq, torch, w, dev):
     spare = dq.alloc_cache(fmt, w.batch, w.kv_heads, 1, dev)
     k_blk, v_blk = kd[:, :, :tb].contiguous(), vd[:, :, :tb].contiguous()
     zero_idx = torch.zeros(w.batch, dtype=torch.int32, device=dev)
+    # (as a serving loop calls it: the fp32 large tensors are not read back)
     for _ in range(3):
-        dq.compress_kv(spare, k_blk, v_blk, zero_idx, None, cws)
+        dq.compress_kv(spare, k_blk, v_blk, zero_idx, None, cws, keep_large=False)
     e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
     e0.record()
     for _ in range(10):
-        dq.compress_kv(spare, k_blk, v_blk, zero_idx, None, cws)
+        dq.compress_kv(spare, k_blk, v_blk, zero_idx, None, cws, keep_large=False)
     e1.record()
     torch.cuda.synchronize()
     compress_ms = e0.elapsed_time(e1) / 10

@@ -238,6 +238,27 @@ int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint1
                               const int32_t* n_valid, void* workspace, size_t workspace_bytes,
                               void* hip_stream);
 
+/* Flags of dq_compress_kv_ex. */
+#define DQ_COMPRESS_KEEP_LARGE 0u /* the fp32 large tensors are left in the workspace (as dq_compress_kv) */
+#define DQ_COMPRESS_NO_LARGE 1u   /* the caller will not read them: the library may skip that hand-off */
+
+/*
+ * dq_compress_kv_blocks with flags (t_new <= T_b makes it dq_compress_kv): for callers that do not
+ * read the fp32 large tensors back, such as a serving loop that compresses a block whenever a
+ * tail fills (Section 3.2).  With DQ_COMPRESS_NO_LARGE the large-tensor region of the workspace
+ * holds nothing defined after the call; where the library supports it (head_dim 128, j1 16, two
+ * local tensors, group 128 or 64, at most 1024 blocks per call, keys and values counted apart) the
+ * large tensor is quantized inside the decomposition kernel and never goes through memory.  Cache
+ * contents and status words are the same bits either way.  The workspace is sized as before; its
+ * first 256 bytes must be zero before the first call with this flag (dq_workspace_init on the
+ * workspace, or on its first 256 bytes, does that) and are left so: they hold a counter of finished
+ * blocks besides the status words.
+ */
+int32_t dq_compress_kv_ex(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                          const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                          const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                          uint32_t flags, void* hip_stream);
+
 /*
  * Quantize and pack a caller-supplied large tensor (Preliminary, Eq. 1 per group; Section 3.1
  * step 2).  step = fp16(max|x| / qmax), the exact quotient rounded once, ties to even;

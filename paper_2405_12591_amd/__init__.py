@@ -9,6 +9,7 @@ from .binding import (  # noqa: F401
     Cache,
     KVCacheLayer,
     ABI_VERSION,
+    COMPRESS_NO_LARGE,
     DECODE_AUTO,
     DECODE_FORCE_GENERIC,
     DECODE_FORCE_MFMA,

@@ -12,6 +12,7 @@ from . import build as _build
 
 DECODE_AUTO = 0
 ABI_VERSION = 3   # dq_version() of the library whose struct layouts this file mirrors
+COMPRESS_NO_LARGE = 1
 DECODE_FORCE_GENERIC = 1
 DECODE_FORCE_MFMA = 2
 
@@ -19,6 +20,7 @@ EXPORTED_SYMBOLS = [
     "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
     "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed", "dq_attn_decode_tail",
     "dq_compress_workspace_bytes", "dq_compress_kv", "dq_compress_blocks_workspace_bytes", "dq_compress_kv_blocks",
+    "dq_compress_kv_ex",
     "dq_quantize_pack", "dq_stream_read",
 ]
 
@@ -82,6 +84,8 @@ def _load() -> C.CDLL:
     l.dq_compress_blocks_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32, C.c_int32]
     l.dq_compress_kv_blocks.restype = C.c_int32
     l.dq_compress_kv_blocks.argtypes = l.dq_compress_kv.argtypes
+    l.dq_compress_kv_ex.restype = C.c_int32
+    l.dq_compress_kv_ex.argtypes = l.dq_compress_kv.argtypes[:-1] + [C.c_uint32, C.c_void_p]
     l.dq_quantize_pack.restype = C.c_int32
     l.dq_quantize_pack.argtypes = [C.POINTER(_CFormat), C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
@@ -225,7 +229,9 @@ def compress_workspace(fmt: Format, batch: int, kv_heads: int, device="cuda:0",
         n = lib.dq_compress_blocks_workspace_bytes(C.byref(cf), batch, kv_heads, t_new)
     if n == 0:
         raise DQError("the compression workspace query rejected the arguments")
-    return torch.empty((n + 15) // 16 * 16, dtype=torch.uint8, device=device)
+    ws = torch.empty((n + 15) // 16 * 16, dtype=torch.uint8, device=device)
+    ws[:256].zero_()   # status words and the counter the no-hand-off path of compress_kv keeps there
+    return ws
 
 
 def workspace_init(ws: torch.Tensor) -> None:
@@ -269,17 +275,24 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
 
 
 def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
-                n_valid: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
-    """Compress k_new, v_new [B, H, t_new, d] into block slot blk_idx[b] (dq_compress_kv)."""
+                n_valid: Optional[torch.Tensor], workspace: torch.Tensor, keep_large: bool = True) -> None:
+    """Compress k_new, v_new [B, H, t_new, d] into block slot blk_idx[b] (dq_compress_kv).
+    keep_large=False: the fp32 large tensors need not be left in the workspace
+    (dq_compress_kv_ex with DQ_COMPRESS_NO_LARGE)."""
     for t in (k_new, v_new):
         if t.dtype != torch.float16 or not t.is_contiguous():
             raise DQError("k_new/v_new must be contiguous fp16")
-    cf = fmt_c = cache.fmt.c()
+    fmt_c = cache.fmt.c()
     t_new = k_new.shape[2]
-    st = lib.dq_compress_kv(C.byref(fmt_c), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(), t_new,
-                            blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
-                            workspace.data_ptr(), workspace.numel(), _stream_ptr(k_new.device))
-    _check(st, "dq_compress_kv")
+    if t_new > cache.fmt.block_tokens:
+        raise DQError("compress_kv takes at most one block of rows; compress_kv_blocks takes more")
+    args = (C.byref(fmt_c), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(), t_new,
+            blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
+            workspace.data_ptr(), workspace.numel())
+    if keep_large:
+        _check(lib.dq_compress_kv(*args, _stream_ptr(k_new.device)), "dq_compress_kv")
+    else:
+        _check(lib.dq_compress_kv_ex(*args, COMPRESS_NO_LARGE, _stream_ptr(k_new.device)), "dq_compress_kv_ex")
 
 
 def compress_kv_blocks(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
@@ -399,7 +412,7 @@ class KVCacheLayer:
                 raise DQError("sequence %d exceeds the cache capacity" % b)
             idx[b] = self.n_blocks[b]
         blk_idx = torch.tensor(idx, dtype=torch.int32, device=self.device)
-        compress_kv(self.cache, self.k_tail, self.v_tail, blk_idx, None, self.ws_compress)
+        compress_kv(self.cache, self.k_tail, self.v_tail, blk_idx, None, self.ws_compress, keep_large=False)
         for b in seqs:
             self.n_blocks[b] += 1
             self.n_tail[b] = 0

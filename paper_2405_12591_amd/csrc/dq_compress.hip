@@ -84,6 +84,83 @@ __device__ __forceinline__ int settle_code(float x, float c0, float step, double
   return c;
 }
 
+// The stored fields (code + bias, one byte each) of four elements that share a step; the same
+// arithmetic as in quantize_tile: the reciprocal estimate decides unless the quotient sits within
+// 2^-12 of a half-integer, then the exact residual does.
+template <int BITS, bool FULL>
+__device__ __forceinline__ uint32_t fields_of_four(float x0, float x1, float x2, float x3, float step, float inv) {
+  constexpr int QMAX = (1 << (BITS - 1)) - 1;
+  constexpr int QMIN = FULL ? -QMAX - 1 : -QMAX;
+  constexpr int BIAS = 1 << (BITS - 1);
+  const float xs[4] = {x0, x1, x2, x3};
+  uint32_t fields = 0;
+  bool near = false;
+#pragma unroll
+  for (int e = 0; e < 4; ++e) {
+    const float q = xs[e] * inv;
+    const float cf = __builtin_rintf(q);
+    near |= fabsf(q - cf) > kNearTie;
+    fields |= (uint32_t)(min(max((int)cf, QMIN), QMAX) + BIAS) << (8 * e);
+  }
+  if (near) {   // rare
+    const double hs = 0.5 * (double)step;
+    fields = 0;
+#pragma unroll
+    for (int e = 0; e < 4; ++e) {
+      const int c = settle_code(xs[e], __builtin_rintf(xs[e] * inv), step, hs);
+      fields |= (uint32_t)(min(max(c, QMIN), QMAX) + BIAS) << (8 * e);
+    }
+  }
+  return fields;
+}
+
+// Second half of the quantizer: the tile's stored fields, one byte per element in lds_u[128][D],
+// leave as packed codes in key layout (rows of D elements) or value layout ([b2][r][128 tokens]).
+// All NT threads of the workgroup call it, after a barrier that follows the last field's store;
+// it ends with a barrier (lds_u may be reused).  The value layout needs D * (128 * BITS / 32 + 1)
+// words of staging behind the fields.
+template <int BITS, int D, int NT>
+__device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1, int j2, int value_layout,
+                                            uint8_t* __restrict__ codes_out) {
+  constexpr int d = D;
+  const int tid = threadIdx.x;
+  constexpr int PER_WORD = 32 / BITS;
+  const int total_words = kTileTokens * d / PER_WORD;
+  uint32_t* out32 = reinterpret_cast<uint32_t*>(codes_out);
+  if (!value_layout) {
+    // key layout: rows of d elements, element index contiguous
+    for (int w = tid; w < total_words; w += NT) {
+      const uint32_t* f = reinterpret_cast<const uint32_t*>(lds_u + w * PER_WORD);
+      uint32_t word = 0;
+#pragma unroll
+      for (int k4 = 0; k4 < PER_WORD / 4; ++k4) {
+        const uint32_t x = f[k4];
+#pragma unroll
+        for (int k = 0; k < 4; ++k) word |= ((x >> (8 * k)) & 0xFFu) << ((4 * k4 + k) * BITS);
+      }
+      out32[w] = word;
+    }
+  } else {
+    // value layout: [b2][r][128 tokens], tokens contiguous.  Consecutive lanes take consecutive
+    // columns (conflict-free byte reads), the words are transposed through a padded LDS buffer and
+    // leave in output order.
+    constexpr int WPR = kTileTokens / PER_WORD;   // words per (b2, r) row
+    uint32_t* stage = reinterpret_cast<uint32_t*>(lds_u + kTileTokens * d);
+    for (int idx = tid; idx < total_words; idx += NT) {
+      const int col = idx % d, wi = idx / d;
+      const int b2 = col % j2, r = col / j2;
+      uint32_t word = 0;
+#pragma unroll
+      for (int k = 0; k < PER_WORD; ++k)
+        word |= (uint32_t)lds_u[(wi * PER_WORD + k) * d + col] << (k * BITS);
+      stage[(b2 * j1 + r) * (WPR + 1) + wi] = word;
+    }
+    __syncthreads();
+    for (int w = tid; w < total_words; w += NT) out32[w] = stage[(w / WPR) * (WPR + 1) + w % WPR];
+  }
+  __syncthreads();
+}
+
 // FULL: the non-default level set (format.levels == 1): codes in [-QMAX - 1, QMAX], and the step is
 // the larger of max(x) / QMAX and max(-x) / (QMAX + 1), each rounded once to fp16 (rounding is
 // monotonic, so that is the rounded larger quotient; the second divisor is a power of two).
@@ -194,42 +271,7 @@ __device__ __forceinline__ void quantize_tile(const float* __restrict__ src,  //
     }
   }
   __syncthreads();
-
-  constexpr int PER_WORD = 32 / BITS;
-  const int total_words = kTileTokens * d / PER_WORD;
-  uint32_t* out32 = reinterpret_cast<uint32_t*>(codes_out);
-  if (!value_layout) {
-    // key layout: rows of d elements, element index contiguous
-    for (int w = tid; w < total_words; w += 256) {
-      const uint32_t* f = reinterpret_cast<const uint32_t*>(lds_u + w * PER_WORD);
-      uint32_t word = 0;
-#pragma unroll
-      for (int k4 = 0; k4 < PER_WORD / 4; ++k4) {
-        const uint32_t x = f[k4];
-#pragma unroll
-        for (int k = 0; k < 4; ++k) word |= ((x >> (8 * k)) & 0xFFu) << ((4 * k4 + k) * BITS);
-      }
-      out32[w] = word;
-    }
-  } else {
-    // value layout: [b2][r][128 tokens], tokens contiguous.  Consecutive lanes take consecutive
-    // columns (conflict-free byte reads), the words are transposed through a padded LDS buffer and
-    // leave in output order.
-    constexpr int WPR = kTileTokens / PER_WORD;   // words per (b2, r) row
-    uint32_t* stage = reinterpret_cast<uint32_t*>(lds_u + kTileTokens * d);
-    for (int idx = tid; idx < total_words; idx += 256) {
-      const int col = idx % d, wi = idx / d;
-      const int b2 = col % j2, r = col / j2;
-      uint32_t word = 0;
-#pragma unroll
-      for (int k = 0; k < PER_WORD; ++k)
-        word |= (uint32_t)lds_u[(wi * PER_WORD + k) * d + col] << (k * BITS);
-      stage[(b2 * j1 + r) * (WPR + 1) + wi] = word;
-    }
-    __syncthreads();
-    for (int w = tid; w < total_words; w += 256) out32[w] = stage[(w / WPR) * (WPR + 1) + w % WPR];
-  }
-  __syncthreads();
+  pack_fields<BITS, D, 256>(lds_u, j1, j2, value_layout, codes_out);
 }
 
 // LDS bytes quantize_tile needs: one byte per element plus the padded transpose buffer.
@@ -250,6 +292,25 @@ __global__ __launch_bounds__(256) void quantize_pack_kernel(const float* __restr
                          codes + tile * tile_code_bytes, scales + tile * kTileTokens * (D / G), lds_u);
 }
 
+// The per-block status words of the decomposition become the call's two status words (flags OR-ed,
+// sweeps at their maximum).  One workgroup of 256 threads.
+__device__ __forceinline__ void fold_status(const int32_t* __restrict__ unit_status, int n_units,
+                                            int32_t* __restrict__ status) {
+  __shared__ int red[2];
+  if (threadIdx.x < 2) red[threadIdx.x] = 0;
+  __syncthreads();
+  int flags = 0, sweeps = 0;
+  for (int u = threadIdx.x; u < n_units; u += 256) {
+    const int w = unit_status[u];
+    flags |= w & 0xFF;
+    sweeps = max(sweeps, w >> 8);
+  }
+  atomicOr(&red[0], flags);
+  atomicMax(&red[1], sweeps);
+  __syncthreads();
+  if (threadIdx.x < 2) status[threadIdx.x] = red[threadIdx.x];
+}
+
 // Compress path: tile `blockIdx.x % tiles_per_block` of work unit `blockIdx.x / tiles_per_block`.
 template <int BITS, int D, bool FULL>
 __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __restrict__ large_ws,
@@ -259,22 +320,7 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __rest
                                                              int n_units, int32_t* __restrict__ status) {
   extern __shared__ uint8_t lds_u[];
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
-  if (blockIdx.x == 0) {
-    // fold the per-block status words of the decomposition into the call's two status words
-    __shared__ int red[2];
-    if (threadIdx.x < 2) red[threadIdx.x] = 0;
-    __syncthreads();
-    int flags = 0, sweeps = 0;
-    for (int u = threadIdx.x; u < n_units; u += 256) {
-      const int w = unit_status[u];
-      flags |= w & 0xFF;
-      sweeps = max(sweeps, w >> 8);
-    }
-    atomicOr(&red[0], flags);
-    atomicMax(&red[1], sweeps);
-    __syncthreads();
-    if (threadIdx.x < 2) status[threadIdx.x] = red[threadIdx.x];
-  }
+  if (blockIdx.x == 0) fold_status(unit_status, n_units, status);
   const int tile = blockIdx.x % g.tiles_per_block;
   const int unit = blockIdx.x / g.tiles_per_block;
   const UnitRef ur = unit_ref(g, job, unit);
@@ -552,10 +598,43 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
 // zero, after which every rotation between the two halves is the identity and the iteration solves
 // the two 8 x 8 problems side by side (the rotations, their order and the stopping rule are those of
 // the 16 x 16 case).  Ordering, small tensors, projection and outputs are per head.
-template <int NWV, bool PAIR>
+// QB, FULL: QB != 0 quantizes the large tensor here, straight from the projection's registers, to
+// QB-bit codes (FULL: all 2^QB of them) and writes codes and steps into the cache; the fp32 rows do
+// not go to the workspace then and no quantizer launch follows (d = 128, one or two step groups per
+// row).  QB == 0 leaves the fp32 rows in the workspace for quantize_tiles_kernel.
+// Then the kernel also ends the call: the last workgroup to finish (a ticket counter in the third
+// word of the workspace header, zero between calls) folds the blocks' status words into the call's
+// two; status words travel as device-scope stores and loads, as the counter does, so no cache
+// write-back or invalidation is needed between the XCDs.
+template <int NWV, bool PAIR, int QB = 0, bool FULL = false>
 __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                                float* __restrict__ large_ws,
-                                                               int32_t* __restrict__ unit_status) {
+                                                               int32_t* __restrict__ unit_status,
+                                                               int32_t* __restrict__ call_status) {
+  static_assert(QB == 0 || !PAIR, "the fused quantizer is built for heads of 128 channels");
+  __shared__ int s_last_block;
+  auto end_call = [&]() __attribute__((always_inline)) {   // QB != 0 only; every workgroup, once, at its end
+    __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
+    __syncthreads();   // every thread's stores above have been acknowledged
+    if (threadIdx.x == 0) {
+      const int ticket = __hip_atomic_fetch_add(call_status + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      s_last_block = (ticket == (int)gridDim.x - 1);
+      if (s_last_block) __hip_atomic_store(call_status + 2, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+    }
+    __syncthreads();
+    if (!s_last_block || threadIdx.x >= 64) return;
+    int flags = 0, sweeps = 0;
+    for (int u = threadIdx.x; u < (int)gridDim.x; u += 64) {
+      const int w = __hip_atomic_load(unit_status + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      flags |= w & 0xFF;
+      sweeps = max(sweeps, w >> 8);
+    }
+    for (int o = 32; o > 0; o >>= 1) {
+      flags |= __shfl_xor(flags, o);
+      sweeps = max(sweeps, __shfl_xor(sweeps, o));
+    }
+    if (threadIdx.x == 0) { call_status[0] = flags; call_status[1] = sweeps; }
+  };
   const Geometry g = make_geometry(fmt, cache.kv_heads, cache.block_capacity);
   // the work unit (of the pair's first head); the second head's unit lies `unit_gap` further on
   int unit = blockIdx.x;
@@ -570,9 +649,11 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   const long bh = ur.bh;
   if (slot < 0) {
     if (threadIdx.x == 0) {
-      unit_status[unit] = 0;
+      if (QB != 0) __hip_atomic_store(unit_status + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else unit_status[unit] = 0;
       if (PAIR) unit_status[unit + unit_gap] = 0;
     }
+    if constexpr (QB != 0) end_call();
     return;
   }
   const int l = threadIdx.x & 63, wv = threadIdx.x >> 6;
@@ -586,6 +667,9 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   __shared__ double P[(NWV > 1 ? NWV - 1 : 1) * j1 * ld];   // Gram partials of the other waves
   __shared__ double lam[j1], sigma[j1];
   __shared__ int order[j1];
+  // fused quantizer: one byte per element of a 128-token tile, then the value layout's staging
+  constexpr int kFieldBytes = QB ? kTileTokens * 128 + 128 * (kTileTokens * QB / 32 + 1) * 4 : 16;
+  __shared__ __attribute__((aligned(16))) uint8_t lds_u[kFieldBytes];
 
   // ---- Gram matrix G[p][q] = sum_{t, b2} X[t, p*8+b2] X[t, q*8+b2] ----
   // A and B operand of one MFMA are the same register: lane (b1 = l%16, k = l/16) holds
@@ -737,8 +821,10 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     // this block's status word: bit 0 = T_S saturated, bits 8.. = Jacobi sweeps used
     const bool any_sat = __any(sat);
     if (l == 0) {
-      unit_status[unit] = (any_sat ? 1 : 0) | (sweeps << 8);
-      if (PAIR) unit_status[unit + unit_gap] = (any_sat ? 1 : 0) | (sweeps << 8);   // one word for both heads
+      const int word = (any_sat ? 1 : 0) | (sweeps << 8);
+      if (QB != 0) __hip_atomic_store(unit_status + unit, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      else unit_status[unit] = word;
+      if (PAIR) unit_status[unit + unit_gap] = word;   // one word for both heads
     }
   }
   __syncthreads();
@@ -780,17 +866,84 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
           for (int b2 = 0; b2 < 8; ++b2)
             acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64(wreg[s], (double)(float)h[b2], acc[b2], 0, 0, 0);
         }
+        if constexpr (QB == 0) {
 #pragma unroll
-        for (int i = 0; i < 4; ++i) {
-          // row r = l / 16 + 4 i of the large tensor (a pair: row r % 8 of head r / 8 = i / 2)
-          float* dst = PAIR ? out + (i >> 1) * out_gap + (long)t * d + (((l >> 4) + 4 * i) & 7) * 8
-                            : out + (long)t * d + ((l >> 4) + 4 * i) * 8;
-          *reinterpret_cast<float4*>(dst) = make_float4((float)acc[0][i], (float)acc[1][i], (float)acc[2][i], (float)acc[3][i]);
-          *reinterpret_cast<float4*>(dst + 4) = make_float4((float)acc[4][i], (float)acc[5][i], (float)acc[6][i], (float)acc[7][i]);
+          for (int i = 0; i < 4; ++i) {
+            // row r = l / 16 + 4 i of the large tensor (a pair: row r % 8 of head r / 8 = i / 2)
+            float* dst = PAIR ? out + (i >> 1) * out_gap + (long)t * d + (((l >> 4) + 4 * i) & 7) * 8
+                              : out + (long)t * d + ((l >> 4) + 4 * i) * 8;
+            *reinterpret_cast<float4*>(dst) = make_float4((float)acc[0][i], (float)acc[1][i], (float)acc[2][i], (float)acc[3][i]);
+            *reinterpret_cast<float4*>(dst + 4) = make_float4((float)acc[4][i], (float)acc[5][i], (float)acc[6][i], (float)acc[7][i]);
+          }
+        } else {
+          // ---- Eq. 1 on the token's row, from the registers: the lane holds rows r = l / 16 + 4 i
+          // (i = 0..3) of token t, eight b2 each; the token's other rows sit in the lanes 16, 32 and
+          // 48 further on.  Step groups: the whole row, or rows r < 8 (i < 2) and r >= 8.
+          constexpr int QMAX = (1 << (QB - 1)) - 1;
+          float f[4][8];
+#pragma unroll
+          for (int i = 0; i < 4; ++i)
+#pragma unroll
+            for (int b2 = 0; b2 < 8; ++b2) f[i][b2] = (float)acc[b2][i];
+          float up[2] = {0.f, 0.f}, dn[2] = {0.f, 0.f};   // max |x| (FULL: max x and max -x) per group
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+#pragma unroll
+            for (int b2 = 0; b2 < 8; ++b2) {
+              if (FULL) {
+                up[i >> 1] = fmaxf(up[i >> 1], f[i][b2]);
+                dn[i >> 1] = fmaxf(dn[i >> 1], -f[i][b2]);
+              } else {
+                up[i >> 1] = fmaxf(up[i >> 1], fabsf(f[i][b2]));
+              }
+            }
+          }
+          if (g.groups == 1) {
+            up[0] = up[1] = fmaxf(up[0], up[1]);
+            dn[0] = dn[1] = fmaxf(dn[0], dn[1]);
+          }
+          uint16_t sb[2];
+          float step[2], inv[2];
+#pragma unroll
+          for (int gi = 0; gi < 2; ++gi) {
+            up[gi] = fmaxf(up[gi], __shfl_xor(up[gi], 16));
+            up[gi] = fmaxf(up[gi], __shfl_xor(up[gi], 32));
+            sb[gi] = group_step_bits<QMAX>(up[gi]);
+            if (FULL) {
+              dn[gi] = fmaxf(dn[gi], __shfl_xor(dn[gi], 16));
+              dn[gi] = fmaxf(dn[gi], __shfl_xor(dn[gi], 32));
+              const uint16_t down = f2h_rne(dn[gi] * (1.0f / (float)(QMAX + 1)));
+              sb[gi] = sb[gi] > down ? sb[gi] : down;
+            }
+            step[gi] = h2f(sb[gi]);
+            inv[gi] = step[gi] > 0.f ? __builtin_amdgcn_rcpf(step[gi]) : 0.f;
+          }
+          const int tl = 16 * (tg * NWV + wv) + (l & 15);   // the token's row in the tile
+          if ((l >> 4) == 0) {
+            uint16_t* sc = (which ? cache.v_scales : cache.k_scales) + ((long)bh * g.NB + slot) * g.scales_per_block +
+                           (long)(t0 + tl) * g.groups;
+            sc[0] = sb[0];
+            if (g.groups == 2) sc[1] = sb[1];
+          }
+#pragma unroll
+          for (int i = 0; i < 4; ++i) {
+            uint2 w;
+            w.x = fields_of_four<QB, FULL>(f[i][0], f[i][1], f[i][2], f[i][3], step[i >> 1], inv[i >> 1]);
+            w.y = fields_of_four<QB, FULL>(f[i][4], f[i][5], f[i][6], f[i][7], step[i >> 1], inv[i >> 1]);
+            *reinterpret_cast<uint2*>(lds_u + tl * 128 + ((l >> 4) + 4 * i) * 8) = w;
+          }
         }
+      }
+      if constexpr (QB != 0) {
+        // every wave has left the fields of its tokens: pack the tile and send it off
+        __syncthreads();
+        uint8_t* codes = (which ? cache.v_codes : cache.k_codes) + ((long)bh * g.NB + slot) * g.codes_per_block +
+                         (long)t0 * g.row_bytes;
+        pack_fields<QB, 128, 64 * NWV>(lds_u, 16, 8, which, codes);
       }
     }
   }
+  if constexpr (QB != 0) end_call();
 }
 
 // ------------------------------------------------------------------------------------------
@@ -1007,7 +1160,7 @@ extern "C" int32_t dq_quantize_pack(const dq_format* fmt, const float* t_large, 
 
 static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
                              const uint16_t* v_new, int32_t t_new, int n_blocks, const int32_t* blk_idx,
-                             const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                             const int32_t* n_valid, void* workspace, size_t workspace_bytes, uint32_t flags,
                              void* hip_stream) {
   if (!cache->k_codes || !cache->k_scales || !cache->k_small || !cache->v_codes || !cache->v_scales ||
       !cache->v_small)
@@ -1030,6 +1183,41 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   static const bool force_general = getenv("DQ_COMPRESS_GENERAL") != nullptr;   // for A/B timing
   // heads of 64 channels with j1 = 8 go through the same kernel two at a time
   const bool pair_heads = fmt->head_dim == 64 && fmt->j1 == 8 && (cache->kv_heads & 1) == 0;
+  // Calls of a few hundred blocks are bound by the latency of one block's chain of kernels: where the
+  // caller does not need the fp32 large tensors the decomposition kernel quantizes them itself, which
+  // saves their trip through memory and the quantizer's launch.  (Calls of thousands of blocks are
+  // bound by throughput and keep the leaner kernels.)
+  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->head_dim == 128 && fmt->j1 == 16 && fmt->i3 == 1 &&
+                     (fmt->group == 128 || fmt->group == 64) && units <= 1024 && !force_general;
+  if (fused) {
+#define DQ_LAUNCH_FUSED(N_, B_)                                                                                 \
+  do {                                                                                                          \
+    if (fmt->levels)                                                                                            \
+      hipLaunchKernelGGL((decompose16_kernel<N_, false, B_, true>), dim3(units), dim3(64 * N_), 0, st, *fmt,    \
+                         *cache, job, large_ws, unit_status, status);                                           \
+    else                                                                                                        \
+      hipLaunchKernelGGL((decompose16_kernel<N_, false, B_, false>), dim3(units), dim3(64 * N_), 0, st, *fmt,   \
+                         *cache, job, large_ws, unit_status, status);                                           \
+  } while (0)
+    int fused_waves = units <= 256 ? 4 : units <= 512 ? 2 : 1;
+    if (const char* e = getenv("DQ_COMPRESS_WAVES")) fused_waves = atoi(e) >= 4 ? 4 : atoi(e) >= 2 ? 2 : 1;   // for sweeps
+    if (fused_waves == 4) {
+      if (fmt->bits == 2) DQ_LAUNCH_FUSED(4, 2);
+      else if (fmt->bits == 4) DQ_LAUNCH_FUSED(4, 4);
+      else DQ_LAUNCH_FUSED(4, 8);
+    } else if (fused_waves == 2) {
+      if (fmt->bits == 2) DQ_LAUNCH_FUSED(2, 2);
+      else if (fmt->bits == 4) DQ_LAUNCH_FUSED(2, 4);
+      else DQ_LAUNCH_FUSED(2, 8);
+    } else {
+      if (fmt->bits == 2) DQ_LAUNCH_FUSED(1, 2);
+      else if (fmt->bits == 4) DQ_LAUNCH_FUSED(1, 4);
+      else DQ_LAUNCH_FUSED(1, 8);
+    }
+#undef DQ_LAUNCH_FUSED
+    DQ_HIP_CHECK(hipGetLastError());
+    return DQ_OK;
+  }
   if (((fmt->head_dim == 128 && fmt->j1 == 16) || pair_heads) && !force_general) {
     // At most one workgroup per compute unit (256 on the chip) gets more waves per block: the
     // eigen-solver wave is issue-bound and slows down when two of them share a SIMD.
@@ -1037,10 +1225,10 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   do {                                                                                                        \
     if (pair_heads)                                                                                           \
       hipLaunchKernelGGL((decompose16_kernel<N_, true>), dim3(units / 2), dim3(64 * N_), 0, st, *fmt, *cache, \
-                         job, large_ws, unit_status);                                                         \
+                         job, large_ws, unit_status, (int32_t*)nullptr);                                      \
     else                                                                                                      \
       hipLaunchKernelGGL((decompose16_kernel<N_, false>), dim3(units), dim3(64 * N_), 0, st, *fmt, *cache,    \
-                         job, large_ws, unit_status);                                                         \
+                         job, large_ws, unit_status, (int32_t*)nullptr);                                      \
   } while (0)
     const int groups16 = pair_heads ? units / 2 : units;
     int nwv = groups16 <= 256 ? 4 : groups16 <= 512 ? 2 : 1;
@@ -1099,7 +1287,7 @@ extern "C" int32_t dq_compress_kv(const dq_format* fmt, dq_cache* cache, const u
   if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
   if (t_new < 1 || t_new > fmt->block_tokens) return DQ_EINVAL;
   return compress_impl(fmt, cache, k_new, v_new, t_new, 1, blk_idx, n_valid, workspace, workspace_bytes,
-                       hip_stream);
+                       DQ_COMPRESS_KEEP_LARGE, hip_stream);
 }
 
 extern "C" int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
@@ -1111,5 +1299,17 @@ extern "C" int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, 
   const int n_blocks = (t_new + fmt->block_tokens - 1) / fmt->block_tokens;
   if (n_blocks > cache->block_capacity) return DQ_EINVAL;
   return compress_impl(fmt, cache, k_new, v_new, t_new, n_blocks, blk_idx, n_valid, workspace,
-                       workspace_bytes, hip_stream);
+                       workspace_bytes, DQ_COMPRESS_KEEP_LARGE, hip_stream);
+}
+
+extern "C" int32_t dq_compress_kv_ex(const dq_format* fmt, dq_cache* cache, const uint16_t* k_new,
+                                     const uint16_t* v_new, int32_t t_new, const int32_t* blk_idx,
+                                     const int32_t* n_valid, void* workspace, size_t workspace_bytes,
+                                     uint32_t flags, void* hip_stream) {
+  if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
+  if (t_new < 1 || (flags & ~DQ_COMPRESS_NO_LARGE)) return DQ_EINVAL;
+  const int n_blocks = (t_new + fmt->block_tokens - 1) / fmt->block_tokens;
+  if (n_blocks > cache->block_capacity) return DQ_EINVAL;
+  return compress_impl(fmt, cache, k_new, v_new, t_new, n_blocks, blk_idx, n_valid, workspace,
+                       workspace_bytes, flags, hip_stream);
 }
