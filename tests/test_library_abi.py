@@ -103,6 +103,11 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     assert st == -1
     st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, None)
     assert st == -2
+    # the flagged variant: unknown flag bits, then the same size checks
+    st = dq.lib.dq_compress_kv_ex(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed, 2, None)
+    assert st == -1
+    st = dq.lib.dq_compress_kv_ex(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, 1, None)
+    assert st == -2
     # several blocks per call: the workspace grows with the number of blocks; more blocks than the cache holds
     assert dq.lib.dq_compress_blocks_workspace_bytes(C.byref(good), 2, 4, 128) == cneed
     bneed = dq.lib.dq_compress_blocks_workspace_bytes(C.byref(good), 2, 4, 300)
