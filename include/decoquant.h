@@ -246,8 +246,9 @@ int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint1
  * dq_compress_kv_blocks with flags (t_new <= T_b makes it dq_compress_kv): for callers that do not
  * read the fp32 large tensors back, such as a serving loop that compresses a block whenever a
  * tail fills (Section 3.2).  With DQ_COMPRESS_NO_LARGE the large-tensor region of the workspace
- * holds nothing defined after the call; where the library supports it (head_dim 128, j1 16, two
- * local tensors, group 128 or 64, at most 1024 blocks per call, keys and values counted apart) the
+ * holds nothing defined after the call; where the library supports it (two local tensors, at most
+ * 1024 blocks per call, keys and values counted apart; head_dim 128 with j1 16 and group 128 or 64,
+ * or head_dim 64 with j1 8, group 64 and an even number of kv heads) the
  * large tensor is quantized inside the decomposition kernel and never goes through memory.  Cache
  * contents and status words are the same bits either way.  The workspace is sized as before; its
  * first 256 bytes must be zero before the first call with this flag (dq_workspace_init on the

@@ -611,7 +611,6 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
                                                                float* __restrict__ large_ws,
                                                                int32_t* __restrict__ unit_status,
                                                                int32_t* __restrict__ call_status) {
-  static_assert(QB == 0 || !PAIR, "the fused quantizer is built for heads of 128 channels");
   __shared__ int s_last_block;
   auto end_call = [&]() __attribute__((always_inline)) {   // QB != 0 only; every workgroup, once, at its end
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
@@ -624,7 +623,8 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     __syncthreads();
     if (!s_last_block || threadIdx.x >= 64) return;
     int flags = 0, sweeps = 0;
-    for (int u = threadIdx.x; u < (int)gridDim.x; u += 64) {
+    const int n_units = (PAIR ? 2 : 1) * (int)gridDim.x;
+    for (int u = threadIdx.x; u < n_units; u += 64) {
       const int w = __hip_atomic_load(unit_status + u, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       flags |= w & 0xFF;
       sweeps = max(sweeps, w >> 8);
@@ -649,9 +649,13 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   const long bh = ur.bh;
   if (slot < 0) {
     if (threadIdx.x == 0) {
-      if (QB != 0) __hip_atomic_store(unit_status + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      else unit_status[unit] = 0;
-      if (PAIR) unit_status[unit + unit_gap] = 0;
+      if (QB != 0) {
+        __hip_atomic_store(unit_status + unit, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (PAIR) __hip_atomic_store(unit_status + unit + unit_gap, 0, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        unit_status[unit] = 0;
+        if (PAIR) unit_status[unit + unit_gap] = 0;
+      }
     }
     if constexpr (QB != 0) end_call();
     return;
@@ -668,7 +672,9 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   __shared__ double lam[j1], sigma[j1];
   __shared__ int order[j1];
   // fused quantizer: one byte per element of a 128-token tile, then the value layout's staging
-  constexpr int kFieldBytes = QB ? kTileTokens * 128 + 128 * (kTileTokens * QB / 32 + 1) * 4 : 16;
+  // (a pair: one such area per head, of 64 channels each)
+  constexpr int kHeadArea = kTileTokens * d + d * (kTileTokens * (QB ? QB : 8) / 32 + 1) * 4;
+  constexpr int kFieldBytes = QB ? (PAIR ? 2 : 1) * kHeadArea : 16;
   __shared__ __attribute__((aligned(16))) uint8_t lds_u[kFieldBytes];
 
   // ---- Gram matrix G[p][q] = sum_{t, b2} X[t, p*8+b2] X[t, q*8+b2] ----
@@ -822,9 +828,14 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     const bool any_sat = __any(sat);
     if (l == 0) {
       const int word = (any_sat ? 1 : 0) | (sweeps << 8);
-      if (QB != 0) __hip_atomic_store(unit_status + unit, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
-      else unit_status[unit] = word;
-      if (PAIR) unit_status[unit + unit_gap] = word;   // one word for both heads
+      // (a pair: one word for both heads)
+      if (QB != 0) {
+        __hip_atomic_store(unit_status + unit, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+        if (PAIR) __hip_atomic_store(unit_status + unit + unit_gap, word, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
+      } else {
+        unit_status[unit] = word;
+        if (PAIR) unit_status[unit + unit_gap] = word;
+      }
     }
   }
   __syncthreads();
@@ -898,7 +909,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
               }
             }
           }
-          if (g.groups == 1) {
+          if (!PAIR && g.groups == 1) {   // (a pair: group i / 2 is head i / 2's row, its only group)
             up[0] = up[1] = fmaxf(up[0], up[1]);
             dn[0] = dn[1] = fmaxf(dn[0], dn[1]);
           }
@@ -923,14 +934,17 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
             uint16_t* sc = (which ? cache.v_scales : cache.k_scales) + ((long)bh * g.NB + slot) * g.scales_per_block +
                            (long)(t0 + tl) * g.groups;
             sc[0] = sb[0];
-            if (g.groups == 2) sc[1] = sb[1];
+            if (PAIR) sc[(long)g.NB * g.scales_per_block] = sb[1];   // the second head's block, NB blocks further on
+            else if (g.groups == 2) sc[1] = sb[1];
           }
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
             uint2 w;
             w.x = fields_of_four<QB, FULL>(f[i][0], f[i][1], f[i][2], f[i][3], step[i >> 1], inv[i >> 1]);
             w.y = fields_of_four<QB, FULL>(f[i][4], f[i][5], f[i][6], f[i][7], step[i >> 1], inv[i >> 1]);
-            *reinterpret_cast<uint2*>(lds_u + tl * 128 + ((l >> 4) + 4 * i) * 8) = w;
+            uint8_t* dst = PAIR ? lds_u + (i >> 1) * kHeadArea + tl * d + (((l >> 4) + 4 * i) & 7) * 8
+                                : lds_u + tl * d + ((l >> 4) + 4 * i) * 8;
+            *reinterpret_cast<uint2*>(dst) = w;
           }
         }
       }
@@ -939,7 +953,12 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
         __syncthreads();
         uint8_t* codes = (which ? cache.v_codes : cache.k_codes) + ((long)bh * g.NB + slot) * g.codes_per_block +
                          (long)t0 * g.row_bytes;
-        pack_fields<QB, 128, 64 * NWV>(lds_u, 16, 8, which, codes);
+        if (PAIR) {
+          pack_fields<QB, d, 64 * NWV>(lds_u, 8, 8, which, codes);
+          pack_fields<QB, d, 64 * NWV>(lds_u + kHeadArea, 8, 8, which, codes + (long)g.NB * g.codes_per_block);
+        } else {
+          pack_fields<QB, d, 64 * NWV>(lds_u, 16, 8, which, codes);
+        }
       }
     }
   }
@@ -1187,19 +1206,27 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   // caller does not need the fp32 large tensors the decomposition kernel quantizes them itself, which
   // saves their trip through memory and the quantizer's launch.  (Calls of thousands of blocks are
   // bound by throughput and keep the leaner kernels.)
-  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->head_dim == 128 && fmt->j1 == 16 && fmt->i3 == 1 &&
-                     (fmt->group == 128 || fmt->group == 64) && units <= 1024 && !force_general;
+  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->i3 == 1 && units <= 1024 && !force_general &&
+                     ((fmt->head_dim == 128 && fmt->j1 == 16 && (fmt->group == 128 || fmt->group == 64)) ||
+                      (pair_heads && fmt->group == 64));
   if (fused) {
 #define DQ_LAUNCH_FUSED(N_, B_)                                                                                 \
   do {                                                                                                          \
-    if (fmt->levels)                                                                                            \
+    if (pair_heads && fmt->levels)                                                                              \
+      hipLaunchKernelGGL((decompose16_kernel<N_, true, B_, true>), dim3(units / 2), dim3(64 * N_), 0, st, *fmt, \
+                         *cache, job, large_ws, unit_status, status);                                           \
+    else if (pair_heads)                                                                                        \
+      hipLaunchKernelGGL((decompose16_kernel<N_, true, B_, false>), dim3(units / 2), dim3(64 * N_), 0, st,      \
+                         *fmt, *cache, job, large_ws, unit_status, status);                                     \
+    else if (fmt->levels)                                                                                       \
       hipLaunchKernelGGL((decompose16_kernel<N_, false, B_, true>), dim3(units), dim3(64 * N_), 0, st, *fmt,    \
                          *cache, job, large_ws, unit_status, status);                                           \
     else                                                                                                        \
       hipLaunchKernelGGL((decompose16_kernel<N_, false, B_, false>), dim3(units), dim3(64 * N_), 0, st, *fmt,   \
                          *cache, job, large_ws, unit_status, status);                                           \
   } while (0)
-    int fused_waves = units <= 256 ? 4 : units <= 512 ? 2 : 1;
+    const int fused_groups = pair_heads ? units / 2 : units;
+    int fused_waves = fused_groups <= 256 ? 4 : fused_groups <= 512 ? 2 : 1;
     if (const char* e = getenv("DQ_COMPRESS_WAVES")) fused_waves = atoi(e) >= 4 ? 4 : atoi(e) >= 2 ? 2 : 1;   // for sweeps
     if (fused_waves == 4) {
       if (fmt->bits == 2) DQ_LAUNCH_FUSED(4, 2);

@@ -51,10 +51,16 @@ def _both_ways(w, t_new, n_valid, blk):
     (4, 64, 1, 128, 2, 6),
     (8, 64, 0, 256, 2, 2),
     (2, 128, 1, 128, 3, 3),
+    # heads of 64 channels, two per workgroup (group = 64 = a head's row)
+    (4, -64, 0, 128, 16, 32),    # 1024 blocks = 512 pairs
+    (2, -64, 1, 256, 3, 6),
+    (8, -64, 0, 128, 5, 2),
 ])
 def test_fused_quantizer_writes_the_same_cache(bits, group, levels, tb, batch, kvh):
     w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=kvh, kv_heads=kvh, bits=bits,
-                            group=group, levels=levels, block_tokens=tb, max_seq=tb, min_seq=tb)
+                            group=abs(group), levels=levels, block_tokens=tb, max_seq=tb, min_seq=tb)
+    if group < 0:
+        w = dataclasses.replace(w, head_dim=64, j1=8, j2=8, n_outlier=2)
     _say("fused quantizer: bits=%d G=%d levels=%d Tb=%d B=%d H=%d" % (bits, group, levels, tb, batch, kvh))
     _both_ways(w, tb, None, [1] * batch)
     n_valid = [[tb, 37, 1, 0, tb - 1, 5, 2, tb][b % 8] for b in range(batch)]
@@ -68,12 +74,12 @@ def test_fused_quantizer_writes_the_same_cache(bits, group, levels, tb, batch, k
 
 
 def test_calls_the_fused_kernel_does_not_cover_fall_back():
-    """More than 1024 blocks, three local tensors, heads of 64 channels, groups of 32: the flag is a
+    """More than 1024 blocks, three local tensors, 64-channel heads that do not pair up, groups of 32: the flag is a
     permission, not a demand; the call gives the same cache as without it."""
     base = workloads.get_workload("llama7b_4bit")
     for kw in (dict(batch=17, q_heads=32, kv_heads=32),                                   # 1088 blocks
                dict(batch=2, q_heads=4, kv_heads=4, i3=8),
-               dict(batch=2, q_heads=4, kv_heads=4, head_dim=64, j1=8, j2=8, group=64),
+               dict(batch=2, q_heads=3, kv_heads=3, head_dim=64, j1=8, j2=8, group=64),   # an odd head is left over
                dict(batch=2, q_heads=4, kv_heads=4, group=32)):
         w = dataclasses.replace(base, max_seq=128, min_seq=128, **kw)
         _say("fused quantizer, fall-back: %s" % kw)
