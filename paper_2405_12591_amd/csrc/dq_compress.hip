@@ -339,7 +339,6 @@ __global__ __launch_bounds__(256) void quantize_tiles_kernel(const float* __rest
 // Decomposition: Gram matrix in fp64, parallel cyclic Jacobi, projection.  One wavefront per
 // (sequence, kv head, K|V) block, so all synchronisation is inside one wave.
 // ------------------------------------------------------------------------------------------
-constexpr int kJMax = 32;
 constexpr int kGramTile = 8;  // tokens staged in LDS per Gram step
 
 // Reciprocal and reciprocal square root in fp64 from the hardware estimates plus Newton steps
