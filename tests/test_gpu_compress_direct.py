@@ -5,7 +5,6 @@ groups, level sets, block sizes, ragged and short inputs, skipped sequences, and
 the fused kernel is launched with; calls it does not cover must fall back to the ordinary kernels."""
 import dataclasses
 
-import numpy as np
 import pytest
 import torch
 
