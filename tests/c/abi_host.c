@@ -1,0 +1,36 @@
+/* A plain C caller of the library's host-side entry points (no GPU needed): version, status
+ * strings, workspace queries and the argument checks that precede any launch. */
+#include <stdio.h>
+#include <string.h>
+
+#include "decoquant.h"
+
+#define CHECK(cond)                                                   \
+  do {                                                                \
+    if (!(cond)) {                                                    \
+      fprintf(stderr, "failed at line %d: %s\n", __LINE__, #cond);    \
+      return 1;                                                       \
+    }                                                                 \
+  } while (0)
+
+int main(void) {
+  dq_format fmt = {4, 128, 128, 16, 8, 128, 1, 0};
+  dq_format bad = {3, 128, 128, 16, 8, 128, 1, 0};
+  dq_cache cache;
+  char fake[64];
+  memset(&cache, 0, sizeof cache);
+  CHECK(dq_version() == 3);
+  CHECK(strcmp(dq_status_string(DQ_OK), "ok") == 0);
+  CHECK(dq_decode_workspace_bytes(&fmt, 8, 32, 32, 4096) > 0);
+  CHECK(dq_decode_workspace_bytes(&bad, 8, 32, 32, 4096) == 0);
+  CHECK(dq_compress_workspace_bytes(&fmt, 4, 40) == 256u + 4u * 40u * 2u * 128u * 128u * 4u + 1280u);
+  CHECK(dq_decode_mfma_supported(&fmt, 32, 8) == 1);
+  /* null pointers inside the cache struct are rejected before anything is launched */
+  cache.batch = 1; cache.kv_heads = 1; cache.block_capacity = 1;
+  CHECK(dq_attn_decode(&fmt, &cache, (const uint16_t*)fake, 1, (const int32_t*)fake, 128, 0.0f,
+                       (uint16_t*)fake, NULL, fake, 1u << 20, DQ_DECODE_AUTO, NULL) == DQ_EINVAL);
+  CHECK(dq_compress_kv_ex(&fmt, &cache, (const uint16_t*)fake, (const uint16_t*)fake, 128, (const int32_t*)fake,
+                          NULL, fake, 1u << 20, DQ_COMPRESS_NO_LARGE, NULL) == DQ_EINVAL);
+  printf("abi ok\n");
+  return 0;
+}

@@ -155,3 +155,23 @@ def test_public_header_is_plain_c():
     proc = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", "-fsyntax-only", "-x", "c", header],
                           capture_output=True, text=True)
     assert proc.returncode == 0, proc.stderr
+
+
+def test_a_plain_c_program_links_and_calls_the_library(dq, tmp_path):
+    """tests/c/abi_host.c: compiled with gcc against include/decoquant.h, linked to the built library,
+    run on the host (it makes no call that reaches the GPU)."""
+    import shutil
+    import subprocess
+    gcc = shutil.which("gcc")
+    if gcc is None:
+        pytest.skip("no C compiler here")
+    from paper_2405_12591_amd import build as B
+    lib_dir = os.path.dirname(B.LIB_PATH)
+    exe = str(tmp_path / "abi_host")
+    proc = subprocess.run([gcc, "-std=c99", "-Wall", "-Wextra", "-Werror", os.path.join(ROOT, "tests", "c", "abi_host.c"),
+                           "-I", os.path.join(ROOT, "include"), "-L", lib_dir, "-ldecoquant",
+                           "-Wl,-rpath," + lib_dir, "-Wl,-rpath,/opt/rocm/lib", "-L/opt/rocm/lib", "-o", exe],
+                          capture_output=True, text=True)
+    assert proc.returncode == 0, proc.stderr
+    run = subprocess.run([exe], capture_output=True, text=True)
+    assert run.returncode == 0 and "abi ok" in run.stdout, run.stdout + run.stderr
