@@ -700,3 +700,35 @@ def test_decode_peaked_softmax_keeps_a_margin(kw, lens):
     ratio = np.abs(got32.astype(np.float64) - want) / np.maximum(2e-3, 1e-4 * np.abs(want))
     _say("peaked softmax %s: worst fp32 error / tolerance %.3f, max |out| %.1f" % (kw, ratio.max(), np.abs(want).max()))
     assert ratio.max() <= 0.5
+
+
+def test_kv_cache_layer_with_blocks_of_512_tokens():
+    """The same policy with blocks of 512 tokens: the fp16 tail grows to 511 rows before it is
+    compressed; decode attends to blocks + tail throughout."""
+    w = _small("llama7b_4bit", batch=2, q_heads=4, kv_heads=2, max_seq=1024, min_seq=1024, block_tokens=512)
+    fmt, ofmt = formats(w)
+    _say("KVCacheLayer policy, blocks of 512 tokens")
+    layer = dq.KVCacheLayer(fmt, w.batch, w.q_heads, w.kv_heads, 1024, DEV)
+    k, v = workloads.kv_tensor(w)                      # [2, 2, 1024, 128]
+    kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
+    prefill = [700, 505]
+    layer.append(kd[:, :, :700].contiguous(), vd[:, :, :700].contiguous(), counts=prefill)
+    assert layer.n_blocks == [1, 0] and layer.n_tail == [188, 505]
+    q = workloads.query(w)
+    qd = torch.from_numpy(q).to(DEV)
+    pos = list(prefill)
+    for step in range(10):                             # sequence 1 fills its first block at 512
+        rows_k = torch.stack([kd[b, :, pos[b]:pos[b] + 1] for b in range(w.batch)])
+        rows_v = torch.stack([vd[b, :, pos[b]:pos[b] + 1] for b in range(w.batch)])
+        layer.append(rows_k.contiguous(), rows_v.contiguous())
+        pos = [p + 1 for p in pos]
+        if step in (0, 5, 6, 9):
+            out = layer.decode(qd)
+            torch.cuda.synchronize()
+            arrs = {n: t.cpu().numpy() for n, t in layer.cache.t.items()}
+            lens = np.array([nb * 512 for nb in layer.n_blocks], np.int32)
+            want = O.attention_decode(arrs, ofmt, q, lens, k_tail=layer.k_tail.cpu().numpy(),
+                                      v_tail=layer.v_tail.cpu().numpy(), tail_lens=np.array(layer.n_tail, np.int32))
+            got = out.cpu().numpy().astype(np.float64)
+            assert (np.abs(got - want) <= tolerance(want)).all(), (step, np.abs(got - want).max())
+    assert layer.n_blocks == [1, 1] and layer.n_tail == [198, 3]
