@@ -61,6 +61,10 @@ constexpr int kMantBits = 3 * kLimbBits;  // weights: 21-bit integers, limb0 * 2
 // largest |q'|.  With three limbs the rounding of the small entries of q' (2^-21 of the largest one,
 // times 128 channels) was the largest error of the whole kernel on peaked softmaxes.
 constexpr int kQueryBits = 4 * kLimbBits;
+// With three local tensors the weights are signed mixtures over a run of tokens and what they
+// multiply cancels across the run: they take all four columns as well (27 bits and a sign relative
+// to the tile's largest weight, i.e. every bit an fp32 weight has).
+constexpr int kSignedWeightBits = 4 * kLimbBits;
 
 // ---- per-bit-width pieces -------------------------------------------------------------------
 // Chunk: what one lane loads of a 16-row piece of codes (32 bytes at 8 bits, 16 at 4, 8 at 2); it
@@ -333,7 +337,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   unsigned char* Qs = wl;                                        // [NC][8 row pairs][16 slots] bytes
   unsigned char* Ps = wl + QS_BYTES;                             // [NC][8 token groups][16 slots] bytes
   int* Ss = reinterpret_cast<int*>(wl + QS_BYTES + PS_BYTES);    // [NC][SS] ints
-  const bool col_live = (n < NC) && ((n & 3) != 3);   // value side: three limbs per group of four columns
+  const bool col_live = (n < NC) && (N3 || (n & 3) != 3);   // value side: three limbs per group of four columns (four with three local tensors)
   const bool col_live_k = n < NC;                      // key side: four
   // the epilogue's packed columns (see PK): column n holds head packed_head, slot packed_slot of its set
   const int packed_head = (R == 1) ? 0 : (R == 4) ? (n >> 2) : (NG == 1) ? ((n >> 2) & 1) : (n >> 3);
@@ -700,22 +704,23 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       }
     }
     if (N3) {
-      // limbs relative to the largest weight of the tile: |w * vs| < 2^20, top limb signed
+      // limbs relative to the largest weight of the tile: |w * vs| < 2^27, top limb signed
       wmax = wave_allmax_nonneg(wmax);
       int e = 0;
       if (wmax > 0.f && wmax < INFINITY) e = __builtin_amdgcn_frexp_expf(wmax);
       e = max(min(e, 100), -100);
-      vs = pow2i(kMantBits - 1 - e);
-      v_unscale = pow2i(e - (kMantBits - 1));
+      vs = pow2i(kSignedWeightBits - 1 - e);
+      v_unscale = pow2i(e - (kSignedWeightBits - 1));
 #pragma unroll
       for (int hd = 0; hd < R; ++hd) {
 #pragma unroll
         for (int gr = 0; gr < NG; ++gr) {
           const int iA = (int)__builtin_rintf(wA[hd][gr] * vs), iB = (int)__builtin_rintf(wB[hd][gr] * vs);
           unsigned char* dst = Ps + (CPH * hd + 4 * gr) * 128 + G16 * 16 + 2 * pi;
-          *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(((iA >> 14) & 255) | (((iB >> 14) & 255) << 8));
-          *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 7) & 127) | (((iB >> 7) & 127) << 8));
-          *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)((iA & 127) | ((iB & 127) << 8));
+          *reinterpret_cast<uint16_t*>(dst) = (uint16_t)(((iA >> 21) & 255) | (((iB >> 21) & 255) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 128) = (uint16_t)(((iA >> 14) & 127) | (((iB >> 14) & 127) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 256) = (uint16_t)(((iA >> 7) & 127) | (((iB >> 7) & 127) << 8));
+          *reinterpret_cast<uint16_t*>(dst + 384) = (uint16_t)((iA & 127) | ((iB & 127) << 8));
         }
       }
     }
@@ -849,7 +854,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   float* Mml = Macc + NC * D;                            // [R] m, [R] l
 #pragma unroll
   for (int hd = 0; hd < R; ++hd) l_run[hd] = wave_allsum(l_run[hd]);
-  if ((n & 3) != 3) {   // [head][limb][channel b1 * 8 + b2]
+  if (N3 || (n & 3) != 3) {   // [head][limb][channel b1 * 8 + b2]
 #pragma unroll
     for (int st = 0; st < NSET; ++st) {
 #pragma unroll
@@ -874,7 +879,8 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
       const float* col = base + 4 * hd * D + cv;
-      const float v = col[0] * 16384.f + col[D] * 128.f + col[2 * D];
+      const float v = N3 ? ((col[0] * 128.f + col[D]) * 128.f + col[2 * D]) * 128.f + col[3 * D]
+                         : col[0] * 16384.f + col[D] * 128.f + col[2 * D];
       o = fmaf(v, wgt, o);
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
