@@ -40,7 +40,7 @@ PROFILED_TRAFFIC_BYTES = {
     ("gqa_long", "mfma"): (287272 + 764) * 1.9997 * 1024,
     ("gqa8_long", "mfma"): (359155 + 256) * 1.9997 * 1024,
     ("opt_d64_4bit", "mfma"): (71851 + 64) * 1.9988 * 1024,
-    ("llama7b_4bit_n3", "mfma"): (72855 + 64) * 1.9988 * 1024,
+    ("llama7b_4bit_n3", "mfma"): (72852 + 64) * 1.9988 * 1024,
 }
 
 
