@@ -170,6 +170,7 @@ def test_compress_kv_random_cases(seed, monkeypatch):
 
 
 def _check_compress(w, t_new, n_valid):
+    assert w.batch <= 3 and w.i3 == 1          # three block slots below; two local tensors
     fmt, ofmt = formats(w)
     tb, d, j1, j2 = fmt.block_tokens, fmt.head_dim, fmt.j1, fmt.j2
     k = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[0] for h in range(w.kv_heads)]) for b in range(w.batch)])
@@ -217,8 +218,8 @@ def _check_compress(w, t_new, n_valid):
                 slack = 2.0 ** -10 * (np.abs(small.astype(np.float64)) @ np.abs(t_l)) + 1e-6 * np.abs(m).max() + 1e-7
                 assert (resid <= slack).all(), (b, h, which, resid.max())
                 # (3) codes and steps are the oracle's quantization of that very T_L
-                steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax)
-                codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax)
+                steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax, ofmt.full_range)
+                codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax, ofmt.full_range)
                 assert np.array_equal(steps.view(np.uint16), steps_o.view(np.uint16))
                 assert np.array_equal(codes, codes_o)
                 # (4) reconstruction within the half-step bound
