@@ -252,9 +252,19 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
     fmt = cache.fmt
     if q.dtype != torch.float16 or not q.is_contiguous() or seq_lens.dtype != torch.int32:
         raise DQError("q must be contiguous fp16 and seq_lens int32")
+    # the library sees pointers only: sizes are checked here, so that a tensor of the wrong shape
+    # raises instead of sending a kernel past its end
+    if q.dim() != 3 or q.shape[0] != cache.batch or q.shape[2] != fmt.head_dim:
+        raise DQError("q must be [batch, q_heads, head_dim] with the cache's batch and head_dim")
     bsz, hq, d = q.shape
+    if seq_lens.numel() != bsz or not seq_lens.is_contiguous():
+        raise DQError("seq_lens must hold one length per sequence")
     if out is None:
         out = torch.empty_like(q)
+    elif out.shape != q.shape or out.dtype != torch.float16 or not out.is_contiguous():
+        raise DQError("out must be contiguous fp16 of q's shape")
+    if out_f32 is not None and (out_f32.shape != q.shape or out_f32.dtype != torch.float32 or not out_f32.is_contiguous()):
+        raise DQError("out_f32 must be contiguous fp32 of q's shape")
     cf = fmt.c()
     args = (C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
             softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
@@ -264,6 +274,9 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
         if kt.dtype != torch.float16 or vt.dtype != torch.float16 or tl.dtype != torch.int32 \
                 or not kt.is_contiguous() or not vt.is_contiguous():
             raise DQError("tail tensors must be contiguous fp16 with int32 lengths")
+        if kt.dim() != 4 or kt.shape != vt.shape or kt.shape[0] != bsz or kt.shape[1] != cache.kv_heads \
+                or kt.shape[3] != fmt.head_dim or tl.numel() != bsz or not tl.is_contiguous():
+            raise DQError("tail tensors must be [batch, kv_heads, capacity, head_dim] with one length per sequence")
         ct = _CTail(kt.data_ptr(), vt.data_ptr(), tl.data_ptr(), kt.shape[2])
         st = lib.dq_attn_decode_tail(*args[:6], C.byref(ct), *args[6:])
     elif kernel_events is None:
@@ -274,14 +287,25 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
     return out
 
 
+def _check_compress_args(cache: Cache, k_new, v_new, blk_idx, n_valid) -> None:
+    # sizes are checked here (the library sees pointers only)
+    for t in (k_new, v_new):
+        if t.dtype != torch.float16 or not t.is_contiguous():
+            raise DQError("k_new/v_new must be contiguous fp16")
+    if k_new.dim() != 4 or k_new.shape != v_new.shape or k_new.shape[0] != cache.batch \
+            or k_new.shape[1] != cache.kv_heads or k_new.shape[3] != cache.fmt.head_dim:
+        raise DQError("k_new/v_new must be [batch, kv_heads, t_new, head_dim] of the cache's sizes")
+    for name, t in (("blk_idx", blk_idx), ("n_valid", n_valid)):
+        if t is not None and (t.dtype != torch.int32 or t.numel() != cache.batch or not t.is_contiguous()):
+            raise DQError("%s must hold one int32 per sequence" % name)
+
+
 def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
                 n_valid: Optional[torch.Tensor], workspace: torch.Tensor, keep_large: bool = True) -> None:
     """Compress k_new, v_new [B, H, t_new, d] into block slot blk_idx[b] (dq_compress_kv).
     keep_large=False: the fp32 large tensors need not be left in the workspace
     (dq_compress_kv_ex with DQ_COMPRESS_NO_LARGE)."""
-    for t in (k_new, v_new):
-        if t.dtype != torch.float16 or not t.is_contiguous():
-            raise DQError("k_new/v_new must be contiguous fp16")
+    _check_compress_args(cache, k_new, v_new, blk_idx, n_valid)
     fmt_c = cache.fmt.c()
     t_new = k_new.shape[2]
     if t_new > cache.fmt.block_tokens:
@@ -299,9 +323,7 @@ def compress_kv_blocks(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, b
                        n_valid: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
     """Compress k_new, v_new [B, H, t_new, d], any t_new >= 1, into the block slots from blk_idx[b]
     on (dq_compress_kv_blocks)."""
-    for t in (k_new, v_new):
-        if t.dtype != torch.float16 or not t.is_contiguous():
-            raise DQError("k_new/v_new must be contiguous fp16")
+    _check_compress_args(cache, k_new, v_new, blk_idx, n_valid)
     cf = cache.fmt.c()
     st = lib.dq_compress_kv_blocks(C.byref(cf), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
                                    k_new.shape[2], blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),

@@ -733,3 +733,31 @@ def test_kv_cache_layer_with_blocks_of_512_tokens():
             got = out.cpu().numpy().astype(np.float64)
             assert (np.abs(got - want) <= tolerance(want)).all(), (step, np.abs(got - want).max())
     assert layer.n_blocks == [1, 1] and layer.n_tail == [198, 3]
+
+
+def test_binding_rejects_tensors_of_the_wrong_size():
+    """The library sees pointers only; the binding checks the sizes that go with them."""
+    w = _small("llama7b_4bit", batch=3, q_heads=4, kv_heads=2, max_seq=128, min_seq=128)
+    fmt, _ = formats(w)
+    cache = dq.alloc_cache(fmt, 3, 2, 1, DEV)
+    ws = dq.compress_workspace(fmt, 3, 2, DEV)
+    k = torch.zeros((3, 2, 128, 128), dtype=torch.float16, device=DEV)
+    idx3, idx2 = torch.zeros(3, dtype=torch.int32, device=DEV), torch.zeros(2, dtype=torch.int32, device=DEV)
+    with pytest.raises(dq.DQError):
+        dq.compress_kv(cache, k, k, idx2, None, ws)                      # one block index short
+    with pytest.raises(dq.DQError):
+        dq.compress_kv(cache, k, k, idx3, idx2, ws)                      # one row count short
+    with pytest.raises(dq.DQError):
+        dq.compress_kv(cache, k[:2].contiguous(), k[:2].contiguous(), idx3, None, ws)   # a sequence short
+    with pytest.raises(dq.DQError):
+        dq.compress_kv(cache, k[:, :, :, :64].contiguous(), k[:, :, :, :64].contiguous(), idx3, None, ws)
+    dws = dq.decode_workspace(fmt, 3, 4, 2, 128, DEV)
+    q = torch.zeros((3, 4, 128), dtype=torch.float16, device=DEV)
+    with pytest.raises(dq.DQError):
+        dq.attn_decode(cache, q, idx2, 128, dws)                         # one length short
+    with pytest.raises(dq.DQError):
+        dq.attn_decode(cache, q[:2].contiguous(), idx3, 128, dws)
+    with pytest.raises(dq.DQError):
+        dq.attn_decode(cache, q, idx3, 128, dws, tail=(k[:, :, :16].contiguous(), k[:, :, :16].contiguous(), idx2))
+    dq.attn_decode(cache, q, idx3, 128, dws)                             # and the right sizes go through
+    torch.cuda.synchronize()
