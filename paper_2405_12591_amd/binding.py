@@ -147,6 +147,9 @@ class Cache:
         for name, ten in tensors.items():
             if not (ten.is_cuda and ten.is_contiguous()):
                 raise DQError("cache tensor %s must be a contiguous device tensor" % name)
+        for name, (shape, dtype) in _shapes(fmt, batch, kv_heads, block_capacity).items():
+            if name not in tensors or tuple(tensors[name].shape) != tuple(shape) or tensors[name].dtype != dtype:
+                raise DQError("cache tensor %s must be %s of shape %s" % (name, dtype, tuple(shape)))
         small3 = [tensors[n].data_ptr() if n in tensors else None for n in ("k_small3", "v_small3")]
         self.c = _CCache(*(tensors[n].data_ptr() for n in
                            ("k_codes", "k_scales", "k_small", "v_codes", "v_scales", "v_small")),
@@ -335,6 +338,8 @@ def quantize_pack(fmt: Format, t_large: torch.Tensor, value_layout: bool):
     """Quantize + pack fp32 rows [n_rows, d]; returns (codes u8, scales f16) (dq_quantize_pack)."""
     if t_large.dtype != torch.float32 or not t_large.is_contiguous():
         raise DQError("t_large must be contiguous fp32")
+    if t_large.dim() != 2 or t_large.shape[1] != fmt.head_dim or t_large.shape[0] % 128:
+        raise DQError("t_large must be [n_rows, head_dim] with n_rows a multiple of 128")
     n_rows, d = t_large.shape
     if value_layout:
         codes = torch.empty((n_rows // 128, fmt.j2, fmt.j1, 128 * fmt.bits // 8), dtype=torch.uint8,
