@@ -3,6 +3,8 @@ validation that happens before any kernel launch."""
 import ctypes as C
 import os
 import re
+import subprocess
+import sys
 
 import pytest
 
@@ -175,3 +177,29 @@ def test_a_plain_c_program_links_and_calls_the_library(dq, tmp_path):
     assert proc.returncode == 0, proc.stderr
     run = subprocess.run([exe], capture_output=True, text=True)
     assert run.returncode == 0 and "abi ok" in run.stdout, run.stdout + run.stderr
+
+
+def test_a_missing_library_is_an_error_not_a_fall_back(tmp_path):
+    """With the library path pointing at nothing the package raises as soon as it is imported: there is no other path."""
+    code = ("try:\n"
+            "    import paper_2405_12591_amd as dq\n"
+            "    dq.decode_mfma_supported(dq.Format(4, 128, 128, 16, 8, 128), 1, 1)\n"
+            "except Exception as e:\n"
+            "    print(type(e).__name__, e)\n"
+            "    raise SystemExit(7)\n")
+    env = dict(os.environ, DQ_LIBRARY_PATH=str(tmp_path / "nothing_here.so"))
+    r = subprocess.run([sys.executable, "-c", code], cwd=ROOT, env=env, capture_output=True, text=True, timeout=300)
+    assert r.returncode == 7, (r.stdout, r.stderr)
+    assert r.stdout.startswith("DQError") and "missing" in r.stdout
+
+
+def test_the_package_does_not_know_the_oracle():
+    """The product path and the oracle share no code: no source file of the package names the oracle's module."""
+    pkg = os.path.join(ROOT, "paper_2405_12591_amd")
+    for dirpath, _, files in os.walk(pkg):
+        for f in files:
+            if f.endswith((".py", ".h", ".hip", ".c", ".cpp")):
+                text = open(os.path.join(dirpath, f), encoding="utf-8").read()
+                assert "oracle" not in text.lower(), os.path.join(dirpath, f)
+    text = open(os.path.join(ROOT, "oracle", "decoquant_oracle.py"), encoding="utf-8").read()
+    assert "paper_2405_12591_amd" not in text and "ctypes" not in text
