@@ -107,6 +107,12 @@ typedef struct dq_cache {
 #define DQ_DECODE_AUTO 0u          /* fastest kernel that supports the format           */
 #define DQ_DECODE_FORCE_GENERIC 1u /* scalar reference-grade HIP kernel, any format     */
 #define DQ_DECODE_FORCE_MFMA 2u    /* matrix-core kernel; DQ_EINVAL if format unsupported */
+/* Launch-shape overrides in the same word, for sweeps and tuning; a field of 0 leaves that choice to
+ * the library, any other bit of the word is rejected with DQ_EINVAL.  They change how the work is
+ * dealt to workgroups, never what is computed (results agree to the rounding of the partial sums). */
+#define DQ_DECODE_SPLITS(n) (((uint32_t)(n) & 0x7Fu) << 8)       /* workgroups per (sequence, kv head): 1..64 */
+#define DQ_DECODE_WAVES(n) (((uint32_t)(n) & 0xFu) << 16)        /* wavefronts per workgroup: 4 or 8 (matrix-core kernel) */
+#define DQ_DECODE_UNIT_MAP(m) ((((uint32_t)(m) + 1u) & 0xFu) << 20) /* order of the units over the grid: 0..5 */
 
 int32_t dq_version(void);
 const char* dq_status_string(int32_t status);
@@ -241,6 +247,9 @@ int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint1
 /* Flags of dq_compress_kv_ex. */
 #define DQ_COMPRESS_KEEP_LARGE 0u /* the fp32 large tensors are left in the workspace (as dq_compress_kv) */
 #define DQ_COMPRESS_NO_LARGE 1u   /* the caller will not read them: the library may skip that hand-off */
+#define DQ_COMPRESS_PLAIN 2u      /* use the plain vector-code decomposition kernel whatever the shape (for comparison) */
+#define DQ_COMPRESS_WAVES(n) (((uint32_t)(n) & 0xFu) << 8) /* wavefronts per block of the tuned decomposition
+                                     kernel: 1, 2 or 4; 0 leaves the choice to the library (for sweeps) */
 
 /*
  * dq_compress_kv_blocks with flags (t_new <= T_b makes it dq_compress_kv): for callers that do not

@@ -10,6 +10,9 @@ from .binding import (  # noqa: F401
     KVCacheLayer,
     ABI_VERSION,
     COMPRESS_NO_LARGE,
+    COMPRESS_PLAIN,
+    decode_flags,
+    compress_flags,
     DECODE_AUTO,
     DECODE_FORCE_GENERIC,
     DECODE_FORCE_MFMA,

@@ -11,10 +11,22 @@ import torch
 from . import build as _build
 
 DECODE_AUTO = 0
-ABI_VERSION = 3   # dq_version() of the library whose struct layouts this file mirrors
+ABI_VERSION = 4   # dq_version() of the library whose struct layouts this file mirrors
 COMPRESS_NO_LARGE = 1
+COMPRESS_PLAIN = 2
 DECODE_FORCE_GENERIC = 1
 DECODE_FORCE_MFMA = 2
+
+
+def decode_flags(kernel: int = DECODE_AUTO, splits: int = 0, waves: int = 0, unit_map: Optional[int] = None) -> int:
+    """The flags word of dq_attn_decode: kernel choice plus the launch-shape overrides
+    DQ_DECODE_SPLITS / DQ_DECODE_WAVES / DQ_DECODE_UNIT_MAP (0 / None: the library's choice)."""
+    return kernel | ((splits & 0x7F) << 8) | ((waves & 0xF) << 16) | (0 if unit_map is None else ((unit_map + 1) & 0xF) << 20)
+
+
+def compress_flags(keep_large: bool = True, waves: int = 0, plain: bool = False) -> int:
+    """The flags word of dq_compress_kv_ex (DQ_COMPRESS_NO_LARGE, DQ_COMPRESS_PLAIN, DQ_COMPRESS_WAVES)."""
+    return (0 if keep_large else COMPRESS_NO_LARGE) | (COMPRESS_PLAIN if plain else 0) | ((waves & 0xF) << 8)
 
 EXPORTED_SYMBOLS = [
     "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
@@ -269,18 +281,13 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
     if out_f32 is not None and (out_f32.shape != q.shape or out_f32.dtype != torch.float32 or not out_f32.is_contiguous()):
         raise DQError("out_f32 must be contiguous fp32 of q's shape")
     cf = fmt.c()
+    ct = None
+    if tail is not None:
+        ct = _tail_struct(cache, tail, bsz)
     args = (C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
             softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
             workspace.data_ptr(), workspace.numel(), flags, _stream_ptr(q.device))
     if tail is not None:
-        kt, vt, tl = tail
-        if kt.dtype != torch.float16 or vt.dtype != torch.float16 or tl.dtype != torch.int32 \
-                or not kt.is_contiguous() or not vt.is_contiguous():
-            raise DQError("tail tensors must be contiguous fp16 with int32 lengths")
-        if kt.dim() != 4 or kt.shape != vt.shape or kt.shape[0] != bsz or kt.shape[1] != cache.kv_heads \
-                or kt.shape[3] != fmt.head_dim or tl.numel() != bsz or not tl.is_contiguous():
-            raise DQError("tail tensors must be [batch, kv_heads, capacity, head_dim] with one length per sequence")
-        ct = _CTail(kt.data_ptr(), vt.data_ptr(), tl.data_ptr(), kt.shape[2])
         st = lib.dq_attn_decode_tail(*args[:6], C.byref(ct), *args[6:])
     elif kernel_events is None:
         st = lib.dq_attn_decode(*args)
@@ -288,6 +295,17 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
         st = lib.dq_attn_decode_timed(*args, kernel_events[0].cuda_event, kernel_events[1].cuda_event)
     _check(st, "dq_attn_decode")
     return out
+
+
+def _tail_struct(cache: Cache, tail, bsz: int) -> _CTail:
+    kt, vt, tl = tail
+    if kt.dtype != torch.float16 or vt.dtype != torch.float16 or tl.dtype != torch.int32 \
+            or not kt.is_contiguous() or not vt.is_contiguous():
+        raise DQError("tail tensors must be contiguous fp16 with int32 lengths")
+    if kt.dim() != 4 or kt.shape != vt.shape or kt.shape[0] != bsz or kt.shape[1] != cache.kv_heads \
+            or kt.shape[3] != cache.fmt.head_dim or tl.numel() != bsz or not tl.is_contiguous():
+        raise DQError("tail tensors must be [batch, kv_heads, capacity, head_dim] with one length per sequence")
+    return _CTail(kt.data_ptr(), vt.data_ptr(), tl.data_ptr(), kt.shape[2])
 
 
 def _check_compress_args(cache: Cache, k_new, v_new, blk_idx, n_valid) -> None:
@@ -304,10 +322,11 @@ def _check_compress_args(cache: Cache, k_new, v_new, blk_idx, n_valid) -> None:
 
 
 def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
-                n_valid: Optional[torch.Tensor], workspace: torch.Tensor, keep_large: bool = True) -> None:
+                n_valid: Optional[torch.Tensor], workspace: torch.Tensor, keep_large: bool = True,
+                waves: int = 0, plain: bool = False) -> None:
     """Compress k_new, v_new [B, H, t_new, d] into block slot blk_idx[b] (dq_compress_kv).
     keep_large=False: the fp32 large tensors need not be left in the workspace
-    (dq_compress_kv_ex with DQ_COMPRESS_NO_LARGE)."""
+    (dq_compress_kv_ex with DQ_COMPRESS_NO_LARGE); waves, plain: its launch overrides."""
     _check_compress_args(cache, k_new, v_new, blk_idx, n_valid)
     fmt_c = cache.fmt.c()
     t_new = k_new.shape[2]
@@ -316,10 +335,11 @@ def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx:
     args = (C.byref(fmt_c), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(), t_new,
             blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
             workspace.data_ptr(), workspace.numel())
-    if keep_large:
+    if keep_large and not waves and not plain:
         _check(lib.dq_compress_kv(*args, _stream_ptr(k_new.device)), "dq_compress_kv")
     else:
-        _check(lib.dq_compress_kv_ex(*args, COMPRESS_NO_LARGE, _stream_ptr(k_new.device)), "dq_compress_kv_ex")
+        _check(lib.dq_compress_kv_ex(*args, compress_flags(keep_large, waves, plain), _stream_ptr(k_new.device)),
+               "dq_compress_kv_ex")
 
 
 def compress_kv_blocks(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,

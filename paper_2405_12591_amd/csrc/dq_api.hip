@@ -1,6 +1,5 @@
 // Host side of the C ABI: argument checks, workspace carve-up, kernel selection.
 #include <atomic>
-#include <cstdlib>
 
 #include "dq_decode.h"
 
@@ -42,7 +41,7 @@ static void choose_mfma_shape(int units, int max_tiles, int rep, int bits, int* 
 }
 
 int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma,
-                  int* nw_out) {
+                  uint32_t flags, int* nw_out) {
   const int max_tiles = (max_seq_len + kTileTokens - 1) / kTileTokens;
   int n = 1, nw = 4;
   if (max_tiles > 0) {
@@ -60,14 +59,9 @@ int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int 
       if (n > by_len) n = by_len;
     }
   }
-  if (const char* env = getenv("DQ_DECODE_SPLITS")) {  // tuning aids
-    const int v = atoi(env);
-    if (v > 0) n = v;
-  }
-  if (const char* env = getenv("DQ_DECODE_WAVES")) {
-    const int v = atoi(env);
-    if (v == 4 || v == 8) nw = v;
-  }
+  // the caller's overrides (validated by the entry point)
+  if (const int v = (int)((flags >> 8) & 0x7Fu)) n = v;
+  if (const int v = (int)((flags >> 16) & 0xFu)) nw = v;
   if (n < 1) n = 1;
   if (n > kMaxSplits) n = kMaxSplits;
   if (max_tiles > 0 && n > max_tiles) n = max_tiles;
@@ -116,7 +110,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 
 using namespace dq;
 
-extern "C" int32_t dq_version(void) { return 3; }
+extern "C" int32_t dq_version(void) { return 4; }
 
 extern "C" const char* dq_status_string(int32_t status) {
   switch (status) {
@@ -171,6 +165,11 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   if ((long)cache->batch * q_heads > kMaxGridY) return DQ_EINVAL;
   if (max_seq_len < 0 || (long)max_seq_len > (long)cache->block_capacity * fmt->block_tokens) return DQ_EINVAL;
   if ((flags & DQ_DECODE_FORCE_GENERIC) && (flags & DQ_DECODE_FORCE_MFMA)) return DQ_EINVAL;
+  {
+    const uint32_t splits = (flags >> 8) & 0x7Fu, waves = (flags >> 16) & 0xFu, umap = (flags >> 20) & 0xFu;
+    if (flags & ~(3u | DQ_DECODE_SPLITS(0x7F) | DQ_DECODE_WAVES(0xF) | (0xFu << 20))) return DQ_EINVAL;
+    if (splits > (uint32_t)kMaxSplits || (waves != 0 && waves != 4 && waves != 8) || umap > 6) return DQ_EINVAL;
+  }
   const size_t need = dq_decode_workspace_bytes(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len);
   if (need == 0) return DQ_EINVAL;
   if (workspace_bytes < need) return DQ_ENOSPACE;
@@ -195,7 +194,7 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   a.partials = reinterpret_cast<float*>(ws + kWsHeaderBytes + decode_counter_bytes(cache->batch, q_heads));
   a.heads_per_group = q_heads / cache->kv_heads;
   a.head_groups = use_mfma ? mfma_head_groups(fmt, q_heads, cache->kv_heads, &a.heads_per_group) : 1;
-  a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, &a.nw);
+  a.n_split = choose_splits(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len, use_mfma, flags, &a.nw);
   // With one workgroup per compute unit and equal shares, a launch ends with its slowest XCD.
   // Dealing the units so that every XCD sees every residue class of them (mod 8) brings the XCDs
   // closer together: measured 4 - 5 % faster on the 256-unit benchmark shapes (4- and 8-bit), neutral
@@ -203,7 +202,7 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   a.pair_heads = (use_mfma && mfma_pair_heads(fmt, q_heads, cache->kv_heads)) ? 1 : 0;
   const int units = cache->batch * cache->kv_heads / (a.pair_heads ? 2 : 1);
   a.unit_map = (a.n_split == 1 && a.head_groups == 1 && units <= 256) ? 3 : 0;
-  if (const char* env = getenv("DQ_DECODE_UNIT_MAP")) a.unit_map = atoi(env);   // tuning aid
+  if (const uint32_t umap = (flags >> 20) & 0xFu) a.unit_map = (int)umap - 1;   // the caller's override
   a.n_slots = a.n_split + (tail ? 1 : 0);
   if (tail) a.tail = *tail;
   else a.tail = dq_tail{nullptr, nullptr, nullptr, 0};

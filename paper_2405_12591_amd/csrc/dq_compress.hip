@@ -6,8 +6,6 @@
 // `quantize_tiles_kernel` turns fp32 rows into packed codes and fp16 steps.
 #include "dq_common.h"
 
-#include <stdlib.h>
-
 namespace dq {
 
 // What one dq_compress_kv call works on: t_new rows per (sequence, kv head), cut into n_blocks
@@ -612,8 +610,11 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
                                                                int32_t* __restrict__ call_status) {
   __shared__ int s_last_block;
   auto end_call = [&]() __attribute__((always_inline)) {   // QB != 0 only; every workgroup, once, at its end
+    // every wave waits for its own device-scope stores (the status words) to be acknowledged; after
+    // the barrier all of the workgroup's have been, and only then is the ticket taken
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
-    __syncthreads();   // every thread's stores above have been acknowledged
+    __syncthreads();
     if (threadIdx.x == 0) {
       const int ticket = __hip_atomic_fetch_add(call_status + 2, 1, __ATOMIC_RELAXED, __HIP_MEMORY_SCOPE_AGENT);
       s_last_block = (ticket == (int)gridDim.x - 1);
@@ -1198,7 +1199,8 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
 #define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                      \
   hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, job, large_ws, \
                      unit_status)
-  static const bool force_general = getenv("DQ_COMPRESS_GENERAL") != nullptr;   // for A/B timing
+  const bool force_general = (flags & DQ_COMPRESS_PLAIN) != 0;
+  const int want_waves = (int)((flags >> 8) & 0xFu);   // 0: the library's choice
   // heads of 64 channels with j1 = 8 go through the same kernel two at a time
   const bool pair_heads = fmt->head_dim == 64 && fmt->j1 == 8 && (cache->kv_heads & 1) == 0;
   // Calls of a few hundred blocks are bound by the latency of one block's chain of kernels: where the
@@ -1226,7 +1228,7 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   } while (0)
     const int fused_groups = pair_heads ? units / 2 : units;
     int fused_waves = fused_groups <= 256 ? 4 : fused_groups <= 512 ? 2 : 1;
-    if (const char* e = getenv("DQ_COMPRESS_WAVES")) fused_waves = atoi(e) >= 4 ? 4 : atoi(e) >= 2 ? 2 : 1;   // for sweeps
+    if (want_waves) fused_waves = want_waves;
     if (fused_waves == 4) {
       if (fmt->bits == 2) DQ_LAUNCH_FUSED(4, 2);
       else if (fmt->bits == 4) DQ_LAUNCH_FUSED(4, 4);
@@ -1258,7 +1260,7 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   } while (0)
     const int groups16 = pair_heads ? units / 2 : units;
     int nwv = groups16 <= 256 ? 4 : groups16 <= 512 ? 2 : 1;
-    if (const char* e = getenv("DQ_COMPRESS_WAVES")) nwv = atoi(e);   // for sweeps
+    if (want_waves) nwv = want_waves;
     if (nwv >= 4) DQ_LAUNCH_D16(4);
     else if (nwv >= 2) DQ_LAUNCH_D16(2);
     else DQ_LAUNCH_D16(1);
@@ -1333,7 +1335,11 @@ extern "C" int32_t dq_compress_kv_ex(const dq_format* fmt, dq_cache* cache, cons
                                      const int32_t* n_valid, void* workspace, size_t workspace_bytes,
                                      uint32_t flags, void* hip_stream) {
   if (!format_ok(fmt) || !cache || !k_new || !v_new || !blk_idx || !workspace) return DQ_EINVAL;
-  if (t_new < 1 || (flags & ~DQ_COMPRESS_NO_LARGE)) return DQ_EINVAL;
+  if (t_new < 1 || (flags & ~(DQ_COMPRESS_NO_LARGE | DQ_COMPRESS_PLAIN | DQ_COMPRESS_WAVES(0xF)))) return DQ_EINVAL;
+  {
+    const uint32_t wv = (flags >> 8) & 0xFu;
+    if (wv != 0 && wv != 1 && wv != 2 && wv != 4) return DQ_EINVAL;
+  }
   const int n_blocks = (t_new + fmt->block_tokens - 1) / fmt->block_tokens;
   if (n_blocks > cache->block_capacity) return DQ_EINVAL;
   return compress_impl(fmt, cache, k_new, v_new, t_new, n_blocks, blk_idx, n_valid, workspace,

@@ -59,6 +59,6 @@ bool mfma_supported(const dq_format* f, int q_heads, int kv_heads);
 bool mfma_pair_heads(const dq_format* f, int q_heads, int kv_heads);
 int mfma_head_groups(const dq_format* f, int q_heads, int kv_heads, int* heads_per_group);
 int choose_splits(const dq_format* f, int batch, int q_heads, int kv_heads, int max_seq_len, bool mfma,
-                  int* nw_out);
+                  uint32_t flags, int* nw_out);
 
 }  // namespace dq

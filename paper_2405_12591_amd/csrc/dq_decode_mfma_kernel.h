@@ -40,7 +40,6 @@
 
 #include <hip/hip_ext.h>
 
-#include <cstdlib>
 #include <type_traits>
 
 #include "dq_decode.h"
@@ -261,8 +260,16 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   int32_t* const ticket_counter = a.counters + (long)bh * a.head_groups + hgrp;
   const int n_contrib = a.n_split;   // workgroups that hand in partials
   auto ticket_and_merge = [&]() __attribute__((always_inline)) {
-    // The barrier waits for every thread's stores above to be acknowledged; only then does one
-    // thread take a ticket.  The merging workgroup reads the partials with device-scope loads.
+    // Ordering of the hand-over.  Producer: the partials above are device-scope (sc1) stores, which
+    // write through the XCD's L2; every wave waits here until all of its own stores have been
+    // acknowledged (the vector memory counter counts stores on this chip), and only after the
+    // barrier that follows, i.e. after every wave of the workgroup has done so, does one thread take
+    // a ticket, itself a device-scope read-modify-write performed at the memory side.  Consumer: the
+    // workgroup that draws the last ticket knows that every other workgroup's increment, and so
+    // every store ahead of it, has been performed; its loads of the partials are device-scope
+    // loads (never served from this XCD's stale lines) issued after the second barrier, which the
+    // compiler may not move them across.  No cache write-back or invalidation is involved.
+    asm volatile("s_waitcnt vmcnt(0)" ::: "memory");
     __builtin_amdgcn_fence(__ATOMIC_RELEASE, "workgroup");
     __syncthreads();
     if (tid == 0) {

@@ -19,7 +19,7 @@ int main(void) {
   dq_cache cache;
   char fake[64];
   memset(&cache, 0, sizeof cache);
-  CHECK(dq_version() == 3);
+  CHECK(dq_version() == 4);
   CHECK(strcmp(dq_status_string(DQ_OK), "ok") == 0);
   CHECK(dq_decode_workspace_bytes(&fmt, 8, 32, 32, 4096) > 0);
   CHECK(dq_decode_workspace_bytes(&bad, 8, 32, 32, 4096) == 0);
@@ -31,6 +31,10 @@ int main(void) {
                        (uint16_t*)fake, NULL, fake, 1u << 20, DQ_DECODE_AUTO, NULL) == DQ_EINVAL);
   CHECK(dq_compress_kv_ex(&fmt, &cache, (const uint16_t*)fake, (const uint16_t*)fake, 128, (const int32_t*)fake,
                           NULL, fake, 1u << 20, DQ_COMPRESS_NO_LARGE, NULL) == DQ_EINVAL);
+  /* launch-shape overrides travel in the flags word; an unknown bit is rejected */
+  CHECK(dq_attn_decode(&fmt, &cache, (const uint16_t*)fake, 1, (const int32_t*)fake, 128, 0.0f, (uint16_t*)fake, NULL,
+                       fake, 1u << 20, DQ_DECODE_SPLITS(65), NULL) == DQ_EINVAL);
+  CHECK((DQ_DECODE_SPLITS(5) | DQ_DECODE_WAVES(8) | DQ_DECODE_UNIT_MAP(3)) == ((5u << 8) | (8u << 16) | (4u << 20)));
   printf("abi ok\n");
   return 0;
 }

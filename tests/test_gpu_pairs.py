@@ -61,7 +61,7 @@ def test_decode_pairs_against_the_oracle(kw, lens):
 
 
 @pytest.mark.parametrize("seed", [31, 32, 33])
-def test_random_pair_cases(seed, monkeypatch):
+def test_random_pair_cases(seed):
     """Seeded sweep: code widths, block sizes, head counts, ragged lengths, tails, forced launch shapes."""
     rng = np.random.default_rng(seed)
     for case in range(12):
@@ -79,11 +79,7 @@ def test_random_pair_cases(seed, monkeypatch):
         cap = int(rng.choice([16, 128, 256]))
         tl = np.array([int(rng.choice([0, 1, cap, int(rng.integers(0, cap + 1))])) for _ in range(batch)], np.int32)
         splits, waves = str(rng.choice(["", "1", "2", "3", "5"])), str(rng.choice(["", "4", "8"]))
-        for key, val in (("DQ_DECODE_SPLITS", splits), ("DQ_DECODE_WAVES", waves)):
-            if val:
-                monkeypatch.setenv(key, val)
-            else:
-                monkeypatch.delenv(key, raising=False)
+        shape = dq.decode_flags(splits=int(splits or 0), waves=int(waves or 0))   # launch-shape overrides in the flags word
         _say("seed %d case %d: bits=%d kvh=%d B=%d Tb=%d max_seq=%d lens=%s tail=%s cap=%d tl=%s splits=%r waves=%r"
              % (seed, case, bits, kvh, batch, tb, max_seq, lens.tolist(), use_tail, cap, tl.tolist(), splits, waves))
         pairs = [(b, h) for b in range(batch) for h in range(kvh)]
@@ -103,8 +99,8 @@ def test_random_pair_cases(seed, monkeypatch):
         qd, ld = torch.from_numpy(q).to(DEV), torch.from_numpy(lens).to(DEV)
         tail = (torch.from_numpy(kt).to(DEV), torch.from_numpy(vt).to(DEV), torch.from_numpy(tl).to(DEV)) if use_tail else None
         o32 = torch.empty((batch, kvh, 64), dtype=torch.float32, device=DEV)
-        out = dq.attn_decode(dcache, qd, ld, max_seq, ws, out_f32=o32, flags=dq.DECODE_FORCE_MFMA, tail=tail)
-        again = dq.attn_decode(dcache, qd, ld, max_seq, ws, flags=dq.DECODE_FORCE_MFMA, tail=tail)   # counters left clean
+        out = dq.attn_decode(dcache, qd, ld, max_seq, ws, out_f32=o32, flags=dq.DECODE_FORCE_MFMA | shape, tail=tail)
+        again = dq.attn_decode(dcache, qd, ld, max_seq, ws, flags=dq.DECODE_FORCE_MFMA | shape, tail=tail)   # counters left clean
         torch.cuda.synchronize()
         g16, g32 = out.cpu().numpy().astype(np.float64), o32.cpu().numpy().astype(np.float64)
         assert torch.equal(out, again), (seed, case)
@@ -144,19 +140,15 @@ def test_decode_full_size_64_channel_heads():
 # compression of 64-channel heads: two heads per workgroup of the tuned decomposition kernel
 # ------------------------------------------------------------------------------------------
 @pytest.mark.parametrize("bits,kvh,tb,waves", [(4, 2, 128, ""), (2, 6, 256, "1"), (8, 4, 128, "2"), (4, 4, 256, "4")])
-def test_compress_pairs_properties(bits, kvh, tb, waves, monkeypatch):
+def test_compress_pairs_properties(bits, kvh, tb, waves):
     """Exact product, orthonormal rows of the large tensor, codes and steps equal to the oracle's
     quantizer on the GPU's large tensor, untouched neighbours: the checks every compression test
     runs, on shapes that go through the paired kernel, full and ragged."""
     from test_gpu_parity import _check_compress
-    if waves:
-        monkeypatch.setenv("DQ_COMPRESS_WAVES", waves)
-    else:
-        monkeypatch.delenv("DQ_COMPRESS_WAVES", raising=False)
     w = _w64(batch=3, q_heads=kvh, kv_heads=kvh, max_seq=tb, block_tokens=tb, bits=bits, n_outlier=2)
     _say("compress_kv, pairs of 64-channel heads: bits=%d H=%d Tb=%d waves=%r" % (bits, kvh, tb, waves))
-    _check_compress(w, tb, [tb, 37, 1])
-    _check_compress(w, tb - 5, None)
+    _check_compress(w, tb, [tb, 37, 1], waves=int(waves or 0))
+    _check_compress(w, tb - 5, None, waves=int(waves or 0))
 
 
 def test_compress_pairs_heads_of_very_different_size():

@@ -143,7 +143,7 @@ def test_compress_kv_properties(name, t_new, n_valid):
 
 
 @pytest.mark.parametrize("seed", [21, 22])
-def test_compress_kv_random_cases(seed, monkeypatch):
+def test_compress_kv_random_cases(seed):
     """Seeded sweep: code widths, group sizes, head dimensions, ragged n_valid (1, a few, full),
     short t_new, skipped sequences, and forced waves-per-block of the decomposition kernel."""
     rng = np.random.default_rng(seed)
@@ -157,19 +157,15 @@ def test_compress_kv_random_cases(seed, monkeypatch):
         t_new = int(rng.choice([tb, tb, int(rng.integers(1, tb + 1))]))
         n_valid = None if rng.integers(0, 2) else [int(rng.choice([1, 2, t_new, int(rng.integers(1, t_new + 1))])) for _ in range(batch)]
         waves = str(rng.choice(["", "1", "2", "4"]))
-        if waves:
-            monkeypatch.setenv("DQ_COMPRESS_WAVES", waves)
-        else:
-            monkeypatch.delenv("DQ_COMPRESS_WAVES", raising=False)
         w = _small("llama7b_4bit", batch=batch, q_heads=kvh, kv_heads=kvh, head_dim=d, j1=j1, j2=d // j1, bits=bits,
                    group=group, block_tokens=tb, max_seq=tb, min_seq=tb, seed=4000 + 100 * seed + case,
                    n_outlier=int(rng.choice([0, 2, 6])))
         _say("compress_kv random seed %d case %d: d=%d j1=%d bits=%d G=%d Tb=%d B=%d H=%d t_new=%d n_valid=%s waves=%r"
              % (seed, case, d, j1, bits, group, tb, batch, kvh, t_new, n_valid, waves))
-        _check_compress(w, t_new, n_valid)
+        _check_compress(w, t_new, n_valid, waves=int(waves or 0))
 
 
-def _check_compress(w, t_new, n_valid):
+def _check_compress(w, t_new, n_valid, waves=0):
     assert w.batch <= 3 and w.i3 == 1          # three block slots below; two local tensors
     fmt, ofmt = formats(w)
     tb, d, j1, j2 = fmt.block_tokens, fmt.head_dim, fmt.j1, fmt.j2
@@ -184,7 +180,7 @@ def _check_compress(w, t_new, n_valid):
         slots = np.array([1, -1], np.int32)      # second sequence is skipped
     nv = None if n_valid is None else torch.tensor(n_valid, dtype=torch.int32, device=DEV)
     dq.compress_kv(cache, torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV),
-                   torch.from_numpy(slots).to(DEV), nv, ws)
+                   torch.from_numpy(slots).to(DEV), nv, ws, waves=waves)
     torch.cuda.synchronize()
     arrs = {n: t.cpu().numpy() for n, t in cache.t.items()}
     status = int(ws[:4].view(torch.int32).item())

@@ -17,7 +17,7 @@ pytestmark = pytest.mark.gpu
 
 
 @pytest.mark.parametrize("seed,i3", [(11, 1), (12, 1), (13, 1), (21, 8), (22, 8), (23, 8)])
-def test_random_decode_cases(seed, i3, monkeypatch):
+def test_random_decode_cases(seed, i3):
     """i3 = 8: the same sweep over caches in the three-tensor form."""
     rng = np.random.default_rng(seed)
     for case in range(16):
@@ -38,11 +38,7 @@ def test_random_decode_cases(seed, i3, monkeypatch):
         cap = int(rng.choice([16, 128, 256]))
         tl = np.array([int(rng.choice([0, 1, cap, int(rng.integers(0, cap + 1))])) for _ in range(batch)], np.int32)
         splits, waves = str(rng.choice(["", "1", "2", "3", "5"])), str(rng.choice(["", "4", "8"]))
-        for key, val in (("DQ_DECODE_SPLITS", splits), ("DQ_DECODE_WAVES", waves)):
-            if val:
-                monkeypatch.setenv(key, val)
-            else:
-                monkeypatch.delenv(key, raising=False)
+        shape = dq.decode_flags(splits=int(splits or 0), waves=int(waves or 0))   # launch-shape overrides in the flags word
         print("seed %d i3=%d case %d: bits=%d G=%d rep=%d kvh=%d B=%d Tb=%d max_seq=%d lens=%s tail=%s cap=%d tl=%s splits=%r waves=%r"
               % (seed, i3, case, bits, group, rep, kvh, batch, tb, max_seq, lens.tolist(), use_tail, cap, tl.tolist(), splits, waves),
               flush=True)
@@ -64,8 +60,8 @@ def test_random_decode_cases(seed, i3, monkeypatch):
         tail = (torch.from_numpy(kt).to(DEV), torch.from_numpy(vt).to(DEV), torch.from_numpy(tl).to(DEV)) if use_tail else None
         o32 = torch.empty((batch, w.q_heads, 128), dtype=torch.float32, device=DEV)
         for flags in (dq.DECODE_AUTO, dq.DECODE_FORCE_GENERIC):
-            out = dq.attn_decode(dcache, qd, ld, max_seq, ws, out_f32=o32, flags=flags, tail=tail)
-            again = dq.attn_decode(dcache, qd, ld, max_seq, ws, flags=flags, tail=tail)   # counters left clean
+            out = dq.attn_decode(dcache, qd, ld, max_seq, ws, out_f32=o32, flags=flags | shape, tail=tail)
+            again = dq.attn_decode(dcache, qd, ld, max_seq, ws, flags=flags | shape, tail=tail)   # counters left clean
             torch.cuda.synchronize()
             g16, g32 = out.cpu().numpy().astype(np.float64), o32.cpu().numpy().astype(np.float64)
             assert torch.equal(out, again), (seed, case, flags)

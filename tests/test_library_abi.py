@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol(dq):
 
 
 def test_status_strings_and_version(dq):
-    assert dq.version() == dq.ABI_VERSION == 3
+    assert dq.version() == dq.ABI_VERSION == 4
     assert dq.status_string(0) == "ok"
     assert "workspace" in dq.status_string(-2)
     assert "invalid" in dq.status_string(-1)
@@ -99,6 +99,14 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     # both force flags
     st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need, 3, None)
     assert st == -1
+    # launch-shape overrides in the flags word: more splits than the library has, a wave count it
+    # does not build, an order of units it does not know, a bit that means nothing
+    for bad in (dq.decode_flags(splits=65), dq.decode_flags(waves=3), dq.decode_flags(unit_map=6), 1 << 4, 1 << 24):
+        st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need, bad, None)
+        assert st == -1, hex(bad)
+    for fine in (dq.decode_flags(splits=64, waves=8, unit_map=5), dq.decode_flags(dq.DECODE_FORCE_GENERIC, splits=1, waves=4)):
+        st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, need - 1, fine, None)
+        assert st == -2, hex(fine)     # accepted as far as the workspace check
     # compress: t_new out of range, workspace too small
     cneed = dq.lib.dq_compress_workspace_bytes(C.byref(good), 2, 4)
     st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 129, ptr, None, ptr, cneed, None)
@@ -106,8 +114,12 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     st = dq.lib.dq_compress_kv(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, None)
     assert st == -2
     # the flagged variant: unknown flag bits, then the same size checks
-    st = dq.lib.dq_compress_kv_ex(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed, 2, None)
-    assert st == -1
+    for bad in (4, 1 << 12, dq.compress_flags(waves=3), dq.compress_flags(waves=8)):
+        st = dq.lib.dq_compress_kv_ex(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed, bad, None)
+        assert st == -1, hex(bad)
+    st = dq.lib.dq_compress_kv_ex(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1,
+                                  dq.compress_flags(keep_large=False, waves=2, plain=True), None)
+    assert st == -2
     st = dq.lib.dq_compress_kv_ex(C.byref(good), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed - 1, 1, None)
     assert st == -2
     # several blocks per call: the workspace grows with the number of blocks; more blocks than the cache holds
