@@ -63,7 +63,8 @@ typedef enum dq_status {
   DQ_OK = 0,
   DQ_EINVAL = -1,   /* null pointer, unsupported format, inconsistent sizes */
   DQ_ENOSPACE = -2, /* workspace smaller than dq_*_workspace_bytes() */
-  DQ_EHIP = -3      /* a HIP runtime call failed; see dq_last_hip_error() */
+  DQ_EHIP = -3,     /* a HIP runtime call failed; see dq_last_hip_error() */
+  DQ_ELIMIT = -4    /* dq_attn_decode_static: the sizes exceed what its built-in scratch memory holds */
 } dq_status;
 
 /* Format of a compressed cache.  Constraints: bits in {2, 4, 8}; head_dim == j1*j2;
@@ -193,6 +194,24 @@ int32_t dq_attn_decode_tail(const dq_format* fmt, const dq_cache* cache, const u
                             int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
                             const dq_tail* tail, float softmax_scale, uint16_t* out, float* out_f32,
                             void* workspace, size_t workspace_bytes, uint32_t flags, void* hip_stream);
+
+/*
+ * dq_attn_decode_tail without a workspace argument, for callers that cannot allocate device memory
+ * or have nowhere to keep a workspace: code under HIP graph capture, tight serving loops, harnesses
+ * that forbid allocation.  The split partials and tickets live in a device array inside the library
+ * (about 16.5 MiB per GPU the library is used on, held until the process ends); the call allocates
+ * and frees nothing and needs no dq_workspace_init.  Same arguments, kernels and results (bit for
+ * bit) as dq_attn_decode_tail (`tail` may be NULL), with these limits and rules:
+ *   - batch * q_heads <= 512, else DQ_ELIMIT (nothing is launched);
+ *   - the device that is current when the call is made must be the stream's device; the array's
+ *     address on that device is looked up on the first call there;
+ *   - all calls on one GPU share that GPU's array: calls must be ordered on one stream (or otherwise
+ *     serialised); calls that overlap on one GPU race.
+ */
+int32_t dq_attn_decode_static(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                              int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                              const dq_tail* tail, float softmax_scale, uint16_t* out, float* out_f32,
+                              uint32_t flags, void* hip_stream);
 
 /* Bytes of workspace dq_compress_kv needs for n_blocks = B * H blocks of keys plus as many of
  * values (0 on invalid arguments). */

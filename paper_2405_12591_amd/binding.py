@@ -31,6 +31,7 @@ def compress_flags(keep_large: bool = True, waves: int = 0, plain: bool = False)
 EXPORTED_SYMBOLS = [
     "dq_version", "dq_status_string", "dq_last_hip_error", "dq_decode_mfma_supported",
     "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed", "dq_attn_decode_tail",
+    "dq_attn_decode_static",
     "dq_compress_workspace_bytes", "dq_compress_kv", "dq_compress_blocks_workspace_bytes", "dq_compress_kv_blocks",
     "dq_compress_kv_ex",
     "dq_quantize_pack", "dq_stream_read",
@@ -87,6 +88,10 @@ def _load() -> C.CDLL:
     l.dq_attn_decode_tail.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_int32, C.c_void_p,
                                       C.c_int32, C.POINTER(_CTail), C.c_float, C.c_void_p, C.c_void_p,
                                       C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
+    l.dq_attn_decode_static.restype = C.c_int32
+    l.dq_attn_decode_static.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_int32, C.c_void_p,
+                                        C.c_int32, C.POINTER(_CTail), C.c_float, C.c_void_p, C.c_void_p,
+                                        C.c_uint32, C.c_void_p]
     l.dq_compress_workspace_bytes.restype = C.c_size_t
     l.dq_compress_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32]
     l.dq_compress_kv.restype = C.c_int32
@@ -254,9 +259,10 @@ def workspace_init(ws: torch.Tensor) -> None:
 
 
 def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_len: int,
-                workspace: torch.Tensor, out: Optional[torch.Tensor] = None,
+                workspace: Optional[torch.Tensor], out: Optional[torch.Tensor] = None,
                 out_f32: Optional[torch.Tensor] = None, softmax_scale: float = 0.0,
                 flags: int = DECODE_AUTO, kernel_events=None, tail=None) -> torch.Tensor:
+    # workspace=None: dq_attn_decode_static (the library's built-in scratch memory, batch * q_heads <= 512)
     """out[b, h_q] = softmax(q . K_hat^T * scale) V_hat over the compressed cache (dq_attn_decode).
 
     kernel_events: optional (start, stop) torch.cuda.Event pair, each already recorded once so
@@ -284,6 +290,14 @@ def attn_decode(cache: Cache, q: torch.Tensor, seq_lens: torch.Tensor, max_seq_l
     ct = None
     if tail is not None:
         ct = _tail_struct(cache, tail, bsz)
+    if workspace is None:
+        if kernel_events is not None:
+            raise DQError("kernel events need a workspace call")
+        st = lib.dq_attn_decode_static(C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
+                                       None if ct is None else C.byref(ct), softmax_scale, out.data_ptr(),
+                                       0 if out_f32 is None else out_f32.data_ptr(), flags, _stream_ptr(q.device))
+        _check(st, "dq_attn_decode_static")
+        return out
     args = (C.byref(cf), C.byref(cache.c), q.data_ptr(), hq, seq_lens.data_ptr(), max_seq_len,
             softmax_scale, out.data_ptr(), 0 if out_f32 is None else out_f32.data_ptr(),
             workspace.data_ptr(), workspace.numel(), flags, _stream_ptr(q.device))

@@ -1,5 +1,6 @@
 // Host side of the C ABI: argument checks, workspace carve-up, kernel selection.
 #include <atomic>
+#include <mutex>
 
 #include "dq_decode.h"
 
@@ -118,6 +119,7 @@ extern "C" const char* dq_status_string(int32_t status) {
     case DQ_EINVAL: return "invalid argument or unsupported format";
     case DQ_ENOSPACE: return "workspace too small";
     case DQ_EHIP: return "HIP runtime error";
+    case DQ_ELIMIT: return "sizes beyond the limit of the allocation-free entry point";
     default: return "unknown status";
   }
 }
@@ -236,6 +238,57 @@ extern "C" int32_t dq_attn_decode(const dq_format* fmt, const dq_cache* cache, c
                                   size_t workspace_bytes, uint32_t flags, void* hip_stream) {
   return dq_attn_decode_timed(fmt, cache, q, q_heads, seq_lens, max_seq_len, softmax_scale, out, out_f32,
                               workspace, workspace_bytes, flags, hip_stream, nullptr, nullptr);
+}
+
+// ---- decode without a workspace argument: for callers that cannot allocate -------------------
+// The split partials and tickets live in a file-scope device array.  Every GPU the library runs on
+// holds its own copy at its own address, which is looked up once per device; host code uses that
+// address only, never the array's name.
+constexpr int kStaticMaxPairs = 512;   // (sequence, query head) pairs one call may hold
+constexpr size_t kStaticScratchBytes =
+    (size_t)kWsHeaderBytes + (size_t)kStaticMaxPairs * sizeof(int32_t) /* tickets, a multiple of 256 */ +
+    (size_t)kStaticMaxPairs * (kMaxSplits + 1) * (128 + 2) * sizeof(float);
+static_assert(((size_t)kStaticMaxPairs * sizeof(int32_t)) % 256 == 0, "ticket area is a multiple of 256 bytes");
+static __device__ __align__(256) unsigned char scratch[kStaticScratchBytes];
+
+constexpr int kMaxDevices = 64;
+static std::mutex g_scratch_mutex;
+static void* g_scratch_ptr[kMaxDevices];   // the array's device address, per device; null until looked up
+
+// The current device's copy of the array; on its first use the ticket area is cleared on `st` (a
+// small kernel, safe under stream capture).  The kernels leave the tickets at zero afterwards.
+static int32_t static_scratch(hipStream_t st, void** out) {
+  int dev = -1;
+  DQ_HIP_CHECK(hipGetDevice(&dev));
+  if (dev < 0 || dev >= kMaxDevices) return DQ_EINVAL;
+  std::lock_guard<std::mutex> lock(g_scratch_mutex);
+  if (!g_scratch_ptr[dev]) {
+    void* ptr = nullptr;
+    DQ_HIP_CHECK(hipGetSymbolAddress(&ptr, HIP_SYMBOL(scratch)));
+    if (!ptr) return DQ_EHIP;
+    const size_t head = (size_t)kWsHeaderBytes + (size_t)kStaticMaxPairs * sizeof(int32_t);
+    hipLaunchKernelGGL(fill_zero_kernel, dim3(1), dim3(256), 0, st, reinterpret_cast<uint4*>(ptr), head / 16);
+    DQ_HIP_CHECK(hipGetLastError());
+    g_scratch_ptr[dev] = ptr;
+  }
+  *out = g_scratch_ptr[dev];
+  return DQ_OK;
+}
+
+extern "C" int32_t dq_attn_decode_static(const dq_format* fmt, const dq_cache* cache, const uint16_t* q,
+                                         int32_t q_heads, const int32_t* seq_lens, int32_t max_seq_len,
+                                         const dq_tail* tail, float softmax_scale, uint16_t* out,
+                                         float* out_f32, uint32_t flags, void* hip_stream) {
+  if (!format_ok(fmt) || !cache || cache->batch <= 0 || q_heads <= 0) return DQ_EINVAL;
+  if ((long)cache->batch * q_heads > kStaticMaxPairs) return DQ_ELIMIT;
+  const size_t need = dq_decode_workspace_bytes(fmt, cache->batch, q_heads, cache->kv_heads, max_seq_len);
+  if (need == 0) return DQ_EINVAL;
+  if (need > kStaticScratchBytes) return DQ_ELIMIT;
+  void* ptr = nullptr;
+  const int32_t rc = static_scratch((hipStream_t)hip_stream, &ptr);
+  if (rc != DQ_OK) return rc;
+  return decode_impl(fmt, cache, q, q_heads, seq_lens, max_seq_len, tail, softmax_scale, out, out_f32, ptr,
+                     kStaticScratchBytes, flags, hip_stream, nullptr, nullptr);
 }
 
 extern "C" int32_t dq_stream_read(const void* src, size_t bytes, uint32_t* sink, void* hip_stream) {

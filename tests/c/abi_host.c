@@ -35,6 +35,10 @@ int main(void) {
   CHECK(dq_attn_decode(&fmt, &cache, (const uint16_t*)fake, 1, (const int32_t*)fake, 128, 0.0f, (uint16_t*)fake, NULL,
                        fake, 1u << 20, DQ_DECODE_SPLITS(65), NULL) == DQ_EINVAL);
   CHECK((DQ_DECODE_SPLITS(5) | DQ_DECODE_WAVES(8) | DQ_DECODE_UNIT_MAP(3)) == ((5u << 8) | (8u << 16) | (4u << 20)));
+  /* the entry point without a workspace refuses more than 512 (sequence, query head) pairs */
+  cache.batch = 513;
+  CHECK(dq_attn_decode_static(&fmt, &cache, (const uint16_t*)fake, 1, (const int32_t*)fake, 128, NULL, 0.0f,
+                              (uint16_t*)fake, NULL, DQ_DECODE_AUTO, NULL) == DQ_ELIMIT);
   printf("abi ok\n");
   return 0;
 }

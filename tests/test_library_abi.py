@@ -31,6 +31,7 @@ def test_status_strings_and_version(dq):
     assert dq.status_string(0) == "ok"
     assert "workspace" in dq.status_string(-2)
     assert "invalid" in dq.status_string(-1)
+    assert "limit" in dq.status_string(-4)
 
 
 def test_workspace_queries_validate_the_format(dq):
@@ -141,6 +142,13 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     assert st == -1
     st = dq.lib.dq_compress_kv(C.byref(three), cache_p, ptr, ptr, 128, ptr, None, ptr, cneed, None)
     assert st == -1
+    # the entry point without a workspace: more (sequence, query head) pairs than its scratch memory holds
+    fake.p[6] = 0x1000
+    fake.p[7] = 0x1000
+    fake.batch = 129
+    st = dq.lib.dq_attn_decode_static(C.byref(good), cache_p, ptr, 4, ptr, 1024, None, 0.0, ptr, None, 0, None)
+    assert st == -4
+    fake.batch = 2
     # quantize_pack: rows not a multiple of 128
     st = dq.lib.dq_quantize_pack(C.byref(good), ptr, 100, 0, ptr, ptr, None)
     assert st == -1
