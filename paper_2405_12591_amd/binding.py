@@ -357,15 +357,20 @@ def compress_kv(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx:
 
 
 def compress_kv_blocks(cache: Cache, k_new: torch.Tensor, v_new: torch.Tensor, blk_idx: torch.Tensor,
-                       n_valid: Optional[torch.Tensor], workspace: torch.Tensor) -> None:
+                       n_valid: Optional[torch.Tensor], workspace: torch.Tensor, keep_large: bool = True,
+                       waves: int = 0, plain: bool = False) -> None:
     """Compress k_new, v_new [B, H, t_new, d], any t_new >= 1, into the block slots from blk_idx[b]
-    on (dq_compress_kv_blocks)."""
+    on (dq_compress_kv_blocks; dq_compress_kv_ex when a flag is given)."""
     _check_compress_args(cache, k_new, v_new, blk_idx, n_valid)
     cf = cache.fmt.c()
-    st = lib.dq_compress_kv_blocks(C.byref(cf), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
-                                   k_new.shape[2], blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
-                                   workspace.data_ptr(), workspace.numel(), _stream_ptr(k_new.device))
-    _check(st, "dq_compress_kv_blocks")
+    args = (C.byref(cf), C.byref(cache.c), k_new.data_ptr(), v_new.data_ptr(),
+            k_new.shape[2], blk_idx.data_ptr(), 0 if n_valid is None else n_valid.data_ptr(),
+            workspace.data_ptr(), workspace.numel())
+    if keep_large and not waves and not plain:
+        _check(lib.dq_compress_kv_blocks(*args, _stream_ptr(k_new.device)), "dq_compress_kv_blocks")
+    else:
+        _check(lib.dq_compress_kv_ex(*args, compress_flags(keep_large, waves, plain), _stream_ptr(k_new.device)),
+               "dq_compress_kv_ex")
 
 
 def quantize_pack(fmt: Format, t_large: torch.Tensor, value_layout: bool):
