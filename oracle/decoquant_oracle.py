@@ -25,8 +25,10 @@ What follows which passage of the paper
                                    Length of Local Tensors"
 
 Readings taken where the paper is silent (each is listed in the design notes of
-the repository): per-head blocks of `block_tokens` rows; i_1 = 1 so the small
-tensor mixes only channels; no bond truncation; singular values kept in the
+the repository): per-head blocks of `block_tokens` rows; i_1 = 1 by default so the small
+tensor mixes only channels (`i1` > 1: Eq. 2 as printed with a token factor on the small tensor,
+which then is (i1*j1) x (i1*j1) and mixes i1 token groups too; the large tensor keeps the block's
+row count and row length, row a2*i1 + rho holding bond slice rho of position a2); no bond truncation; singular values kept in the
 small tensor; per-group fp16 steps with groups of `group` consecutive elements
 inside one token row of the large tensor; ties round to even; 2-bit uses the
 literal Eq. 1 levels {-1, 0, +1}; codes stored offset-binary.  Non-default level set
@@ -65,6 +67,13 @@ class Format:
     block_tokens: int
     i3: int = 1   # 1: two local tensors; > 1: three, the third one i3 x i3 on the token side
     levels: int = 0   # 0: Eq. 1's symmetric codes [-qmax, qmax]; 1: all 2^bits codes [-qmax - 1, qmax]
+    i1: int = 1   # Eq. 2's i_1: the small tensor's share of the token index (i_2 = block_tokens / i1);
+                  # > 1: T_S is (i1*j1) x (i1*j1) and mixes i1 groups of tokens as well as channels
+
+    @property
+    def small_side(self) -> int:
+        """Rows (= columns = bond dimension) of the small tensor: i1 * j1."""
+        return self.i1 * self.j1
 
     def check(self) -> None:
         if self.bits not in (2, 4, 8):
@@ -79,6 +88,12 @@ class Format:
             raise ValueError("i3 must divide block_tokens")
         if self.levels not in (0, 1):
             raise ValueError("levels must be 0 (symmetric) or 1 (all codes)")
+        if self.i1 < 1 or self.block_tokens % self.i1:
+            raise ValueError("i1 must divide block_tokens")
+        if self.i1 > 1 and self.i3 > 1:
+            raise ValueError("i1 > 1 is defined for two local tensors only")
+        if self.i1 * self.j1 > (self.block_tokens // self.i1) * self.j2:
+            raise ValueError("the small tensor's side must not exceed the large tensor's (bond = i1*j1)")
 
     @property
     def qmax(self) -> int:
@@ -238,17 +253,21 @@ def token_major_to_middle(kp: np.ndarray, j1: int, j2: int, i3: int) -> np.ndarr
 # Hand-off precision and layout of the large tensor
 # --------------------------------------------------------------------------------------
 
-def large_to_token_major(t_l: np.ndarray, n_tok: int, j2: int) -> np.ndarray:
-    """T_L[r, (t, b2)] -> K'[t, r*j2 + b2] rounded to fp32 (the precision the quantizer sees)."""
-    j1 = t_l.shape[0]
+def large_to_token_major(t_l: np.ndarray, n_tok: int, j2: int, i1: int = 1) -> np.ndarray:
+    """T_L[r, (a2, b2)] -> K'[a2*i1 + rho, r'*j2 + b2] with r = rho*j1 + r', rounded to fp32 (the
+    precision the quantizer sees).  n_tok = i1 * i2 rows of d = j1*j2 elements: with i1 = 1 row t
+    is token t; with i1 > 1 the i1 rows a2*i1 + rho hold the i1 slices of the bond index that
+    belong to position a2, so the row count and the row length are those of the block itself."""
+    i2 = n_tok // i1
+    j1 = t_l.shape[0] // i1
     return np.ascontiguousarray(
-        t_l.reshape(j1, n_tok, j2).transpose(1, 0, 2).reshape(n_tok, j1 * j2)).astype(np.float32)
+        t_l.reshape(i1, j1, i2, j2).transpose(2, 0, 1, 3).reshape(i2 * i1, j1 * j2)).astype(np.float32)
 
 
-def token_major_to_large(kp: np.ndarray, j1: int, j2: int) -> np.ndarray:
+def token_major_to_large(kp: np.ndarray, j1: int, j2: int, i1: int = 1) -> np.ndarray:
     """Inverse layout change of `large_to_token_major` (values untouched)."""
-    n_tok = kp.shape[0]
-    return kp.reshape(n_tok, j1, j2).transpose(1, 0, 2).reshape(j1, n_tok * j2)
+    i2 = kp.shape[0] // i1
+    return kp.reshape(i2, i1, j1, j2).transpose(1, 2, 0, 3).reshape(i1 * j1, i2 * j2)
 
 
 # --------------------------------------------------------------------------------------
@@ -359,7 +378,7 @@ def value_tiles_to_codes(tiles: np.ndarray) -> np.ndarray:
 @dataclass
 class Block:
     """One compressed [block_tokens, head_dim] block of keys or of values (natural layouts)."""
-    small: np.ndarray    # fp16 [j1 (b1), j1 (r)]   T_S
+    small: np.ndarray    # fp16 [j1 (b1), j1 (r)]   T_S  (i1 > 1: [i1*j1 (a1, b1), i1*j1 (r)])
     steps: np.ndarray    # fp16 [block_tokens, head_dim/group]
     codes: np.ndarray    # int32 [block_tokens, head_dim], element index r*j2 + b2
     large32: np.ndarray  # fp32 [block_tokens, head_dim], the unquantized large tensor, token-major
@@ -389,11 +408,11 @@ def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
             small3 = t_3.astype(np.float16)
     else:
         if identity_small:
-            t_s = np.eye(fmt.j1)
-            t_l = matricise(xb, 1, fmt.j1)
+            t_s = np.eye(fmt.small_side)
+            t_l = matricise(xb, fmt.i1, fmt.j1)
         else:
-            t_s, t_l = mpo_split(xb, fmt.j1, 1, sigma_in)
-        kp = large_to_token_major(t_l, tb, fmt.j2)
+            t_s, t_l = mpo_split(xb, fmt.j1, fmt.i1, sigma_in)
+        kp = large_to_token_major(t_l, tb, fmt.j2, fmt.i1)
     steps = group_steps(kp, fmt.group, fmt.qmax, fmt.full_range)
     codes = quantize_codes(kp, steps, fmt.group, fmt.qmax, fmt.full_range)
     with np.errstate(over="ignore"):
@@ -414,9 +433,9 @@ def reconstruct_block(small: np.ndarray, steps: np.ndarray, codes: np.ndarray, f
             right = np.einsum("racd,de->raec", t_2_hat, small3.astype(np.float64))  # [r, a2, a3, b2]
             t_l_hat = right.reshape(fmt.j1, fmt.block_tokens * fmt.j2)
         else:
-            t_l_hat = token_major_to_large(deq, fmt.j1, fmt.j2)
+            t_l_hat = token_major_to_large(deq, fmt.j1, fmt.j2, fmt.i1)
         m_hat = small.astype(np.float64) @ t_l_hat
-    return unmatricise(m_hat, fmt.block_tokens, fmt.head_dim, 1, fmt.j1)
+    return unmatricise(m_hat, fmt.block_tokens, fmt.head_dim, fmt.i1, fmt.j1)
 
 
 def reconstruction_bound(small: np.ndarray, steps: np.ndarray, fmt: Format,
@@ -431,9 +450,9 @@ def reconstruction_bound(small: np.ndarray, steps: np.ndarray, fmt: Format,
         right = np.einsum("racd,de->raec", dm, np.abs(small3.astype(np.float64)))
         delta_l = right.reshape(fmt.j1, tb * fmt.j2)
     else:
-        delta_l = token_major_to_large(delta, fmt.j1, fmt.j2)           # [r, (t, b2)]
+        delta_l = token_major_to_large(delta, fmt.j1, fmt.j2, fmt.i1)   # [r, (a2, b2)]
     m_bound = 0.5 * np.abs(small.astype(np.float64)) @ delta_l
-    return unmatricise(m_bound, tb, d, 1, fmt.j1)
+    return unmatricise(m_bound, tb, d, fmt.i1, fmt.j1)
 
 
 # --------------------------------------------------------------------------------------
@@ -445,6 +464,7 @@ def empty_cache(fmt: Format, batch: int, kv_heads: int, block_capacity: int) -> 
       k_codes  u8  [B, H, NB, T_b, d*bits/8]              token-major rows
       k_scales f16 [B, H, NB, T_b, d/G]
       k_small  f16 [B, H, NB, j1 (r), j1 (b1)]             T_S of keys, TRANSPOSED (bond index first)
+                                                           (i1 > 1: both sides i1*j1, rows (a1, b1))
       v_codes  u8  [B, H, NB, T_b/128, j2, j1, 128*bits/8] token-contiguous inside 128-token tiles
       v_scales f16 [B, H, NB, T_b, d/G]
       v_small  f16 [B, H, NB, j1 (b1), j1 (r)]             T_S of values, natural
@@ -463,10 +483,10 @@ def empty_cache(fmt: Format, batch: int, kv_heads: int, block_capacity: int) -> 
         **extra,
         "k_codes": np.zeros((b, h, nb, tb, fmt.row_bytes), np.uint8),
         "k_scales": np.zeros((b, h, nb, tb, fmt.groups_per_row), np.float16),
-        "k_small": np.zeros((b, h, nb, fmt.j1, fmt.j1), np.float16),
+        "k_small": np.zeros((b, h, nb, fmt.small_side, fmt.small_side), np.float16),
         "v_codes": np.zeros((b, h, nb, tiles, fmt.j2, fmt.j1, TILE_TOKENS * fmt.bits // 8), np.uint8),
         "v_scales": np.zeros((b, h, nb, tb, fmt.groups_per_row), np.float16),
-        "v_small": np.zeros((b, h, nb, fmt.j1, fmt.j1), np.float16),
+        "v_small": np.zeros((b, h, nb, fmt.small_side, fmt.small_side), np.float16),
     }
 
 
@@ -582,7 +602,7 @@ def compression_ratio(fmt: Format, step_bits: int = 16) -> float:
     """mu = (#T_L * B + #T_S * 16 + bits of the steps) / (#W * 16) for one block (Eq. 4)."""
     n_w = fmt.block_tokens * fmt.head_dim
     n_l = fmt.j1 * fmt.block_tokens * fmt.j2
-    n_s = fmt.j1 * fmt.j1 + (fmt.i3 * fmt.i3 if fmt.i3 > 1 else 0)
+    n_s = fmt.small_side * fmt.small_side + (fmt.i3 * fmt.i3 if fmt.i3 > 1 else 0)
     n_delta = fmt.block_tokens * fmt.groups_per_row
     return (n_l * fmt.bits + n_s * 16 + n_delta * step_bits) / (n_w * 16.0)
 
@@ -590,4 +610,4 @@ def compression_ratio(fmt: Format, step_bits: int = 16) -> float:
 def cache_bytes_per_block(fmt: Format) -> int:
     """Bytes one key (or value) block occupies in the storage arrays."""
     return (fmt.block_tokens * fmt.row_bytes + fmt.block_tokens * fmt.groups_per_row * 2
-            + fmt.j1 * fmt.j1 * 2 + (fmt.i3 * fmt.i3 * 2 if fmt.i3 > 1 else 0))
+            + fmt.small_side * fmt.small_side * 2 + (fmt.i3 * fmt.i3 * 2 if fmt.i3 > 1 else 0))
