@@ -67,7 +67,7 @@ def _cpu_worker(rank, n_workers, wname, pairs, barrier, queue):
         pass
     from oracle import decoquant_oracle as O
     w = workloads.get_workload(wname)
-    fmt = O.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels)
+    fmt = O.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels, w.i1)
     mine = pairs[rank::n_workers]
     lens = workloads.seq_lens(w)
     q = workloads.query(w)
@@ -164,7 +164,7 @@ def build_cache(dq, torch, w, dev, pool):
     """Host-generate the layer's K/V, upload, compress the whole prompt with one
     dq_compress_kv_blocks call (timed), then time the companion step: compressing one new block
     per (sequence, kv head)."""
-    fmt = dq.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels)
+    fmt = dq.Format(w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels, w.i1)
     tb = w.block_tokens
     total = w.max_seq + w.append_tokens
     nb = -(-total // tb)

@@ -48,6 +48,18 @@
  * A real token a2*8 + a3 then depends on all eight rows a2*8 + e: in the last, partly valid block
  * of a sequence every row of a run that contains a valid token must hold what dq_compress_kv
  * wrote (it writes whole blocks); runs wholly past seq_lens[b] may hold anything.
+ *
+ * A token factor on the small tensor (format field i1 = 2 or 4; Eq. 2 with n = 2 as printed, i_1 > 1):
+ * the block's row index is factored as i1 * i2 (token t = a1*i2 + a2 of the block) and
+ *   X[(a1, a2), (b1, b2)] = sum_r T_S[(a1, b1), r] T_L[r, (a2, b2)],   r = 0 .. i1*j1 - 1.
+ * The large tensor keeps the block's shape: T_b rows of d elements, row a2*i1 + rho holding the
+ * elements T_L[rho*j1 + r', (a2, b2)] at index r'*j2 + b2, with codes, steps and their layouts as
+ * above (a "token row" is now one bond slice of one position a2).  The small tensors grow:
+ *   k_small  f16  [B, H, NB, i1*j1, i1*j1]    entry [r][(a1, b1)] = T_S[(a1, b1)][r]  (transposed)
+ *   v_small  f16  [B, H, NB, i1*j1, i1*j1]    entry [(a1, b1)][r]
+ * A token then depends on rows all over its block: every row of a block that contains a valid
+ * token must hold what dq_compress_kv wrote.  Decoding costs i1 times the multiply-adds; the plain
+ * kernel serves these formats (the matrix-core kernel is built for i1 = 1).
  */
 #ifndef DECOQUANT_H
 #define DECOQUANT_H
@@ -70,7 +82,7 @@ typedef enum dq_status {
 /* Format of a compressed cache.  Constraints: bits in {2, 4, 8}; head_dim == j1*j2;
  * head_dim in {64, 128}; j1 in {8, 16, 32}; group divides head_dim and group >= head_dim/2
  * or group divides head_dim/2; block_tokens is a positive multiple of 128; i3 in {1, 8};
- * levels in {0, 1}. */
+ * levels in {0, 1}; i1 in {1, 2, 4} with i1 * j1 <= 32 and, for i1 > 1, i3 == 1. */
 typedef struct dq_format {
   int32_t bits;         /* m of Eq. 1; qmax = 2^(m-1) - 1                         */
   int32_t group;        /* G: elements per step, consecutive inside one token row  */
@@ -85,6 +97,10 @@ typedef struct dq_format {
                            step = fp16(max(max(x) / qmax, max(-x) / (qmax + 1))) so that neither
                            end clips.  Only the quantizer differs; decoding reads the stored
                            field c + 2^(m-1) the same way.                          */
+  int32_t i1;           /* Eq. 2's i_1, the small tensor's share of the token index: 1 (the default
+                           this library is built around), 2 or 4; then i_2 = T_b / i1, T_S is
+                           (i1*j1) x (i1*j1) and mixes i1 groups of tokens as well as channels.
+                           Needs i1*j1 <= 32 and i3 == 1.  See "A token factor" above.      */
 } dq_format;
 
 /* Device pointers to the arrays described above; shapes are fixed by (format, batch,

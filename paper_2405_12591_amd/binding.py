@@ -11,7 +11,7 @@ import torch
 from . import build as _build
 
 DECODE_AUTO = 0
-ABI_VERSION = 4   # dq_version() of the library whose struct layouts this file mirrors
+ABI_VERSION = 5   # dq_version() of the library whose struct layouts this file mirrors
 COMPRESS_NO_LARGE = 1
 COMPRESS_PLAIN = 2
 DECODE_FORCE_GENERIC = 1
@@ -45,7 +45,7 @@ class DQError(RuntimeError):
 class _CFormat(C.Structure):
     _fields_ = [("bits", C.c_int32), ("group", C.c_int32), ("head_dim", C.c_int32),
                 ("j1", C.c_int32), ("j2", C.c_int32), ("block_tokens", C.c_int32), ("i3", C.c_int32),
-                ("levels", C.c_int32)]
+                ("levels", C.c_int32), ("i1", C.c_int32)]
 
 
 class _CTail(C.Structure):
@@ -140,10 +140,15 @@ class Format:
     block_tokens: int
     i3: int = 1   # 8: three local tensors (T_3 is 8 x 8 on the token side)
     levels: int = 0   # 1: the quantizer uses all 2^bits codes (not the paper's symmetric range)
+    i1: int = 1   # 2 or 4: a token factor on the small tensor, which is then (i1*j1) x (i1*j1)
 
     def c(self) -> _CFormat:
         return _CFormat(self.bits, self.group, self.head_dim, self.j1, self.j2, self.block_tokens, self.i3,
-                        self.levels)
+                        self.levels, self.i1)
+
+    @property
+    def small_side(self) -> int:
+        return self.i1 * self.j1
 
     @property
     def row_bytes(self) -> int:
@@ -190,10 +195,10 @@ def _shapes(fmt: Format, b: int, h: int, nb: int):
         **extra,
         "k_codes": ((b, h, nb, fmt.block_tokens, fmt.row_bytes), torch.uint8),
         "k_scales": ((b, h, nb, fmt.block_tokens, fmt.groups), torch.float16),
-        "k_small": ((b, h, nb, fmt.j1, fmt.j1), torch.float16),
+        "k_small": ((b, h, nb, fmt.small_side, fmt.small_side), torch.float16),
         "v_codes": ((b, h, nb, tiles, fmt.j2, fmt.j1, 128 * fmt.bits // 8), torch.uint8),
         "v_scales": ((b, h, nb, fmt.block_tokens, fmt.groups), torch.float16),
-        "v_small": ((b, h, nb, fmt.j1, fmt.j1), torch.float16),
+        "v_small": ((b, h, nb, fmt.small_side, fmt.small_side), torch.float16),
     }
 
 

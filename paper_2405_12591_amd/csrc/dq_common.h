@@ -42,6 +42,8 @@ inline bool format_ok(const dq_format* f) {
   if (f->block_tokens <= 0 || f->block_tokens % kTileTokens) return false;
   if (f->i3 != 1 && f->i3 != kRun) return false;
   if (f->levels != 0 && f->levels != 1) return false;
+  if (f->i1 != 1 && f->i1 != 2 && f->i1 != 4) return false;
+  if (f->i1 > 1 && (f->i3 != 1 || f->i1 * f->j1 > 32)) return false;
   return true;
 }
 
@@ -69,7 +71,7 @@ __host__ __device__ inline Geometry make_geometry(const dq_format& f, int kv_hea
   g.vrow_bytes = kTileTokens * f.bits / 8;
   g.codes_per_block = (long)f.block_tokens * g.row_bytes;
   g.scales_per_block = (long)f.block_tokens * g.groups;
-  g.small_per_block = (long)f.j1 * f.j1;
+  g.small_per_block = (long)(f.i1 * f.j1) * (f.i1 * f.j1);
   g.NB = block_capacity; g.H = kv_heads;
   return g;
 }

@@ -355,13 +355,18 @@ __device__ __forceinline__ double fast_rsqrt(double x) {
   return y;
 }
 
-__host__ __device__ inline size_t decompose_lds_bytes(int j1, int d) {
-  const size_t mat = (size_t)j1 * (j1 + 1);
-  return (5 * mat + 5 * (size_t)j1) * sizeof(double) + 3 * (size_t)j1 * sizeof(int) +
-         (size_t)kGramTile * d * sizeof(float) + 64;
+// n: side of the small tensor (i1 * j1); i1 rows are staged per token position
+__host__ __device__ inline size_t decompose_lds_bytes(int n, int d, int i1) {
+  const size_t mat = (size_t)n * (n + 1);
+  return (5 * mat + 5 * (size_t)n) * sizeof(double) + 3 * (size_t)n * sizeof(int) +
+         (size_t)kGramTile * d * i1 * sizeof(float) + 64;
 }
 
-template <int J1, int DD>
+// I1 > 1: a token factor on the small tensor (Eq. 2 with n = 2, i_1 = I1).  The regrouped matrix has
+// rows (a1, b1) and columns (a2, b2), M[(a1, b1), (a2, b2)] = X[a1*i2 + a2, b1*j2 + b2]; everything
+// below runs on its side I1*J1 instead of J1, and row a2*I1 + rho of the large tensor holds the
+// elements T_L[rho*J1 + r', (a2, b2)].
+template <int J1, int DD, int I1 = 1>
 __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                        float* __restrict__ large_ws,
                                                        int32_t* __restrict__ unit_status) {
@@ -375,9 +380,11 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
     return;
   }
   const int tid = threadIdx.x;
-  constexpr int j1 = J1, d = DD, j2 = DD / J1;   // compile-time shapes: loops unroll, no divisions
+  constexpr int cj1 = J1, d = DD, j2 = DD / J1;   // compile-time shapes: loops unroll, no divisions
+  constexpr int j1 = I1 * J1;            // side of the regrouped matrix's row index (a1, b1)
   constexpr int ld = j1 + 1;             // padded leading dimension of the small matrices
   constexpr int nent = j1 * j1;
+  const int i2 = g.Tb / I1;              // positions a2 per block
   const uint16_t* X = ur.X;  // [nv, d] fp16 bits
 
   extern __shared__ __attribute__((aligned(16))) unsigned char lds_raw[];
@@ -394,9 +401,9 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
   int* partner = reinterpret_cast<int*>(offarr + j1);
   int* is_p = partner + j1;                          // 1 if the index is the first member of its pair
   int* order = is_p + j1;
-  float* xs = reinterpret_cast<float*>(order + j1 + (j1 & 1));   // [kGramTile][d]
+  float* xs = reinterpret_cast<float*>(order + j1 + (j1 & 1));   // [I1][kGramTile][d]
 
-  // ---- Gram matrix: Gm[p][q] = sum_{t, b2} X[t, p*j2+b2] * X[t, q*j2+b2] ----
+  // ---- Gram matrix: Gm[p][q] = sum_{a2, b2} M[p, (a2, b2)] M[q, (a2, b2)], p = (a1, b1) ----
   // lane (pb, qb) of an 8 x 8 grid owns a (j1/8) x (j1/8) block of entries
   constexpr int BS = j1 / 8;
   const int pb = (tid >> 3) * BS, qb = (tid & 7) * BS;
@@ -405,9 +412,22 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
   for (int i = 0; i < BS; ++i)
 #pragma unroll
     for (int j = 0; j < BS; ++j) acc[i][j] = 0.0;
-  for (int t0 = 0; t0 < nv; t0 += kGramTile) {
-    const int nt = min(kGramTile, nv - t0);
-    for (int i = tid; i < nt * d; i += 64) xs[i] = h2f(X[(long)t0 * d + i]);
+  // row p = (a1, b1) of M takes channel b1*j2 + b2 of token group a1's staged row
+  int off_p[BS], off_q[BS];
+#pragma unroll
+  for (int i = 0; i < BS; ++i) {
+    off_p[i] = ((pb + i) / cj1) * kGramTile * d + ((pb + i) % cj1) * j2;
+    off_q[i] = ((qb + i) / cj1) * kGramTile * d + ((qb + i) % cj1) * j2;
+  }
+  // (positions past the last valid row of the first token group hold zeros in every group)
+  const int np = min(i2, nv);
+  for (int t0 = 0; t0 < np; t0 += kGramTile) {
+    const int nt = min(kGramTile, np - t0);
+    for (int i = tid; i < I1 * nt * d; i += 64) {
+      const int a1 = i / (nt * d), rest = i % (nt * d);
+      const int row = a1 * i2 + t0 + rest / d;
+      xs[a1 * kGramTile * d + rest] = row < nv ? h2f(X[(long)row * d + rest % d]) : 0.f;
+    }
     __syncthreads();
     for (int t = 0; t < nt; ++t) {
       const float* xr = xs + t * d;
@@ -416,8 +436,8 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
         double xp[BS], xq[BS];
 #pragma unroll
         for (int i = 0; i < BS; ++i) {
-          xp[i] = (double)xr[(pb + i) * j2 + b2];
-          xq[i] = (double)xr[(qb + i) * j2 + b2];
+          xp[i] = (double)xr[off_p[i] + b2];
+          xq[i] = (double)xr[off_q[i] + b2];
         }
         // every product of two fp16 values is exact in fp64; only the sum rounds
 #pragma unroll
@@ -524,22 +544,26 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
   }
   __syncthreads();
 
-  // ---- projection: K'[t, r*j2+b2] = sum_b1 W[r][b1] * X[t, b1*j2+b2], fp64 -> fp32 ----
+  // ---- projection: T_L[r, (a2, b2)] = sum_p W[r][p] M[p, (a2, b2)], fp64 -> fp32, to row
+  // a2*I1 + r / J1, element (r % J1)*j2 + b2 ----
   float* out = large_ws + (long)unit * g.Tb * d;
-  for (int item = tid; item < g.Tb * j2; item += 64) {
+  for (int item = tid; item < i2 * j2; item += 64) {
     const int t = item / j2, b2 = item % j2;
     if (t < nv) {
       double xv[j1];
 #pragma unroll
-      for (int b1 = 0; b1 < j1; ++b1) xv[b1] = (double)h2f(X[(long)t * d + b1 * j2 + b2]);
+      for (int p = 0; p < j1; ++p) {
+        const int row = (p / cj1) * i2 + t;
+        xv[p] = row < nv ? (double)h2f(X[(long)row * d + (p % cj1) * j2 + b2]) : 0.0;
+      }
       for (int r = 0; r < j1; ++r) {
         double a = 0.0;
 #pragma unroll
-        for (int b1 = 0; b1 < j1; ++b1) a = fma(W[r * ld + b1], xv[b1], a);
-        out[(long)t * d + r * j2 + b2] = (float)a;
+        for (int p = 0; p < j1; ++p) a = fma(W[r * ld + p], xv[p], a);
+        out[((long)t * I1 + r / cj1) * d + (r % cj1) * j2 + b2] = (float)a;
       }
     } else {
-      for (int r = 0; r < j1; ++r) out[(long)t * d + r * j2 + b2] = 0.f;
+      for (int r = 0; r < j1; ++r) out[((long)t * I1 + r / cj1) * d + (r % cj1) * j2 + b2] = 0.f;
     }
   }
 }
@@ -1195,19 +1219,22 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   const int units = cache->batch * cache->kv_heads * 2 * n_blocks;
   int32_t* unit_status = reinterpret_cast<int32_t*>(large_ws + (size_t)units * fmt->block_tokens * fmt->head_dim);
   const CompressJob job = {k_new, v_new, t_new, n_blocks, blk_idx, n_valid};
-  const size_t dlds = decompose_lds_bytes(fmt->j1, fmt->head_dim);
+  const size_t dlds = decompose_lds_bytes(fmt->i1 * fmt->j1, fmt->head_dim, fmt->i1);
 #define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                      \
   hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, job, large_ws, \
                      unit_status)
+#define DQ_LAUNCH_DECOMPOSE_I1(J, DD_, I_)                                                               \
+  hipLaunchKernelGGL((decompose_kernel<J, DD_, I_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, job, \
+                     large_ws, unit_status)
   const bool force_general = (flags & DQ_COMPRESS_PLAIN) != 0;
   const int want_waves = (int)((flags >> 8) & 0xFu);   // 0: the library's choice
   // heads of 64 channels with j1 = 8 go through the same kernel two at a time
-  const bool pair_heads = fmt->head_dim == 64 && fmt->j1 == 8 && (cache->kv_heads & 1) == 0;
+  const bool pair_heads = fmt->head_dim == 64 && fmt->j1 == 8 && (cache->kv_heads & 1) == 0 && fmt->i1 == 1;
   // Calls of a few hundred blocks are bound by the latency of one block's chain of kernels: where the
   // caller does not need the fp32 large tensors the decomposition kernel quantizes them itself, which
   // saves their trip through memory and the quantizer's launch.  (Calls of thousands of blocks are
   // bound by throughput and keep the leaner kernels.)
-  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->i3 == 1 && units <= 1024 && !force_general &&
+  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->i3 == 1 && fmt->i1 == 1 && units <= 1024 && !force_general &&
                      ((fmt->head_dim == 128 && fmt->j1 == 16 && (fmt->group == 128 || fmt->group == 64)) ||
                       (pair_heads && fmt->group == 64));
   if (fused) {
@@ -1246,7 +1273,20 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
     DQ_HIP_CHECK(hipGetLastError());
     return DQ_OK;
   }
-  if (((fmt->head_dim == 128 && fmt->j1 == 16) || pair_heads) && !force_general) {
+  if (fmt->i1 > 1) {   // a token factor on the small tensor: the plain kernel on the side i1 * j1
+    const int dd = fmt->head_dim, jj = fmt->j1;
+    if (fmt->i1 == 2) {
+      if (dd == 128 && jj == 16) DQ_LAUNCH_DECOMPOSE_I1(16, 128, 2);
+      else if (dd == 128 && jj == 8) DQ_LAUNCH_DECOMPOSE_I1(8, 128, 2);
+      else if (dd == 64 && jj == 16) DQ_LAUNCH_DECOMPOSE_I1(16, 64, 2);
+      else if (dd == 64 && jj == 8) DQ_LAUNCH_DECOMPOSE_I1(8, 64, 2);
+      else return DQ_EINVAL;
+    } else {
+      if (dd == 128 && jj == 8) DQ_LAUNCH_DECOMPOSE_I1(8, 128, 4);
+      else if (dd == 64 && jj == 8) DQ_LAUNCH_DECOMPOSE_I1(8, 64, 4);
+      else return DQ_EINVAL;
+    }
+  } else if (((fmt->head_dim == 128 && fmt->j1 == 16) || pair_heads) && !force_general) {
     // At most one workgroup per compute unit (256 on the chip) gets more waves per block: the
     // eigen-solver wave is issue-bound and slows down when two of them share a SIMD.
 #define DQ_LAUNCH_D16(N_)                                                                                     \
@@ -1275,6 +1315,7 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
     else DQ_LAUNCH_DECOMPOSE(32, 64);
   }
 #undef DQ_LAUNCH_DECOMPOSE
+#undef DQ_LAUNCH_DECOMPOSE_I1
   DQ_HIP_CHECK(hipGetLastError());
   if (fmt->i3 == kRun) {   // three local tensors: cut the right factor again before it is quantized
     if (fmt->head_dim == 128)

@@ -207,6 +207,200 @@ __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
   if (tid == 0) { part[d] = m_run; part[d + 1] = l_run; }
 }
 
+// The same computation for formats with a token factor on the small tensor (format.i1 = I1 > 1;
+// Eq. 2 with n = 2, i_1 > 1).  Token t = a1*i2 + a2 of a block, bond index r = rho*j1 + r':
+//   q'_a1[r, b2] = scale * sum_b1 T_S^K[(a1, b1), r] q[b1, b2]              (I1 folded queries)
+//   s_(a1, a2)   = sum_rho sum_c' step^K[row] code^K[row, c'] q'_a1[rho*d + c'],   row = a2*I1 + rho
+//   o'_a1[r, b2] = sum_a2 p_(a1, a2) step^V[row] code^V[row, r'*j2 + b2]
+//   acc[b1, b2]  = alpha * acc[b1, b2] + sum_a1 sum_r T_S^V[(a1, b1), r] o'_a1[r, b2]
+// A tile of 128 rows holds 128 / I1 positions a2 and gives the scores of 128 tokens, I1 runs of
+// 128 / I1 consecutive ones.  A token's rows lie all over its block, so a block with a valid token
+// is worked whole.
+template <int BITS, int I1>
+__global__ __launch_bounds__(256) void decode_generic_i1_kernel(DecodeArgs a) {
+  const Geometry g = make_geometry(a.fmt, a.cache.kv_heads, a.cache.block_capacity);
+  const int d = g.d, j1 = g.j1, j2 = g.j2, G = g.G;
+  const int N = I1 * j1;           // side of the small tensor, <= 32
+  const int i2 = g.Tb / I1;
+  constexpr int PPT = kTileTokens / I1;   // positions a2 per tile
+  const int split = blockIdx.x;
+  const int bhq = blockIdx.y;
+  const int b = bhq / a.q_heads, hq = bhq % a.q_heads;
+  const int rep = a.q_heads / g.H;
+  const int h = hq / rep;
+  const int tid = threadIdx.x;
+  const int S = min(max(a.seq_lens[b], 0), a.max_seq_len);
+  const int tpb = g.tiles_per_block;
+  const int tiles_total = (S + g.Tb - 1) / g.Tb * tpb;            // whole blocks
+  const int max_tiles = (a.max_seq_len + g.Tb - 1) / g.Tb * tpb;
+  const int tps = (max_tiles + a.n_split - 1) / a.n_split;
+  const int tile_begin = split * tps;
+  const int tile_end = min(tile_begin + tps, tiles_total);
+
+  __shared__ float qs[128];                 // the query as fp32
+  __shared__ float qf[I1 * I1 * 128];       // folded queries q'_a1[rho*d + c']
+  __shared__ float ys[I1][kTileTokens];     // row sums per a1
+  __shared__ float sc[kTileTokens];         // scores, then weights, token index a1*PPT + a2 - a2_0
+  __shared__ float red[8];
+  __shared__ float opart[4][I1 * I1][128];  // [token part][a1*I1 + rho][c']
+  __shared__ float sK[32 * 32];             // T_S^K as stored: [r][(a1, b1)]
+  __shared__ float sV[32 * 32];             // T_S^V as stored: [(a1, b1)][r]
+
+  if (tid < d) qs[tid] = h2f(a.q[(long)bhq * d + tid]);
+  float acc = 0.f;                 // thread c < d owns output channel c = b1*j2 + b2
+  float m_run = -INFINITY, l_run = 0.f;
+  const long bh = (long)b * g.H + h;
+  int cur_blk = -1;
+  const int nparts = 256 / d;      // row parts in the value phase
+  const int seg = d / 2;
+  __syncthreads();
+
+  for (int tile = tile_begin; tile < tile_end; ++tile) {
+    const int blk = tile / tpb;
+    const int tib = tile % tpb;
+    const long blkid = bh * g.NB + blk;
+    if (blk != cur_blk) {
+      cur_blk = blk;
+      const uint16_t* ks = a.cache.k_small + blkid * g.small_per_block;
+      const uint16_t* vs = a.cache.v_small + blkid * g.small_per_block;
+      for (int i = tid; i < N * N; i += blockDim.x) { sK[i] = h2f(ks[i]); sV[i] = h2f(vs[i]); }
+      __syncthreads();
+      for (int i = tid; i < I1 * N * j2; i += blockDim.x) {
+        const int a1 = i / (N * j2), r = (i / j2) % N, b2 = i % j2;
+        float s = 0.f;
+        for (int b1 = 0; b1 < j1; ++b1) s = fmaf(sK[r * N + a1 * j1 + b1], qs[b1 * j2 + b2], s);
+        qf[i] = s * a.scale;       // index a1*(I1*d) + rho*d + r'*j2 + b2
+      }
+      __syncthreads();
+    }
+    const int a2_0 = tib * PPT;    // the tile's first position
+    // ---- row sums: two threads per row, each one half row, against every folded query ----
+    {
+      const int tt = tid >> 1, half = tid & 1;
+      const int a2 = a2_0 + tt / I1, rho = tt % I1;
+      const int row = tib * kTileTokens + tt;
+      float y[I1];
+#pragma unroll
+      for (int a1 = 0; a1 < I1; ++a1) y[a1] = 0.f;
+      // a row is needed as soon as its position holds a valid token; a1 = 0 is the first of them
+      if (blk * g.Tb + a2 < S) {
+        const uint8_t* rowp = a.cache.k_codes + blkid * g.codes_per_block + (long)row * g.row_bytes;
+        const uint16_t* scp = a.cache.k_scales + blkid * g.scales_per_block + (long)row * g.groups;
+        const uint32_t* words = reinterpret_cast<const uint32_t*>(rowp) + half * seg * BITS / 32;
+#pragma unroll
+        for (int a1 = 0; a1 < I1; ++a1) {
+          const float* qa = qf + (a1 * I1 + rho) * d + half * seg;
+          if (G >= seg) {
+            y[a1] = h2f(scp[(half * seg) / G]) * dot_codes<BITS>(words, qa, seg);
+          } else {
+            const int gps = seg / G;
+            for (int k = 0; k < gps; ++k)
+              y[a1] = fmaf(h2f(scp[half * gps + k]), dot_codes<BITS>(words + k * G * BITS / 32, qa + k * G, G), y[a1]);
+          }
+        }
+      }
+#pragma unroll
+      for (int a1 = 0; a1 < I1; ++a1) {
+        y[a1] += __shfl_xor(y[a1], 1);
+        if (half == 0) ys[a1][tt] = y[a1];
+      }
+    }
+    __syncthreads();
+    // ---- scores of the tile's 128 tokens: token (a1, a2) sums its position's I1 rows ----
+    if (tid < kTileTokens) {
+      const int a1 = tid / PPT, pl = tid % PPT;
+      const int t = blk * g.Tb + a1 * i2 + a2_0 + pl;
+      float s = -INFINITY;
+      if (t < S) {
+        s = 0.f;
+#pragma unroll
+        for (int rho = 0; rho < I1; ++rho) s += ys[a1][pl * I1 + rho];
+      }
+      sc[tid] = s;
+    }
+    __syncthreads();
+    // ---- tile max ----
+    float v = (tid < kTileTokens) ? sc[tid] : -INFINITY;
+    for (int o = 32; o > 0; o >>= 1) v = fmaxf(v, __shfl_xor(v, o));
+    if ((tid & 63) == 0) red[tid >> 6] = v;
+    __syncthreads();
+    const float m_tile = fmaxf(fmaxf(red[0], red[1]), fmaxf(red[2], red[3]));
+    const float m_new = fmaxf(m_run, m_tile);
+    // a tile of a partly valid block may hold no valid token at all: nothing moves then
+    const float alpha = (m_new == -INFINITY) ? 1.f : __expf(m_run - m_new);
+    __syncthreads();
+    float p = 0.f;
+    if (tid < kTileTokens) {
+      p = (m_new == -INFINITY) ? 0.f : __expf(sc[tid] - m_new);
+      sc[tid] = p;
+    }
+    float ps = p;
+    for (int o = 32; o > 0; o >>= 1) ps += __shfl_xor(ps, o);
+    if ((tid & 63) == 0) red[4 + (tid >> 6)] = ps;
+    __syncthreads();
+    l_run = l_run * alpha + (red[4] + red[5] + red[6] + red[7]);
+    m_run = m_new;
+    // ---- values: thread (c', part) accumulates its share of the tile's rows, per (a1, rho) ----
+    {
+      const int cp = tid % d, part = tid / d;
+      const int r = cp / j2, b2 = cp % j2;
+      const int gi = cp / G;
+      const uint8_t* vrow = a.cache.v_codes + blkid * g.codes_per_block +
+                            ((long)(tib * j2 + b2) * j1 + r) * g.vrow_bytes;
+      const uint16_t* vsc = a.cache.v_scales + blkid * g.scales_per_block +
+                            (long)tib * kTileTokens * g.groups;
+      const int rows_per_part = kTileTokens / nparts;
+      const int t0 = part * rows_per_part;
+      constexpr int PER = 32 / BITS;            // a multiple of I1
+      constexpr int MASK = (1 << BITS) - 1;
+      constexpr int BIAS = 1 << (BITS - 1);
+      static_assert(PER % I1 == 0, "a word of codes holds whole positions");
+      const uint32_t* words = reinterpret_cast<const uint32_t*>(vrow) + t0 / PER;
+      float o[I1][I1];
+#pragma unroll
+      for (int a1 = 0; a1 < I1; ++a1)
+#pragma unroll
+        for (int rho = 0; rho < I1; ++rho) o[a1][rho] = 0.f;
+      for (int w = 0; w < rows_per_part / PER; ++w) {
+        const uint32_t x = words[w];
+#pragma unroll
+        for (int k = 0; k < PER; ++k) {
+          const int tt = t0 + w * PER + k;      // row in the tile: position tt / I1, slice k % I1
+          const float code = (float)((int)((x >> (k * BITS)) & MASK) - BIAS);
+#pragma unroll
+          for (int a1 = 0; a1 < I1; ++a1) {
+            const float pt = sc[a1 * PPT + tt / I1];
+            if (pt != 0.f)   // rows of positions without a valid token may carry any step bits
+              o[a1][k % I1] = fmaf(pt * h2f(vsc[(long)tt * g.groups + gi]), code, o[a1][k % I1]);
+          }
+        }
+      }
+#pragma unroll
+      for (int a1 = 0; a1 < I1; ++a1)
+#pragma unroll
+        for (int rho = 0; rho < I1; ++rho) opart[part][a1 * I1 + rho][cp] = o[a1][rho];
+    }
+    __syncthreads();
+    if (tid < d) {
+      const int b1 = tid / j2, b2 = tid % j2;
+      float s = 0.f;
+      for (int a1 = 0; a1 < I1; ++a1) {
+        for (int r = 0; r < N; ++r) {
+          const int rho = r / j1, rp = r % j1;
+          float o = 0.f;
+          for (int part = 0; part < nparts; ++part) o += opart[part][a1 * I1 + rho][rp * j2 + b2];
+          s = fmaf(sV[(a1 * j1 + b1) * N + r], o, s);
+        }
+      }
+      acc = acc * alpha + s;
+    }
+    __syncthreads();
+  }
+  float* part = a.partials + ((long)bhq * a.n_slots + split) * (d + 2);
+  if (tid < d) part[tid] = acc;
+  if (tid == 0) { part[d] = m_run; part[d + 1] = l_run; }
+}
+
 // Merge split partials: out = sum_s acc_s e^{m_s - M} / sum_s l_s e^{m_s - M}.
 __global__ void combine_kernel(const float* __restrict__ partials, int n_split, int d,
                                uint16_t* __restrict__ out, float* __restrict__ out_f32) {
@@ -279,6 +473,21 @@ int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st) {
   }
   const dim3 grid(a.n_split, a.cache.batch * a.q_heads);
   // the events, when given, receive the streaming kernel's own begin and end timestamps
+  if (a.fmt.i1 > 1) {   // a token factor on the small tensor
+#define DQ_LAUNCH_I1(B_)                                                                                          \
+  do {                                                                                                            \
+    if (a.fmt.i1 == 2)                                                                                            \
+      hipExtLaunchKernelGGL((decode_generic_i1_kernel<B_, 2>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); \
+    else                                                                                                          \
+      hipExtLaunchKernelGGL((decode_generic_i1_kernel<B_, 4>), grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); \
+  } while (0)
+    if (a.fmt.bits == 2) DQ_LAUNCH_I1(2);
+    else if (a.fmt.bits == 4) DQ_LAUNCH_I1(4);
+    else DQ_LAUNCH_I1(8);
+#undef DQ_LAUNCH_I1
+    DQ_HIP_CHECK(hipGetLastError());
+    return launch_combine(a, st);
+  }
   switch (a.fmt.bits) {
     case 2: hipExtLaunchKernelGGL(decode_generic_kernel<2>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;
     case 4: hipExtLaunchKernelGGL(decode_generic_kernel<4>, grid, dim3(256), 0, st, a.ev_start, a.ev_stop, 0, a); break;

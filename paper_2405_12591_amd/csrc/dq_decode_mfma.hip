@@ -21,11 +21,12 @@ static int heads_per_workgroup(const dq_format* f, int rep) {
 // heads, two local tensors.
 bool mfma_pair_heads(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads != kv_heads || (kv_heads & 1)) return false;
-  return f->head_dim == 64 && f->j1 == 8 && f->j2 == 8 && f->group == 64 && f->i3 == 1;
+  return f->head_dim == 64 && f->j1 == 8 && f->j2 == 8 && f->group == 64 && f->i3 == 1 && f->i1 == 1;
 }
 
 bool mfma_supported(const dq_format* f, int q_heads, int kv_heads) {
   if (!format_ok(f) || kv_heads <= 0 || q_heads <= 0 || q_heads % kv_heads) return false;
+  if (f->i1 != 1) return false;   // a token factor on the small tensor: the plain kernel's
   if (mfma_pair_heads(f, q_heads, kv_heads)) return true;
   if (f->head_dim != 128 || f->j1 != 16 || f->j2 != 8) return false;
   if (f->bits != 8 && f->bits != 4 && f->bits != 2) return false;

@@ -14,12 +14,12 @@
   } while (0)
 
 int main(void) {
-  dq_format fmt = {4, 128, 128, 16, 8, 128, 1, 0};
-  dq_format bad = {3, 128, 128, 16, 8, 128, 1, 0};
+  dq_format fmt = {4, 128, 128, 16, 8, 128, 1, 0, 1};
+  dq_format bad = {3, 128, 128, 16, 8, 128, 1, 0, 1};
   dq_cache cache;
   char fake[64];
   memset(&cache, 0, sizeof cache);
-  CHECK(dq_version() == 4);
+  CHECK(dq_version() == 5);
   CHECK(strcmp(dq_status_string(DQ_OK), "ok") == 0);
   CHECK(dq_decode_workspace_bytes(&fmt, 8, 32, 32, 4096) > 0);
   CHECK(dq_decode_workspace_bytes(&bad, 8, 32, 32, 4096) == 0);

@@ -9,7 +9,7 @@ DEV = "cuda:0"
 
 
 def formats(w):
-    args = (w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels)
+    args = (w.bits, w.group, w.head_dim, w.j1, w.j2, w.block_tokens, w.i3, w.levels, w.i1)
     return dq.Format(*args), O.Format(*args)
 
 
@@ -42,6 +42,8 @@ def _poison_tail(cache, ofmt, b, h, n, r):
     tb = ofmt.block_tokens
     blk, row = (n - 1) // tb, (n - 1) % tb + 1
     row = -(-row // ofmt.i3) * ofmt.i3   # three tensors: the rows of a run with a valid token all count
+    if ofmt.i1 > 1:
+        return                           # a token factor: every row of a block with a valid token counts
     if row >= tb:
         return
     cache["k_codes"][b, h, blk, row:] = r.integers(0, 256, size=cache["k_codes"][b, h, blk, row:].shape, dtype=np.uint8)

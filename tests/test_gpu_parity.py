@@ -201,7 +201,7 @@ def _check_compress(w, t_new, n_valid, waves=0):
                 x[:n_ok] = x_all[b, h, :n_ok].astype(np.float64)
                 small, steps, codes = O.load_block(arrs, ofmt, b, h, slot, which)
                 kp = large[(b * w.kv_heads + h) * 2 + (which == "v")]
-                t_l = O.token_major_to_large(kp.astype(np.float64), j1, j2)
+                t_l = O.token_major_to_large(kp.astype(np.float64), j1, j2, ofmt.i1)
                 # (1) rows of T_L orthonormal (or zero for dropped directions)
                 gram = t_l @ t_l.T
                 diag = np.diag(gram)
@@ -209,7 +209,7 @@ def _check_compress(w, t_new, n_valid, waves=0):
                 worst_ortho = max(worst_ortho, np.abs(gram - np.diag(live.astype(np.float64))).max())
                 assert worst_ortho <= 2e-6, (b, h, which)     # fp32 storage of T_L allows about 1e-6
                 # (2) exact factorisation up to the fp16 rounding of T_S and fp32 of T_L
-                m = O.matricise(x, 1, j1)
+                m = O.matricise(x, ofmt.i1, j1)
                 resid = np.abs(small.astype(np.float64) @ t_l - m)
                 slack = 2.0 ** -10 * (np.abs(small.astype(np.float64)) @ np.abs(t_l)) + 1e-6 * np.abs(m).max() + 1e-7
                 assert (resid <= slack).all(), (b, h, which, resid.max())
@@ -221,7 +221,7 @@ def _check_compress(w, t_new, n_valid, waves=0):
                 # (4) reconstruction within the half-step bound
                 x_hat = O.reconstruct_block(small, steps, codes, ofmt)
                 bound = O.reconstruction_bound(small, steps, ofmt)
-                slack_x = O.unmatricise(slack, tb, d, 1, j1)
+                slack_x = O.unmatricise(slack, tb, d, ofmt.i1, j1)
                 assert (np.abs(x_hat - x) <= bound + slack_x).all(), (b, h, which)
                 # (5) other block slots of this head untouched
                 for other in range(nb):

@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol(dq):
 
 
 def test_status_strings_and_version(dq):
-    assert dq.version() == dq.ABI_VERSION == 4
+    assert dq.version() == dq.ABI_VERSION == 5
     assert dq.status_string(0) == "ok"
     assert "workspace" in dq.status_string(-2)
     assert "invalid" in dq.status_string(-1)
@@ -42,7 +42,9 @@ def test_workspace_queries_validate_the_format(dq):
     for bad in [dq.Format(3, 128, 128, 16, 8, 128), dq.Format(4, 128, 128, 16, 4, 128),
                 dq.Format(4, 96, 128, 16, 8, 128), dq.Format(4, 128, 128, 16, 8, 100),
                 dq.Format(4, 128, 256, 16, 16, 128), dq.Format(4, 128, 128, 16, 8, 128, 4),
-                dq.Format(4, 128, 128, 16, 8, 128, 1, 2)]:
+                dq.Format(4, 128, 128, 16, 8, 128, 1, 2), dq.Format(4, 128, 128, 16, 8, 128, 1, 0, 3),
+                dq.Format(4, 128, 128, 16, 8, 128, 8, 0, 2), dq.Format(4, 128, 128, 16, 8, 128, 1, 0, 4),
+                dq.Format(4, 128, 128, 16, 8, 128, 1, 0, 0)]:
         c = bad.c()
         assert dq.lib.dq_decode_workspace_bytes(C.byref(c), 8, 32, 32, 4096) == 0
         assert dq.lib.dq_compress_workspace_bytes(C.byref(c), 4, 40) == 0

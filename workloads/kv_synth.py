@@ -43,6 +43,7 @@ class Workload:
     append_tokens: int = 0  # tokens appended (and compressed) before the decode step
     i3: int = 1             # 8: three local tensors (the third one 8 x 8 on the token side)
     levels: int = 0         # 1: the quantizer's non-default level set (all 2^bits codes)
+    i1: int = 1             # 2 or 4: a token factor on the small tensor (Eq. 2 with i_1 > 1)
 
 
 WORKLOADS = {
