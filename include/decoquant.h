@@ -305,6 +305,56 @@ int32_t dq_compress_kv_ex(const dq_format* fmt, dq_cache* cache, const uint16_t*
                           uint32_t flags, void* hip_stream);
 
 /*
+ * The cache policy of Section 3.2 ("KV Cache Quantization") with every decision on the device: new
+ * key/value rows are buffered in fp16 (the tail), and a sequence's tail is compressed into its next
+ * block slot as soon as it holds block_tokens rows.  The state below, all device memory owned by
+ * the caller, together with the dq_cache is one layer's complete cache; the host keeps no mirror of
+ * the lengths and reads nothing back, so a step (append, then decode) can be captured in a graph
+ * and replayed across block boundaries.
+ *   k_tail, v_tail  f16 [B, H, block_tokens, d]   rows not yet compressed (16-byte aligned)
+ *   tail_lens       i32 [B]   rows in the tail, 0 <= tail_lens[b] < block_tokens between calls
+ *   seq_lens        i32 [B]   compressed tokens, a multiple of block_tokens
+ * Decoding over the whole cache is dq_attn_decode_tail (or dq_attn_decode_static) with seq_lens and
+ * the tail {k_tail, v_tail, tail_lens, capacity = block_tokens}.  block_tokens <= 1024.
+ */
+typedef struct dq_kv_state {
+  uint16_t* k_tail;
+  uint16_t* v_tail;
+  int32_t* tail_lens;
+  int32_t* seq_lens;
+} dq_kv_state;
+
+/* Flags of dq_cache_append. */
+#define DQ_APPEND_NO_COMPRESS 1u /* the caller knows that no tail can fill in this call (every tail length +
+                                    n_rows < block_tokens): the compression launch is left out.  Should a
+                                    tail fill all the same, bit 1 of the status word below is set, that tail
+                                    stays full and the rows that do not fit are dropped. */
+
+/* Bytes of workspace dq_cache_append needs (0 on invalid arguments): the workspace of dq_compress_kv
+ * followed by four int32 per sequence.  It must be zeroed once before its first use
+ * (dq_workspace_init) and belongs to the calls of one cache, ordered on one stream. */
+size_t dq_cache_append_workspace_bytes(const dq_format* fmt, int32_t batch, int32_t kv_heads);
+
+/*
+ * Append rows to the sequences of a layer (Section 3.2: the rows a decoding step generates, or a
+ * piece of a prompt): sequence b takes the first counts[b] of the n_rows rows given for it.
+ *   k_rows, v_rows  f16 [B, H, n_rows, d], 1 <= n_rows <= block_tokens (host integer), 16-byte aligned
+ *   counts          i32 [B] device, clamped to [0, n_rows]; NULL: every sequence takes all n_rows
+ * Enqueues, on `hip_stream`: a copy of the rows that fit behind each tail's end, which also moves
+ * the lengths; dq_compress_kv (fp32 large tensors not kept) of every tail that has reached
+ * block_tokens rows into slot seq_lens[b] / block_tokens, after which seq_lens[b] has grown by
+ * block_tokens; and, when n_rows > 1, a copy of the rows that did not fit to the start of the emptied
+ * tail.  Sequences whose tail did not fill are skipped by the compression.  Status: the int32 at
+ * byte 12 of the workspace gets bit 0 set (and keeps it) when a tail filled but the cache had no free
+ * block slot; that tail then stays full and further rows for it are dropped.  Bytes 0..7 are the
+ * status words of the last compression as dq_compress_kv documents them.
+ */
+int32_t dq_cache_append(const dq_format* fmt, dq_cache* cache, const dq_kv_state* state,
+                        const uint16_t* k_rows, const uint16_t* v_rows, int32_t n_rows,
+                        const int32_t* counts, void* workspace, size_t workspace_bytes, uint32_t flags,
+                        void* hip_stream);
+
+/*
  * Quantize and pack a caller-supplied large tensor (Preliminary, Eq. 1 per group; Section 3.1
  * step 2).  step = fp16(max|x| / qmax), the exact quotient rounded once, ties to even;
  * code = clamp(nearest integer of the exact x / step, ties to even, +-qmax); step == 0 gives

@@ -28,6 +28,9 @@ from .binding import (  # noqa: F401
     attn_decode,
     compress_kv,
     compress_kv_blocks,
+    cache_append,
+    cache_append_workspace,
+    APPEND_NO_COMPRESS,
     quantize_pack,
     stream_read,
     decode_mfma_supported,

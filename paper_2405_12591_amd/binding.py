@@ -11,7 +11,7 @@ import torch
 from . import build as _build
 
 DECODE_AUTO = 0
-ABI_VERSION = 5   # dq_version() of the library whose struct layouts this file mirrors
+ABI_VERSION = 6   # dq_version() of the library whose struct layouts this file mirrors
 COMPRESS_NO_LARGE = 1
 COMPRESS_PLAIN = 2
 DECODE_FORCE_GENERIC = 1
@@ -33,7 +33,7 @@ EXPORTED_SYMBOLS = [
     "dq_decode_workspace_bytes", "dq_workspace_init", "dq_attn_decode", "dq_attn_decode_timed", "dq_attn_decode_tail",
     "dq_attn_decode_static",
     "dq_compress_workspace_bytes", "dq_compress_kv", "dq_compress_blocks_workspace_bytes", "dq_compress_kv_blocks",
-    "dq_compress_kv_ex",
+    "dq_compress_kv_ex", "dq_cache_append_workspace_bytes", "dq_cache_append",
     "dq_quantize_pack", "dq_stream_read",
 ]
 
@@ -103,6 +103,11 @@ def _load() -> C.CDLL:
     l.dq_compress_kv_blocks.argtypes = l.dq_compress_kv.argtypes
     l.dq_compress_kv_ex.restype = C.c_int32
     l.dq_compress_kv_ex.argtypes = l.dq_compress_kv.argtypes[:-1] + [C.c_uint32, C.c_void_p]
+    l.dq_cache_append_workspace_bytes.restype = C.c_size_t
+    l.dq_cache_append_workspace_bytes.argtypes = [C.POINTER(_CFormat), C.c_int32, C.c_int32]
+    l.dq_cache_append.restype = C.c_int32
+    l.dq_cache_append.argtypes = [C.POINTER(_CFormat), C.POINTER(_CCache), C.c_void_p, C.c_void_p, C.c_void_p,
+                                  C.c_int32, C.c_void_p, C.c_void_p, C.c_size_t, C.c_uint32, C.c_void_p]
     l.dq_quantize_pack.restype = C.c_int32
     l.dq_quantize_pack.argtypes = [C.POINTER(_CFormat), C.c_void_p, C.c_int64, C.c_int32, C.c_void_p,
                                    C.c_void_p, C.c_void_p]
@@ -408,11 +413,57 @@ def decode_mfma_supported(fmt: Format, q_heads: int, kv_heads: int) -> bool:
     return bool(lib.dq_decode_mfma_supported(C.byref(cf), q_heads, kv_heads))
 
 
+class _CKVState(C.Structure):
+    _fields_ = [("k_tail", C.c_void_p), ("v_tail", C.c_void_p), ("tail_lens", C.c_void_p), ("seq_lens", C.c_void_p)]
+
+
+APPEND_NO_COMPRESS = 1
+
+
+def cache_append_workspace(fmt: Format, batch: int, kv_heads: int, device="cuda:0") -> torch.Tensor:
+    cf = fmt.c()
+    n = lib.dq_cache_append_workspace_bytes(C.byref(cf), batch, kv_heads)
+    if n == 0:
+        raise DQError("dq_cache_append_workspace_bytes rejected the arguments")
+    ws = torch.empty((n + 15) // 16 * 16, dtype=torch.uint8, device=device)
+    workspace_init(ws)
+    return ws
+
+
+def cache_append(cache: Cache, k_tail: torch.Tensor, v_tail: torch.Tensor, tail_lens: torch.Tensor,
+                 seq_lens: torch.Tensor, k_rows: torch.Tensor, v_rows: torch.Tensor,
+                 counts: Optional[torch.Tensor], workspace: torch.Tensor, flags: int = 0) -> None:
+    """Append k_rows, v_rows [B, H, n_rows, d] (sequence b takes the first counts[b]) to the fp16
+    tails and compress every tail that fills, all decided on the device (dq_cache_append)."""
+    fmt = cache.fmt
+    want_tail = (cache.batch, cache.kv_heads, fmt.block_tokens, fmt.head_dim)
+    for name, t in (("k_tail", k_tail), ("v_tail", v_tail)):
+        if t.dtype != torch.float16 or not t.is_contiguous() or tuple(t.shape) != want_tail:
+            raise DQError("%s must be contiguous fp16 [batch, kv_heads, block_tokens, head_dim]" % name)
+    for name, t in (("tail_lens", tail_lens), ("seq_lens", seq_lens), ("counts", counts)):
+        if t is not None and (t.dtype != torch.int32 or t.numel() != cache.batch or not t.is_contiguous()):
+            raise DQError("%s must hold one int32 per sequence" % name)
+    for t in (k_rows, v_rows):
+        if t.dtype != torch.float16 or not t.is_contiguous():
+            raise DQError("k_rows/v_rows must be contiguous fp16")
+    if k_rows.dim() != 4 or k_rows.shape != v_rows.shape or tuple(k_rows.shape[:2]) != want_tail[:2] \
+            or k_rows.shape[3] != fmt.head_dim or not 1 <= k_rows.shape[2] <= fmt.block_tokens:
+        raise DQError("k_rows/v_rows must be [batch, kv_heads, n_rows <= block_tokens, head_dim]")
+    cf = fmt.c()
+    state = _CKVState(k_tail.data_ptr(), v_tail.data_ptr(), tail_lens.data_ptr(), seq_lens.data_ptr())
+    st = lib.dq_cache_append(C.byref(cf), C.byref(cache.c), C.byref(state), k_rows.data_ptr(), v_rows.data_ptr(),
+                             k_rows.shape[2], 0 if counts is None else counts.data_ptr(), workspace.data_ptr(),
+                             workspace.numel(), flags, _stream_ptr(k_rows.device))
+    _check(st, "dq_cache_append")
+
+
 class KVCacheLayer:
     """One layer's KV cache under the paper's policy (Section 3.2): new key/value rows go to an
     fp16 tail; whenever a sequence's tail holds a whole block it is compressed into the next block
-    slot; decode attends to the compressed blocks and the tail.  Host bookkeeping only: the
-    compression and the attention run in the library's kernels."""
+    slot; decode attends to the compressed blocks and the tail.  The lengths live on the device and
+    every decision is taken there (dq_cache_append); this class only holds the tensors and passes
+    pointers.  The one thing the host tracks is an upper bound on the rows any sequence can hold,
+    which sizes the decode launch."""
 
     def __init__(self, fmt: Format, batch: int, q_heads: int, kv_heads: int, max_tokens: int, device="cuda:0"):
         self.fmt, self.batch, self.q_heads, self.kv_heads, self.device = fmt, batch, q_heads, kv_heads, device
@@ -421,75 +472,82 @@ class KVCacheLayer:
         self.cache = alloc_cache(fmt, batch, kv_heads, self.capacity_blocks, device)
         self.k_tail = torch.zeros((batch, kv_heads, tb, fmt.head_dim), dtype=torch.float16, device=device)
         self.v_tail = torch.zeros_like(self.k_tail)
-        self.n_blocks = [0] * batch          # compressed blocks per sequence (host mirror)
-        self.n_tail = [0] * batch            # tail rows per sequence (host mirror)
-        self.seq_lens = torch.zeros(batch, dtype=torch.int32, device=device)
-        self.tail_lens = torch.zeros(batch, dtype=torch.int32, device=device)
+        self.seq_lens = torch.zeros(batch, dtype=torch.int32, device=device)    # compressed tokens per sequence
+        self.tail_lens = torch.zeros(batch, dtype=torch.int32, device=device)   # rows in the fp16 tail
         self.ws_decode = decode_workspace(fmt, batch, q_heads, kv_heads, self.capacity_blocks * tb, device)
-        self.ws_compress = compress_workspace(fmt, batch, kv_heads, device)
+        self.ws_append = cache_append_workspace(fmt, batch, kv_heads, device)
+        self._ws_prefill = None
+        self.rows_upper = 0                  # no sequence holds more rows than this (host-side bound)
+
+    # ---- the device-side lengths, read back (tests and diagnostics; not used on the step path) ----
+    @property
+    def n_blocks(self):
+        return (self.seq_lens // self.fmt.block_tokens).tolist()
+
+    @property
+    def n_tail(self):
+        return self.tail_lens.tolist()
+
+    @property
+    def status(self) -> int:
+        """Bit 0: a tail filled while its sequence had no free block slot (rows were dropped)."""
+        return int(self.ws_append[12:16].view(torch.int32).item())
 
     def append(self, k_new: torch.Tensor, v_new: torch.Tensor, counts=None) -> None:
         """Append rows k_new, v_new [B, H_kv, n, d]; sequence b takes the first counts[b] rows
-        (default: all n).  Full tails are compressed on the way."""
+        (counts: int32 device tensor, a list, or None for all n).  Full tails are compressed on the way."""
         tb = self.fmt.block_tokens
         n = k_new.shape[2]
-        counts = [n] * self.batch if counts is None else list(counts)
-        done = [0] * self.batch
-        while any(done[b] < counts[b] for b in range(self.batch)):
-            for b in range(self.batch):
-                take = min(counts[b] - done[b], tb - self.n_tail[b])
-                if take > 0:
-                    self.k_tail[b, :, self.n_tail[b]:self.n_tail[b] + take] = k_new[b, :, done[b]:done[b] + take]
-                    self.v_tail[b, :, self.n_tail[b]:self.n_tail[b] + take] = v_new[b, :, done[b]:done[b] + take]
-                    self.n_tail[b] += take
-                    done[b] += take
-            full = [b for b in range(self.batch) if self.n_tail[b] == tb]
-            if full:
-                self._compress(full)
-        self.tail_lens.copy_(torch.tensor(self.n_tail, dtype=torch.int32))
+        if counts is not None and not torch.is_tensor(counts):
+            counts = torch.tensor(list(counts), dtype=torch.int32, device=self.device)
+        for lo in range(0, n, tb):           # at most one block's worth of rows per call
+            hi = min(n, lo + tb)
+            kr, vr = k_new[:, :, lo:hi], v_new[:, :, lo:hi]
+            if not kr.is_contiguous():
+                kr, vr = kr.contiguous(), vr.contiguous()
+            c = None if counts is None else torch.clamp(counts - lo, 0, hi - lo).to(torch.int32)
+            cache_append(self.cache, self.k_tail, self.v_tail, self.tail_lens, self.seq_lens, kr, vr, c, self.ws_append)
+        self.rows_upper += n
 
     def prefill(self, k_new: torch.Tensor, v_new: torch.Tensor, counts=None) -> None:
-        """Append the rows of a prompt, k_new, v_new [B, H_kv, n, d], to empty sequences; sequence b
+        """Append the rows of a prompt, k_new, v_new [B, H_kv, n, d], to EMPTY sequences; sequence b
         takes the first counts[b] rows (default: all n).  The whole blocks of all sequences are
-        compressed by one dq_compress_kv_blocks call, the rest goes to the tails."""
-        if any(self.n_blocks) or any(self.n_tail):
+        compressed by one dq_compress_kv_ex call, the rest goes to the tails."""
+        if self.rows_upper:
             raise DQError("prefill needs empty sequences; use append")
         tb = self.fmt.block_tokens
         n = k_new.shape[2]
-        counts = [n] * self.batch if counts is None else list(counts)
-        whole = [c // tb for c in counts]
-        if max(whole) > self.capacity_blocks:
+        if n // tb > self.capacity_blocks:
             raise DQError("the prompt exceeds the cache capacity")
-        if max(whole) > 0:
-            rows = max(whole) * tb
-            ws = compress_workspace(self.fmt, self.batch, self.kv_heads, self.device, t_new=rows)
-            first = torch.tensor([0 if w else -1 for w in whole], dtype=torch.int32, device=self.device)
-            valid = torch.tensor([w * tb for w in whole], dtype=torch.int32, device=self.device)
+        if counts is None:
+            counts = torch.full((self.batch,), n, dtype=torch.int32, device=self.device)
+        elif not torch.is_tensor(counts):
+            counts = torch.tensor(list(counts), dtype=torch.int32, device=self.device)
+        counts = torch.clamp(counts, 0, n).to(torch.int32)
+        whole = (counts // tb) * tb                                     # rows that fill whole blocks
+        if n >= tb:
+            rows = (n // tb) * tb
+            if self._ws_prefill is None or self._ws_prefill[0] != rows:
+                self._ws_prefill = (rows, compress_workspace(self.fmt, self.batch, self.kv_heads, self.device, t_new=rows))
+            first = torch.where(whole > 0, torch.zeros_like(whole), torch.full_like(whole, -1))
             compress_kv_blocks(self.cache, k_new[:, :, :rows].contiguous(), v_new[:, :, :rows].contiguous(),
-                               first, valid, ws)
-        for b in range(self.batch):
-            rest = counts[b] - whole[b] * tb
-            if rest:
-                self.k_tail[b, :, :rest] = k_new[b, :, whole[b] * tb:counts[b]]
-                self.v_tail[b, :, :rest] = v_new[b, :, whole[b] * tb:counts[b]]
-            self.n_blocks[b], self.n_tail[b] = whole[b], rest
-        self.seq_lens.copy_(torch.tensor([nb * tb for nb in self.n_blocks], dtype=torch.int32))
-        self.tail_lens.copy_(torch.tensor(self.n_tail, dtype=torch.int32))
+                               first, whole, self._ws_prefill[1], keep_large=False)
+            self.seq_lens.copy_(whole)
+        # what is left of every prompt (fewer than block_tokens rows) goes to the tails
+        width = min(tb, n)
+        idx = torch.clamp(whole.long()[:, None] + torch.arange(width, device=self.device)[None, :], max=n - 1)
+        idx = idx[:, None, :, None].expand(self.batch, self.kv_heads, width, self.fmt.head_dim)
+        cache_append(self.cache, self.k_tail, self.v_tail, self.tail_lens, self.seq_lens,
+                     torch.gather(k_new, 2, idx).contiguous(), torch.gather(v_new, 2, idx).contiguous(),
+                     (counts - whole).to(torch.int32), self.ws_append, flags=APPEND_NO_COMPRESS)   # fewer than a block each
+        self.rows_upper = n
 
-    def _compress(self, seqs) -> None:
-        idx = [-1] * self.batch
-        for b in seqs:
-            if self.n_blocks[b] >= self.capacity_blocks:
-                raise DQError("sequence %d exceeds the cache capacity" % b)
-            idx[b] = self.n_blocks[b]
-        blk_idx = torch.tensor(idx, dtype=torch.int32, device=self.device)
-        compress_kv(self.cache, self.k_tail, self.v_tail, blk_idx, None, self.ws_compress, keep_large=False)
-        for b in seqs:
-            self.n_blocks[b] += 1
-            self.n_tail[b] = 0
-        self.seq_lens.copy_(torch.tensor([nb * self.fmt.block_tokens for nb in self.n_blocks], dtype=torch.int32))
-
-    def decode(self, q: torch.Tensor, out: Optional[torch.Tensor] = None, flags: int = DECODE_AUTO) -> torch.Tensor:
-        max_seq = max(self.n_blocks) * self.fmt.block_tokens
-        return attn_decode(self.cache, q, self.seq_lens, max_seq, self.ws_decode, out=out, flags=flags,
+    def decode(self, q: torch.Tensor, out: Optional[torch.Tensor] = None, flags: int = DECODE_AUTO,
+               max_seq_len: Optional[int] = None) -> torch.Tensor:
+        """Attention of one query per (sequence, query head) over blocks and tail.  max_seq_len: host
+        bound on the compressed tokens of any sequence (default: from the rows appended so far)."""
+        tb = self.fmt.block_tokens
+        if max_seq_len is None:
+            max_seq_len = min(self.capacity_blocks, self.rows_upper // tb) * tb
+        return attn_decode(self.cache, q, self.seq_lens, max_seq_len, self.ws_decode, out=out, flags=flags,
                            tail=(self.k_tail, self.v_tail, self.tail_lens))

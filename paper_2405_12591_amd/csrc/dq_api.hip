@@ -111,7 +111,7 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 
 using namespace dq;
 
-extern "C" int32_t dq_version(void) { return 5; }
+extern "C" int32_t dq_version(void) { return 6; }
 
 extern "C" const char* dq_status_string(int32_t status) {
   switch (status) {

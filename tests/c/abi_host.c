@@ -19,7 +19,7 @@ int main(void) {
   dq_cache cache;
   char fake[64];
   memset(&cache, 0, sizeof cache);
-  CHECK(dq_version() == 5);
+  CHECK(dq_version() == 6);
   CHECK(strcmp(dq_status_string(DQ_OK), "ok") == 0);
   CHECK(dq_decode_workspace_bytes(&fmt, 8, 32, 32, 4096) > 0);
   CHECK(dq_decode_workspace_bytes(&bad, 8, 32, 32, 4096) == 0);

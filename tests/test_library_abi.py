@@ -27,7 +27,7 @@ def test_library_exports_every_declared_symbol(dq):
 
 
 def test_status_strings_and_version(dq):
-    assert dq.version() == dq.ABI_VERSION == 5
+    assert dq.version() == dq.ABI_VERSION == 6
     assert dq.status_string(0) == "ok"
     assert "workspace" in dq.status_string(-2)
     assert "invalid" in dq.status_string(-1)
@@ -151,6 +151,27 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     st = dq.lib.dq_attn_decode_static(C.byref(good), cache_p, ptr, 4, ptr, 1024, None, 0.0, ptr, None, 0, None)
     assert st == -4
     fake.batch = 2
+    # the device-side cache policy: a state with a null pointer, row counts outside [1, block_tokens], unknown
+    # flags, a workspace one byte short (all before anything is launched)
+    class State(C.Structure):
+        _fields_ = [("p", C.c_void_p * 4)]
+
+    state = State()
+    for i in range(4):
+        state.p[i] = 0x1000
+    aneed = dq.lib.dq_cache_append_workspace_bytes(C.byref(good), 2, 4)
+    assert aneed == cneed + 256                                   # four int32 per sequence, padded to 256 bytes
+    append = lambda st_p, n, ws_bytes, flags: dq.lib.dq_cache_append(   # noqa: E731
+        C.byref(good), cache_p, st_p, ptr, ptr, n, None, ptr, ws_bytes, flags, None)
+    assert append(C.byref(state), 0, aneed, 0) == -1
+    assert append(C.byref(state), 129, aneed, 0) == -1
+    assert append(C.byref(state), 1, aneed, 2) == -1
+    assert append(C.byref(state), 1, aneed - 1, 0) == -2
+    assert append(None, 1, aneed, 0) == -1
+    state.p[2] = 0
+    assert append(C.byref(state), 1, aneed, 0) == -1
+    big_block = dq.Format(4, 128, 128, 16, 8, 2048).c()           # a tail of more rows than a decode call takes
+    assert dq.lib.dq_cache_append_workspace_bytes(C.byref(big_block), 2, 4) == 0
     # quantize_pack: rows not a multiple of 128
     st = dq.lib.dq_quantize_pack(C.byref(good), ptr, 100, 0, ptr, ptr, None)
     assert st == -1
