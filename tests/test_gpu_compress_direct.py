@@ -5,6 +5,7 @@ groups, level sets, block sizes, ragged and short inputs, skipped sequences, and
 the fused kernel is launched with; calls it does not cover must fall back to the ordinary kernels."""
 import dataclasses
 
+import numpy as np
 import pytest
 import torch
 
@@ -83,3 +84,53 @@ def test_calls_the_fused_kernel_does_not_cover_fall_back():
         w = dataclasses.replace(base, max_seq=128, min_seq=128, **kw)
         _say("fused quantizer, fall-back: %s" % kw)
         _both_ways(w, 128, None, [0] * w.batch)
+
+
+@pytest.mark.parametrize("name,batch,kvh", [("llama13b_mixed", 4, 40), ("llama7b_4bit", 8, 32), ("llama7b_2bit", 16, 32)])
+def test_properties_at_the_call_sizes_that_ship(name, batch, kvh):
+    """Calls of 320, 512 and 1024 blocks (the 13B-shaped configuration's appended rows, the benchmark's
+    companion step, the 2-bit configuration's) with the library's own choice of waves per block: on
+    sampled blocks the two-kernel path's output has the properties the paper fixes (orthonormal rows
+    of T_L, exact factorisation, codes and steps equal to the oracle's quantization of the GPU's own
+    T_L, reconstruction within the half-step bound); the one-kernel path then writes the same cache
+    bit for bit, so the same holds for it."""
+    from oracle import decoquant_oracle as O
+    from test_gpu_parity import block_properties
+    w = dataclasses.replace(workloads.get_workload(name), batch=batch, q_heads=kvh, kv_heads=kvh, max_seq=128, min_seq=128,
+                            append_tokens=0)
+    fmt, ofmt = formats(w)
+    _say("compress properties at %d blocks per call (%s)" % (2 * batch * kvh, name))
+    gen = torch.Generator(device=DEV).manual_seed(11)
+    kd = (torch.randn((batch, kvh, 128, 128), device=DEV, generator=gen) * 1.5).to(torch.float16)
+    vd = (torch.randn((batch, kvh, 128, 128), device=DEV, generator=gen) * 1.5).to(torch.float16)
+    sample = [(0, 0), (batch - 1, kvh - 1), (1, 5), (batch // 2, kvh // 2), (2, kvh - 2), (batch - 1, 0)]
+    host = {}
+    for b, h in sample:                                  # the workload's rows (outlier channels and all)
+        kk, vv = workloads.kv_pair(w, b, h, 128)
+        host[b, h] = (kk, vv)
+        kd[b, h], vd[b, h] = torch.from_numpy(kk).to(DEV), torch.from_numpy(vv).to(DEV)
+    n_valid = torch.full((batch,), 128, dtype=torch.int32, device=DEV)
+    n_valid[1] = 77                                      # one ragged sequence
+    slot = torch.zeros(batch, dtype=torch.int32, device=DEV)
+    caches = []
+    for keep in (True, False):
+        cache = dq.alloc_cache(fmt, batch, kvh, 1, DEV, fill=0xA5)
+        ws = dq.compress_workspace(fmt, batch, kvh, DEV)
+        dq.compress_kv(cache, kd, vd, slot, n_valid, ws, keep_large=keep)
+        torch.cuda.synchronize()
+        assert int(ws[:4].view(torch.int32).item()) == 0
+        caches.append((cache, ws))
+    (two, ws2), (one, _) = caches
+    for n in two.t:
+        assert torch.equal(two.t[n], one.t[n]), n
+    arrs = {n: t.cpu().numpy() for n, t in two.t.items()}
+    units = batch * kvh * 2
+    large = ws2[256:256 + 4 * units * 128 * 128].view(torch.float32).cpu().numpy().reshape(units, 128, 128)
+    worst = 0.0
+    for b, h in sample:
+        for which, rows in (("k", host[b, h][0]), ("v", host[b, h][1])):
+            nv = 77 if b == 1 else 128
+            x = np.zeros((128, 128))
+            x[:nv] = rows[:nv].astype(np.float64)
+            worst = max(worst, block_properties(arrs, ofmt, x, large[(b * kvh + h) * 2 + (which == "v")], b, h, 0, which))
+    _say("  worst |T_L T_L^T - I| = %.3g over %d sampled blocks" % (worst, 2 * len(sample)))

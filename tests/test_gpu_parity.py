@@ -102,6 +102,26 @@ def test_decode_generic_tiny_full():
     _say("  worst fp32 abs err %.3g" % worst)
 
 
+@pytest.mark.parametrize("flags", [dq.DECODE_FORCE_GENERIC, dq.DECODE_FORCE_MFMA])
+def test_tiny_worst_error_where_the_plain_bound_applies(flags):
+    """The Tiny configuration's outputs reach |20| (x20 outlier channels), where half an fp16 ulp alone
+    is 8e-3; this reports, and holds to the plain 2e-3, the error of the elements with |exact| < 2."""
+    w = workloads.get_workload("tiny")
+    fmt, ofmt = formats(w)
+    lens = workloads.seq_lens(w)
+    pairs = [(0, h) for h in range(w.kv_heads)]
+    cache = oracle_cache_for_pairs(w, ofmt, pairs, lens)
+    q = workloads.query(w)
+    want = O.attention_decode(cache, ofmt, q, lens)
+    got16, got32 = run_decode(fmt, cache, q, lens, int(w.max_seq), flags)
+    plain = np.abs(want) < 2.0
+    e16 = np.abs(got16.astype(np.float64) - want)[plain].max()
+    e32 = np.abs(got32.astype(np.float64) - want)[plain].max()
+    _say("tiny, flags=%d, %d of %d elements with |exact| < 2: worst fp16-output err %.3g, fp32-output err %.3g; max |exact| %.3g"
+         % (flags, int(plain.sum()), want.size, e16, e32, np.abs(want).max()))
+    assert e16 <= 2e-3 and e32 <= 2e-3
+
+
 @pytest.mark.parametrize("lens", [[256], [1], [0], [129], [255]])
 def test_decode_generic_tiny_ragged(lens):
     w = workloads.get_workload("tiny")
@@ -165,6 +185,36 @@ def test_compress_kv_random_cases(seed):
         _check_compress(w, t_new, n_valid, waves=int(waves or 0))
 
 
+def block_properties(arrs, ofmt, x, kp, b, h, slot, which):
+    """What the paper fixes about one GPU-compressed block (the factors themselves are not unique):
+    x: the block's rows as given (fp64, missing rows zero); kp: the GPU's fp32 large tensor in
+    token-major form.  Returns the largest |T_L T_L^T - I| entry."""
+    tb, d, j1, j2 = ofmt.block_tokens, ofmt.head_dim, ofmt.j1, ofmt.j2
+    small, steps, codes = O.load_block(arrs, ofmt, b, h, slot, which)
+    t_l = O.token_major_to_large(kp.astype(np.float64), j1, j2, ofmt.i1)
+    # (1) rows of T_L orthonormal (or zero for dropped directions)
+    gram = t_l @ t_l.T
+    live = np.diag(gram) > 0.5
+    ortho = np.abs(gram - np.diag(live.astype(np.float64))).max()
+    assert ortho <= 2e-6, (b, h, which, ortho)       # fp32 storage of T_L allows about 1e-6
+    # (2) exact factorisation up to the fp16 rounding of T_S and fp32 of T_L (Eq. 3)
+    m = O.matricise(x, ofmt.i1, j1)
+    resid = np.abs(small.astype(np.float64) @ t_l - m)
+    slack = 2.0 ** -10 * (np.abs(small.astype(np.float64)) @ np.abs(t_l)) + 1e-6 * np.abs(m).max() + 1e-7
+    assert (resid <= slack).all(), (b, h, which, resid.max())
+    # (3) codes and steps are the oracle's quantization of that very T_L (Eq. 1)
+    steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax, ofmt.full_range)
+    codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax, ofmt.full_range)
+    assert np.array_equal(steps.view(np.uint16), steps_o.view(np.uint16)), (b, h, which)
+    assert np.array_equal(codes, codes_o), (b, h, which)
+    # (4) reconstruction within the half-step bound
+    x_hat = O.reconstruct_block(small, steps, codes, ofmt)
+    bound = O.reconstruction_bound(small, steps, ofmt)
+    slack_x = O.unmatricise(slack, tb, d, ofmt.i1, j1)
+    assert (np.abs(x_hat - x) <= bound + slack_x).all(), (b, h, which)
+    return ortho
+
+
 def _check_compress(w, t_new, n_valid, waves=0):
     assert w.batch <= 3 and w.i3 == 1          # three block slots below; two local tensors
     fmt, ofmt = formats(w)
@@ -199,30 +249,8 @@ def _check_compress(w, t_new, n_valid, waves=0):
                 n_ok = t_new if n_valid is None else min(n_valid[b], t_new)
                 x = np.zeros((tb, d))
                 x[:n_ok] = x_all[b, h, :n_ok].astype(np.float64)
-                small, steps, codes = O.load_block(arrs, ofmt, b, h, slot, which)
                 kp = large[(b * w.kv_heads + h) * 2 + (which == "v")]
-                t_l = O.token_major_to_large(kp.astype(np.float64), j1, j2, ofmt.i1)
-                # (1) rows of T_L orthonormal (or zero for dropped directions)
-                gram = t_l @ t_l.T
-                diag = np.diag(gram)
-                live = diag > 0.5
-                worst_ortho = max(worst_ortho, np.abs(gram - np.diag(live.astype(np.float64))).max())
-                assert worst_ortho <= 2e-6, (b, h, which)     # fp32 storage of T_L allows about 1e-6
-                # (2) exact factorisation up to the fp16 rounding of T_S and fp32 of T_L
-                m = O.matricise(x, ofmt.i1, j1)
-                resid = np.abs(small.astype(np.float64) @ t_l - m)
-                slack = 2.0 ** -10 * (np.abs(small.astype(np.float64)) @ np.abs(t_l)) + 1e-6 * np.abs(m).max() + 1e-7
-                assert (resid <= slack).all(), (b, h, which, resid.max())
-                # (3) codes and steps are the oracle's quantization of that very T_L
-                steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax, ofmt.full_range)
-                codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax, ofmt.full_range)
-                assert np.array_equal(steps.view(np.uint16), steps_o.view(np.uint16))
-                assert np.array_equal(codes, codes_o)
-                # (4) reconstruction within the half-step bound
-                x_hat = O.reconstruct_block(small, steps, codes, ofmt)
-                bound = O.reconstruction_bound(small, steps, ofmt)
-                slack_x = O.unmatricise(slack, tb, d, ofmt.i1, j1)
-                assert (np.abs(x_hat - x) <= bound + slack_x).all(), (b, h, which)
+                worst_ortho = max(worst_ortho, block_properties(arrs, ofmt, x, kp, b, h, slot, which))
                 # (5) other block slots of this head untouched
                 for other in range(nb):
                     if other != slot:
@@ -346,8 +374,10 @@ def test_decode_full_size_llama7b_sampled_pairs():
         _say("  pair %s max fp32 err %.3g, max |out| %.3g" % ((b, h), e32.max(), np.abs(want[b, h]).max()))
 
 
-def _full_size_case(name, pairs, flags=0, append=False):
-    """Sampled (sequence, kv head) pairs of a full-size workload, default launch configuration."""
+def _full_size_case(name, pairs, flags=0):
+    """Sampled (sequence, kv head) pairs of a full-size workload, default launch configuration.
+    Also reports the worst error over the elements with |exact| < 2, where the tolerance is the plain
+    2e-3 (the relative branch of the fp16 bound only starts at |exact| = 2.048)."""
     w = workloads.get_workload(name)
     fmt, ofmt = formats(w)
     lens = workloads.seq_lens(w)
@@ -357,13 +387,20 @@ def _full_size_case(name, pairs, flags=0, append=False):
     want = O.attention_decode(cache, ofmt, q, lens, pairs=pairs)
     got16, got32 = run_decode(fmt, cache, q, lens, int(lens.max()), flags)
     rep = w.q_heads // w.kv_heads
+    small16, small32, n_small = 0.0, 0.0, 0
     for b, h in pairs:
         for hq in range(h * rep, (h + 1) * rep):
             e16 = np.abs(got16[b, hq].astype(np.float64) - want[b, hq])
             assert (e16 <= tolerance(want[b, hq])).all(), (b, hq, e16.max())
             e32 = np.abs(got32[b, hq].astype(np.float64) - want[b, hq])
             assert (e32 <= np.maximum(2e-3, 1e-4 * np.abs(want[b, hq]))).all(), (b, hq, e32.max())
+            plain = np.abs(want[b, hq]) < 2.0
+            if plain.any():
+                small16, small32, n_small = max(small16, e16[plain].max()), max(small32, e32[plain].max()), n_small + int(plain.sum())
         _say("  pair %s max fp32 err %.3g" % ((b, h), e32.max()))
+    assert small16 <= 2e-3 and small32 <= 2e-3
+    _say("  where |exact| < 2 (%d elements, plain 2e-3 bound): worst fp16-output err %.3g, worst fp32-output err %.3g"
+         % (n_small, small16, small32))
 
 
 def test_decode_full_size_llama13b_mixed_lengths():
