@@ -117,16 +117,19 @@ __device__ __forceinline__ uint32_t fields_of_four(float x0, float x1, float x2,
 // All NT threads of the workgroup call it, after a barrier that follows the last field's store;
 // it ends with a barrier (lds_u may be reused).  The value layout needs D * (128 * BITS / 32 + 1)
 // words of staging behind the fields.
-template <int BITS, int D, int NT>
+// QT < 128: lds_u holds QT rows, the rows [part * QT, (part + 1) * QT) of the tile that begins at
+// codes_out (staging D * (QT * BITS / 32 + 1) words).
+template <int BITS, int D, int NT, int QT = kTileTokens>
 __device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1, int j2, int value_layout,
-                                            uint8_t* __restrict__ codes_out) {
+                                            uint8_t* __restrict__ codes_out, int part = 0) {
   constexpr int d = D;
   const int tid = threadIdx.x;
   constexpr int PER_WORD = 32 / BITS;
-  const int total_words = kTileTokens * d / PER_WORD;
+  constexpr int total_words = QT * d / PER_WORD;
   uint32_t* out32 = reinterpret_cast<uint32_t*>(codes_out);
   if (!value_layout) {
     // key layout: rows of d elements, element index contiguous
+    out32 += part * total_words;
     for (int w = tid; w < total_words; w += NT) {
       const uint32_t* f = reinterpret_cast<const uint32_t*>(lds_u + w * PER_WORD);
       uint32_t word = 0;
@@ -142,8 +145,9 @@ __device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1,
     // value layout: [b2][r][128 tokens], tokens contiguous.  Consecutive lanes take consecutive
     // columns (conflict-free byte reads), the words are transposed through a padded LDS buffer and
     // leave in output order.
-    constexpr int WPR = kTileTokens / PER_WORD;   // words per (b2, r) row
-    uint32_t* stage = reinterpret_cast<uint32_t*>(lds_u + kTileTokens * d);
+    constexpr int WPR = QT / PER_WORD;            // words per (b2, r) row held here
+    constexpr int WPR_TILE = kTileTokens / PER_WORD;   // ... and in the tile
+    uint32_t* stage = reinterpret_cast<uint32_t*>(lds_u + QT * d);
     for (int idx = tid; idx < total_words; idx += NT) {
       const int col = idx % d, wi = idx / d;
       const int b2 = col % j2, r = col / j2;
@@ -154,7 +158,8 @@ __device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1,
       stage[(b2 * j1 + r) * (WPR + 1) + wi] = word;
     }
     __syncthreads();
-    for (int w = tid; w < total_words; w += NT) out32[w] = stage[(w / WPR) * (WPR + 1) + w % WPR];
+    for (int w = tid; w < total_words; w += NT)
+      out32[(w / WPR) * WPR_TILE + part * WPR + w % WPR] = stage[(w / WPR) * (WPR + 1) + w % WPR];
   }
   __syncthreads();
 }
@@ -627,8 +632,14 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
 // word of the workspace header, zero between calls) folds the blocks' status words into the call's
 // two; status words travel as device-scope stores and loads, as the counter does, so no cache
 // write-back or invalidation is needed between the XCDs.
-template <int NWV, bool PAIR, int QB = 0, bool FULL = false>
-__global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
+// LEAN: the build for calls of thousands of blocks (a prompt), which are bound by throughput, not by
+// one block's latency: one wave per block, several blocks resident per SIMD so that one block's
+// eigen-solver (a chain of dependent instructions) overlaps the other blocks' contractions.  For
+// that the wave keeps fewer registers (loads in smaller batches, the solver's rounds not unrolled) and
+// less LDS (the quantizer works on 64 rows at a time in the space the solver's matrices leave).  The
+// arithmetic, and so every bit written, is that of the other builds.
+template <int NWV, bool PAIR, int QB = 0, bool FULL = false, bool LEAN = false>
+__global__ __launch_bounds__(64 * NWV, LEAN ? 4 : 1) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                                float* __restrict__ large_ws,
                                                                int32_t* __restrict__ unit_status,
                                                                int32_t* __restrict__ call_status) {
@@ -691,15 +702,25 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   const uint16_t* X = ur.X;  // [nv, d] fp16 bits
   const long head_gap = (long)job.t_new * d;   // PAIR: from a row of the first head to the same row of the second
 
-  __shared__ double A[j1 * ld], V[j1 * ld], W[j1 * ld];
-  __shared__ double P[(NWV > 1 ? NWV - 1 : 1) * j1 * ld];   // Gram partials of the other waves
+  static_assert(!LEAN || NWV == 1, "the lean build is one wave per block");
+  constexpr int kMat = j1 * ld;                              // doubles per 16 x 16 matrix (padded rows)
+  constexpr int kMatBytes = (3 + (NWV > 1 ? NWV - 1 : 1)) * kMat * (int)sizeof(double);
+  // fused quantizer: one byte per element of QT token rows, then the value layout's staging
+  // (a pair: one such area per head, of 64 channels each)
+  constexpr int QT = LEAN ? 32 : kTileTokens;                // rows quantized and packed at a time
+  constexpr int kHeadArea = QT * d + d * (QT * (QB ? QB : 8) / 32 + 1) * 4;
+  constexpr int kFieldBytes = QB ? (PAIR ? 2 : 1) * kHeadArea : 16;
+  // the lean build's fields take the place of the matrices, which are dead by then (one wave: its
+  // LDS operations execute in program order)
+  constexpr int kPoolBytes = LEAN ? (kMatBytes > kFieldBytes ? kMatBytes : kFieldBytes) : kMatBytes + kFieldBytes;
+  __shared__ __attribute__((aligned(16))) unsigned char pool[kPoolBytes];
+  double* const A = reinterpret_cast<double*>(pool);
+  double* const V = A + kMat;
+  double* const W = V + kMat;
+  double* const P = W + kMat;                                // Gram partials of the other waves
+  uint8_t* const lds_u = LEAN ? pool : pool + kMatBytes;
   __shared__ double lam[j1], sigma[j1];
   __shared__ int order[j1];
-  // fused quantizer: one byte per element of a 128-token tile, then the value layout's staging
-  // (a pair: one such area per head, of 64 channels each)
-  constexpr int kHeadArea = kTileTokens * d + d * (kTileTokens * (QB ? QB : 8) / 32 + 1) * 4;
-  constexpr int kFieldBytes = QB ? (PAIR ? 2 : 1) * kHeadArea : 16;
-  __shared__ __attribute__((aligned(16))) uint8_t lds_u[kFieldBytes];
 
   // ---- Gram matrix G[p][q] = sum_{t, b2} X[t, p*8+b2] X[t, q*8+b2] ----
   // A and B operand of one MFMA are the same register: lane (b1 = l%16, k = l/16) holds
@@ -712,23 +733,27 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     f64x4 acc[4];
 #pragma unroll
     for (int i = 0; i < 4; ++i) acc[i] = f64x4{0.0, 0.0, 0.0, 0.0};
+    constexpr int GC = LEAN ? 8 : NG;   // groups requested together (the same order of products either way)
     for (int t0 = 0; t0 < nv; t0 += 128) {
-      u32x4 x[NG];
+#pragma unroll 1
+      for (int u0 = 0; u0 < NG; u0 += GC) {
+        u32x4 x[GC];
 #pragma unroll
-      for (int u = 0; u < NG; ++u) {
-        const int t = t0 + 4 * (u * NWV + wv) + tk;
-        x[u] = u32x4{0u, 0u, 0u, 0u};
-        if (t < nv)
-          x[u] = *reinterpret_cast<const u32x4*>(PAIR ? X + (b1 >> 3) * head_gap + (long)t * d + (b1 & 7) * 8
-                                                      : X + (long)t * d + b1 * 8);
-      }
+        for (int u = 0; u < GC; ++u) {
+          const int t = t0 + 4 * ((u0 + u) * NWV + wv) + tk;
+          x[u] = u32x4{0u, 0u, 0u, 0u};
+          if (t < nv)
+            x[u] = *reinterpret_cast<const u32x4*>(PAIR ? X + (b1 >> 3) * head_gap + (long)t * d + (b1 & 7) * 8
+                                                        : X + (long)t * d + b1 * 8);
+        }
 #pragma unroll
-      for (int u = 0; u < NG; ++u) {
-        const f16x8 h = __builtin_bit_cast(f16x8, x[u]);
+        for (int u = 0; u < GC; ++u) {
+          const f16x8 h = __builtin_bit_cast(f16x8, x[u]);
 #pragma unroll
-        for (int b2 = 0; b2 < 8; ++b2) {
-          const double a = (double)(float)h[b2];
-          acc[b2 & 3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, a, acc[b2 & 3], 0, 0, 0);
+          for (int b2 = 0; b2 < 8; ++b2) {
+            const double a = (double)(float)h[b2];
+            acc[b2 & 3] = __builtin_amdgcn_mfma_f64_16x16x4f64(a, a, acc[b2 & 3], 0, 0, 0);
+          }
         }
       }
     }
@@ -770,9 +795,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
     for (int sweep = 0; sweep < 16; ++sweep) {
       ++sweeps;
       bool unsettled = false;
-      // unrolled: the LDS addresses of a round depend only on the lane and are computed once
-#pragma unroll
-      for (int round = 0; round < 15; ++round) {
+      auto one_round = [&](const int round) __attribute__((always_inline)) {
         int p, q, u, v;
         pair16(round, I, p, q);
         pair16(round, J, u, v);
@@ -801,6 +824,16 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
         // One wave: its LDS operations execute in program order, so the next round's reads see these
         // writes without waiting for them; the compiler only has to keep the order.
         __builtin_amdgcn_wave_barrier();
+      };
+      if constexpr (LEAN) {
+        // (the round number stays a run-time value: fifteen rounds' worth of addresses would cost
+        // the registers that let several blocks share a SIMD)
+#pragma unroll 1
+        for (int round = 0; round < 15; ++round) one_round(round);
+      } else {
+        // unrolled: the LDS addresses of a round depend only on the lane and are computed once
+#pragma unroll
+        for (int round = 0; round < 15; ++round) one_round(round);
       }
       // every entry rotated in this sweep was below 3e-5 of its diagonal pair, so the sweep (one
       // more quadratic step) has left them near 1e-9, two orders under the fp32 rounding of T_L
@@ -868,35 +901,40 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
   // One MFMA chain per b2: rows r, columns 16 tokens, contraction over b1 in 4 steps of 4.
   // Wave wv takes every NWV-th group of 16 tokens.
   {
-    constexpr int NT = 8 / NWV;   // token groups per wave in a chunk of 128 tokens
+    constexpr int NT = QT / 16 / NWV;   // token groups per wave in a chunk of QT tokens
+    constexpr int TB = LEAN ? 1 : NT;   // groups whose rows are requested together
     double wreg[4];
 #pragma unroll
     for (int s = 0; s < 4; ++s) wreg[s] = W[(l & 15) * ld + 4 * s + (l >> 4)];
+    if (LEAN) __builtin_amdgcn_wave_barrier();   // W is read; the fields may take the matrices' place
     float* out = large_ws + (long)unit * g.Tb * d;
     const long out_gap = (long)unit_gap * g.Tb * d;   // PAIR: to the second head's rows in the workspace
-    for (int t0 = 0; t0 < g.Tb; t0 += 128) {
-      u32x4 x[NT][4];
+    for (int t0 = 0; t0 < g.Tb; t0 += QT) {
+#pragma unroll 1
+     for (int tg0 = 0; tg0 < NT; tg0 += TB) {
+      u32x4 x[TB][4];
 #pragma unroll
-      for (int tg = 0; tg < NT; ++tg) {
-        const int t = t0 + 16 * (tg * NWV + wv) + (l & 15);
+      for (int tgi = 0; tgi < TB; ++tgi) {
+        const int t = t0 + 16 * ((tg0 + tgi) * NWV + wv) + (l & 15);
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          x[tg][s] = u32x4{0u, 0u, 0u, 0u};
+          x[tgi][s] = u32x4{0u, 0u, 0u, 0u};
           // b1 = 4 s + l / 16 (a pair: row b1 % 8 of head b1 / 8 = s / 2)
           if (t < nv)
-            x[tg][s] = *reinterpret_cast<const u32x4*>(PAIR ? X + (s >> 1) * head_gap + (long)t * d + ((4 * s + (l >> 4)) & 7) * 8
-                                                            : X + (long)t * d + (4 * s + (l >> 4)) * 8);
+            x[tgi][s] = *reinterpret_cast<const u32x4*>(PAIR ? X + (s >> 1) * head_gap + (long)t * d + ((4 * s + (l >> 4)) & 7) * 8
+                                                             : X + (long)t * d + (4 * s + (l >> 4)) * 8);
         }
       }
 #pragma unroll
-      for (int tg = 0; tg < NT; ++tg) {
+      for (int tgi = 0; tgi < TB; ++tgi) {
+        const int tg = tg0 + tgi;
         const int t = t0 + 16 * (tg * NWV + wv) + (l & 15);
         f64x4 acc[8];
 #pragma unroll
         for (int b2 = 0; b2 < 8; ++b2) acc[b2] = f64x4{0.0, 0.0, 0.0, 0.0};
 #pragma unroll
         for (int s = 0; s < 4; ++s) {
-          const f16x8 h = __builtin_bit_cast(f16x8, x[tg][s]);
+          const f16x8 h = __builtin_bit_cast(f16x8, x[tgi][s]);
 #pragma unroll
           for (int b2 = 0; b2 < 8; ++b2)
             acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64(wreg[s], (double)(float)h[b2], acc[b2], 0, 0, 0);
@@ -953,7 +991,7 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
             step[gi] = h2f(sb[gi]);
             inv[gi] = step[gi] > 0.f ? __builtin_amdgcn_rcpf(step[gi]) : 0.f;
           }
-          const int tl = 16 * (tg * NWV + wv) + (l & 15);   // the token's row in the tile
+          const int tl = 16 * (tg * NWV + wv) + (l & 15);   // the token's row among the QT rows in LDS
           if ((l >> 4) == 0) {
             uint16_t* sc = (which ? cache.v_scales : cache.k_scales) + ((long)bh * g.NB + slot) * g.scales_per_block +
                            (long)(t0 + tl) * g.groups;
@@ -972,16 +1010,18 @@ __global__ __launch_bounds__(64 * NWV) void decompose16_kernel(dq_format fmt, dq
           }
         }
       }
+     }
       if constexpr (QB != 0) {
-        // every wave has left the fields of its tokens: pack the tile and send it off
+        // every wave has left the fields of its tokens: pack these rows of the tile and send them off
         __syncthreads();
         uint8_t* codes = (which ? cache.v_codes : cache.k_codes) + ((long)bh * g.NB + slot) * g.codes_per_block +
-                         (long)t0 * g.row_bytes;
+                         (long)(t0 & ~(kTileTokens - 1)) * g.row_bytes;
+        const int part = (t0 & (kTileTokens - 1)) / QT;
         if (PAIR) {
-          pack_fields<QB, d, 64 * NWV>(lds_u, 8, 8, which, codes);
-          pack_fields<QB, d, 64 * NWV>(lds_u + kHeadArea, 8, 8, which, codes + (long)g.NB * g.codes_per_block);
+          pack_fields<QB, d, 64 * NWV, QT>(lds_u, 8, 8, which, codes, part);
+          pack_fields<QB, d, 64 * NWV, QT>(lds_u + kHeadArea, 8, 8, which, codes + (long)g.NB * g.codes_per_block, part);
         } else {
-          pack_fields<QB, d, 64 * NWV>(lds_u, 16, 8, which, codes);
+          pack_fields<QB, d, 64 * NWV, QT>(lds_u, 16, 8, which, codes, part);
         }
       }
     }
@@ -1230,11 +1270,12 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   const int want_waves = (int)((flags >> 8) & 0xFu);   // 0: the library's choice
   // heads of 64 channels with j1 = 8 go through the same kernel two at a time
   const bool pair_heads = fmt->head_dim == 64 && fmt->j1 == 8 && (cache->kv_heads & 1) == 0 && fmt->i1 == 1;
-  // Calls of a few hundred blocks are bound by the latency of one block's chain of kernels: where the
-  // caller does not need the fp32 large tensors the decomposition kernel quantizes them itself, which
-  // saves their trip through memory and the quantizer's launch.  (Calls of thousands of blocks are
-  // bound by throughput and keep the leaner kernels.)
-  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->i3 == 1 && fmt->i1 == 1 && units <= 1024 && !force_general &&
+  // Where the caller does not need the fp32 large tensors the decomposition kernel quantizes them
+  // itself, which saves their trip through memory (four times the bytes the method needs) and the
+  // quantizer's launch.  Calls of a few hundred blocks are bound by the latency of one block's chain
+  // and give a block several waves; calls of more than 1024 blocks are bound by throughput and take
+  // the lean build (one wave per block, three blocks per SIMD).
+  const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->i3 == 1 && fmt->i1 == 1 && !force_general &&
                      ((fmt->head_dim == 128 && fmt->j1 == 16 && (fmt->group == 128 || fmt->group == 64)) ||
                       (pair_heads && fmt->group == 64));
   if (fused) {
@@ -1253,10 +1294,29 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
       hipLaunchKernelGGL((decompose16_kernel<N_, false, B_, false>), dim3(units), dim3(64 * N_), 0, st, *fmt,   \
                          *cache, job, large_ws, unit_status, status);                                           \
   } while (0)
+#define DQ_LAUNCH_FUSED_LEAN(B_)                                                                                \
+  do {                                                                                                          \
+    if (pair_heads && fmt->levels)                                                                              \
+      hipLaunchKernelGGL((decompose16_kernel<1, true, B_, true, true>), dim3(units / 2), dim3(64), 0, st, *fmt, \
+                         *cache, job, large_ws, unit_status, status);                                           \
+    else if (pair_heads)                                                                                        \
+      hipLaunchKernelGGL((decompose16_kernel<1, true, B_, false, true>), dim3(units / 2), dim3(64), 0, st,      \
+                         *fmt, *cache, job, large_ws, unit_status, status);                                     \
+    else if (fmt->levels)                                                                                       \
+      hipLaunchKernelGGL((decompose16_kernel<1, false, B_, true, true>), dim3(units), dim3(64), 0, st, *fmt,    \
+                         *cache, job, large_ws, unit_status, status);                                           \
+    else                                                                                                        \
+      hipLaunchKernelGGL((decompose16_kernel<1, false, B_, false, true>), dim3(units), dim3(64), 0, st, *fmt,   \
+                         *cache, job, large_ws, unit_status, status);                                           \
+  } while (0)
     const int fused_groups = pair_heads ? units / 2 : units;
-    int fused_waves = fused_groups <= 256 ? 4 : fused_groups <= 512 ? 2 : 1;
+    int fused_waves = fused_groups <= 256 ? 4 : fused_groups <= 512 ? 2 : fused_groups <= 1024 ? 1 : 0;   // 0: the lean build
     if (want_waves) fused_waves = want_waves;
-    if (fused_waves == 4) {
+    if (fused_waves == 0) {
+      if (fmt->bits == 2) DQ_LAUNCH_FUSED_LEAN(2);
+      else if (fmt->bits == 4) DQ_LAUNCH_FUSED_LEAN(4);
+      else DQ_LAUNCH_FUSED_LEAN(8);
+    } else if (fused_waves == 4) {
       if (fmt->bits == 2) DQ_LAUNCH_FUSED(4, 2);
       else if (fmt->bits == 4) DQ_LAUNCH_FUSED(4, 4);
       else DQ_LAUNCH_FUSED(4, 8);
@@ -1270,6 +1330,7 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
       else DQ_LAUNCH_FUSED(1, 8);
     }
 #undef DQ_LAUNCH_FUSED
+#undef DQ_LAUNCH_FUSED_LEAN
     DQ_HIP_CHECK(hipGetLastError());
     return DQ_OK;
   }
@@ -1299,9 +1360,16 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
                          job, large_ws, unit_status, (int32_t*)nullptr);                                      \
   } while (0)
     const int groups16 = pair_heads ? units / 2 : units;
-    int nwv = groups16 <= 256 ? 4 : groups16 <= 512 ? 2 : 1;
+    int nwv = groups16 <= 256 ? 4 : groups16 <= 512 ? 2 : groups16 <= 1024 ? 1 : 0;   // 0: the lean build
     if (want_waves) nwv = want_waves;
-    if (nwv >= 4) DQ_LAUNCH_D16(4);
+    if (nwv == 0) {
+      if (pair_heads)
+        hipLaunchKernelGGL((decompose16_kernel<1, true, 0, false, true>), dim3(units / 2), dim3(64), 0, st, *fmt, *cache,
+                           job, large_ws, unit_status, (int32_t*)nullptr);
+      else
+        hipLaunchKernelGGL((decompose16_kernel<1, false, 0, false, true>), dim3(units), dim3(64), 0, st, *fmt, *cache,
+                           job, large_ws, unit_status, (int32_t*)nullptr);
+    } else if (nwv >= 4) DQ_LAUNCH_D16(4);
     else if (nwv >= 2) DQ_LAUNCH_D16(2);
     else DQ_LAUNCH_D16(1);
 #undef DQ_LAUNCH_D16

@@ -134,3 +134,34 @@ def test_properties_at_the_call_sizes_that_ship(name, batch, kvh):
             x[:nv] = rows[:nv].astype(np.float64)
             worst = max(worst, block_properties(arrs, ofmt, x, large[(b * kvh + h) * 2 + (which == "v")], b, h, 0, which))
     _say("  worst |T_L T_L^T - I| = %.3g over %d sampled blocks" % (worst, 2 * len(sample)))
+
+
+@pytest.mark.parametrize("bits,group,levels,d", [(4, 128, 0, 128), (2, 64, 1, 128), (8, 128, 0, 128), (4, 64, 0, 64)])
+def test_the_lean_build_for_large_calls_writes_the_same_bits(bits, group, levels, d):
+    """Calls of more than 1024 blocks take a build of the decomposition kernel that keeps fewer
+    registers and less LDS (several blocks per SIMD).  Same arithmetic: with and without the fp32
+    rows kept, the cache must equal, bit for bit, what the one-wave build of the small calls writes
+    (selected through the flags word), ragged rows and skipped sequences included."""
+    batch, kvh = 9, 64 if d == 64 else 32
+    w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=kvh, kv_heads=kvh, bits=bits,
+                            group=group, levels=levels, max_seq=256, min_seq=256, head_dim=d, j1=d // 8, j2=8)
+    fmt, _ = formats(w)
+    units = batch * kvh * 2 * 2
+    _say("lean build: bits=%d G=%d levels=%d d=%d, %d blocks per call" % (bits, group, levels, d, units))
+    gen = torch.Generator(device=DEV).manual_seed(3)
+    kd = (torch.randn((batch, kvh, 256, d), device=DEV, generator=gen) * 2).to(torch.float16)
+    vd = (torch.randn((batch, kvh, 256, d), device=DEV, generator=gen) * 2).to(torch.float16)
+    kd[:, :, :, 5] *= 20
+    n_valid = torch.tensor([256, 130, 1, 0, 255, 128, 129, 256, 77][:batch], dtype=torch.int32, device=DEV)
+    first = torch.tensor([0, 1, 0, 0, 0, -1, 0, 0, 1][:batch], dtype=torch.int32, device=DEV)
+    out = []
+    for keep, waves in ((True, 0), (False, 0), (True, 1), (False, 1)):
+        cache = dq.alloc_cache(fmt, batch, kvh, 2, DEV, fill=0xA5)
+        ws = dq.compress_workspace(fmt, batch, kvh, DEV, t_new=256)
+        dq.compress_kv_blocks(cache, kd, vd, first, n_valid, ws, keep_large=keep, waves=waves)
+        torch.cuda.synchronize()
+        out.append((cache, ws[:8].clone()))
+    for cache, status in out[1:]:
+        for name in cache.t:
+            assert torch.equal(cache.t[name], out[0][0].t[name]), name
+        assert torch.equal(status, out[0][1])
