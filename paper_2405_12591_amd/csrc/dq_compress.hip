@@ -639,7 +639,7 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
 // less LDS (the quantizer works on 64 rows at a time in the space the solver's matrices leave).  The
 // arithmetic, and so every bit written, is that of the other builds.
 template <int NWV, bool PAIR, int QB = 0, bool FULL = false, bool LEAN = false>
-__global__ __launch_bounds__(64 * NWV, LEAN ? 4 : 1) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
+__global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                                float* __restrict__ large_ws,
                                                                int32_t* __restrict__ unit_status,
                                                                int32_t* __restrict__ call_status) {
