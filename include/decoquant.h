@@ -159,7 +159,7 @@ int32_t dq_workspace_init(void* workspace, size_t workspace_bytes, void* hip_str
  * tokens t < seq_lens[b] of kv head h_q / (q_heads / kv_heads), where K_hat and V_hat are the
  * dequantized blocks T_S16 * (step * code).  No intermediate rounding to fp16; fp32
  * accumulation; one final round-to-nearest-even to fp16.
- *   q         f16 [B, q_heads, d]; B * q_heads <= 65535 (DQ_EINVAL beyond)
+ *   q         f16 [B, q_heads, d]; B * q_heads <= 2^24 (DQ_EINVAL beyond)
  *   seq_lens  i32 [B]; 0 <= seq_lens[b] <= max_seq_len; a sequence of length 0 yields zeros
  *   max_seq_len  host integer upper bound on seq_lens, <= block_capacity * T_b (sizes the grid)
  *   softmax_scale  <= 0 selects 1/sqrt(d)

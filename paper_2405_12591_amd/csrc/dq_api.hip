@@ -163,8 +163,7 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   if (fmt->i3 != 1 && (!cache->k_small3 || !cache->v_small3)) return DQ_EINVAL;
   if (cache->batch <= 0 || cache->kv_heads <= 0 || cache->block_capacity <= 0) return DQ_EINVAL;
   if (q_heads <= 0 || q_heads % cache->kv_heads) return DQ_EINVAL;
-  // (sequence, head) pairs are the y index of every grid here
-  if ((long)cache->batch * q_heads > kMaxGridY) return DQ_EINVAL;
+  if ((long)cache->batch * q_heads > kMaxDecodeRows) return DQ_EINVAL;
   if (max_seq_len < 0 || (long)max_seq_len > (long)cache->block_capacity * fmt->block_tokens) return DQ_EINVAL;
   if ((flags & DQ_DECODE_FORCE_GENERIC) && (flags & DQ_DECODE_FORCE_MFMA)) return DQ_EINVAL;
   {
@@ -205,6 +204,7 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   const int units = cache->batch * cache->kv_heads / (a.pair_heads ? 2 : 1);
   a.unit_map = (a.n_split == 1 && a.head_groups == 1 && units <= 256) ? 3 : 0;
   if (const uint32_t umap = (flags >> 20) & 0xFu) a.unit_map = (int)umap - 1;   // the caller's override
+  a.rows_on_x = ((long)cache->batch * q_heads > kMaxGridY) ? 1 : 0;   // rows: at most batch * q_heads of them
   a.n_slots = a.n_split + (tail ? 1 : 0);
   if (tail) a.tail = *tail;
   else a.tail = dq_tail{nullptr, nullptr, nullptr, 0};

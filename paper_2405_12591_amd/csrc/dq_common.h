@@ -13,7 +13,8 @@ constexpr int kMaxSplits = 64;     // upper bound on split-sequence partials per
 constexpr int kWsHeaderBytes = 256;
 constexpr int kMaxCompressUnits = 1 << 22;   // blocks (keys and values counted apart) one compression call takes
 constexpr int kMaxHeadGroups = 16; // matrix-core decode: groups of query heads per kv head
-constexpr int kMaxGridY = 65535;   // largest y extent of a launch: (sequence, query head) pairs per decode call
+constexpr int kMaxGridY = 65535;   // largest y extent of a launch; more rows than that ride on the x index
+constexpr int kMaxDecodeRows = 1 << 24;   // (sequence, query head) pairs one decode call takes (index arithmetic stays in 32 bits)
 constexpr int kMaxTailRows = 1024; // rows of the fp16 tail a decode call takes per sequence and kv head
 constexpr int kRun = 8;            // side of the third local tensor: tokens per run it mixes
 

@@ -24,6 +24,7 @@ struct DecodeArgs {
   int heads_per_group;     // ... each with this many query heads (1, 2 or 4; the last one what is left)
   int pair_heads;          // matrix-core kernel: 1 = two kv heads of 64 channels per workgroup (one query head each)
   int unit_map;            // which (sequence, kv head) a workgroup row takes: 0 = its own index, see unit_of_row()
+  int rows_on_x;           // 0: grid (splits, rows); 1: grid (rows, splits), for more rows than a grid's y extent takes
   hipEvent_t ev_start;     // optional: recorded around the main kernel
   hipEvent_t ev_stop;
 };

@@ -35,8 +35,8 @@ template <int BITS>
 __global__ __launch_bounds__(256) void decode_generic_kernel(DecodeArgs a) {
   const Geometry g = make_geometry(a.fmt, a.cache.kv_heads, a.cache.block_capacity);
   const int d = g.d, j1 = g.j1, j2 = g.j2, G = g.G;
-  const int split = blockIdx.x;
-  const int bhq = blockIdx.y;
+  const int split = a.rows_on_x ? blockIdx.y : blockIdx.x;
+  const int bhq = a.rows_on_x ? blockIdx.x : blockIdx.y;
   const int b = bhq / a.q_heads, hq = bhq % a.q_heads;
   const int rep = a.q_heads / g.H;
   const int h = hq / rep;
@@ -223,8 +223,8 @@ __global__ __launch_bounds__(256) void decode_generic_i1_kernel(DecodeArgs a) {
   const int N = I1 * j1;           // side of the small tensor, <= 32
   const int i2 = g.Tb / I1;
   constexpr int PPT = kTileTokens / I1;   // positions a2 per tile
-  const int split = blockIdx.x;
-  const int bhq = blockIdx.y;
+  const int split = a.rows_on_x ? blockIdx.y : blockIdx.x;
+  const int bhq = a.rows_on_x ? blockIdx.x : blockIdx.y;
   const int b = bhq / a.q_heads, hq = bhq % a.q_heads;
   const int rep = a.q_heads / g.H;
   const int h = hq / rep;
@@ -471,7 +471,7 @@ int32_t launch_decode_generic(const DecodeArgs& a, hipStream_t st) {
     const int32_t rc = launch_tail_partial(a, 0.6931471805599453f, st);
     if (rc != DQ_OK) return rc;
   }
-  const dim3 grid(a.n_split, a.cache.batch * a.q_heads);
+  const dim3 grid = a.rows_on_x ? dim3(a.cache.batch * a.q_heads, a.n_split) : dim3(a.n_split, a.cache.batch * a.q_heads);
   // the events, when given, receive the streaming kernel's own begin and end timestamps
   if (a.fmt.i1 > 1) {   // a token factor on the small tensor
 #define DQ_LAUNCH_I1(B_)                                                                                          \

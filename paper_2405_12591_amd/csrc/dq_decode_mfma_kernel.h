@@ -230,10 +230,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // workgroups of one (sequence, kv head) are a multiple of eight apart in launch order (whenever
   // the number of units is one) and land on the same XCD: while they run side by side, the second
   // to ask for a line finds it in that XCD's L2.
-  const int split = blockIdx.x;
-  const int n_units = gridDim.y / a.head_groups;
-  const int hgrp = blockIdx.y / n_units;
-  const int bh = unit_of_row(blockIdx.y % n_units, n_units, a.unit_map);
+  // (rows normally ride on the grid's y index, splits of a row next to each other in launch order;
+  // more rows than a y extent takes ride on x)
+  const int split = a.rows_on_x ? blockIdx.y : blockIdx.x;
+  const int row = a.rows_on_x ? blockIdx.x : blockIdx.y;
+  const int n_units = (a.rows_on_x ? gridDim.x : gridDim.y) / a.head_groups;
+  const int hgrp = row / n_units;
+  const int bh = unit_of_row(row % n_units, n_units, a.unit_map);
   const int H = a.cache.kv_heads, NB = a.cache.block_capacity;
   constexpr int HPU = P2 ? 2 : 1;              // kv heads per unit
   const int b = bh / (H / HPU), h = (bh % (H / HPU)) * HPU;
@@ -931,7 +934,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
 template <int BITS, int NG, int R, int TM, bool N3, bool P2>
 inline void launch_tm(const DecodeArgs& a, hipStream_t st) {
   const int units = a.cache.batch * a.cache.kv_heads / (P2 ? 2 : 1);
-  const dim3 grid(a.n_split, units * a.head_groups);
+  const dim3 grid = a.rows_on_x ? dim3(units * a.head_groups, a.n_split) : dim3(a.n_split, units * a.head_groups);
   // the events, when given, receive the kernel's own begin and end timestamps
   // (8-bit codes: a wave's ring of chunks is twice as large and an 8-wave workgroup runs out of
   // registers, so that width always takes 4 waves)

@@ -794,3 +794,38 @@ def test_binding_rejects_tensors_of_the_wrong_size():
         dq.attn_decode(cache, q, idx3, 128, dws, tail=(k[:, :, :16].contiguous(), k[:, :, :16].contiguous(), idx2))
     dq.attn_decode(cache, q, idx3, 128, dws)                             # and the right sizes go through
     torch.cuda.synchronize()
+
+
+@pytest.mark.parametrize("flags", [dq.DECODE_FORCE_MFMA, dq.DECODE_FORCE_GENERIC])
+def test_more_sequence_head_pairs_than_a_grid_extent(flags):
+    """65 600 (sequence, query head) pairs: beyond the 65 535 rows a launch's y index takes, the rows
+    ride on the x index.  Sampled pairs hold oracle-compressed blocks and are compared with the oracle;
+    the rest of the cache is zero-filled (every code dequantizes to zero there)."""
+    import dataclasses
+    batch, heads = 16400, 4
+    w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=heads, kv_heads=heads,
+                            max_seq=128, min_seq=128, seed=9100)
+    fmt, ofmt = formats(w)
+    _say("decode with %d (sequence, head) pairs, flags=%d" % (batch * heads, flags))
+    cache = dq.alloc_cache(fmt, batch, heads, 1, DEV, fill=0)
+    sample = [(0, 0), (batch - 1, heads - 1), (8191, 2), (16383, 1), (12345, 3)]
+    q = np.zeros((batch, heads, 128), np.float16)
+    lens = np.full(batch, 128, np.int32)
+    lens[12345] = 77
+    want = {}
+    r = np.random.default_rng(4)
+    for b, h in sample:
+        k, v = workloads.kv_pair(w, b, h, 128)
+        one = O.empty_cache(ofmt, 1, 1, 1)
+        O.compress_sequence(one, ofmt, 0, 0, k, v)
+        for name, arr in one.items():
+            cache.t[name][b, h] = torch.from_numpy(arr[0, 0]).to(DEV)
+        q[b, h] = r.standard_normal(128).astype(np.float16)
+        want[b, h] = O.attention_decode(one, ofmt, q[b:b + 1, h:h + 1], lens[b:b + 1])[0, 0]
+    ws = dq.decode_workspace(fmt, batch, heads, heads, 128, DEV)
+    out = dq.attn_decode(cache, torch.from_numpy(q).to(DEV), torch.from_numpy(lens).to(DEV), 128, ws, flags=flags)
+    torch.cuda.synchronize()
+    got = out.cpu().numpy().astype(np.float64)
+    for b, h in sample:
+        assert (np.abs(got[b, h] - want[b, h]) <= tolerance(want[b, h])).all(), (b, h)
+    assert np.isfinite(got).all() and np.abs(got[1]).max() == 0.0     # zero-filled pairs give zeros

@@ -87,8 +87,8 @@ def test_decode_rejects_a_small_workspace_and_bad_sizes_before_launching(dq):
     st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 6, ptr, 1024, 0.0, ptr, None, ptr, need, 0, None)
     assert st == -1
     # more (sequence, query head) pairs than one launch takes
-    fake.batch = 16384
-    big = dq.lib.dq_decode_workspace_bytes(C.byref(good), 16384, 4, 4, 1024)
+    fake.batch = (1 << 22) + 1
+    big = dq.lib.dq_decode_workspace_bytes(C.byref(good), (1 << 22) + 1, 4, 4, 1024)
     st = dq.lib.dq_attn_decode(C.byref(good), cache_p, ptr, 4, ptr, 1024, 0.0, ptr, None, ptr, big, 0, None)
     assert st == -1
     fake.batch = 2
