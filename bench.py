@@ -141,6 +141,19 @@ def _gen_pair(task):
     return b, h, k, v
 
 
+class _InProcess:
+    """Stand-in for the worker pool: draws the inputs in the calling process."""
+
+    def imap_unordered(self, fn, tasks, chunksize=1):
+        return map(fn, tasks)
+
+    def close(self):
+        pass
+
+    def join(self):
+        pass
+
+
 # --------------------------------------------------------------------------------------------
 # GPU side
 # --------------------------------------------------------------------------------------------
@@ -360,6 +373,8 @@ def main():
                     help="(sequence, head) pairs the CPU oracle is timed on for the headline workload "
                          "(half as many for the other entries of per_config)")
     ap.add_argument("--no-cpu-baseline", action="store_true")
+    ap.add_argument("--gen-workers", type=int, default=16,
+                    help="host processes that draw the synthetic inputs (0: in this process, for runs under a profiler)")
     ap.add_argument("--generic", action="store_true", help="force the reference-grade HIP kernel")
     args = ap.parse_args()
     if args.gpus != 1:
@@ -372,7 +387,7 @@ def main():
         for n in names:
             cpu[n] = cpu_baseline(n, args.cpu_pairs if n == args.workload else max(1, args.cpu_pairs // 2))
     # workers that draw the synthetic inputs (forked before the GPU is initialised; they never touch it)
-    pool = mp.get_context("fork").Pool(min(os.cpu_count() or 1, 16))
+    pool = mp.get_context("fork").Pool(min(os.cpu_count() or 1, args.gen_workers)) if args.gen_workers > 0 else _InProcess()
 
     import torch
     import paper_2405_12591_amd as dq

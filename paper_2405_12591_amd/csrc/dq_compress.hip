@@ -117,8 +117,14 @@ __device__ __forceinline__ uint32_t fields_of_four(float x0, float x1, float x2,
 // All NT threads of the workgroup call it, after a barrier that follows the last field's store;
 // it ends with a barrier (lds_u may be reused).  The value layout needs D * (128 * BITS / 32 + 1)
 // words of staging behind the fields.
+// Parts of a tile whose value rows are collected before they are stored: enough for 32 bytes.
+__host__ __device__ constexpr int pack_parts(int bits, int qt) {
+  const int want = bits == 8 ? 64 : 32;   // bytes per store and row
+  return (qt * bits / 8 >= want || qt >= kTileTokens) ? 1 : (want * 8 / (qt * bits) < kTileTokens / qt ? want * 8 / (qt * bits) : kTileTokens / qt);
+}
+
 // QT < 128: lds_u holds QT rows, the rows [part * QT, (part + 1) * QT) of the tile that begins at
-// codes_out (staging D * (QT * BITS / 32 + 1) words).
+// codes_out (staging D * (pack_parts(BITS, QT) * QT * BITS / 32 + 1) words).
 template <int BITS, int D, int NT, int QT = kTileTokens>
 __device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1, int j2, int value_layout,
                                             uint8_t* __restrict__ codes_out, int part = 0) {
@@ -147,7 +153,13 @@ __device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1,
     // leave in output order.
     constexpr int WPR = QT / PER_WORD;            // words per (b2, r) row held here
     constexpr int WPR_TILE = kTileTokens / PER_WORD;   // ... and in the tile
+    // A row's words of AP successive parts are collected in the staging area (it lies behind the
+    // fields and survives from part to part) and leave together, so that no store is shorter
+    // than 32 bytes: shorter pieces of a row cost the memory system a whole request each.
+    constexpr int AP = pack_parts(BITS, QT);
+    constexpr int WST = AP * WPR;                 // words per row in the staging area
     uint32_t* stage = reinterpret_cast<uint32_t*>(lds_u + QT * d);
+    const int sub = part % AP;
     for (int idx = tid; idx < total_words; idx += NT) {
       const int col = idx % d, wi = idx / d;
       const int b2 = col % j2, r = col / j2;
@@ -155,11 +167,14 @@ __device__ __forceinline__ void pack_fields(uint8_t* __restrict__ lds_u, int j1,
 #pragma unroll
       for (int k = 0; k < PER_WORD; ++k)
         word |= (uint32_t)lds_u[(wi * PER_WORD + k) * d + col] << (k * BITS);
-      stage[(b2 * j1 + r) * (WPR + 1) + wi] = word;
+      stage[(b2 * j1 + r) * (WST + 1) + sub * WPR + wi] = word;
     }
     __syncthreads();
-    for (int w = tid; w < total_words; w += NT)
-      out32[(w / WPR) * WPR_TILE + part * WPR + w % WPR] = stage[(w / WPR) * (WPR + 1) + w % WPR];
+    if (sub == AP - 1) {
+      const int first = (part - sub) * WPR;       // the collected words' place in the tile's row
+      for (int w = tid; w < AP * total_words; w += NT)
+        out32[(w / WST) * WPR_TILE + first + w % WST] = stage[(w / WST) * (WST + 1) + w % WST];
+    }
   }
   __syncthreads();
 }
@@ -535,7 +550,8 @@ __global__ __launch_bounds__(64) void decompose_kernel(dq_format fmt, dq_cache c
     uint16_t* small = (which ? cache.v_small : cache.k_small) + blk * g.small_per_block;
     bool sat = false;
     for (int idx = tid; idx < nent; idx += 64) {
-      const int b1 = idx / j1, r = idx % j1;
+      // neighbouring lanes write neighbouring entries of the stored array (keys are stored transposed)
+      const int b1 = which ? idx / j1 : idx % j1, r = which ? idx % j1 : idx / j1;
       const double u = Vc[b1 * ld + order[r]];
       const double sg = sigma[r];
       W[r * ld + b1] = sg > 0.0 ? u / sg : 0.0;
@@ -708,7 +724,7 @@ __global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose
   // fused quantizer: one byte per element of QT token rows, then the value layout's staging
   // (a pair: one such area per head, of 64 channels each)
   constexpr int QT = LEAN ? 32 : kTileTokens;                // rows quantized and packed at a time
-  constexpr int kHeadArea = QT * d + d * (QT * (QB ? QB : 8) / 32 + 1) * 4;
+  constexpr int kHeadArea = QT * d + d * (pack_parts(QB ? QB : 8, QT) * QT * (QB ? QB : 8) / 32 + 1) * 4;
   constexpr int kFieldBytes = QB ? (PAIR ? 2 : 1) * kHeadArea : 16;
   // the lean build's fields take the place of the matrices, which are dead by then (one wave: its
   // LDS operations execute in program order)
@@ -862,7 +878,8 @@ __global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose
     uint16_t* small = (which ? cache.v_small : cache.k_small) + blk * g.small_per_block;
     bool sat = false;
     for (int idx = l; idx < j1 * j1; idx += 64) {
-      const int b1 = idx >> 4, r = idx & 15;
+      // neighbouring lanes write neighbouring entries of the stored array (keys are stored transposed)
+      const int b1 = which ? idx >> 4 : idx & 15, r = which ? idx & 15 : idx >> 4;
       const double uv = V[b1 * ld + order[r]];
       const double sg = sigma[r];
       W[r * ld + b1] = sg > 0.0 ? uv / sg : 0.0;
