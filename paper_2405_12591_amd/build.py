@@ -58,14 +58,20 @@ def _split_remarks(log: str):
     return kernels, "\n".join(rest)
 
 
-def build_library(verbose: bool = False) -> str:
+TIMELINE_LIB_PATH = os.path.join(PKG_DIR, "libdecoquant_timeline.so")
+
+
+def build_library(verbose: bool = False, timeline: bool = False) -> str:
     """Compile every HIP source (in parallel, one hipcc per file) and link one shared library;
-    returns its path."""
+    returns its path.  timeline=True builds the instrumented copy (-DDQ_TIMELINE: the matrix-core
+    decode kernel stamps a time line per wave; see timeline.py) beside the product library, which it
+    leaves alone."""
     from concurrent.futures import ThreadPoolExecutor
     hipcc = os.environ.get("HIPCC", "/opt/rocm/bin/hipcc")
-    obj_dir = os.path.join(PKG_DIR, "_build")
+    obj_dir = os.path.join(PKG_DIR, "_build_timeline" if timeline else "_build")
     os.makedirs(obj_dir, exist_ok=True)
-    flags = [f for f in HIPCC_FLAGS if f != "-shared"]
+    flags = [f for f in HIPCC_FLAGS if f != "-shared"] + (["-DDQ_TIMELINE"] if timeline else [])
+    out_path = TIMELINE_LIB_PATH if timeline else LIB_PATH
     includes = ["-I" + os.path.join(ROOT, "include"), "-I" + os.path.join(PKG_DIR, "csrc")]
     jobs = []
     for src in sources():
@@ -81,16 +87,18 @@ def build_library(verbose: bool = False) -> str:
             raise RuntimeError("hipcc failed on %s:\n%s" % (os.path.basename(src), log))
         resources.update(kernels)
         logs.append(log)
-    with open(RESOURCES_PATH, "w") as f:
-        json.dump(resources, f, indent=0, sort_keys=True)
-    rc, log = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[j[1] for j in jobs], "-o", LIB_PATH + ".tmp"])
+    if not timeline:
+        with open(RESOURCES_PATH, "w") as f:
+            json.dump(resources, f, indent=0, sort_keys=True)
+    rc, log = _run([hipcc, "--offload-arch=gfx950", "-shared", "-fPIC", *[j[1] for j in jobs], "-o", out_path + ".tmp"])
     if rc != 0:
         raise RuntimeError("link failed:\n" + log)
-    os.replace(LIB_PATH + ".tmp", LIB_PATH)
+    os.replace(out_path + ".tmp", out_path)
     if verbose and any(l.strip() for l in logs + [log]):
         print("\n".join(l for l in logs + [log] if l.strip()))
-    return LIB_PATH
+    return out_path
 
 
 if __name__ == "__main__":
-    print(build_library(verbose=True))
+    import sys
+    print(build_library(verbose=True, timeline="--timeline" in sys.argv))

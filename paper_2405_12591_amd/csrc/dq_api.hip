@@ -111,6 +111,14 @@ __global__ __launch_bounds__(256) void stream_read_kernel(const u32x4* __restric
 
 using namespace dq;
 
+#ifdef DQ_TIMELINE
+namespace dq { unsigned long long* g_timeline = nullptr; }
+// Instrumented build only: the device buffer ([workgroups * waves, kTimelineSlots] u64, zero-filled by the
+// caller) the matrix-core decode kernel's waves stamp their time line into; NULL switches it off.
+extern "C" void dq_debug_timeline(void* buffer) { dq::g_timeline = reinterpret_cast<unsigned long long*>(buffer); }
+extern "C" int32_t dq_debug_timeline_slots(void) { return dq::kTimelineSlots; }
+#endif
+
 extern "C" int32_t dq_version(void) { return 6; }
 
 extern "C" const char* dq_status_string(int32_t status) {
@@ -208,6 +216,9 @@ static int32_t decode_impl(const dq_format* fmt, const dq_cache* cache, const ui
   a.n_slots = a.n_split + (tail ? 1 : 0);
   if (tail) a.tail = *tail;
   else a.tail = dq_tail{nullptr, nullptr, nullptr, 0};
+#ifdef DQ_TIMELINE
+  a.timeline = g_timeline;
+#endif
   a.ev_start = (hipEvent_t)ev_kernel_start;
   a.ev_stop = (hipEvent_t)ev_kernel_stop;
   hipStream_t st = (hipStream_t)hip_stream;

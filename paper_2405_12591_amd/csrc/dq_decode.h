@@ -27,7 +27,20 @@ struct DecodeArgs {
   int rows_on_x;           // 0: grid (splits, rows); 1: grid (rows, splits), for more rows than a grid's y extent takes
   hipEvent_t ev_start;     // optional: recorded around the main kernel
   hipEvent_t ev_stop;
+#ifdef DQ_TIMELINE
+  // Instrumented build only (-DDQ_TIMELINE, see timeline.py): every wave of the matrix-core kernel
+  // leaves kTimelineSlots time stamps of the 100 MHz real-time counter here, or nothing if null.
+  unsigned long long* timeline;
+#endif
 };
+
+#ifdef DQ_TIMELINE
+// slot 0: wave entry; 1: lengths known, first tile's arithmetic starts; 2 + k: the wave's k-th tile
+// starts (k < 16, later tiles overwrite the last of them); 18: its last tile is done; 19: exit (merge and
+// output done); 20: not a time, the number of waves per workgroup
+constexpr int kTimelineSlots = 21;
+extern unsigned long long* g_timeline;   // set by dq_debug_timeline(), read by the decode entry points
+#endif
 
 // Which (sequence, kv head) unit the workgroups with blockIdx.y == row work on.  Workgroups go to
 // the XCDs round-robin, so with the plain mapping an XCD only ever sees the units of one residue

@@ -220,6 +220,23 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   __shared__ float s_sum[4];
 
   const int tid = threadIdx.x, lane = tid & 63;
+#ifdef DQ_TIMELINE
+  // time line of this wave (instrumented build only): slot numbers in dq_decode.h
+  unsigned long long* const tl_wave = a.timeline
+      ? a.timeline + ((long)(blockIdx.y * gridDim.x + blockIdx.x) * NW + (tid >> 6)) * kTimelineSlots : nullptr;
+#define DQ_STAMP(slot)                                                          \
+  do {                                                                          \
+    if (tl_wave && lane == 0) tl_wave[slot] = __builtin_amdgcn_s_memrealtime(); \
+  } while (0)
+#else
+#define DQ_STAMP(slot) \
+  do {                 \
+  } while (0)
+#endif
+  DQ_STAMP(0);
+#ifdef DQ_TIMELINE
+  if (tl_wave && lane == 0) tl_wave[20] = NW;
+#endif
   // the wave's number as a scalar: everything derived from it (its tiles, their addresses) is then
   // computed once per wave on the scalar unit instead of once per lane
   const int wave = __builtin_amdgcn_readfirstlane(tid >> 6);
@@ -662,8 +679,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         const int* s1 = s0 + SS;
         const int* s2 = s1 + SS;
         const int* s3 = s2 + SS;
-        sA += (((float)s0[tA] * 128.f + (float)s1[tA]) * 16384.f + ((float)s2[tA] * 128.f + (float)s3[tA])) * dkA[gr];
-        sB += (((float)s0[tB] * 128.f + (float)s1[tB]) * 16384.f + ((float)s2[tB] * 128.f + (float)s3[tB])) * dkB[gr];
+        // limb pairs are joined as integers (|S| < 2^17 per limb: 128 channels x 8 x 127), then as floats
+        sA += ((float)(s0[tA] * 128 + s1[tA]) * 16384.f + (float)(s2[tA] * 128 + s3[tA])) * dkA[gr];
+        sB += ((float)(s0[tB] * 128 + s1[tB]) * 16384.f + (float)(s2[tB] * 128 + s3[tB])) * dkB[gr];
       }
       if (N3) {   // rows -> tokens with T_3^K
         const float yA = sA, yB = sB;
@@ -850,14 +868,21 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   }
   S = min(max(seq_len_raw, 0), a.max_seq_len);
   const int tiles_total = (S + kTileTokens - 1) / kTileTokens;
+  DQ_STAMP(1);
   {
     int tile = first_tile;
+    [[maybe_unused]] int nth = 0;
     if (tile < tiles_total) {
       if (!spec_ok) issue_tile(tile);   // cannot happen while seq_len <= max_seq_len; kept for safety
-      for (; tile + tile_stride < tiles_total; tile += tile_stride) compute_tile(tile, std::true_type{});
+      for (; tile + tile_stride < tiles_total; tile += tile_stride) {
+        DQ_STAMP(2 + min(nth++, 15));
+        compute_tile(tile, std::true_type{});
+      }
+      DQ_STAMP(2 + min(nth++, 15));
       compute_tile(tile, std::false_type{});
     }
   }
+  DQ_STAMP(18);
 
   // ---- merge the waves of the workgroup ----
   float* Macc = reinterpret_cast<float*>(wl);            // [NC][128] per wave (reuses the wave's LDS)
@@ -927,10 +952,15 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       }
     }
   }
-  if (a.n_split == 1) return;
+  if (a.n_split == 1) {
+    DQ_STAMP(19);
+    return;
+  }
 
   ticket_and_merge();
+  DQ_STAMP(19);
 }
+#undef DQ_STAMP
 template <int BITS, int NG, int R, int TM, bool N3, bool P2>
 inline void launch_tm(const DecodeArgs& a, hipStream_t st) {
   const int units = a.cache.batch * a.cache.kv_heads / (P2 ? 2 : 1);
