@@ -38,21 +38,21 @@ FP64_MFMA_PEAK_TFLOPS = 78.6
 LARGE_CONFIGS = ["llama7b_4bit", "llama7b_2bit", "llama13b_mixed", "gqa_long"]
 
 # HBM bytes per launch of the streaming kernel from the rocprofv3 FETCH_SIZE + WRITE_SIZE runs kept
-# under profiles/ (counter values in KiB, scaled by what the same counters read for the plain read
-# kernel of known size).  A constant of the profiled build, not a quantity of this run: the run
+# under profiles/ (counter values in KiB; FETCH_SIZE scaled by what it reads for the plain read kernel
+# of known size, WRITE_SIZE as it is: it reads 1.0 x a known write).  A constant of the profiled build, not a quantity of this run: the run
 # cannot host the profiler.  None where no such run exists.
 PROFILED_TRAFFIC_BYTES = {
-    ("llama7b_4bit", "mfma"): (71822 + 64) * 1.9988 * 1024,
-    ("llama7b_2bit", "mfma"): (164026 + 128) * 1.9994 * 1024,
-    ("llama7b_8bit", "mfma"): (137581 + 64) * 1.9994 * 1024,
-    ("llama13b_mixed", "mfma"): (152212 + 352) * 2.0150 * 1024,
-    ("gqa_long", "mfma"): (287272 + 764) * 1.9997 * 1024,
-    ("gqa8_long", "mfma"): (359155 + 256) * 1.9997 * 1024,
-    ("opt_d64_4bit", "mfma"): (71851 + 64) * 1.9988 * 1024,
-    ("llama7b_4bit_n3", "mfma"): (72852 + 64) * 1.9988 * 1024,
+    ("llama7b_4bit", "mfma"): (71814.0 * 1.9994 + 64.0) * 1024,
+    ("llama7b_2bit", "mfma"): (164017.5 * 1.9997 + 128.0) * 1024,
+    ("llama7b_8bit", "mfma"): (137574.9 * 1.9997 + 64.0) * 1024,
+    ("llama13b_mixed", "mfma"): (152202.1 * 1.9998 + 352.5) * 1024,
+    ("gqa_long", "mfma"): (287270.8 * 1.9999 + 764.0) * 1024,
+    ("gqa8_long", "mfma"): (363217.2 * 1.9999 + 256.0) * 1024,
+    ("opt_d64_4bit", "mfma"): (71839.5 * 1.9994 + 64.0) * 1024,
+    ("llama7b_4bit_n3", "mfma"): (72855.0 * 1.9994 + 64.0) * 1024,
 }
 TRAFFIC_SOURCE = ("profiles/decode_mfma_llama7b_4bit.md, profiles/decode_mfma_other_workloads.md: rocprofv3 --pmc "
-                  "FETCH_SIZE / WRITE_SIZE per launch, scaled by the read-kernel calibration (a constant of the "
+                  "FETCH_SIZE (scaled by the read-kernel calibration) + WRITE_SIZE per launch (a constant of the "
                   "profiled build, not measured in this run)")
 
 
