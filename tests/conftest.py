@@ -8,6 +8,17 @@ if ROOT not in sys.path:
     sys.path.insert(0, ROOT)
 
 
+def pytest_addoption(parser):
+    parser.addoption("--sweep-scale", type=int, default=1,
+                     help="multiplies the number of seeds of the random sweeps in tests/test_gpu_sweep.py")
+
+
+def pytest_generate_tests(metafunc):
+    # a test that takes `sweep_seed` runs once per seed: two seeds by default, 2 * --sweep-scale on request
+    if "sweep_seed" in metafunc.fixturenames:
+        metafunc.parametrize("sweep_seed", list(range(2 * max(1, metafunc.config.getoption("--sweep-scale")))))
+
+
 def pytest_configure(config):
     config.addinivalue_line("markers", "gpu: needs a real MI355X (run with -m gpu)")
 

@@ -20,7 +20,7 @@ def _say(msg):
     print(msg, flush=True)
 
 
-def _both_ways(w, t_new, n_valid, blk):
+def _both_ways(w, t_new, n_valid, blk, waves=0):
     fmt, _ = formats(w)
     k, v = workloads.kv_tensor(w, t_new)
     kd, vd = torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV)
@@ -31,7 +31,7 @@ def _both_ways(w, t_new, n_valid, blk):
         cache = dq.alloc_cache(fmt, w.batch, w.kv_heads, 2, DEV, fill=0xA5)
         ws = dq.compress_workspace(fmt, w.batch, w.kv_heads, DEV)
         ws[256:].fill_(0x5A)                       # whatever the large-tensor region held before
-        dq.compress_kv(cache, kd, vd, bi, nv, ws, keep_large=keep)
+        dq.compress_kv(cache, kd, vd, bi, nv, ws, keep_large=keep, waves=waves)
         torch.cuda.synchronize()
         out.append((cache, ws[:8].clone()))
     (a, sa), (b, sb) = out
