@@ -20,8 +20,8 @@ What follows which passage of the paper
                                    ordinary attention); "Kernel Fusion for Dequantization"
                                    (scale x integer, then the product of T_L and T_S)
   * compression ratio mu           Section 3.3, Eq. 4
-  * n = 3 variant (T_1 x T_2 x T_3, middle tensor quantized)
-                                   Preliminary, Eq. 2 with n = 3; Section 4.3 "Analysis of
+  * n = 3 and n = 4 variants (T_1 x T_2 x T_3 [x T_4], T_2 quantized)
+                                   Preliminary, Eq. 2 with n = 3, 4; Section 4.3 "Analysis of
                                    Length of Local Tensors"
 
 Readings taken where the paper is silent (each is listed in the design notes of
@@ -38,7 +38,10 @@ clips, Delta = fp16(max(max(x) / (2^(m-1) - 1), max(-x) / 2^(m-1))).  Three loca
 (`i3` > 1): factors I = 1 * (T_b/i3) * i3, J = j1 * j2 * 1, so the third tensor mixes
 the i3 tokens of a run of consecutive tokens; the singular values of the first cut stay in
 T_1 and those of the second cut in T_3, which leaves the quantized middle tensor T_2 with
-orthonormal columns.
+orthonormal columns.  Four local tensors (`i4` > 1, this module only: the HIP library has no
+such format): I = 1 * i2 * i3 * i4, J = j1 * j2 * 1 * 1, three cuts, the singular values of the
+second cut pushed on into the third and those of the third kept in T_4, so that the quantized T_2
+again has orthonormal columns; T_3 [i3*i4, i3, i4] and T_4 [i4, i4] are kept in fp16.
 
 Parity pins (tests/test_oracle_*.py): exact reconstruction <= 1e-10, orthonormal
 rows of T_L, textbook SVD special cases, exact-rational brute force of the
@@ -69,6 +72,8 @@ class Format:
     levels: int = 0   # 0: Eq. 1's symmetric codes [-qmax, qmax]; 1: all 2^bits codes [-qmax - 1, qmax]
     i1: int = 1   # Eq. 2's i_1: the small tensor's share of the token index (i_2 = block_tokens / i1);
                   # > 1: T_S is (i1*j1) x (i1*j1) and mixes i1 groups of tokens as well as channels
+    i4: int = 1   # > 1 (with i3 > 1): four local tensors, the token index split as (a2, a3, a4) with
+                  # a4 < i4 fastest; not a format of the HIP library
 
     @property
     def small_side(self) -> int:
@@ -92,8 +97,15 @@ class Format:
             raise ValueError("i1 must divide block_tokens")
         if self.i1 > 1 and self.i3 > 1:
             raise ValueError("i1 > 1 is defined for two local tensors only")
+        if self.i4 < 1 or (self.i4 > 1 and (self.i3 == 1 or self.block_tokens % (self.i3 * self.i4))):
+            raise ValueError("i4 > 1 needs i3 > 1 and i3*i4 dividing block_tokens")
         if self.i1 * self.j1 > (self.block_tokens // self.i1) * self.j2:
             raise ValueError("the small tensor's side must not exceed the large tensor's (bond = i1*j1)")
+
+    @property
+    def bond3(self) -> int:
+        """Bond dimension between T_2 and T_3 (rows of the large tensor per position a2)."""
+        return self.i3 * self.i4
 
     @property
     def qmax(self) -> int:
@@ -234,6 +246,51 @@ def mpo3_contract(t_1: np.ndarray, t_2: np.ndarray, t_3: np.ndarray) -> np.ndarr
     j1, i2, j2, i3 = t_2.shape
     x = np.einsum("br,racd,de->aebc", t_1, t_2, t_3)    # [a2, a3, b1, b2]
     return x.reshape(i2 * i3, j1 * j2)
+
+
+def mpo4_split(x: np.ndarray, j1: int, i3: int, i4: int
+               ) -> Tuple[np.ndarray, np.ndarray, np.ndarray, np.ndarray]:
+    """Four-site MPO of X[T_b, d] (Eq. 2 with n = 4) for the factor shapes I = 1 * i2 * i3 * i4,
+    J = j1 * j2 * 1 * 1 (token index (a2, a3, a4), a4 fastest):
+      X[(a2, a3, a4), (b1, b2)] = sum_{r, e, f} T_1[b1, r] T_2[r, a2, b2, e] T_3[e, a3, f] T_4[f, a4].
+
+    Three SVDs, no truncation.  The first is `mpo_split` (T_1 = U S).  Its right factor, regrouped
+    as A[(r, a2, b2), (a3, a4)], is cut into T_2 = U' (orthonormal columns, bond e of size i3*i4,
+    the large tensor) and S' V'^T, which, regrouped as B[(e, a3), a4], is cut into T_3 = U''
+    (bond f of size i4) and T_4 = S'' V''^T.  Returns (T_1 [j1, j1], T_2 [j1, i2, j2, i3*i4],
+    T_3 [i3*i4, i3, i4], T_4 [i4, i4]).  Signs: as in `mpo3_split`, fixed by the largest entry of
+    the right-hand factor's row at each of the two later cuts (reproducibility only).
+    """
+    x = np.asarray(x, dtype=np.float64)
+    n_tok, d = x.shape
+    j2, run = d // j1, i3 * i4
+    i2 = n_tok // run
+    if i2 * run != n_tok:
+        raise ValueError("i3*i4 must divide the number of rows")
+    if j1 * i2 * j2 < run:
+        raise ValueError("the large tensor's side must not be smaller than i3*i4")
+    t_1, right = mpo_split(x, j1)                       # right[r, (t, b2)], t = (a2, a3, a4)
+    a = right.reshape(j1, i2, run, j2).transpose(0, 1, 3, 2).reshape(j1 * i2 * j2, run)
+    u, s, vt = np.linalg.svd(a, full_matrices=False)
+    rest = s[:, None] * vt                              # [e, (a3, a4)]
+    piv = np.argmax(np.abs(rest), axis=1)
+    sign = np.where(rest[np.arange(run), piv] < 0, -1.0, 1.0)
+    t_2 = (u * sign[None, :]).reshape(j1, i2, j2, run)
+    rest = rest * sign[:, None]
+    b = rest.reshape(run * i3, i4)                      # [(e, a3), a4]
+    u2, s2, vt2 = np.linalg.svd(b, full_matrices=False)
+    t_4 = s2[:, None] * vt2
+    piv = np.argmax(np.abs(t_4), axis=1)
+    sign = np.where(t_4[np.arange(i4), piv] < 0, -1.0, 1.0)
+    return t_1, t_2, (u2 * sign[None, :]).reshape(run, i3, i4), t_4 * sign[:, None]
+
+
+def mpo4_contract(t_1: np.ndarray, t_2: np.ndarray, t_3: np.ndarray, t_4: np.ndarray) -> np.ndarray:
+    """X[(a2, a3, a4), (b1, b2)] from the four local tensors of `mpo4_split`, term by term."""
+    j1, i2, j2, run = t_2.shape
+    _, i3, i4 = t_3.shape
+    x = np.einsum("br,racd,def,fg->aegbc", t_1, t_2, t_3, t_4)   # [a2, a3, a4, b1, b2]
+    return x.reshape(i2 * i3 * i4, j1 * j2)
 
 
 def middle_to_token_major(t_2: np.ndarray) -> np.ndarray:
@@ -382,7 +439,9 @@ class Block:
     steps: np.ndarray    # fp16 [block_tokens, head_dim/group]
     codes: np.ndarray    # int32 [block_tokens, head_dim], element index r*j2 + b2
     large32: np.ndarray  # fp32 [block_tokens, head_dim], the unquantized large tensor, token-major
-    small3: Optional[np.ndarray] = None   # fp16 [i3 (bond e), i3 (token a3)]   T_3, three tensors only
+    small3: Optional[np.ndarray] = None   # fp16 [i3 (bond e), i3 (token a3)]   T_3, three tensors
+                                          # (four: [i3*i4 (bond e), i3 (token a3), i4 (bond f)])
+    small4: Optional[np.ndarray] = None   # fp16 [i4 (bond f), i4 (token a4)]   T_4, four tensors only
 
 
 def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
@@ -398,14 +457,19 @@ def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
     n = x.shape[0] if n_valid is None else n_valid
     xb = np.zeros((tb, d), np.float64)
     xb[:n] = np.asarray(x[:n], dtype=np.float64)
-    small3 = None
+    small3 = small4 = None
     if fmt.i3 > 1:
         if identity_small or sigma_in != "small":
-            raise ValueError("the three-tensor form has no identity / sigma-in-large variant")
-        t_s, t_2, t_3 = mpo3_split(xb, fmt.j1, fmt.i3)
+            raise ValueError("the three- and four-tensor forms have no identity / sigma-in-large variant")
+        if fmt.i4 > 1:
+            t_s, t_2, t_3, t_4 = mpo4_split(xb, fmt.j1, fmt.i3, fmt.i4)
+        else:
+            t_s, t_2, t_3 = mpo3_split(xb, fmt.j1, fmt.i3)
         kp = middle_to_token_major(t_2)
         with np.errstate(over="ignore"):
             small3 = t_3.astype(np.float16)
+            if fmt.i4 > 1:
+                small4 = t_4.astype(np.float16)
     else:
         if identity_small:
             t_s = np.eye(fmt.small_side)
@@ -417,20 +481,33 @@ def compress_block(x: np.ndarray, fmt: Format, n_valid: Optional[int] = None,
     codes = quantize_codes(kp, steps, fmt.group, fmt.qmax, fmt.full_range)
     with np.errstate(over="ignore"):
         small = t_s.astype(np.float16)
-    return Block(small=small, steps=steps, codes=codes, large32=kp, small3=small3)
+    return Block(small=small, steps=steps, codes=codes, large32=kp, small3=small3, small4=small4)
+
+
+def _token_factor(small3: np.ndarray, small4: Optional[np.ndarray], fmt: Format, absolute: bool = False) -> np.ndarray:
+    """What multiplies the middle tensor on the token side, as one matrix [bond e, token in run]:
+    T_3 itself (three tensors), or T_3 contracted with T_4 over the bond f (four; token (a3, a4)).
+    absolute: the same with every entry replaced by its magnitude (for error bounds)."""
+    t_3 = small3.astype(np.float64)
+    if fmt.i4 == 1:
+        return np.abs(t_3) if absolute else t_3
+    t_4 = small4.astype(np.float64)
+    if absolute:
+        t_3, t_4 = np.abs(t_3), np.abs(t_4)
+    return np.einsum("def,fg->deg", t_3, t_4).reshape(fmt.bond3, fmt.bond3)
 
 
 def reconstruct_block(small: np.ndarray, steps: np.ndarray, codes: np.ndarray, fmt: Format,
-                      small3: Optional[np.ndarray] = None) -> np.ndarray:
+                      small3: Optional[np.ndarray] = None, small4: Optional[np.ndarray] = None) -> np.ndarray:
     """X_hat[block_tokens, head_dim] = un-matricise(T_S16 @ (Delta * c)) in fp64, no rounding.
     Three tensors: the dequantized middle tensor is first multiplied by T_3 (fp16 values) over
-    the bond e, which gives the right factor of the first cut back."""
+    the bond e, which gives the right factor of the first cut back; four: by T_3 and T_4."""
     # rows past the valid tokens of a partly filled block may hold anything (NaN steps included)
     with np.errstate(invalid="ignore", over="ignore"):
         deq = dequantize(codes, steps, fmt.group)
         if fmt.i3 > 1:
-            t_2_hat = token_major_to_middle(deq, fmt.j1, fmt.j2, fmt.i3)          # [r, a2, b2, e]
-            right = np.einsum("racd,de->raec", t_2_hat, small3.astype(np.float64))  # [r, a2, a3, b2]
+            t_2_hat = token_major_to_middle(deq, fmt.j1, fmt.j2, fmt.bond3)       # [r, a2, b2, e]
+            right = np.einsum("racd,de->raec", t_2_hat, _token_factor(small3, small4, fmt))  # [r, a2, token in run, b2]
             t_l_hat = right.reshape(fmt.j1, fmt.block_tokens * fmt.j2)
         else:
             t_l_hat = token_major_to_large(deq, fmt.j1, fmt.j2, fmt.i1)
@@ -439,15 +516,16 @@ def reconstruct_block(small: np.ndarray, steps: np.ndarray, codes: np.ndarray, f
 
 
 def reconstruction_bound(small: np.ndarray, steps: np.ndarray, fmt: Format,
-                         small3: Optional[np.ndarray] = None) -> np.ndarray:
+                         small3: Optional[np.ndarray] = None, small4: Optional[np.ndarray] = None) -> np.ndarray:
     """Elementwise bound on |X_hat - T_S16 @ T_L| from the Delta/2 code error:
     0.5 * sum_r |T_S16[b1, r]| * Delta[t, group(r*j2 + b2)], shape [block_tokens, head_dim].
-    Three tensors: Delta[t, .] is replaced by sum_e |T_3[e, a3]| * Delta[(a2, e), .]."""
+    Three tensors: Delta[t, .] is replaced by sum_e |T_3[e, a3]| * Delta[(a2, e), .]; four: by the
+    same sum with sum_f |T_3[e, a3, f]| |T_4[f, a4]| in the place of |T_3[e, a3]|."""
     tb, d = fmt.block_tokens, fmt.head_dim
     delta = np.repeat(steps.astype(np.float64), fmt.group, axis=1)      # [t, r*j2+b2]
     if fmt.i3 > 1:
-        dm = token_major_to_middle(delta, fmt.j1, fmt.j2, fmt.i3)       # [r, a2, b2, e]
-        right = np.einsum("racd,de->raec", dm, np.abs(small3.astype(np.float64)))
+        dm = token_major_to_middle(delta, fmt.j1, fmt.j2, fmt.bond3)    # [r, a2, b2, e]
+        right = np.einsum("racd,de->raec", dm, _token_factor(small3, small4, fmt, absolute=True))
         delta_l = right.reshape(fmt.j1, tb * fmt.j2)
     else:
         delta_l = token_major_to_large(delta, fmt.j1, fmt.j2, fmt.i1)   # [r, (a2, b2)]
@@ -471,14 +549,20 @@ def empty_cache(fmt: Format, batch: int, kv_heads: int, block_capacity: int) -> 
     and, with three local tensors,
       k_small3 f16 [B, H, NB, i3 (token a3), i3 (bond e)]  T_3 of keys, TRANSPOSED (token first)
       v_small3 f16 [B, H, NB, i3 (bond e), i3 (token a3)]  T_3 of values, natural
+    and, with four (this module's own arrangement: no library reads it), both T_3 natural and flat,
+      k_small3, v_small3 f16 [B, H, NB, i3*i4 (bond e), i3*i4 ((a3, f))]
+      k_small4, v_small4 f16 [B, H, NB, i4 (bond f), i4 (token a4)]
     """
     fmt.check()
     b, h, nb, tb, d = batch, kv_heads, block_capacity, fmt.block_tokens, fmt.head_dim
     tiles = tb // TILE_TOKENS
     extra = {}
     if fmt.i3 > 1:
-        extra = {"k_small3": np.zeros((b, h, nb, fmt.i3, fmt.i3), np.float16),
-                 "v_small3": np.zeros((b, h, nb, fmt.i3, fmt.i3), np.float16)}
+        extra = {"k_small3": np.zeros((b, h, nb, fmt.bond3, fmt.bond3), np.float16),
+                 "v_small3": np.zeros((b, h, nb, fmt.bond3, fmt.bond3), np.float16)}
+    if fmt.i4 > 1:
+        extra["k_small4"] = np.zeros((b, h, nb, fmt.i4, fmt.i4), np.float16)
+        extra["v_small4"] = np.zeros((b, h, nb, fmt.i4, fmt.i4), np.float16)
     return {
         **extra,
         "k_codes": np.zeros((b, h, nb, tb, fmt.row_bytes), np.uint8),
@@ -499,7 +583,11 @@ def store_block(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: int, blk: 
     cache["v_codes"][b, h, blk] = pack_rows(value_codes_to_tiles(vblock.codes, fmt.j1, fmt.j2), fmt.bits)
     cache["v_scales"][b, h, blk] = vblock.steps
     cache["v_small"][b, h, blk] = vblock.small
-    if fmt.i3 > 1:
+    if fmt.i4 > 1:
+        for name, blk_ in (("k", kblock), ("v", vblock)):
+            cache[name + "_small3"][b, h, blk] = blk_.small3.reshape(fmt.bond3, fmt.bond3)
+            cache[name + "_small4"][b, h, blk] = blk_.small4
+    elif fmt.i3 > 1:
         cache["k_small3"][b, h, blk] = kblock.small3.T
         cache["v_small3"][b, h, blk] = vblock.small3
 
@@ -507,7 +595,17 @@ def store_block(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: int, blk: 
 def load_block(cache: Dict[str, np.ndarray], fmt: Format, b: int, h: int, blk: int, which: str
                ) -> Tuple:
     """Read (small [b1, r] fp16, steps, signed codes [t, r*j2+b2]) of a key ('k') or value ('v')
-    block; with three local tensors a fourth item, T_3 [e, a3] fp16, follows."""
+    block; with three local tensors a fourth item, T_3 [e, a3] fp16, follows; with four, T_3
+    [e, a3, f] and T_4 [f, a4]."""
+    if fmt.i4 > 1:
+        if which == "k":
+            codes = unpack_rows(cache["k_codes"][b, h, blk], fmt.bits)
+            first = (cache["k_small"][b, h, blk].T, cache["k_scales"][b, h, blk], codes)
+        else:
+            codes = value_tiles_to_codes(unpack_rows(cache["v_codes"][b, h, blk], fmt.bits))
+            first = (cache["v_small"][b, h, blk], cache["v_scales"][b, h, blk], codes)
+        return first + (cache[which + "_small3"][b, h, blk].reshape(fmt.bond3, fmt.i3, fmt.i4),
+                        cache[which + "_small4"][b, h, blk])
     if which == "k":
         codes = unpack_rows(cache["k_codes"][b, h, blk], fmt.bits)
         out = (cache["k_small"][b, h, blk].T, cache["k_scales"][b, h, blk], codes)
@@ -602,7 +700,7 @@ def compression_ratio(fmt: Format, step_bits: int = 16) -> float:
     """mu = (#T_L * B + #T_S * 16 + bits of the steps) / (#W * 16) for one block (Eq. 4)."""
     n_w = fmt.block_tokens * fmt.head_dim
     n_l = fmt.j1 * fmt.block_tokens * fmt.j2
-    n_s = fmt.small_side * fmt.small_side + (fmt.i3 * fmt.i3 if fmt.i3 > 1 else 0)
+    n_s = fmt.small_side * fmt.small_side + (fmt.bond3 * fmt.bond3 if fmt.i3 > 1 else 0) + (fmt.i4 * fmt.i4 if fmt.i4 > 1 else 0)
     n_delta = fmt.block_tokens * fmt.groups_per_row
     return (n_l * fmt.bits + n_s * 16 + n_delta * step_bits) / (n_w * 16.0)
 
@@ -610,4 +708,5 @@ def compression_ratio(fmt: Format, step_bits: int = 16) -> float:
 def cache_bytes_per_block(fmt: Format) -> int:
     """Bytes one key (or value) block occupies in the storage arrays."""
     return (fmt.block_tokens * fmt.row_bytes + fmt.block_tokens * fmt.groups_per_row * 2
-            + fmt.small_side * fmt.small_side * 2 + (fmt.i3 * fmt.i3 * 2 if fmt.i3 > 1 else 0))
+            + fmt.small_side * fmt.small_side * 2 + (fmt.bond3 * fmt.bond3 * 2 if fmt.i3 > 1 else 0)
+            + (fmt.i4 * fmt.i4 * 2 if fmt.i4 > 1 else 0))
