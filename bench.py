@@ -273,7 +273,7 @@ def settle_clocks(dq, torch, caches, q, lens_d, max_seq, ws, out, flags, ms=150.
     return i
 
 
-def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0"):
+def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0", shape_tag=None):
     fmt, cache0, lens, comp = build_cache(dq, torch, w, dev, pool)
     caches = [cache0] + [cache0.clone() for _ in range(n_layers - 1)]
     q = torch.from_numpy(workloads.query(w)).to(dev)
@@ -332,19 +332,19 @@ def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0"):
     alg = algorithmic_bytes(w, lens)
     achieved = alg / (kernel_ms.mean() * 1e-3) / 1e9
     res = {
-        "workload": w.name,
+        "workload": w.name + (shape_tag or ""),
         "value": w.batch / (ms_per_step * 1e-3),
         "unit": "tokens/s",
         "steps": K, "warmup": W, "clock_settle_steps_before_warmup": settled,
         "ms_per_step": ms_per_step,
         "dtype": ("u%d codes on int8 MFMA, f32 accumulate" if path == "mfma" else "u%d codes, f32") % w.bits,
-        "config": {"workload": w.name, "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
+        "config": {"workload": w.name + (shape_tag or ""), "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "seq_len": [int(lens.min()), int(lens.max())], "bits": w.bits,
                    "group": w.group, "block_tokens": w.block_tokens, "j1": w.j1, "local_tensors": 3 if w.i3 > 1 else 2,
                    "kernel_path": path,
                    "cache_copies_rotated": n_layers, "cache_bytes_per_layer": cache0.nbytes()},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
-                     "frac": achieved / HBM_PEAK_GBPS, "traffic": PROFILED_TRAFFIC_BYTES.get((w.name, path)),
+                     "frac": achieved / HBM_PEAK_GBPS, "traffic": None if shape_tag else PROFILED_TRAFFIC_BYTES.get((w.name, path)),
                      "traffic_source": TRAFFIC_SOURCE,
                      "kernel_ms_mean": float(kernel_ms.mean()), "kernel_ms_median": float(np.median(kernel_ms)),
                      "algorithmic_bytes_per_launch": alg},
@@ -376,11 +376,28 @@ def main():
     ap.add_argument("--gen-workers", type=int, default=16,
                     help="host processes that draw the synthetic inputs (0: in this process, for runs under a profiler)")
     ap.add_argument("--generic", action="store_true", help="force the reference-grade HIP kernel")
+    ap.add_argument("--shape", default=None, metavar="B,HQ,HKV,S",
+                    help="with --only: the workload's format and value distribution on another shape (batch, query "
+                         "heads, kv heads, tokens per sequence); no CPU baseline and no profiled traffic for such a run")
     args = ap.parse_args()
     if args.gpus != 1:
         print("bench.py measures one GPU only (this build has no multi-GPU path); run with --gpus 1", file=sys.stderr)
         sys.exit(2)
 
+    shaped = None
+    if args.shape:
+        if not args.only:
+            print("--shape needs --only", file=sys.stderr)
+            sys.exit(2)
+        import dataclasses
+        b_, hq_, hkv_, s_ = (int(x) for x in args.shape.split(","))
+        base = workloads.get_workload(args.workload)
+        if b_ < 1 or hkv_ < 1 or hq_ % hkv_ or s_ < base.block_tokens or s_ % base.block_tokens or base.append_tokens:
+            print("--shape: B,HQ,HKV,S with HQ a multiple of HKV and S a multiple of the block size; not for workloads "
+                  "that append rows", file=sys.stderr)
+            sys.exit(2)
+        shaped = dataclasses.replace(base, batch=b_, q_heads=hq_, kv_heads=hkv_, max_seq=s_, min_seq=s_)
+        args.no_cpu_baseline = True
     names = [args.workload] if args.only else [n for n in LARGE_CONFIGS if n != args.workload] + [args.workload]
     cpu = {}
     if not args.no_cpu_baseline:      # before any GPU initialisation (fork)
@@ -399,14 +416,15 @@ def main():
     n_layers = max(1, args.layers)
     results = {}
     for n in names:
-        w = workloads.get_workload(n)
-        results[n] = run_config(dq, torch, w, K, W, n_layers, args.generic, pool)
+        w = shaped or workloads.get_workload(n)
+        results[n] = run_config(dq, torch, w, K, W, n_layers, args.generic, pool,
+                                shape_tag=("@" + args.shape) if shaped else None)
         results[n]["cpu_baseline"] = cpu.get(n)
     pool.close()
     pool.join()
 
     head = results[args.workload]
-    w = workloads.get_workload(args.workload)
+    w = shaped or workloads.get_workload(args.workload)
     line = {
         "metric": "decode-attention tokens/s per layer, 4-bit DecoQuant KV cache" if w.bits == 4 else
                   "decode-attention tokens/s per layer, %d-bit DecoQuant KV cache" % w.bits,
