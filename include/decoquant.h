@@ -284,7 +284,9 @@ int32_t dq_compress_kv_blocks(const dq_format* fmt, dq_cache* cache, const uint1
 #define DQ_COMPRESS_NO_LARGE 1u   /* the caller will not read them: the library may skip that hand-off */
 #define DQ_COMPRESS_PLAIN 2u      /* use the plain vector-code decomposition kernel whatever the shape (for comparison) */
 #define DQ_COMPRESS_WAVES(n) (((uint32_t)(n) & 0xFu) << 8) /* wavefronts per block of the tuned decomposition
-                                     kernel: 1, 2 or 4; 0 leaves the choice to the library (for sweeps) */
+                                     kernel: 1, 2 or 4; 0 leaves the choice to the library (for sweeps).  With three
+                                     local tensors 1 selects the build that makes both cuts and quantizes in one
+                                     launch (the library's choice above 512 blocks), 2 and 4 the three launches */
 
 /*
  * dq_compress_kv_blocks with flags (t_new <= T_b makes it dq_compress_kv): for callers that do not

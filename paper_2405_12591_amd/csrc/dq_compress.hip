@@ -17,6 +17,7 @@ struct CompressJob {
   int n_blocks;              // ceil(t_new / T_b)
   const int32_t* blk_idx;    // [B]
   const int32_t* n_valid;    // [B] or null
+  int keep_large;            // the one-kernel three-tensor build also leaves its fp32 rows in the workspace
 };
 
 // Work unit `unit` = (((b * H + h) * n_blocks) + j) * 2 + which.  slot < 0: nothing to do (sequence
@@ -654,8 +655,17 @@ __device__ __forceinline__ void pair16(int round, int k, int& p, int& q) {
 // that the wave keeps fewer registers (loads in smaller batches, the solver's rounds not unrolled) and
 // less LDS (the quantizer works on 64 rows at a time in the space the solver's matrices leave).  The
 // arithmetic, and so every bit written, is that of the other builds.
-template <int NWV, bool PAIR, int QB = 0, bool FULL = false, bool LEAN = false>
-__global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
+// N3 (lean build with the quantizer, d = 128): three local tensors (Eq. 2 with n = 3, factor shapes
+// 1 * (T_b/8) * 8 by j1 * j2 * 1) in the same kernel.  The first cut's right factor R is never
+// stored: a first pass over the rows forms it 16 tokens at a time (rounded to fp32, the precision
+// the three-kernel path keeps it in) and adds it to the 8 x 8 Gram matrix of the second cut,
+// A^T A with A[(r, a2, b2), a3]; the same wave solves that 8 x 8 problem and writes T_3; a second
+// pass forms R again, this time with the tokens down the rows of the matrix-core result, which is
+// the operand layout that lets a second matrix product contract over the eight tokens of a run
+// (T_2 = A V' diag(1/sigma')), and hands the rows of T_2 to the quantizer in the registers it
+// expects them in.  job.keep_large: the fp32 rows of T_2 also go to the workspace.
+template <int NWV, bool PAIR, int QB = 0, bool FULL = false, bool LEAN = false, bool N3 = false>
+__global__ __launch_bounds__(64 * NWV, LEAN ? ((PAIR || N3) ? 3 : 4) : 1) void decompose16_kernel(dq_format fmt, dq_cache cache, CompressJob job,
                                                                float* __restrict__ large_ws,
                                                                int32_t* __restrict__ unit_status,
                                                                int32_t* __restrict__ call_status) {
@@ -719,6 +729,7 @@ __global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose
   const long head_gap = (long)job.t_new * d;   // PAIR: from a row of the first head to the same row of the second
 
   static_assert(!LEAN || NWV == 1, "the lean build is one wave per block");
+  static_assert(!N3 || (LEAN && !PAIR && QB != 0), "three tensors: lean build with the quantizer, d = 128");
   constexpr int kMat = j1 * ld;                              // doubles per 16 x 16 matrix (padded rows)
   constexpr int kMatBytes = (3 + (NWV > 1 ? NWV - 1 : 1)) * kMat * (int)sizeof(double);
   // fused quantizer: one byte per element of QT token rows, then the value layout's staging
@@ -924,6 +935,143 @@ __global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose
 #pragma unroll
     for (int s = 0; s < 4; ++s) wreg[s] = W[(l & 15) * ld + 4 * s + (l >> 4)];
     if (LEAN) __builtin_amdgcn_wave_barrier();   // W is read; the fields may take the matrices' place
+    double w3reg[4] = {0.0, 0.0, 0.0, 0.0};
+    if constexpr (N3) {
+      // ---- second cut: Gram matrix of A[(r, a2, b2), a3] from the right factor, 16 tokens at a time ----
+      constexpr int N = kRun, LD3 = N + 1;
+      double* const Dm = reinterpret_cast<double*>(pool);        // 16 x 16 token products, padded rows
+      double* A0 = Dm + kMat;
+      double* A1 = A0 + N * LD3;
+      double* V0 = A1 + N * LD3;
+      double* V1 = V0 + N * LD3;
+      double* const W3 = V1 + N * LD3;                           // [e][a3] = V'[a3, e] / sigma'_e
+      double* const rc = W3 + N * N;
+      double* const rs = rc + N;
+      double* const lam3 = rs + N;
+      double* const sigma3 = lam3 + N;
+      int* const partner = reinterpret_cast<int*>(sigma3 + N);
+      int* const is_p = partner + N;
+      int* const order3 = is_p + N;
+      static_assert((kMat + 4 * N * LD3 + N * N + 4 * N) * (int)sizeof(double) + 3 * N * (int)sizeof(int) <= kPoolBytes,
+                    "the second cut's matrices fit the pool");
+      f64x4 g3[4];
+#pragma unroll
+      for (int i = 0; i < 4; ++i) g3[i] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll 1
+      for (int t0 = 0; t0 < nv; t0 += 16) {
+        const int t = t0 + (l & 15);
+        u32x4 x[4];
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          x[s] = u32x4{0u, 0u, 0u, 0u};
+          if (t < nv) x[s] = *reinterpret_cast<const u32x4*>(X + (long)t * d + (4 * s + (l >> 4)) * 8);
+        }
+        f64x4 acc[8];
+#pragma unroll
+        for (int b2 = 0; b2 < 8; ++b2) acc[b2] = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+        for (int s = 0; s < 4; ++s) {
+          const f16x8 h = __builtin_bit_cast(f16x8, x[s]);
+#pragma unroll
+          for (int b2 = 0; b2 < 8; ++b2)
+            acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64(wreg[s], (double)(float)h[b2], acc[b2], 0, 0, 0);
+        }
+        // lane (token l % 16, k = l / 16) holds R[r = k + 4 i][token][b2]: both operands of a product
+        // of the 16 tokens with themselves over four r; the runs' own 8 x 8 blocks are kept below
+#pragma unroll
+        for (int i = 0; i < 4; ++i)
+#pragma unroll
+          for (int b2 = 0; b2 < 8; ++b2) {
+            const double v = (double)(float)acc[b2][i];
+            g3[b2 & 3] = __builtin_amdgcn_mfma_f64_16x16x4f64(v, v, g3[b2 & 3], 0, 0, 0);
+          }
+      }
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        Dm[((l >> 4) + 4 * i) * ld + (l & 15)] = (g3[0][i] + g3[1][i]) + (g3[2][i] + g3[3][i]);
+      __builtin_amdgcn_wave_barrier();
+      {
+        const int p = l >> 3, q = l & 7;
+        A0[p * LD3 + q] = Dm[p * ld + q] + Dm[(p + 8) * ld + q + 8];
+        V0[p * LD3 + q] = (p == q) ? 1.0 : 0.0;
+      }
+      __builtin_amdgcn_wave_barrier();
+      double trace3 = 0.0;
+#pragma unroll
+      for (int i = 0; i < N; ++i) trace3 += A0[i * LD3 + i];
+      const double floor3 = 1e-17 * trace3;
+      // parallel cyclic Jacobi: 7 rounds of 4 disjoint rotations per sweep (the iteration of the
+      // three-kernel path's second cut, in this one wave)
+      double* Ac = A0; double* An = A1; double* Vc = V0; double* Vn = V1;
+      constexpr int NM1 = N - 1;
+      for (int sweep = 0; sweep < 16; ++sweep) {
+        bool any_big = false;
+#pragma unroll 1
+        for (int round = 0; round < NM1; ++round) {
+          bool big = false;
+          if (l < N / 2) {
+            int p, q;
+            if (l == 0) { p = NM1; q = round; }
+            else { p = (round + l) % NM1; q = (round - l + NM1) % NM1; }
+            if (p > q) { const int tmp = p; p = q; q = tmp; }
+            double c, sn;
+            jacobi_rotation(Ac[p * LD3 + p], Ac[q * LD3 + q], Ac[p * LD3 + q], floor3, c, sn, big);
+            rc[p] = c; rs[p] = sn; rc[q] = c; rs[q] = sn;
+            partner[p] = q; partner[q] = p;
+            is_p[p] = 1; is_p[q] = 0;
+          }
+          any_big = any_big || __any(big);
+          __builtin_amdgcn_wave_barrier();
+          {
+            const int i = l >> 3, j = l & 7;
+            const int pi = partner[i], pj = partner[j];
+            const double cj = rc[j], sj = is_p[j] ? -rs[j] : rs[j];
+            const double ci = rc[i], si = is_p[i] ? -rs[i] : rs[i];
+            const double aj_i = Ac[i * LD3 + j] * cj + Ac[i * LD3 + pj] * sj;
+            const double aj_pi = Ac[pi * LD3 + j] * cj + Ac[pi * LD3 + pj] * sj;
+            An[i * LD3 + j] = ci * aj_i + si * aj_pi;
+            Vn[i * LD3 + j] = Vc[i * LD3 + j] * cj + Vc[i * LD3 + pj] * sj;
+          }
+          __builtin_amdgcn_wave_barrier();
+          double* tp = Ac; Ac = An; An = tp;
+          tp = Vc; Vc = Vn; Vn = tp;
+        }
+        if (!any_big) break;
+      }
+      if (l < N) lam3[l] = Ac[l * LD3 + l];
+      __builtin_amdgcn_wave_barrier();
+      if (l < N) {
+        int rank = 0;
+        const double me = lam3[l];
+        for (int s2 = 0; s2 < N; ++s2) rank += (lam3[s2] > me) || (lam3[s2] == me && s2 < l);
+        order3[rank] = l;
+      }
+      __builtin_amdgcn_wave_barrier();
+      if (l < N) {
+        const double lmax = fmax(lam3[order3[0]], 0.0);
+        const double lv = lam3[order3[l]];
+        sigma3[l] = (lv > 1e-12 * lmax && lv > 0.0) ? sqrt(lv) : 0.0;
+      }
+      __builtin_amdgcn_wave_barrier();
+      {
+        const int e = l >> 3, a3 = l & 7;
+        const double v = Vc[a3 * LD3 + order3[e]];
+        const double sg = sigma3[e];
+        W3[e * N + a3] = sg > 0.0 ? v / sg : 0.0;
+        const long b3 = ((long)bh * g.NB + slot) * (N * N);
+        const uint16_t hb = f64_to_f16_rne(v * sg, true, nullptr);   // |T_3| <= sqrt(j1): far inside fp16
+        if (which) cache.v_small3[b3 + e * N + a3] = hb;   // values: natural [e][a3]
+        else cache.k_small3[b3 + a3 * N + e] = hb;         // keys: transposed [a3][e]
+      }
+      __builtin_amdgcn_wave_barrier();
+      // the token mix as the right-hand operand of a product over four tokens (k = l / 16, token
+      // k + 4 i of the group): column n = l % 16 is row e = n % 8 of run n / 8; a token of the other
+      // run contributes nothing
+#pragma unroll
+      for (int i = 0; i < 4; ++i)
+        w3reg[i] = ((i >> 1) == ((l & 15) >> 3)) ? W3[(l & 7) * N + (((l >> 4) + 4 * i) & 7)] : 0.0;
+      __builtin_amdgcn_wave_barrier();   // W3 is read; the fields may take the pool
+    }
     float* out = large_ws + (long)unit * g.Tb * d;
     const long out_gap = (long)unit_gap * g.Tb * d;   // PAIR: to the second head's rows in the workspace
     for (int t0 = 0; t0 < g.Tb; t0 += QT) {
@@ -953,8 +1101,24 @@ __global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose
         for (int s = 0; s < 4; ++s) {
           const f16x8 h = __builtin_bit_cast(f16x8, x[tgi][s]);
 #pragma unroll
-          for (int b2 = 0; b2 < 8; ++b2)
-            acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64(wreg[s], (double)(float)h[b2], acc[b2], 0, 0, 0);
+          for (int b2 = 0; b2 < 8; ++b2) {
+            // (three tensors: operands swapped, so that the result has the 16 tokens down its rows)
+            if (N3) acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64((double)(float)h[b2], wreg[s], acc[b2], 0, 0, 0);
+            else acc[b2] = __builtin_amdgcn_mfma_f64_16x16x4f64(wreg[s], (double)(float)h[b2], acc[b2], 0, 0, 0);
+          }
+        }
+        if constexpr (N3) {
+          // lane (r = l % 16, k = l / 16) holds R[r][token k + 4 i][b2], rounded to fp32 as in the first
+          // pass: left operand of the product over the tokens; the result has rows r = l / 16 + 4 i and
+          // columns (run, e), which is where the quantizer below expects a row of the large tensor
+#pragma unroll
+          for (int b2 = 0; b2 < 8; ++b2) {
+            f64x4 o = f64x4{0.0, 0.0, 0.0, 0.0};
+#pragma unroll
+            for (int i = 0; i < 4; ++i)
+              o = __builtin_amdgcn_mfma_f64_16x16x4f64((double)(float)acc[b2][i], w3reg[i], o, 0, 0, 0);
+            acc[b2] = o;
+          }
         }
         if constexpr (QB == 0) {
 #pragma unroll
@@ -975,6 +1139,14 @@ __global__ __launch_bounds__(64 * NWV, LEAN ? (PAIR ? 3 : 4) : 1) void decompose
           for (int i = 0; i < 4; ++i)
 #pragma unroll
             for (int b2 = 0; b2 < 8; ++b2) f[i][b2] = (float)acc[b2][i];
+          if (N3 && job.keep_large) {
+#pragma unroll
+            for (int i = 0; i < 4; ++i) {
+              float* dst = out + (long)t * d + ((l >> 4) + 4 * i) * 8;
+              *reinterpret_cast<float4*>(dst) = make_float4(f[i][0], f[i][1], f[i][2], f[i][3]);
+              *reinterpret_cast<float4*>(dst + 4) = make_float4(f[i][4], f[i][5], f[i][6], f[i][7]);
+            }
+          }
           float up[2] = {0.f, 0.f}, dn[2] = {0.f, 0.f};   // max |x| (FULL: max x and max -x) per group
 #pragma unroll
           for (int i = 0; i < 4; ++i) {
@@ -1275,7 +1447,7 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   float* large_ws = reinterpret_cast<float*>(reinterpret_cast<char*>(workspace) + kWsHeaderBytes);
   const int units = cache->batch * cache->kv_heads * 2 * n_blocks;
   int32_t* unit_status = reinterpret_cast<int32_t*>(large_ws + (size_t)units * fmt->block_tokens * fmt->head_dim);
-  const CompressJob job = {k_new, v_new, t_new, n_blocks, blk_idx, n_valid};
+  const CompressJob job = {k_new, v_new, t_new, n_blocks, blk_idx, n_valid, (flags & DQ_COMPRESS_NO_LARGE) ? 0 : 1};
   const size_t dlds = decompose_lds_bytes(fmt->i1 * fmt->j1, fmt->head_dim, fmt->i1);
 #define DQ_LAUNCH_DECOMPOSE(J, DD_)                                                                      \
   hipLaunchKernelGGL((decompose_kernel<J, DD_>), dim3(units), dim3(64), dlds, st, *fmt, *cache, job, large_ws, \
@@ -1295,6 +1467,30 @@ static int32_t compress_impl(const dq_format* fmt, dq_cache* cache, const uint16
   const bool fused = (flags & DQ_COMPRESS_NO_LARGE) && fmt->i3 == 1 && fmt->i1 == 1 && !force_general &&
                      ((fmt->head_dim == 128 && fmt->j1 == 16 && (fmt->group == 128 || fmt->group == 64)) ||
                       (pair_heads && fmt->group == 64));
+  // Three local tensors (d = 128, j1 = 16): the lean build makes both cuts and quantizes in one
+  // launch, and leaves the fp32 rows of T_2 in the workspace if the caller wants them.  It is one wave
+  // per block, so a call of a few hundred blocks, which is bound by the latency of one block's
+  // chain, keeps the three launches (first cut with several waves per block, second cut,
+  // quantizer); larger calls, and a forced wave count of one, take the one-kernel build.
+  const bool fused3 = fmt->i3 == kRun && fmt->i1 == 1 && !force_general && fmt->head_dim == 128 && fmt->j1 == 16 &&
+                      (fmt->group == 128 || fmt->group == 64) && (want_waves == 1 || (want_waves == 0 && units > 512));
+  if (fused3) {
+#define DQ_LAUNCH_FUSED3(B_)                                                                                     \
+  do {                                                                                                           \
+    if (fmt->levels)                                                                                             \
+      hipLaunchKernelGGL((decompose16_kernel<1, false, B_, true, true, true>), dim3(units), dim3(64), 0, st, *fmt, \
+                         *cache, job, large_ws, unit_status, status);                                            \
+    else                                                                                                         \
+      hipLaunchKernelGGL((decompose16_kernel<1, false, B_, false, true, true>), dim3(units), dim3(64), 0, st,    \
+                         *fmt, *cache, job, large_ws, unit_status, status);                                      \
+  } while (0)
+    if (fmt->bits == 2) DQ_LAUNCH_FUSED3(2);
+    else if (fmt->bits == 4) DQ_LAUNCH_FUSED3(4);
+    else DQ_LAUNCH_FUSED3(8);
+#undef DQ_LAUNCH_FUSED3
+    DQ_HIP_CHECK(hipGetLastError());
+    return DQ_OK;
+  }
   if (fused) {
 #define DQ_LAUNCH_FUSED(N_, B_)                                                                                 \
   do {                                                                                                          \

@@ -134,6 +134,64 @@ def test_compress_kv_three_tensors_properties(name, t_new, n_valid):
     _check_compress3(w, t_new, n_valid)
 
 
+@pytest.mark.parametrize("name,t_new,n_valid", [
+    ("llama7b_4bit", 128, None), ("llama7b_2bit", 100, [100, 37, 1]), ("llama7b_8bit", 128, None), ("gqa_long", 77, None),
+    ("llama13b_mixed", 128, [128, 1, 9]),
+])
+def test_compress_kv_three_tensors_one_kernel_build(name, t_new, n_valid):
+    """The same properties for the build that makes both cuts and quantizes in one launch (what calls
+    of more than 512 blocks take; a forced wave count of one selects it for a small call)."""
+    w = _small(name, batch=3 if n_valid else 2, q_heads=4, kv_heads=2)
+    _say("compress, three tensors, one launch: %s t_new=%d n_valid=%s" % (name, t_new, n_valid))
+    _check_compress3(w, t_new, n_valid, waves=1)
+
+
+@pytest.mark.parametrize("bits,group,levels", [(4, 128, 0), (2, 64, 1), (8, 128, 0)])
+def test_compress_three_tensors_prompt_sized_call(bits, group, levels):
+    """A prompt-sized call (2304 blocks, two per sequence and head, cut inside the kernel) through the
+    one-kernel build: with and without the fp32 rows kept the cache is the same bit for bit, and
+    sampled blocks have the oracle's properties; ragged rows and a skipped sequence included."""
+    batch, kvh = 9, 64
+    w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=kvh, kv_heads=kvh, bits=bits,
+                            group=group, levels=levels, max_seq=256, min_seq=256, i3=8)
+    fmt, ofmt = formats(w)
+    _say("three tensors, prompt-sized call: bits=%d G=%d levels=%d, %d blocks" % (bits, group, levels, batch * kvh * 4))
+    gen = torch.Generator(device=DEV).manual_seed(5)
+    kd = (torch.randn((batch, kvh, 256, 128), device=DEV, generator=gen) * 2).to(torch.float16)
+    vd = (torch.randn((batch, kvh, 256, 128), device=DEV, generator=gen) * 2).to(torch.float16)
+    kd[:, :, :, 5] *= 20
+    lens = [256, 130, 1, 0, 255, 128, 129, 256, 77]
+    firsts = [0, 1, 0, 0, 0, -1, 0, 0, 1]
+    n_valid = torch.tensor(lens, dtype=torch.int32, device=DEV)
+    first = torch.tensor(firsts, dtype=torch.int32, device=DEV)
+    out = []
+    for keep in (True, False):
+        cache = dq.alloc_cache(fmt, batch, kvh, 3, DEV, fill=0xA5)
+        ws = dq.compress_workspace(fmt, batch, kvh, DEV, t_new=256)
+        dq.compress_kv_blocks(cache, kd, vd, first, n_valid, ws, keep_large=keep)
+        torch.cuda.synchronize()
+        assert int(ws[:4].view(torch.int32).item()) == 0
+        out.append((cache, ws))
+    for name in out[0][0].t:
+        assert torch.equal(out[0][0].t[name], out[1][0].t[name]), name
+    arrs = {n: t.cpu().numpy() for n, t in out[0][0].t.items()}
+    units = batch * kvh * 2 * 2
+    large = out[0][1][256:256 + 4 * units * 128 * 128].view(torch.float32).cpu().numpy().reshape(units, 128, 128)
+    kh, vh = kd.cpu().numpy(), vd.cpu().numpy()
+    worst = 0.0
+    for b, h in [(0, 0), (1, 63), (4, 17), (8, 1), (7, 40), (6, 5)]:
+        for j in range(2):
+            nv = min(max(lens[b] - 128 * j, 0), 128)
+            if nv == 0:
+                continue
+            for which, rows in (("k", kh), ("v", vh)):
+                x = np.zeros((128, 128))
+                x[:nv] = rows[b, h, 128 * j:128 * j + nv].astype(np.float64)
+                unit = ((b * kvh + h) * 2 + j) * 2 + (which == "v")
+                worst = max(worst, _block_properties3(arrs, ofmt, x, large[unit], b, h, firsts[b] + j, which))
+    _say("  worst |T_2^T T_2 - I| = %.3g over the sampled blocks" % worst)
+
+
 @pytest.mark.parametrize("seed", [31, 32])
 def test_compress_kv_three_tensors_random_cases(seed):
     """Seeded sweep: code widths, group sizes, head dimensions, block sizes, ragged n_valid, short
@@ -153,7 +211,7 @@ def test_compress_kv_three_tensors_random_cases(seed):
                                 seed=5000 + 100 * seed + case, n_outlier=int(rng.choice([0, 2, 6])), i3=8)
         _say("compress, three tensors, random seed %d case %d: d=%d j1=%d bits=%d G=%d Tb=%d B=%d H=%d t_new=%d n_valid=%s"
              % (seed, case, d, j1, bits, group, tb, batch, kvh, t_new, n_valid))
-        _check_compress3(w, t_new, n_valid)
+        _check_compress3(w, t_new, n_valid, waves=case % 2)    # the library's choice, then the one-kernel build
 
 
 @pytest.mark.parametrize("i3", [1, 8])
@@ -192,7 +250,45 @@ def test_compress_kv_degenerate_blocks(i3):
                 assert (np.abs(x_hat - ref) <= bound + slack).all(), (b, h, which, np.abs(x_hat - ref).max())
 
 
-def _check_compress3(w, t_new, n_valid):
+def _block_properties3(arrs, ofmt, x, kp, b, h, slot, which):
+    """The oracle's properties of one three-tensor block the GPU wrote: x [T_b, d] fp64 is what went
+    in (rows past the valid ones zero), kp [T_b, d] fp32 the middle tensor it left in the workspace
+    (row a2*8 + e).  Returns |T_2^T T_2 - I|."""
+    tb, d, j1, j2 = ofmt.block_tokens, ofmt.head_dim, ofmt.j1, ofmt.j2
+    small, steps, codes, small3 = O.load_block(arrs, ofmt, b, h, slot, which)
+    t_2 = O.token_major_to_middle(kp.astype(np.float64), j1, j2, 8)
+    # (1) columns of T_2 orthonormal over (r, a2, b2), or zero for dropped directions
+    a = t_2.reshape(-1, 8)
+    gram = a.T @ a
+    live = np.diag(gram) > 0.5
+    ortho = np.abs(gram - np.diag(live.astype(np.float64))).max()
+    assert ortho <= 2e-6, (b, h, which)
+    # (2) the three tensors multiply back to the block, up to the fp16 rounding of T_1
+    # and T_3 and the fp32 storage of T_2 and of the first cut's right factor
+    s3 = small3.astype(np.float64)
+    right = np.einsum("racd,de->raec", t_2, s3).reshape(j1, tb * j2)
+    right_abs = np.einsum("racd,de->raec", np.abs(t_2), np.abs(s3)).reshape(j1, tb * j2)
+    m = O.matricise(x, 1, j1)
+    resid = np.abs(small.astype(np.float64) @ right - m)
+    slack = 2.0 ** -9 * (np.abs(small.astype(np.float64)) @ right_abs) + 1e-6 * np.abs(m).max() + 1e-7
+    assert (resid <= slack).all(), (b, h, which, resid.max())
+    # T_3 has orthogonal rows (it is diag(sigma') V'^T), up to its fp16 rounding
+    g3 = s3 @ s3.T
+    assert np.abs(g3 - np.diag(np.diag(g3))).max() <= 4e-3 * max(np.diag(g3).max(), 1e-30)
+    # (3) codes and steps are the oracle's quantization of that very T_2
+    steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax, ofmt.full_range)
+    codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax, ofmt.full_range)
+    assert np.array_equal(steps.view(np.uint16), steps_o.view(np.uint16))
+    assert np.array_equal(codes, codes_o)
+    # (4) reconstruction within the half-step bound
+    x_hat = O.reconstruct_block(small, steps, codes, ofmt, small3)
+    bound = O.reconstruction_bound(small, steps, ofmt, small3)
+    slack_x = O.unmatricise(slack, tb, d, 1, j1)
+    assert (np.abs(x_hat - x) <= bound + slack_x).all(), (b, h, which)
+    return ortho
+
+
+def _check_compress3(w, t_new, n_valid, waves=0):
     fmt, ofmt = formats(w)
     tb, d, j1, j2 = fmt.block_tokens, fmt.head_dim, fmt.j1, fmt.j2
     k = np.stack([np.stack([workloads.kv_pair(w, b, h, t_new)[0] for h in range(w.kv_heads)]) for b in range(w.batch)])
@@ -206,7 +302,7 @@ def _check_compress3(w, t_new, n_valid):
         slots = np.array([1, -1], np.int32)      # second sequence is skipped
     nv = None if n_valid is None else torch.tensor(n_valid, dtype=torch.int32, device=DEV)
     dq.compress_kv(cache, torch.from_numpy(k).to(DEV), torch.from_numpy(v).to(DEV),
-                   torch.from_numpy(slots).to(DEV), nv, ws)
+                   torch.from_numpy(slots).to(DEV), nv, ws, waves=waves)
     torch.cuda.synchronize()
     arrs = {n: t.cpu().numpy() for n, t in cache.t.items()}
     assert int(ws[:4].view(torch.int32).item()) == 0
@@ -224,37 +320,8 @@ def _check_compress3(w, t_new, n_valid):
                 n_ok = t_new if n_valid is None else min(n_valid[b], t_new)
                 x = np.zeros((tb, d))
                 x[:n_ok] = x_all[b, h, :n_ok].astype(np.float64)
-                small, steps, codes, small3 = O.load_block(arrs, ofmt, b, h, slot, which)
                 kp = large[(b * w.kv_heads + h) * 2 + (which == "v")]      # the middle tensor, row a2*8 + e
-                t_2 = O.token_major_to_middle(kp.astype(np.float64), j1, j2, 8)
-                # (1) columns of T_2 orthonormal over (r, a2, b2), or zero for dropped directions
-                a = t_2.reshape(-1, 8)
-                gram = a.T @ a
-                live = np.diag(gram) > 0.5
-                worst_ortho = max(worst_ortho, np.abs(gram - np.diag(live.astype(np.float64))).max())
-                assert worst_ortho <= 2e-6, (b, h, which)
-                # (2) the three tensors multiply back to the block, up to the fp16 rounding of T_1
-                # and T_3 and the fp32 storage of T_2 and of the first cut's right factor
-                s3 = small3.astype(np.float64)
-                right = np.einsum("racd,de->raec", t_2, s3).reshape(j1, tb * j2)
-                right_abs = np.einsum("racd,de->raec", np.abs(t_2), np.abs(s3)).reshape(j1, tb * j2)
-                m = O.matricise(x, 1, j1)
-                resid = np.abs(small.astype(np.float64) @ right - m)
-                slack = 2.0 ** -9 * (np.abs(small.astype(np.float64)) @ right_abs) + 1e-6 * np.abs(m).max() + 1e-7
-                assert (resid <= slack).all(), (b, h, which, resid.max())
-                # T_3 has orthogonal rows (it is diag(sigma') V'^T), up to its fp16 rounding
-                g3 = s3 @ s3.T
-                assert np.abs(g3 - np.diag(np.diag(g3))).max() <= 4e-3 * max(np.diag(g3).max(), 1e-30)
-                # (3) codes and steps are the oracle's quantization of that very T_2
-                steps_o = O.group_steps(kp, ofmt.group, ofmt.qmax)
-                codes_o = O.quantize_codes(kp, steps_o, ofmt.group, ofmt.qmax)
-                assert np.array_equal(steps.view(np.uint16), steps_o.view(np.uint16))
-                assert np.array_equal(codes, codes_o)
-                # (4) reconstruction within the half-step bound
-                x_hat = O.reconstruct_block(small, steps, codes, ofmt, small3)
-                bound = O.reconstruction_bound(small, steps, ofmt, small3)
-                slack_x = O.unmatricise(slack, tb, d, 1, j1)
-                assert (np.abs(x_hat - x) <= bound + slack_x).all(), (b, h, which)
+                worst_ortho = max(worst_ortho, _block_properties3(arrs, ofmt, x, kp, b, h, slot, which))
                 # (5) other block slots of this head untouched
                 for other in range(nb):
                     if other != slot:
