@@ -273,7 +273,7 @@ def settle_clocks(dq, torch, caches, q, lens_d, max_seq, ws, out, flags, ms=150.
     return i
 
 
-def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0", shape_tag=None):
+def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0", shape_tag=None, launch=(0, 0)):
     fmt, cache0, lens, comp = build_cache(dq, torch, w, dev, pool)
     caches = [cache0] + [cache0.clone() for _ in range(n_layers - 1)]
     q = torch.from_numpy(workloads.query(w)).to(dev)
@@ -281,7 +281,7 @@ def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0", shape_
     max_seq = int(lens.max())
     ws = dq.decode_workspace(fmt, w.batch, w.q_heads, w.kv_heads, max_seq, dev)
     out = torch.empty_like(q)
-    flags = dq.DECODE_FORCE_GENERIC if generic else dq.DECODE_AUTO
+    flags = (dq.DECODE_FORCE_GENERIC if generic else dq.DECODE_AUTO) | dq.decode_flags(splits=launch[0], waves=launch[1])
     path = "generic" if (generic or not dq.decode_mfma_supported(fmt, w.q_heads, w.kv_heads)) else "mfma"
 
     kev = [(torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)) for _ in range(K)]
@@ -341,7 +341,7 @@ def run_config(dq, torch, w, K, W, n_layers, generic, pool, dev="cuda:0", shape_
         "config": {"workload": w.name + (shape_tag or ""), "batch": w.batch, "q_heads": w.q_heads, "kv_heads": w.kv_heads,
                    "head_dim": w.head_dim, "seq_len": [int(lens.min()), int(lens.max())], "bits": w.bits,
                    "group": w.group, "block_tokens": w.block_tokens, "j1": w.j1, "local_tensors": 3 if w.i3 > 1 else 2,
-                   "kernel_path": path,
+                   "kernel_path": path, "launch_override": list(launch) if any(launch) else None,
                    "cache_copies_rotated": n_layers, "cache_bytes_per_layer": cache0.nbytes()},
         "roofline": {"bound": "hbm", "achieved": achieved, "peak": HBM_PEAK_GBPS, "unit": "GB/s",
                      "frac": achieved / HBM_PEAK_GBPS, "traffic": None if shape_tag else PROFILED_TRAFFIC_BYTES.get((w.name, path)),
@@ -376,6 +376,9 @@ def main():
     ap.add_argument("--gen-workers", type=int, default=16,
                     help="host processes that draw the synthetic inputs (0: in this process, for runs under a profiler)")
     ap.add_argument("--generic", action="store_true", help="force the reference-grade HIP kernel")
+    ap.add_argument("--launch", default=None, metavar="SPLITS,WAVES",
+                    help="with --only: override the library's launch shape of the matrix-core kernel (workgroups per "
+                         "(sequence, kv head); waves per workgroup, 4 or 8; 0 leaves either to the library)")
     ap.add_argument("--shape", default=None, metavar="B,HQ,HKV,S",
                     help="with --only: the workload's format and value distribution on another shape (batch, query "
                          "heads, kv heads, tokens per sequence); no CPU baseline and no profiled traffic for such a run")
@@ -418,7 +421,8 @@ def main():
     for n in names:
         w = shaped or workloads.get_workload(n)
         results[n] = run_config(dq, torch, w, K, W, n_layers, args.generic, pool,
-                                shape_tag=("@" + args.shape) if shaped else None)
+                                shape_tag=("@" + args.shape) if shaped else None,
+                                launch=tuple(int(x) for x in args.launch.split(",")) if (args.launch and args.only) else (0, 0))
         results[n]["cpu_baseline"] = cpu.get(n)
     pool.close()
     pool.join()
