@@ -27,3 +27,12 @@ def test_no_gpu_means_an_error_and_no_result_line():
     r = _bench("--steps", "1", "--warmup", "1", "--no-cpu-baseline")
     assert r.returncode != 0
     assert "{" not in r.stdout
+
+
+def test_shape_override_needs_one_workload_and_a_whole_number_of_blocks():
+    r = _bench("--shape", "1,32,32,4096")
+    assert r.returncode == 2 and "--only" in r.stderr and r.stdout.strip() == ""
+    r = _bench("--only", "--workload", "llama7b_4bit", "--shape", "1,32,32,4100")
+    assert r.returncode == 2 and "block size" in r.stderr
+    r = _bench("--only", "--workload", "llama13b_mixed", "--shape", "1,40,40,4096")
+    assert r.returncode == 2 and "append" in r.stderr
