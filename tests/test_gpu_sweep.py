@@ -168,3 +168,30 @@ def test_random_compress_cases(sweep_seed):
             _check_compress(w, t_new, n_valid if n_valid is not None and all(v > 0 for v in n_valid) else None, waves=waves)
         blk = [int(rng.choice([0, 1, -1])) for _ in range(batch)]
         _both_ways(w, t_new, n_valid, blk, waves=waves)
+
+
+def test_random_compress_three_tensor_cases(sweep_seed):
+    """dq_compress_kv with three local tensors over random formats and call shapes, every block held
+    to the oracle's properties (orthonormal columns of T_2, exact product, the oracle's quantizer on
+    the GPU's own T_2 bit for bit, half-step bound): the three launches (the library's choice for a
+    small call, or a forced wave count of 2 or 4) and the build that does everything in one launch
+    (a forced wave count of 1; formats it does not cover fall back to the three launches)."""
+    from test_gpu_mpo3 import _check_compress3
+    rng = np.random.default_rng(9000 + sweep_seed)
+    for case in range(8):
+        d = int(rng.choice([128, 128, 128, 64]))
+        j1 = 16 if d == 128 and rng.integers(0, 6) else int(rng.choice([8, 16] if d == 64 else [8, 32]))
+        bits = int(rng.choice([2, 4, 8]))
+        group = int(rng.choice([g for g in (32, 64, 128) if g <= d and (g == d or g <= d // 2) and (g * bits) % 32 == 0]))
+        tb = int(rng.choice([128, 256]))
+        batch, kvh = int(rng.choice([2, 3])), int(rng.choice([1, 2, 5]))
+        levels = int(rng.choice([0, 1]))
+        t_new = int(rng.choice([tb, tb, int(rng.integers(1, tb + 1))]))
+        n_valid = None if rng.integers(0, 2) else [int(rng.choice([1, 2, 8, 9, t_new, int(rng.integers(1, t_new + 1))])) for _ in range(batch)]
+        waves = int(rng.choice([1, 1, 0, 2, 4]))
+        w = dataclasses.replace(workloads.get_workload("llama7b_4bit"), batch=batch, q_heads=kvh, kv_heads=kvh, head_dim=d,
+                                j1=j1, j2=d // j1, bits=bits, group=group, block_tokens=tb, max_seq=tb, min_seq=tb, levels=levels,
+                                seed=9000 + 100 * sweep_seed + case, n_outlier=int(rng.choice([0, 2, 6])), i3=8)
+        print("compress3 seed %d case %d: d=%d j1=%d bits=%d G=%d Tb=%d B=%d H=%d levels=%d t_new=%d n_valid=%s waves=%d"
+              % (sweep_seed, case, d, j1, bits, group, tb, batch, kvh, levels, t_new, n_valid, waves), flush=True)
+        _check_compress3(w, t_new, n_valid, waves=waves)
