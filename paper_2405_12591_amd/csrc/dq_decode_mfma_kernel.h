@@ -199,7 +199,14 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   // The epilogue multiplies o'[r][column] by the values' small tensor, sixteen columns at a time,
   // but one b2 fills only 3 R of them (one limb triple per head, once the two step groups' columns
   // have been merged): the columns of PK = 4 / R successive b2 are packed side by side first.
-  constexpr int PK = 4 / R, NSET = J2 / PK;
+  // With four heads (R = 4) that packing would leave one b2 per set and 32 fp32 matrix instructions
+  // per tile, which on this chip cost what ten vector instructions each cost (matrix and vector
+  // instructions of one SIMD do not run side by side).  There the three limbs of a head are joined
+  // first, as floats, by lane shifts (column 4*head + limb holds limb `limb`, most significant first),
+  // and the joined columns of four successive b2 are packed side by side: 8 matrix instructions
+  // per tile, and a quarter of the accumulators.
+  constexpr bool JOIN = (R == 4 && NG == 1 && !N3 && !P2);
+  constexpr int PK = JOIN ? 4 : 4 / R, NSET = J2 / PK;
   constexpr int RD = P2 ? 64 : D;             // channels of a real head (output, partials, cache rows)
   constexpr int RJ1 = P2 ? 8 : J1;            // rows of a real head's large tensors
   constexpr int ROWB = RD * BITS / 8;         // bytes of a key row in memory
@@ -368,7 +375,7 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   const bool col_live_k = n < NC;                      // key side: four
   // the epilogue's packed columns (see PK): column n holds head packed_head, slot packed_slot of its set
   const int packed_head = (R == 1) ? 0 : (R == 4) ? (n >> 2) : (NG == 1) ? ((n >> 2) & 1) : (n >> 3);
-  const int packed_slot = (R == 1) ? (n >> 2) : (R == 4) ? 0 : (NG == 1) ? (n >> 3) : ((n >> 2) & 1);
+  const int packed_slot = JOIN ? (n & 3) : (R == 1) ? (n >> 2) : (R == 4) ? 0 : (NG == 1) ? (n >> 3) : ((n >> 2) & 1);
 
   // softmax layout: lane = 8*G16 + pi owns the two tokens of token group G16 whose weights sit in
   // B slots 2*pi and 2*pi + 1
@@ -798,10 +805,33 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
         }
       }
     };
+    // JOIN: the limbs of o' joined as floats.  In the lane of column 4*head + k the three limbs of
+    // that head sit k, k - 1 and k - 2 lanes below; every lane computes the combination with the
+    // same shifts and the lanes of slot k = b2 % 4 keep it.  The joined value (|o'| < 2^32) takes one
+    // fp32 rounding, of the size of the accumulation's own.
+    auto pack_joined = [&](i32x4& pk, i32x4 o, auto k_tag) __attribute__((always_inline)) {
+      constexpr int K = decltype(k_tag)::value % 4;
+#pragma unroll
+      for (int i = 0; i < 4; ++i) {
+        const float f = (float)o[i];
+        const int fb = __builtin_bit_cast(int, f);
+        // (shift by zero lanes: the value itself)
+        const float l0 = K == 0 ? f : __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, fb, 0x110 + K /* row_shr:K */, 0xF, 0xF, true));
+        const float l1 = K == 1 ? f : K == 0 ? __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, fb, 0x101 /* row_shl:1 */, 0xF, 0xF, true))
+                                             : __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, fb, 0x110 + (K - 1), 0xF, 0xF, true));
+        const float l2 = K == 2 ? f : K == 3 ? __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, fb, 0x111 /* row_shr:1 */, 0xF, 0xF, true))
+                                             : __builtin_bit_cast(float, __builtin_amdgcn_update_dpp(0, fb, 0x100 + (2 - K) /* row_shl */, 0xF, 0xF, true));
+        const float joined = fmaf(l0, 16384.f, fmaf(l1, 128.f, l2));
+        pk[i] = ((n & 3) == K) ? __builtin_bit_cast(int, joined) : pk[i];
+      }
+    };
     auto epilogue = [&](int st, const i32x4& pk) __attribute__((always_inline)) {
       f32x4 c = acc[st];
 #pragma unroll
-      for (int i = 0; i < 4; ++i) c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], (float)pk[i], c, 0, 0, 0);
+      for (int i = 0; i < 4; ++i) {
+        const int word = pk[i];   // (a copy: the bit cast below wants an object, not an element of a vector)
+        c = __builtin_amdgcn_mfma_f32_16x16x4f32(aT[i], JOIN ? __builtin_bit_cast(float, word) : (float)word, c, 0, 0, 0);
+      }
       acc[st] = c;
     };
     i32x4 pk_cur = izero, pk_done = izero;
@@ -815,7 +845,12 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       o = __builtin_amdgcn_mfma_i32_16x16x64_i8(a1, bp[1], o, 0, 0, 0);
       // the previous set's epilogue runs while this b2's integer MFMAs do
       if (b2 > 0 && b2 % PK == 0) epilogue(b2 / PK - 1, pk_done);
-      if (b2 % PK == 0) pack(pk_cur, o, std::integral_constant<int, 0>{});
+      if constexpr (JOIN) {
+        if (b2 % 4 == 0) pack_joined(pk_cur, o, std::integral_constant<int, 0>{});
+        else if (b2 % 4 == 1) pack_joined(pk_cur, o, std::integral_constant<int, 1>{});
+        else if (b2 % 4 == 2) pack_joined(pk_cur, o, std::integral_constant<int, 2>{});
+        else pack_joined(pk_cur, o, std::integral_constant<int, 3>{});
+      } else if (b2 % PK == 0) pack(pk_cur, o, std::integral_constant<int, 0>{});
       else if (b2 % PK == 1) pack(pk_cur, o, std::integral_constant<int, 1>{});
       else if (b2 % PK == 2) pack(pk_cur, o, std::integral_constant<int, 2>{});
       else pack(pk_cur, o, std::integral_constant<int, 3>{});
@@ -889,7 +924,13 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
   float* Mml = Macc + NC * D;                            // [R] m, [R] l
 #pragma unroll
   for (int hd = 0; hd < R; ++hd) l_run[hd] = wave_allsum(l_run[hd]);
-  if (N3 || (n & 3) != 3) {   // [head][limb][channel b1 * 8 + b2]
+  if (JOIN) {                 // [head][0][channel b1 * 8 + b2]: the limbs are joined already
+#pragma unroll
+    for (int st = 0; st < NSET; ++st) {
+#pragma unroll
+      for (int i = 0; i < 4; ++i) Macc[4 * packed_head * D + (4 * g + i) * J2 + st * PK + packed_slot] = acc[st][i];
+    }
+  } else if (N3 || (n & 3) != 3) {   // [head][limb][channel b1 * 8 + b2]
 #pragma unroll
     for (int st = 0; st < NSET; ++st) {
 #pragma unroll
@@ -914,8 +955,9 @@ __global__ __launch_bounds__(64 * NW, (NW == 4 && BITS < 8) ? 2 : 1) void decode
       const float mw = base[NC * D + hd];
       const float wgt = (mw == -INFINITY) ? 0.f : __builtin_amdgcn_exp2f(mw - M);
       const float* col = base + 4 * hd * D + cv;
-      const float v = N3 ? ((col[0] * 128.f + col[D]) * 128.f + col[2 * D]) * 128.f + col[3 * D]
-                         : col[0] * 16384.f + col[D] * 128.f + col[2 * D];
+      const float v = JOIN ? col[0]
+                      : N3 ? ((col[0] * 128.f + col[D]) * 128.f + col[2 * D]) * 128.f + col[3 * D]
+                           : col[0] * 16384.f + col[D] * 128.f + col[2 * D];
       o = fmaf(v, wgt, o);
       L = fmaf(base[NC * D + R + hd], wgt, L);
     }
