@@ -46,8 +46,8 @@ PROFILED_TRAFFIC_BYTES = {
     ("llama7b_2bit", "mfma"): (164017.5 * 1.9997 + 128.0) * 1024,
     ("llama7b_8bit", "mfma"): (137574.3 * 1.9997 + 64.0) * 1024,
     ("llama13b_mixed", "mfma"): (152201.9 * 1.9998 + 352.5) * 1024,
-    ("gqa_long", "mfma"): (287270.8 * 1.9999 + 764.0) * 1024,
-    ("gqa8_long", "mfma"): (362894.5 * 1.9999 + 256.0) * 1024,
+    ("gqa_long", "mfma"): (287280.5 * 1.9999 + 764.0) * 1024,
+    ("gqa8_long", "mfma"): (353847.3 * 1.9999 + 256.0) * 1024,
     ("opt_d64_4bit", "mfma"): (71839.5 * 1.9994 + 64.0) * 1024,
     ("llama7b_4bit_n3", "mfma"): (72855.0 * 1.9994 + 64.0) * 1024,
 }
