@@ -2,6 +2,7 @@
 
     python -m paper_2405_12591_amd.timeline --build            # here (no GPU needed): builds libdecoquant_timeline.so
     python -m paper_2405_12591_amd.timeline --workload llama7b_4bit     # on the GPU
+    python -m paper_2405_12591_amd.timeline --issue-probe               # on the GPU: do matrix and vector instructions overlap?
 
 The instrumented build is the product's sources compiled with -DDQ_TIMELINE: every wave of
 dq::decode_mfma_kernel stores the 100 MHz real-time counter at its entry, when its first tile's
@@ -10,6 +11,10 @@ run below launches the decode call back to back (clocks settled, caches rotated 
 out the time line of the last launch and prints, per event, the spread over the launch's waves, then
 the median first-tile-to-last-tile time by XCD (workgroups go to the eight XCDs round-robin in launch
 order).  The product library is not touched.
+
+--issue-probe runs the instrumented build's other tool instead: loops of four independent matrix
+instructions of one kind, sixteen independent fp32 FMAs, or both, four waves per SIMD, and prints
+the time per loop body, which tells whether the two kinds of instruction run side by side.
 """
 from __future__ import annotations
 
@@ -23,6 +28,7 @@ ROOT = os.path.dirname(os.path.dirname(os.path.abspath(__file__)))
 def main():
     ap = argparse.ArgumentParser()
     ap.add_argument("--build", action="store_true", help="build the instrumented library and stop")
+    ap.add_argument("--issue-probe", action="store_true", help="time matrix and vector instruction streams, alone and together")
     ap.add_argument("--workload", default="llama7b_4bit")
     ap.add_argument("--launches", type=int, default=2000)
     ap.add_argument("--unit-map", type=int, default=None, help="DQ_DECODE_UNIT_MAP override (default: the library's choice)")
@@ -53,6 +59,9 @@ def main():
     lib = binding.lib
 
     dev = "cuda:0"
+    if args.issue_probe:
+        issue_probe(lib, torch, dev)
+        return
     w = workloads.get_workload(args.workload)
     fmt, cache0, lens, _ = bench.build_cache(dq, torch, w, dev, bench._InProcess())
     if not dq.decode_mfma_supported(fmt, w.q_heads, w.kv_heads):
@@ -122,6 +131,35 @@ def main():
     wg_done = np.array([done[wg == g].max() for g in np.unique(wg)])
     print("workgroups' last tile done: min %.2f, median %.2f, max %.2f us" % (wg_done.min(), np.median(wg_done), wg_done.max()))
     print("launch: first entry to last exit %.2f us; median wave exit %.2f us" % (np.nanmax(us[:, 19]), np.nanmedian(us[:, 19])))
+
+
+def issue_probe(lib, torch, dev, iters=20000):
+    import ctypes as C
+    lib.dq_debug_issue_probe.argtypes = [C.c_int32, C.c_int32, C.c_int32, C.c_void_p, C.c_void_p]
+    lib.dq_debug_issue_probe.restype = C.c_int32
+    sink = torch.zeros(16, dtype=torch.float32, device=dev)
+    stream = torch.cuda.current_stream().cuda_stream
+    kinds = [(0, "none"), (1, "v_mfma_f32_16x16x4_f32"), (2, "v_mfma_f32_16x16x16_f16"), (3, "v_mfma_i32_16x16x64_i8"),
+             (4, "v_mfma_f64_16x16x4_f64")]
+    print("| four matrix instructions of | alone, ns per loop body | with 16 fp32 FMAs | the FMAs alone | sum |  (one wave's loop body; four waves per SIMD)")
+    print("|---|---|---|---|---|")
+    times = {}
+    for kind, _ in kinds:
+        for fma in (0, 1):
+            if kind == 0 and not fma:
+                continue
+            for rep in range(2):       # the first launch warms up
+                e0, e1 = torch.cuda.Event(enable_timing=True), torch.cuda.Event(enable_timing=True)
+                e0.record()
+                rc = lib.dq_debug_issue_probe(kind, fma, iters, sink.data_ptr(), stream)
+                e1.record()
+                torch.cuda.synchronize()
+                if rc != 0:
+                    raise SystemExit("dq_debug_issue_probe failed: %d" % rc)
+            # four waves per SIMD share it: the SIMD's time per loop body of one wave
+            times[kind, fma] = e0.elapsed_time(e1) * 1e6 / (4 * iters) / 4    # four bodies per trip, four waves per SIMD
+    for kind, name in kinds[1:]:
+        print("| %s | %.1f | %.1f | %.1f | %.1f |" % (name, times[kind, 0], times[kind, 1], times[0, 1], times[kind, 0] + times[0, 1]))
 
 
 if __name__ == "__main__":
